@@ -1,0 +1,150 @@
+"""Oracle: loss of ONE perturbed copy of the LoRA-adapted decoder on one token batch.
+
+TEST INFRASTRUCTURE ONLY - never imported by the product path.
+
+This is the function l = L((theta_l, theta_f); B) that Algorithm 1 (line 8) evaluates for each
+perturbed parameter vector.  Every adapted linear is the LoRA layer of Section 2,
+y = x W + x A B (here with an explicit scale s: y = x W + b + s (x A) B), which is what one path
+of the MP-LoRA equation Y = X W + (X A) (.) B of Section 3 computes.  The decoder around it
+(pre-norm blocks, causal attention, LayerNorm/RMSNorm, learned positions or rotary embedding,
+ReLU/GELU/SwiGLU, cross-entropy) is the standard architecture of the evaluated model
+families (Section 4), written out in its plain definition: one copy at a time, whole-tensor
+NumPy operations, binary64 sums, no tiling, no fusion.
+"""
+from __future__ import annotations
+
+from typing import Dict, Tuple
+
+import numpy as np
+from scipy.special import erf
+
+from .precision import Precision
+
+TARGETS = ("q", "k", "v", "o")
+
+
+def _norm(h, gain, bias, kind: str, eps: float):
+    if kind == "layernorm":
+        mu = h.mean(axis=-1, keepdims=True)
+        var = ((h - mu) ** 2).mean(axis=-1, keepdims=True)
+        y = (h - mu) / np.sqrt(var + eps) * gain
+        return y + bias if bias is not None else y
+    ms = (h ** 2).mean(axis=-1, keepdims=True)          # RMSNorm
+    return h / np.sqrt(ms + eps) * gain
+
+
+def rope_tables(S: int, d_head: int, theta: float, prec: Precision) -> Tuple[np.ndarray, np.ndarray]:
+    """cos/sin of p * theta^(-2i/d_head), p < S, i < d_head/2 (stored in binary32 unless exact)."""
+    i = np.arange(d_head // 2, dtype=np.float64)
+    inv_freq = theta ** (-2.0 * i / d_head)
+    ang = np.arange(S, dtype=np.float64)[:, None] * inv_freq[None, :]
+    return prec.stream(np.cos(ang)), prec.stream(np.sin(ang))
+
+
+def _rope(x, cos, sin):
+    """Rotate pairs (i, i + d_head/2) of x [E, S, H, d_head] by the position angle."""
+    half = x.shape[-1] // 2
+    a, b = x[..., :half], x[..., half:]
+    c, s = cos[None, :, None, :], sin[None, :, None, :]
+    return np.concatenate([a * c - b * s, b * c + a * s], axis=-1)
+
+
+def _lora_delta(x, lora, layer: int, target: str, scale: float, prec: Precision):
+    """s (x A) B for one adapted linear, or None when the target carries no adapter."""
+    key = (layer, TARGETS.index(target))
+    if key not in lora:
+        return None
+    A, B = lora[key]
+    t = prec.operand(scale * (x @ prec.lora_factor(A)))
+    return t @ prec.lora_factor(B)
+
+
+def _linear(x, W, b, delta=None):
+    y = x @ np.asarray(W, dtype=np.float64)
+    if b is not None:
+        y = y + b
+    if delta is not None:
+        y = y + delta
+    return y
+
+
+def _attention(q, k, v, n_heads: int, n_kv: int, prec: Precision):
+    """Causal softmax attention; q [E,S,H,dh], k/v [E,S,Hkv,dh] -> [E,S,H*dh]."""
+    E, S, H, dh = q.shape
+    group = n_heads // n_kv
+    out = np.empty((E, S, H, dh))
+    mask = np.triu(np.ones((S, S), dtype=bool), k=1)
+    scale = prec.stream(1.0 / np.sqrt(dh))
+    for h in range(H):
+        kh = h // group
+        s = prec.stream(np.einsum("esd,etd->est", q[:, :, h], k[:, :, kh])) * scale
+        s = np.where(mask[None], -np.inf, s)
+        p = prec.operand(np.exp(s - s.max(axis=-1, keepdims=True)))
+        out[:, :, h] = np.einsum("est,etd->esd", p, v[:, :, kh]) / p.sum(axis=-1, keepdims=True)
+    return out.reshape(E, S, H * dh)
+
+
+def _cross_entropy(logits, target):
+    """-log softmax(logits)[target] row-wise; logits [N, C], target [N]."""
+    m = logits.max(axis=-1, keepdims=True)
+    lse = m[:, 0] + np.log(np.exp(logits - m).sum(axis=-1))
+    return lse - logits[np.arange(logits.shape[0]), target]
+
+
+def copy_loss(w, frozen: Dict[str, object], lora: Dict[Tuple[int, int], Tuple[np.ndarray, np.ndarray]],
+              tokens: np.ndarray, labels, prec: Precision) -> float:
+    """Loss of one copy.  `lora[(layer, target_index)] = (A_c, B_c)` are that copy's factors."""
+    E, S = tokens.shape
+    d, H, Hkv, dh = w.d_model, w.n_heads, w.n_kv_heads, w.d_head
+    h = np.asarray(frozen["emb"], dtype=np.float64)[tokens]                     # [E, S, d]
+    if w.pos == "learned":
+        h = h + np.asarray(frozen["pos_emb"], dtype=np.float64)[None, :S]
+    h = prec.stream(h)
+    if w.pos == "rope":
+        cos, sin = rope_tables(S, dh, w.rope_theta, prec)
+
+    for li, lw in enumerate(frozen["layers"]):
+        x = prec.operand(_norm(h, lw["ln1_g"], lw["ln1_b"], w.norm, w.norm_eps))
+        Wqkv, bqkv = lw["w_qkv"], lw["b_qkv"]
+        cols = {"q": (0, d), "k": (d, d + w.d_kv), "v": (d + w.d_kv, d + 2 * w.d_kv)}
+        proj = {}
+        for name, (c0, c1) in cols.items():
+            b = bqkv[c0:c1] if bqkv is not None else None
+            proj[name] = _linear(x, Wqkv[:, c0:c1], b, _lora_delta(x, lora, li, name, w.lora_scale, prec))
+        qh = proj["q"].reshape(E, S, H, dh)
+        kh = proj["k"].reshape(E, S, Hkv, dh)
+        vh = proj["v"].reshape(E, S, Hkv, dh)
+        if w.pos == "rope":
+            qh, kh = _rope(qh, cos, sin), _rope(kh, cos, sin)
+        qh, kh, vh = prec.operand(qh), prec.operand(kh), prec.operand(vh)
+        attn = prec.operand(_attention(qh, kh, vh, H, Hkv, prec))
+        h = prec.stream(h + _linear(attn, lw["w_o"], lw["b_o"],
+                                    _lora_delta(attn, lora, li, "o", w.lora_scale, prec)))
+
+        x = prec.operand(_norm(h, lw["ln2_g"], lw["ln2_b"], w.norm, w.norm_eps))
+        up = _linear(x, lw["w_up"], lw["b_up"])
+        if w.act == "relu":
+            u = np.maximum(up, 0.0)
+        elif w.act == "gelu":
+            u = 0.5 * up * (1.0 + erf(up / np.sqrt(2.0)))
+        else:                                                                    # SwiGLU
+            gate, lin = up[..., :w.d_ffn], up[..., w.d_ffn:]
+            u = gate / (1.0 + np.exp(-gate)) * lin
+        u = prec.operand(u)
+        h = prec.stream(h + _linear(u, lw["w_down"], lw["b_down"]))
+
+    head = np.asarray(frozen["lm_head"], dtype=np.float64)                       # [V, d]
+    if w.loss_mode == "next_token_all_pos":
+        xf = prec.operand(_norm(h[:, :S - 1], frozen["lnf_g"], frozen["lnf_b"], w.norm, w.norm_eps))
+        logits = prec.stream(xf.reshape(-1, d) @ head.T)
+        ce = _cross_entropy(logits, tokens[:, 1:].reshape(-1))
+    else:
+        xf = prec.operand(_norm(h[:, S - 1], frozen["lnf_g"], frozen["lnf_b"], w.norm, w.norm_eps))
+        labels = np.asarray(labels)
+        if w.loss_mode == "last_pos_label_subset":
+            logits = prec.stream(xf @ head[list(w.label_tokens)].T)              # [E, 2]
+            ce = _cross_entropy(logits, labels)
+        else:                                                                    # last_pos_full_vocab
+            logits = prec.stream(xf @ head.T)
+            ce = _cross_entropy(logits, np.asarray(w.label_tokens)[labels])
+    return float(prec.stream(prec.stream(ce).mean()))
