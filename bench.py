@@ -1,0 +1,133 @@
+#!/usr/bin/env python3
+"""Benchmark: ZO steps of the MP-LoRA hot path on one MI355X, on seeded synthetic inputs.
+
+One step = mpz_regen_noise + mpz_forward_perturbed + mpz_zo_update (all stages of Algorithm 1 for
+q queries x 2 signs in one batched pass).  Prints ONE JSON line (see the fields below).
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_opt125m] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
+PEAK_FP64_VECTOR_TFLOPS = 78.6  # fp32-storage models accumulate in fp64 on the vector ALUs
+
+
+def gemm_flops_per_step(w):
+    """Algorithmic FLOPs of the base-weight GEMMs (+ LM head where the loss needs the whole vocabulary)."""
+    T = 2 * w.q * w.E * w.S
+    d, f = w.d_model, w.d_ffn
+    per_tok = d * (d + 2 * w.d_kv) + d * d + d * f * (2 if w.act == "swiglu" else 1) + f * d
+    fl = 2.0 * T * w.n_layers * per_tok
+    if w.loss_mode == "next_token_all_pos":
+        fl += 2.0 * T * d * w.vocab
+    elif w.loss_mode == "last_pos_full_vocab":
+        fl += 2.0 * 2 * w.q * w.E * d * w.vocab
+    return fl
+
+
+def cpu_baseline(w, frozen, masters, tokens, labels, seed):
+    """The oracle as it stands, timed on the host: one query (both signs) of one step."""
+    import numpy as np
+    import workloads as W
+    from oracle import zo
+    from oracle.precision import Precision
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    lay = W.lora_layout(w)
+    prec = Precision(w.dtype)
+    t0 = time.perf_counter()
+    losses = zo.perturbed_losses(w, lay, frozen, masters, tokens, labels, seed, 0, prec, q=1)
+    g = zo.projected_grads(losses, w.eps)
+    zo.zo_update(masters, g, lay, seed, 0, w.lr, w.perturb_A, prec)
+    dt = time.perf_counter() - t0
+    toks = 2 * w.E * w.S
+    return {"value": toks / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"1 of {w.q} queries (2 of {2 * w.q} copies, {toks} perturbed-copy tokens) of one step "
+                      f"incl. noise and update, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2_opt125m")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (copies would shard across GPUs with one all-gather "
+                 "of q floats, see DESIGN.md); run with --gpus 1")
+
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_2409_15520_amd as M
+
+    w = W.get_workload(args.workload)
+    seeds = {"weights": 1234, "lora": 99, "tokens": 2345, "noise": 3456}
+    frozen = W.make_frozen_weights(w, seeds["weights"])
+    masters = W.make_lora_masters(w, seeds["lora"])
+    tokens, labels = W.make_tokens(w, seeds["tokens"]), W.make_labels(w, seeds["tokens"])
+    m = M.ZoModel(w, frozen, masters, device="cuda:0")
+    tok = torch.from_numpy(tokens).cuda()
+    lab = torch.from_numpy(labels).cuda()
+
+    step = 0
+    for _ in range(args.warmup):
+        m.zo_step(tok, lab, seeds["noise"], step)
+        step += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        m.zo_step(tok, lab, seeds["noise"], step)
+        step += 1
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    tokens_per_step = 2 * w.q * w.E * w.S
+
+    # second pass over the same number of steps with HIP events around every base-weight GEMM launch
+    M.mpz_profile_gemm_begin(m.handle)
+    for _ in range(args.steps):
+        m.zo_step(tok, lab, seeds["noise"], step)
+        step += 1
+    gemm_ms, launches, flops = M.mpz_profile_gemm_end(m.handle)
+    losses = m.losses[:2 * w.q].cpu().numpy()
+    assert np.all(np.isfinite(losses)), losses
+    achieved = flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    alg = gemm_flops_per_step(w)
+    assert abs(flops / args.steps - alg) <= 1e-6 * alg, (flops / args.steps, alg)
+    bf16 = w.dtype == "bf16"
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP64_VECTOR_TFLOPS
+    out = {
+        "metric": "perturbed-copy tokens/sec", "value": tokens_per_step / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "zo_steps_per_sec": 1e3 / ms_per_step, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f64", "data": "synthetic",
+        "config": {"workload": w.name, "q": w.q, "copies": 2 * w.q, "E": w.E, "S": w.S,
+                   "stacked_tokens": tokens_per_step, "layers": w.n_layers, "d_model": w.d_model,
+                   "lora_rank": w.lora_rank, "eps": w.eps, "seeds": seeds},
+        "roofline": {"bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": None, "kernel": "base-weight GEMMs (all launches of a step)",
+                     "launches_per_step": launches / args.steps, "gemm_ms_per_step": gemm_ms / args.steps,
+                     "algorithmic_flops_per_step": alg},
+        "mfma_util_pct": 100.0 * achieved / peak if bf16 else None,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, frozen, masters, tokens, labels, seeds["noise"])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

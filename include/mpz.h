@@ -1,0 +1,207 @@
+/*
+ * mpz - MP-LoRA zeroth-order step on one AMD MI355X (gfx950).
+ *
+ * One "ZO step" is Algorithm 1 of the paper (MobiZO, arXiv 2409.15520): q queries (outer loop)
+ * times the two signs (inner loop) give n = 2q perturbed copies of the LoRA factors; all copies
+ * run through ONE batched forward pass that shares the frozen weights (the MP-LoRA layer of
+ * Section 3, Y = X W + (X A) (.) B with per-copy factors); the per-copy losses give the
+ * two-point estimates g_k (Algorithm 1, the projected gradient) and the update regenerates the noise from
+ * its seed instead of storing it (Algorithm 1, the stored seeds and the update; Section 2, "ZO LLM Fine-Tuning").
+ *
+ * Conventions for every entry point
+ *   - Pointers marked [dev] are device (HBM) addresses, [host] are host addresses.
+ *   - The library allocates no device memory: the caller owns the frozen weights, the LoRA
+ *     masters, token / label / loss buffers and one workspace, and keeps them alive for the
+ *     lifetime of the model handle.  The handle itself is host memory owned by the library.
+ *   - All device work is enqueued on the HIP stream given to mpz_init_model; no entry point
+ *     synchronises with the device except mpz_init_model.  Outputs are valid once the caller
+ *     has synchronised that stream.
+ *   - Errors are returned as mpz_status; nothing throws or aborts across this boundary.
+ *     Arguments are validated on the host before any launch.  mpz_last_error() returns a
+ *     message for the last failing call on that handle (or on the calling thread when there
+ *     is no handle).
+ *   - Copy order: copy c = 2k + s uses +eps z_k for s = 0 and -eps z_k for s = 1, k < q.
+ *     Stacked token row of (copy c, sequence e, position p) is (c*E + e)*S + p.
+ *   - Storage layout of a linear y = x W (+ b), W in R^{k_in x k_out}: output-major, element
+ *     (k, n) of W at w[n*k_in + k], in the model dtype (fp32 or bf16); biases and norm
+ *     parameters are fp32.
+ */
+#ifndef MPZ_H
+#define MPZ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mpz_model mpz_model; /* opaque host-side handle */
+
+typedef enum {
+  MPZ_OK = 0,
+  MPZ_ERR_NULL = 1,      /* a required pointer is NULL */
+  MPZ_ERR_CONFIG = 2,    /* inconsistent or unsupported configuration / argument value */
+  MPZ_ERR_SHAPE = 3,     /* q, E or S outside what the model was initialised for */
+  MPZ_ERR_WORKSPACE = 4, /* workspace too small or misaligned */
+  MPZ_ERR_STATE = 5,     /* call order violated (e.g. update without a preceding regen_noise) */
+  MPZ_ERR_DEVICE = 6     /* a HIP runtime call failed */
+} mpz_status;
+
+enum { MPZ_ACT_RELU = 0, MPZ_ACT_GELU_ERF = 1, MPZ_ACT_SWIGLU = 2 };
+enum { MPZ_NORM_LAYERNORM = 0, MPZ_NORM_RMSNORM = 1 };
+enum { MPZ_POS_LEARNED = 0, MPZ_POS_ROPE = 1 };
+enum { MPZ_DTYPE_F32 = 0, MPZ_DTYPE_BF16 = 1 };
+enum { MPZ_TARGET_Q = 1, MPZ_TARGET_K = 2, MPZ_TARGET_V = 4, MPZ_TARGET_O = 8 };
+enum {
+  MPZ_LOSS_LAST_POS_LABEL_SUBSET = 0, /* 2-way CE over two label-token logits at the last position */
+  MPZ_LOSS_LAST_POS_FULL_VOCAB = 1,   /* CE over the whole vocabulary at the last position (Appendix D.2) */
+  MPZ_LOSS_NEXT_TOKEN_ALL_POS = 2     /* position p predicts token p+1, p < S-1, whole vocabulary */
+};
+
+/* Model description.  Plain data; struct_size = sizeof(mpz_config) guards against layout drift. */
+typedef struct {
+  uint32_t struct_size;
+  int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab, max_seq;
+  int32_t act;            /* MPZ_ACT_* */
+  int32_t norm;           /* MPZ_NORM_* */
+  float norm_eps;
+  int32_t pos;            /* MPZ_POS_* */
+  float rope_theta;       /* rotary base; pairs (i, i + d_head/2), angle p * theta^(-2i/d_head) */
+  int32_t has_bias;       /* linears carry biases (OPT-style) */
+  int32_t dtype;          /* MPZ_DTYPE_*: storage type of weights and GEMM operands.
+                             BF16 accumulates in fp32; F32 accumulates in fp64. */
+  int32_t lora_rank;      /* r, a multiple of 4 */
+  uint32_t lora_targets;  /* OR of MPZ_TARGET_* */
+  float lora_scale;       /* s in y = x W + s (x A) B */
+  int32_t perturb_A;      /* 1: A and B are perturbed and updated; 0: LoRA-FA of Section 3 -
+                             A frozen and shared by all copies, only B perturbed and updated */
+  int32_t loss_mode;      /* MPZ_LOSS_* */
+  int32_t label_token[2]; /* vocabulary ids of the two label words (last-position modes) */
+} mpz_config;
+
+/* Frozen parameters theta_f of one decoder block (Algorithm 1, input line).  All [dev], borrowed. */
+typedef struct {
+  const float* ln1_g; /* [d] */
+  const float* ln1_b; /* [d] or NULL (RMSNorm) */
+  const void* w_qkv;  /* [d + 2*d_kv, d] output-major: rows 0..d-1 = W_q, then W_k, then W_v */
+  const float* b_qkv; /* [d + 2*d_kv] or NULL */
+  const void* w_o;    /* [d, d] */
+  const float* b_o;   /* [d] or NULL */
+  const float* ln2_g;
+  const float* ln2_b;
+  const void* w_up;   /* [d_ffn, d]; SwiGLU: [2*d_ffn, d], rows 0..d_ffn-1 = gate, then up */
+  const float* b_up;  /* [d_ffn] (SwiGLU: [2*d_ffn]) or NULL */
+  const void* w_down; /* [d, d_ffn] */
+  const float* b_down;/* [d] or NULL */
+} mpz_layer_weights;
+
+typedef struct {
+  const void* emb;      /* [dev] [vocab, d] token embedding, model dtype */
+  const void* pos_emb;  /* [dev] [max_seq, d] learned positions, or NULL with MPZ_POS_ROPE */
+  const void* lm_head;  /* [dev] [vocab, d] output-major head; may alias emb (tied) */
+  const float* lnf_g;   /* [dev] [d] final norm */
+  const float* lnf_b;   /* [dev] [d] or NULL */
+  const mpz_layer_weights* layers; /* [host] n_layers entries, copied by mpz_init_model */
+} mpz_weights;
+
+/* One LoRA factor inside the flat fp32 master vector theta_l. */
+typedef struct {
+  int32_t layer;
+  int32_t target;    /* 0 = Q, 1 = K, 2 = V, 3 = O */
+  int32_t factor;    /* 0 = A [k_in, r], 1 = B [r, k_out], both row-major (Section 2, LoRA) */
+  int32_t tensor_id; /* (layer*4 + target)*2 + factor: the noise stream coordinate */
+  int64_t offset;    /* element offset in the master vector */
+  int32_t rows, cols;
+} mpz_lora_tensor;
+
+/* Number of fp32 elements of the LoRA master vector theta_l: layer-major; within a layer the
+ * enabled targets in the order Q, K, V, O; for each target A then B.  0 on an invalid config. */
+size_t mpz_lora_numel(const mpz_config* cfg /*[host]*/);
+/* Number of LoRA factors (2 per adapted linear), and the i-th one's description. */
+int32_t mpz_lora_tensor_count(const mpz_config* cfg /*[host]*/);
+mpz_status mpz_lora_tensor_info(const mpz_config* cfg /*[host]*/, int32_t i, mpz_lora_tensor* out /*[host]*/);
+
+/* Bytes of workspace needed for up to q_max queries on E_max sequences of S_max tokens.
+ * Holds the transient perturbed factor copies (Section 3, inner-loop parallelisation: only the
+ * master factors persist, perturbed copies live for one pass), activations of ONE layer for all
+ * n copies (nothing is retained across layers), and small tables.  0 on an invalid configuration. */
+size_t mpz_workspace_bytes(const mpz_config* cfg /*[host]*/, int32_t q_max, int32_t E_max, int32_t S_max);
+
+/* Build a model handle (Algorithm 1, input line: theta_l, theta_f, q, E).
+ *   frozen        [host] struct of [dev] pointers, borrowed for the handle's lifetime
+ *   lora_masters  [dev] fp32[mpz_lora_numel], theta_l, updated in place by mpz_zo_update
+ *   workspace     [dev] 256-byte aligned, at least mpz_workspace_bytes(cfg, q_max, E_max, S_max)
+ *   hip_stream    hipStream_t (NULL = default stream)
+ * Uploads small tables (rotary cos/sin, layout) into the workspace and synchronises the stream once.
+ * Errors: NULL, CONFIG (d_model % n_heads, n_heads % n_kv_heads, odd d_head with RoPE, rank not a
+ * multiple of 4, label ids outside the vocabulary, S_max > max_seq, ...), WORKSPACE, DEVICE. */
+mpz_status mpz_init_model(const mpz_config* cfg, const mpz_weights* frozen, float* lora_masters,
+                          void* workspace, size_t workspace_bytes, int32_t q_max, int32_t E_max,
+                          int32_t S_max, void* hip_stream, mpz_model** out);
+
+/* Algorithm 1, seed / noise / perturbation steps for all q queries and both signs at once: regenerate z_k ~ N(0, I) from
+ * the counter-based stream (seed, step, k) and write the n = 2q perturbed factor copies
+ * theta_l + (+/-) eps z_k into the workspace.  z is never stored.  The stream: Philox4x32-10
+ * keyed by seed, counter (element/4, tensor_id, step, k), Box-Muller in binary32 without libm.
+ * eps = 0 is legal (all copies equal the masters).  Errors: NULL, SHAPE (q < 1 or q > q_max),
+ * CONFIG (eps not finite or negative). */
+mpz_status mpz_regen_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t q, float eps);
+
+/* Algorithm 1, the loss evaluations of both loops for all copies in one batched pass (Section 3, MP-LoRA; outer- and
+ * inner-loop parallelisation): every copy sees the same E x S token batch, the frozen weights
+ * are shared, each copy's low-rank path uses its own perturbed factors.
+ *   tokens      [dev] int32[E*S], ids in [0, vocab) (not checked on device)
+ *   labels      [dev] int32[E] class ids in {0,1} for the last-position modes; ignored (may be
+ *               NULL) for MPZ_LOSS_NEXT_TOKEN_ALL_POS
+ *   losses_out  [dev] fp32[2q], mean loss of each copy over its loss positions
+ * Requires a preceding mpz_regen_noise (its q is used).  Errors: NULL, STATE, SHAPE
+ * (E < 1, E > E_max, S < 2, S > S_max). */
+mpz_status mpz_forward_perturbed(mpz_model* m, const int32_t* tokens, const int32_t* labels,
+                                 int32_t E, int32_t S, float* losses_out);
+
+/* Algorithm 1, projected gradient and update: g_k = (l_{2k} - l_{2k+1}) / (2 eps) in fp64 from the fp32 losses, then
+ * theta_l <- theta_l - lr (1/q) sum_k g_k z_k on the fp32 masters, z_k replayed from the (seed,
+ * step, q, eps) of the last mpz_regen_noise.
+ *   losses           [dev] fp32[2q]
+ *   proj_grads_out   [dev] fp32[q] receives g_k, or NULL
+ * Errors: NULL, STATE (no preceding regen_noise), CONFIG (that regen_noise used eps = 0: the
+ * two-point quotient is undefined; lr not finite). */
+mpz_status mpz_zo_update(mpz_model* m, const float* losses, float lr, float* proj_grads_out);
+
+/* Test hooks (not on the hot path). */
+/* z for one LoRA factor of one query: z_out [dev] fp32[rows*cols], row-major. */
+mpz_status mpz_debug_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t k, int32_t tensor_id,
+                           float* z_out);
+/* The binary32 normal transform alone: words [dev] uint32[4*n4] -> normals [dev] fp32[4*n4]
+ * (group j: words 4j..4j+3 -> Box-Muller pairs (0,1) and (2,3)).  hip_stream as in init. */
+mpz_status mpz_debug_normals_from_words(const uint32_t* words, size_t n4, float* normals_out, void* hip_stream);
+/* Copy c's perturbed factors as the forward pass sees them, in master layout: out [dev] fp32[numel]. */
+mpz_status mpz_debug_perturbed_copy(mpz_model* m, int32_t c, float* out);
+
+/* The three stages of mpz_forward_perturbed, run separately on a caller-held stacked residual
+ * stream h [dev] fp32[2q*E*S, d_model] (rows in copy-major order), so that each stage can be checked
+ * on given inputs: embedding -> h_out; decoder blocks [layer_begin, layer_end) in place on h; final
+ * norm + head + per-copy mean loss from h.  Same preconditions and errors as mpz_forward_perturbed. */
+mpz_status mpz_debug_embed(mpz_model* m, const int32_t* tokens, int32_t E, int32_t S, float* h_out);
+mpz_status mpz_debug_run_layers(mpz_model* m, float* h, int32_t layer_begin, int32_t layer_end, int32_t E, int32_t S);
+mpz_status mpz_debug_head_loss(mpz_model* m, const float* h, const int32_t* tokens, const int32_t* labels,
+                               int32_t E, int32_t S, float* losses_out);
+
+/* Measurement hook: between _begin and _end every base-weight GEMM launch (the shared-W term X W of the
+ * MP-LoRA layer with its fused per-copy rank-r term, and the LM head) is bracketed by HIP events on the
+ * model's stream.  _end synchronises the stream and returns the summed kernel time in milliseconds, the
+ * number of launches and the algorithmic FLOPs (2 M N K per launch).  Adds event overhead: do not enable
+ * it inside a region whose wall-clock is reported.  Errors: NULL, STATE (end without begin), DEVICE. */
+mpz_status mpz_profile_gemm_begin(mpz_model* m);
+mpz_status mpz_profile_gemm_end(mpz_model* m, double* total_ms /*[host]*/, int64_t* launches /*[host]*/,
+                                double* flops /*[host]*/);
+
+void mpz_destroy(mpz_model* m);
+const char* mpz_last_error(const mpz_model* m /* may be NULL */);
+const char* mpz_status_string(mpz_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MPZ_H */

@@ -2,7 +2,7 @@
 
 TEST INFRASTRUCTURE ONLY - never imported by the product path.
 
-This is the function l = L((theta_l, theta_f); B) that Algorithm 1 (line 8) evaluates for each
+This is the function l = L((theta_l, theta_f); B) that Algorithm 1 (the loss evaluation inside its inner loop) evaluates for each
 perturbed parameter vector.  Every adapted linear is the LoRA layer of Section 2,
 y = x W + x A B (here with an explicit scale s: y = x W + b + s (x A) B), which is what one path
 of the MP-LoRA equation Y = X W + (X A) (.) B of Section 3 computes.  The decoder around it
@@ -91,55 +91,62 @@ def _cross_entropy(logits, target):
     return lse - logits[np.arange(logits.shape[0]), target]
 
 
-def copy_loss(w, frozen: Dict[str, object], lora: Dict[Tuple[int, int], Tuple[np.ndarray, np.ndarray]],
-              tokens: np.ndarray, labels, prec: Precision) -> float:
-    """Loss of one copy.  `lora[(layer, target_index)] = (A_c, B_c)` are that copy's factors."""
-    E, S = tokens.shape
-    d, H, Hkv, dh = w.d_model, w.n_heads, w.n_kv_heads, w.d_head
-    h = np.asarray(frozen["emb"], dtype=np.float64)[tokens]                     # [E, S, d]
+def embed(w, frozen, tokens: np.ndarray, prec: Precision):
+    """Token (+ learned position) embedding -> residual stream h [E, S, d]."""
+    S = tokens.shape[1]
+    h = np.asarray(frozen["emb"], dtype=np.float64)[tokens]
     if w.pos == "learned":
         h = h + np.asarray(frozen["pos_emb"], dtype=np.float64)[None, :S]
-    h = prec.stream(h)
+    return prec.stream(h)
+
+
+def decoder_layer(w, lw, li: int, h, lora, prec: Precision):
+    """One pre-norm decoder block on h [E, S, d] with this copy's LoRA factors."""
+    E, S, d = h.shape
+    H, Hkv, dh = w.n_heads, w.n_kv_heads, w.d_head
+    norm_eps = float(np.float32(w.norm_eps))            # hyper-parameters are binary32 numbers
+    scale = float(np.float32(w.lora_scale))
+    x = prec.operand(_norm(h, lw["ln1_g"], lw["ln1_b"], w.norm, norm_eps))
+    Wqkv, bqkv = lw["w_qkv"], lw["b_qkv"]
+    cols = {"q": (0, d), "k": (d, d + w.d_kv), "v": (d + w.d_kv, d + 2 * w.d_kv)}
+    proj = {}
+    for name, (c0, c1) in cols.items():
+        b = bqkv[c0:c1] if bqkv is not None else None
+        proj[name] = _linear(x, Wqkv[:, c0:c1], b, _lora_delta(x, lora, li, name, scale, prec))
+    qh = proj["q"].reshape(E, S, H, dh)
+    kh = proj["k"].reshape(E, S, Hkv, dh)
+    vh = proj["v"].reshape(E, S, Hkv, dh)
     if w.pos == "rope":
         cos, sin = rope_tables(S, dh, w.rope_theta, prec)
+        qh, kh = _rope(qh, cos, sin), _rope(kh, cos, sin)
+    qh, kh, vh = prec.operand(qh), prec.operand(kh), prec.operand(vh)
+    attn = prec.operand(_attention(qh, kh, vh, H, Hkv, prec))
+    h = prec.stream(h + _linear(attn, lw["w_o"], lw["b_o"], _lora_delta(attn, lora, li, "o", scale, prec)))
 
-    for li, lw in enumerate(frozen["layers"]):
-        x = prec.operand(_norm(h, lw["ln1_g"], lw["ln1_b"], w.norm, w.norm_eps))
-        Wqkv, bqkv = lw["w_qkv"], lw["b_qkv"]
-        cols = {"q": (0, d), "k": (d, d + w.d_kv), "v": (d + w.d_kv, d + 2 * w.d_kv)}
-        proj = {}
-        for name, (c0, c1) in cols.items():
-            b = bqkv[c0:c1] if bqkv is not None else None
-            proj[name] = _linear(x, Wqkv[:, c0:c1], b, _lora_delta(x, lora, li, name, w.lora_scale, prec))
-        qh = proj["q"].reshape(E, S, H, dh)
-        kh = proj["k"].reshape(E, S, Hkv, dh)
-        vh = proj["v"].reshape(E, S, Hkv, dh)
-        if w.pos == "rope":
-            qh, kh = _rope(qh, cos, sin), _rope(kh, cos, sin)
-        qh, kh, vh = prec.operand(qh), prec.operand(kh), prec.operand(vh)
-        attn = prec.operand(_attention(qh, kh, vh, H, Hkv, prec))
-        h = prec.stream(h + _linear(attn, lw["w_o"], lw["b_o"],
-                                    _lora_delta(attn, lora, li, "o", w.lora_scale, prec)))
+    x = prec.operand(_norm(h, lw["ln2_g"], lw["ln2_b"], w.norm, norm_eps))
+    up = _linear(x, lw["w_up"], lw["b_up"])
+    if w.act == "relu":
+        u = np.maximum(up, 0.0)
+    elif w.act == "gelu":
+        u = 0.5 * up * (1.0 + erf(up / np.sqrt(2.0)))
+    else:                                                                    # SwiGLU
+        gate, lin = up[..., :w.d_ffn], up[..., w.d_ffn:]
+        u = gate / (1.0 + np.exp(-gate)) * lin
+    u = prec.operand(u)
+    return prec.stream(h + _linear(u, lw["w_down"], lw["b_down"]))
 
-        x = prec.operand(_norm(h, lw["ln2_g"], lw["ln2_b"], w.norm, w.norm_eps))
-        up = _linear(x, lw["w_up"], lw["b_up"])
-        if w.act == "relu":
-            u = np.maximum(up, 0.0)
-        elif w.act == "gelu":
-            u = 0.5 * up * (1.0 + erf(up / np.sqrt(2.0)))
-        else:                                                                    # SwiGLU
-            gate, lin = up[..., :w.d_ffn], up[..., w.d_ffn:]
-            u = gate / (1.0 + np.exp(-gate)) * lin
-        u = prec.operand(u)
-        h = prec.stream(h + _linear(u, lw["w_down"], lw["b_down"]))
 
+def head_loss(w, frozen, h, tokens: np.ndarray, labels, prec: Precision) -> float:
+    """Final norm, LM head and the mean cross-entropy of this copy in the configured loss mode."""
+    E, S, d = h.shape
+    norm_eps = float(np.float32(w.norm_eps))
     head = np.asarray(frozen["lm_head"], dtype=np.float64)                       # [V, d]
     if w.loss_mode == "next_token_all_pos":
-        xf = prec.operand(_norm(h[:, :S - 1], frozen["lnf_g"], frozen["lnf_b"], w.norm, w.norm_eps))
+        xf = prec.operand(_norm(h[:, :S - 1], frozen["lnf_g"], frozen["lnf_b"], w.norm, norm_eps))
         logits = prec.stream(xf.reshape(-1, d) @ head.T)
         ce = _cross_entropy(logits, tokens[:, 1:].reshape(-1))
     else:
-        xf = prec.operand(_norm(h[:, S - 1], frozen["lnf_g"], frozen["lnf_b"], w.norm, w.norm_eps))
+        xf = prec.operand(_norm(h[:, S - 1], frozen["lnf_g"], frozen["lnf_b"], w.norm, norm_eps))
         labels = np.asarray(labels)
         if w.loss_mode == "last_pos_label_subset":
             logits = prec.stream(xf @ head[list(w.label_tokens)].T)              # [E, 2]
@@ -148,3 +155,17 @@ def copy_loss(w, frozen: Dict[str, object], lora: Dict[Tuple[int, int], Tuple[np
             logits = prec.stream(xf @ head.T)
             ce = _cross_entropy(logits, np.asarray(w.label_tokens)[labels])
     return float(prec.stream(prec.stream(ce).mean()))
+
+
+def copy_loss(w, frozen: Dict[str, object], lora: Dict[Tuple[int, int], Tuple[np.ndarray, np.ndarray]],
+              tokens: np.ndarray, labels, prec: Precision, trace=None) -> float:
+    """Loss of one copy.  `lora[(layer, target_index)] = (A_c, B_c)` are that copy's factors.
+    If `trace` is a list, the residual stream after the embedding and after every block is appended."""
+    h = embed(w, frozen, tokens, prec)
+    if trace is not None:
+        trace.append(h)
+    for li, lw in enumerate(frozen["layers"]):
+        h = decoder_layer(w, lw, li, h, lora, prec)
+        if trace is not None:
+            trace.append(h)
+    return head_loss(w, frozen, h, tokens, labels, prec)

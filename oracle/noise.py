@@ -2,7 +2,7 @@
 
 TEST INFRASTRUCTURE ONLY - never imported by the product path.
 
-Algorithm 1 (lines 4-5) only says that query i samples a seed s_i and draws z_i ~ N(0, I)
+Algorithm 1 (its seed-sampling and noise-drawing steps) only says that query i samples a seed s_i and draws z_i ~ N(0, I)
 from it, and that s_i is stored instead of z_i (the seed trick of Section 2, "ZO LLM
 Fine-Tuning").  The concrete generator is this build's own specification:
 

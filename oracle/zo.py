@@ -29,7 +29,7 @@ def draw_z(layout, seed: int, step: int, k: int, total: int, perturb_A: bool) ->
 
 
 def perturb(masters: np.ndarray, z: np.ndarray, sign: int, eps: float, prec: Precision) -> np.ndarray:
-    """theta_l + sign * eps * z  (Algorithm 1, line 7)."""
+    """theta_l + sign * eps * z  (Algorithm 1, the perturbation step of the inner loop)."""
     e32 = np.float32(eps)
     if prec.exact:
         return masters.astype(np.float64) + sign * float(e32) * z.astype(np.float64)
@@ -47,7 +47,7 @@ def split_factors(layout, flat) -> Dict[Tuple[int, int], Tuple[np.ndarray, np.nd
 
 def perturbed_losses(w, layout, frozen, masters, tokens, labels, seed: int, step: int,
                      prec: Precision, q=None, eps=None) -> np.ndarray:
-    """l_c for c = 0..2q-1 (Algorithm 1, lines 3-9)."""
+    """l_c for c = 0..2q-1 (Algorithm 1, outer and inner loops)."""
     q = w.q if q is None else q
     eps = w.eps if eps is None else eps
     losses = np.zeros(2 * q, dtype=np.float64)
@@ -60,14 +60,14 @@ def perturbed_losses(w, layout, frozen, masters, tokens, labels, seed: int, step
 
 
 def projected_grads(losses: np.ndarray, eps: float) -> np.ndarray:
-    """g_k = (l_k(+) - l_k(-)) / (2 eps)  (Algorithm 1, line 10), in binary64."""
+    """g_k = (l_k(+) - l_k(-)) / (2 eps)  (Algorithm 1, the two-point estimate), in binary64."""
     losses = np.asarray(losses, dtype=np.float64)
     return (losses[0::2] - losses[1::2]) / (2.0 * float(np.float32(eps)))
 
 
 def zo_update(masters: np.ndarray, g: np.ndarray, layout, seed: int, step: int, lr: float,
               perturb_A: bool, prec: Precision) -> np.ndarray:
-    """theta_l <- theta_l - lr * (1/q) sum_k g_k z_k with z_k regenerated (Algorithm 1, line 13)."""
+    """theta_l <- theta_l - lr * (1/q) sum_k g_k z_k with z_k regenerated (Algorithm 1, the parameter update)."""
     q = len(g)
     if prec.exact:
         acc = np.zeros(masters.size, dtype=np.float64)

@@ -1,0 +1,94 @@
+// Internal declarations shared by the HIP translation units of libmpz (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace mpz {
+
+// bf16 stored as its 16-bit pattern; conversions are explicit so rounding is visible in the code.
+struct bf16_t { uint16_t bits; };
+
+__host__ __device__ inline float bf16_to_f32(bf16_t v) {
+  union { uint32_t u; float f; } c; c.u = ((uint32_t)v.bits) << 16; return c.f;
+}
+// round-to-nearest-even from binary32 (finite inputs)
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+  union { uint32_t u; float f; } c; c.f = f;
+  uint32_t r = c.u + 0x7FFFu + ((c.u >> 16) & 1u);
+  bf16_t o; o.bits = (uint16_t)(r >> 16); return o;
+}
+
+// Position of the LoRA factors inside one layer's slice of the flat master vector.
+struct LoraLayerTable {
+  int32_t n_tensors;          // 2 per adapted target
+  int32_t per_layer;          // elements per layer
+  int32_t off[9];             // start of tensor i inside the layer slice; off[n_tensors] = per_layer
+  int32_t local_id[8];        // target*2 + factor
+  int32_t rows[8], cols[8];
+};
+
+// ---- noise.hip -------------------------------------------------------------------------
+void launch_perturb(hipStream_t st, const float* masters, float* pert /*[2q][P]*/, int64_t P,
+                    const LoraLayerTable& tab, uint64_t seed, uint32_t step, int q, float eps, int perturb_A);
+void launch_update(hipStream_t st, float* masters, int64_t P, const LoraLayerTable& tab, uint64_t seed,
+                   uint32_t step, int q, float eps, float lr, int perturb_A, const float* losses,
+                   float* proj_grads_out);
+void launch_debug_noise(hipStream_t st, float* z_out, int64_t numel, uint64_t seed, uint32_t step, int k,
+                        int tensor_id);
+void launch_normals_from_words(hipStream_t st, const uint32_t* words, size_t n4, float* out);
+
+// ---- simple_kernels.hip: straightforward kernels, any shape, fp32 (fp64 accumulate) or bf16 (fp32) --
+struct LoraSeg {              // one adapted column range of a linear
+  int32_t col_begin, col_end; // output columns [begin, end)
+  const void* t;              // [T, t_stride] bottleneck activations OP(s x A_c), model dtype
+  int32_t t_stride, t_off;    // row stride and first column of this target's r values
+  const float* Bc;            // perturbed B copies: copy c at Bc + c*copy_stride, [r, k_out] row-major
+  int64_t copy_stride;
+};
+
+struct LinearArgs {
+  int dtype;                  // MPZ_DTYPE_*
+  int M, N, K;
+  const void* x;              // [M, K] model dtype
+  const void* w;              // [N, K] model dtype (output-major)
+  const float* bias;          // [N] or null
+  int n_seg; LoraSeg seg[3];
+  int rank; int rows_per_copy;
+  int act;                    // -1 none, else MPZ_ACT_RELU / MPZ_ACT_GELU_ERF
+  const float* residual;      // [M, N] fp32 added before the store, or null
+  int out_kind;               // 0: model dtype, 1: fp32, 2: accumulate type staging (double for f32 models, float for bf16)
+  void* out;                  // [M, N]
+};
+void launch_linear_simple(hipStream_t st, const LinearArgs& a);
+
+void launch_embed(hipStream_t st, int dtype, const int32_t* tokens, const void* emb, const void* pos_emb,
+                  float* h, int n_copies, int E, int S, int d);
+void launch_norm(hipStream_t st, int dtype, int kind, float eps, const float* h, int64_t h_row_stride,
+                 const float* g, const float* b, void* out, int rows, int d);
+// t[T, r_tot] = OP(scale * x A_c) for up to 4 targets sharing the input x
+struct LoraDownArgs {
+  int dtype; int T, K, rank, n_targets, rows_per_copy;
+  const void* x; float scale;
+  const float* Ac[4];         // perturbed A copies per target: copy c at Ac[i] + c*copy_stride, [K, r] row-major
+  int64_t copy_stride;
+  void* t;                    // [T, n_targets*rank] model dtype
+};
+void launch_lora_down_simple(hipStream_t st, const LoraDownArgs& a);
+// q/k: rotate (optionally) and convert staging -> model dtype; v: convert. staging is [T, n_cols] accumulate type
+void launch_rope_convert(hipStream_t st, int dtype, const void* staging, void* out, int T, int S, int n_cols,
+                         int d_head, int n_rot_heads, const float* cos_tab, const float* sin_tab);
+void launch_attention_simple(hipStream_t st, int dtype, const void* qkv, int qkv_stride, void* out, int n_seq, int S,
+                             int H, int Hkv, int dh);
+void launch_swiglu(hipStream_t st, int dtype, const void* staging, void* out, int T, int f);
+// per-row CE from fp32 logits; target[r] < 0 => row skipped (ce = 0)
+void launch_ce_rows(hipStream_t st, int dtype, const float* logits, int64_t row_stride, int n_cols, const int32_t* target,
+                    float* ce, int rows);
+void launch_last_pos_subset_logits(hipStream_t st, int dtype, const void* xf, const void* head, int d, int rows,
+                                   int tok0, int tok1, float* logits2);
+void launch_make_targets(hipStream_t st, int mode, const int32_t* tokens, const int32_t* labels, int tok0, int tok1,
+                         int32_t* target, int n_copies, int E, int S);
+void launch_copy_mean(hipStream_t st, const float* ce, int rows_per_copy, int count_per_copy, float* losses, int n_copies);
+void launch_fill_f32(hipStream_t st, float* p, float v, int64_t n);
+
+}  // namespace mpz

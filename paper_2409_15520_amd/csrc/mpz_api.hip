@@ -1,0 +1,547 @@
+// C ABI of libmpz: argument validation, workspace carving and the launch sequence of one ZO step
+// (Algorithm 1) over n = 2q stacked copies (Section 3, MP-LoRA with outer- and inner-loop
+// parallelisation).  Host code only; every arithmetic step runs in the kernels it launches.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "common.h"
+#include "../../include/mpz.h"
+
+using namespace mpz;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+struct Carver {                                  // bump allocator over the caller's workspace
+  unsigned char* base; size_t off = 0;
+  explicit Carver(void* b) : base((unsigned char*)b) {}
+  template <typename T> T* take(size_t count) {
+    off = (off + 255) & ~(size_t)255;
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+};
+
+struct Buffers {
+  float* rope_cos = nullptr; float* rope_sin = nullptr;
+  float* pert = nullptr;      // [2 q_max][P] perturbed factors, master layout, fp32
+  float* h = nullptr;         // [T, d] residual stream, fp32
+  void* x = nullptr;          // [T, d] norm output (GEMM operand)
+  void* qkv = nullptr;        // [T, d + 2 d_kv]
+  void* attn = nullptr;       // [T, d]
+  void* t = nullptr;          // [T, 4 r] LoRA bottleneck activations
+  void* u = nullptr;          // [T, d_ffn]
+  void* stage = nullptr;      // accumulate-type staging for rotary q/k and SwiGLU gate|up
+  float* logits = nullptr;    // [chunk_rows, vocab] or [n E, 2]
+  float* ce = nullptr;        // [T] per-row losses
+  int32_t* target = nullptr;  // [T]
+  int chunk_rows = 0;
+};
+
+size_t elem_size(int dtype) { return dtype == MPZ_DTYPE_F32 ? 4 : 2; }
+size_t acc_size(int dtype) { return dtype == MPZ_DTYPE_F32 ? 8 : 4; }
+
+int count_targets(uint32_t m) { return __builtin_popcount(m & 15u); }
+
+const char* validate_config(const mpz_config* c) {
+  if (c->struct_size != sizeof(mpz_config)) return "struct_size does not match sizeof(mpz_config)";
+  if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 1 || c->vocab < 2 ||
+      c->max_seq < 2) return "non-positive model dimension";
+  if (c->d_model % c->n_heads) return "d_model is not a multiple of n_heads";
+  if (c->n_heads % c->n_kv_heads) return "n_heads is not a multiple of n_kv_heads";
+  if (c->act < 0 || c->act > 2 || c->norm < 0 || c->norm > 1 || c->pos < 0 || c->pos > 1) return "unknown act/norm/pos";
+  if (c->dtype != MPZ_DTYPE_F32 && c->dtype != MPZ_DTYPE_BF16) return "unknown dtype";
+  if (c->pos == MPZ_POS_ROPE && ((c->d_model / c->n_heads) & 1)) return "rotary embedding needs an even d_head";
+  if (c->pos == MPZ_POS_ROPE && !(c->rope_theta > 0.f)) return "rope_theta must be positive";
+  if (c->lora_rank < 4 || c->lora_rank % 4 || c->lora_rank > 64) return "lora_rank must be a multiple of 4 in [4, 64]";
+  if ((c->lora_targets & 15u) == 0 || (c->lora_targets & ~15u)) return "lora_targets must be a non-empty subset of Q|K|V|O";
+  if (c->d_model % 4) return "d_model must be a multiple of 4";
+  if (!(c->norm_eps > 0.f) || !std::isfinite(c->lora_scale)) return "norm_eps must be positive and lora_scale finite";
+  if (c->loss_mode < 0 || c->loss_mode > 2) return "unknown loss_mode";
+  if (c->loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS) {
+    for (int i = 0; i < 2; ++i)
+      if (c->label_token[i] < 0 || c->label_token[i] >= c->vocab) return "label token id outside the vocabulary";
+    if (c->label_token[0] == c->label_token[1]) return "the two label tokens must differ";
+  }
+  return nullptr;
+}
+
+void build_layout(const mpz_config* c, std::vector<mpz_lora_tensor>& out, LoraLayerTable& tab) {
+  out.clear();
+  int d = c->d_model, dkv = c->n_kv_heads * (c->d_model / c->n_heads), r = c->lora_rank;
+  int64_t off = 0;
+  memset(&tab, 0, sizeof(tab));
+  for (int l = 0; l < c->n_layers; ++l) {
+    int i = 0;
+    for (int t = 0; t < 4; ++t) {
+      if (!(c->lora_targets & (1u << t))) continue;
+      int k_out = (t == 0 || t == 3) ? d : dkv;
+      for (int f = 0; f < 2; ++f) {
+        mpz_lora_tensor e;
+        e.layer = l; e.target = t; e.factor = f; e.tensor_id = (l * 4 + t) * 2 + f; e.offset = off;
+        e.rows = f == 0 ? d : r; e.cols = f == 0 ? r : k_out;
+        if (l == 0) { tab.off[i] = (int32_t)off; tab.local_id[i] = t * 2 + f; tab.rows[i] = e.rows; tab.cols[i] = e.cols; }
+        out.push_back(e);
+        off += (int64_t)e.rows * e.cols;
+        ++i;
+      }
+    }
+    if (l == 0) { tab.n_tensors = i; tab.per_layer = (int32_t)off; tab.off[i] = (int32_t)off; }
+  }
+}
+
+size_t carve(const mpz_config* c, int q_max, int E_max, int S_max, void* base, Buffers* b) {
+  Carver cv(base);
+  std::vector<mpz_lora_tensor> lay; LoraLayerTable tab;
+  build_layout(c, lay, tab);
+  int64_t P = (int64_t)tab.per_layer * c->n_layers;
+  int64_t n = 2 * (int64_t)q_max, T = n * E_max * S_max;
+  int d = c->d_model, dh = d / c->n_heads, dkv = c->n_kv_heads * dh, f = c->d_ffn;
+  size_t es = elem_size(c->dtype), as = acc_size(c->dtype);
+  Buffers bb;
+  if (c->pos == MPZ_POS_ROPE) {
+    bb.rope_cos = cv.take<float>((size_t)c->max_seq * (dh / 2));
+    bb.rope_sin = cv.take<float>((size_t)c->max_seq * (dh / 2));
+  }
+  bb.pert = cv.take<float>((size_t)(n * P));
+  bb.h = cv.take<float>((size_t)T * d);
+  bb.x = cv.take<unsigned char>((size_t)T * d * es);
+  bb.qkv = cv.take<unsigned char>((size_t)T * (d + 2 * dkv) * es);
+  bb.attn = cv.take<unsigned char>((size_t)T * d * es);
+  bb.t = cv.take<unsigned char>((size_t)T * 4 * c->lora_rank * es);
+  bb.u = cv.take<unsigned char>((size_t)T * f * es);
+  size_t stage_elems = 0;
+  if (c->pos == MPZ_POS_ROPE) stage_elems = (size_t)T * (d + 2 * dkv);
+  if (c->act == MPZ_ACT_SWIGLU && (size_t)T * 2 * f > stage_elems) stage_elems = (size_t)T * 2 * f;
+  if (stage_elems) bb.stage = cv.take<unsigned char>(stage_elems * as);
+  int64_t loss_rows = c->loss_mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS ? T : n * E_max;
+  if (c->loss_mode == MPZ_LOSS_LAST_POS_LABEL_SUBSET) {
+    bb.chunk_rows = (int)loss_rows;
+    bb.logits = cv.take<float>((size_t)loss_rows * 2);
+  } else {
+    bb.chunk_rows = (int)(loss_rows < 4096 ? loss_rows : 4096);
+    bb.logits = cv.take<float>((size_t)bb.chunk_rows * c->vocab);
+  }
+  bb.ce = cv.take<float>((size_t)loss_rows);
+  bb.target = cv.take<int32_t>((size_t)loss_rows);
+  if (b) *b = bb;
+  return (cv.off + 255) & ~(size_t)255;
+}
+
+}  // namespace
+
+struct mpz_model {
+  mpz_config cfg;
+  std::vector<mpz_layer_weights> layers;
+  mpz_weights w;
+  float* masters = nullptr;
+  hipStream_t stream = nullptr;
+  int q_max = 0, E_max = 0, S_max = 0;
+  Buffers buf;
+  std::vector<mpz_lora_tensor> tensors;
+  LoraLayerTable tab;
+  int64_t P = 0;
+  bool have_noise = false;
+  uint64_t seed = 0; uint32_t step = 0; int q = 0; float eps = 0.f;
+  std::string err;
+  // optional per-launch timing of the base-weight GEMMs (mpz_profile_gemm_begin / _end)
+  bool prof_on = false;
+  std::vector<hipEvent_t> prof_ev;   // start/stop pairs
+  size_t prof_used = 0;
+  double prof_flops = 0.0;
+  ~mpz_model() { for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e); }
+};
+
+namespace {
+
+mpz_status fail(mpz_model* m, mpz_status s, const std::string& msg) {
+  g_last_error = msg;
+  if (m) m->err = msg;
+  return s;
+}
+
+mpz_status check_device(mpz_model* m, const char* where) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(m, MPZ_ERR_DEVICE, std::string(where) + ": " + hipGetErrorString(e));
+  return MPZ_OK;
+}
+
+const mpz_lora_tensor* find_tensor(const mpz_model* m, int layer, int target, int factor) {
+  for (const auto& t : m->tensors)
+    if (t.layer == layer && t.target == target && t.factor == factor) return &t;
+  return nullptr;
+}
+
+// Every base-weight GEMM of the pass goes through here (kernel selection and optional timing).
+void gemm(mpz_model* m, const LinearArgs& a) {
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (m->prof_on) {
+    if (m->prof_used + 2 > m->prof_ev.size()) {
+      hipEvent_t x = nullptr, y = nullptr;
+      if (hipEventCreate(&x) == hipSuccess && hipEventCreate(&y) == hipSuccess) { m->prof_ev.push_back(x); m->prof_ev.push_back(y); }
+    }
+    if (m->prof_used + 2 <= m->prof_ev.size()) {
+      e0 = m->prof_ev[m->prof_used]; e1 = m->prof_ev[m->prof_used + 1];
+      m->prof_used += 2;
+      m->prof_flops += 2.0 * a.M * (double)a.N * a.K;
+      (void)hipEventRecord(e0, m->stream);
+    }
+  }
+  launch_linear_simple(m->stream, a);
+  if (e1) (void)hipEventRecord(e1, m->stream);
+}
+
+void run_embed(mpz_model* m, const int32_t* tokens, int E, int S, float* h) {
+  const mpz_config& c = m->cfg;
+  launch_embed(m->stream, c.dtype, tokens, m->w.emb, c.pos == MPZ_POS_ROPE ? nullptr : m->w.pos_emb, h, 2 * m->q, E, S,
+               c.d_model);
+}
+
+// Decoder blocks [l0, l1) on the stacked residual stream h [T, d]: per adapted linear an optional
+// bottleneck kernel, then the GEMM with the per-copy rank-r term.
+void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
+  const mpz_config& c = m->cfg;
+  hipStream_t st = m->stream;
+  Buffers b = m->buf;
+  b.h = h;
+  const int n = 2 * m->q, rpc = E * S, T = n * rpc;
+  const int d = c.d_model, dh = d / c.n_heads, dkv = c.n_kv_heads * dh, f = c.d_ffn, r = c.lora_rank;
+  const int nqkv = d + 2 * dkv;
+  const bool rope = c.pos == MPZ_POS_ROPE, swiglu = c.act == MPZ_ACT_SWIGLU;
+
+  for (int l = l0; l < l1; ++l) {
+    const mpz_layer_weights& lw = m->layers[l];
+    launch_norm(st, c.dtype, c.norm, c.norm_eps, b.h, d, lw.ln1_g, lw.ln1_b, b.x, T, d);
+
+    // q/k/v projections of the MP-LoRA layer: shared W, per-copy (A_c, B_c)
+    LoraDownArgs da{};
+    da.dtype = c.dtype; da.T = T; da.K = d; da.rank = r; da.rows_per_copy = rpc; da.x = b.x; da.scale = c.lora_scale;
+    da.copy_stride = m->P; da.t = b.t;
+    LinearArgs qa{};
+    qa.dtype = c.dtype; qa.M = T; qa.N = nqkv; qa.K = d; qa.x = b.x; qa.w = lw.w_qkv; qa.bias = lw.b_qkv;
+    qa.rank = r; qa.rows_per_copy = rpc; qa.act = -1; qa.residual = nullptr;
+    const int col0[3] = {0, d, d + dkv}, col1[3] = {d, d + dkv, nqkv};
+    int nt = 0;
+    for (int t = 0; t < 3; ++t) {
+      if (!(c.lora_targets & (1u << t))) continue;
+      da.Ac[nt] = b.pert + find_tensor(m, l, t, 0)->offset;
+      LoraSeg& sg = qa.seg[nt];
+      sg.col_begin = col0[t]; sg.col_end = col1[t]; sg.t = b.t; sg.t_off = nt * r;
+      sg.Bc = b.pert + find_tensor(m, l, t, 1)->offset; sg.copy_stride = m->P;
+      ++nt;
+    }
+    for (int i = 0; i < nt; ++i) qa.seg[i].t_stride = nt * r;
+    da.n_targets = nt; qa.n_seg = nt;
+    if (nt) launch_lora_down_simple(st, da);
+    qa.out_kind = rope ? 2 : 0; qa.out = rope ? b.stage : b.qkv;
+    gemm(m, qa);
+    if (rope) launch_rope_convert(st, c.dtype, b.stage, b.qkv, T, S, nqkv, dh, c.n_heads + c.n_kv_heads, b.rope_cos, b.rope_sin);
+
+    launch_attention_simple(st, c.dtype, b.qkv, nqkv, b.attn, n * E, S, c.n_heads, c.n_kv_heads, dh);
+
+    // output projection (+ adapter) added to the residual stream
+    LinearArgs oa{};
+    oa.dtype = c.dtype; oa.M = T; oa.N = d; oa.K = d; oa.x = b.attn; oa.w = lw.w_o; oa.bias = lw.b_o;
+    oa.rank = r; oa.rows_per_copy = rpc; oa.act = -1; oa.residual = b.h; oa.out_kind = 1; oa.out = b.h;
+    if (c.lora_targets & MPZ_TARGET_O) {
+      LoraDownArgs oda = da;
+      oda.x = b.attn; oda.n_targets = 1; oda.Ac[0] = b.pert + find_tensor(m, l, 3, 0)->offset;
+      launch_lora_down_simple(st, oda);
+      oa.n_seg = 1;
+      oa.seg[0].col_begin = 0; oa.seg[0].col_end = d; oa.seg[0].t = b.t; oa.seg[0].t_stride = r; oa.seg[0].t_off = 0;
+      oa.seg[0].Bc = b.pert + find_tensor(m, l, 3, 1)->offset; oa.seg[0].copy_stride = m->P;
+    }
+    gemm(m, oa);
+
+    // feed-forward block
+    launch_norm(st, c.dtype, c.norm, c.norm_eps, b.h, d, lw.ln2_g, lw.ln2_b, b.x, T, d);
+    LinearArgs ua{};
+    ua.dtype = c.dtype; ua.M = T; ua.N = swiglu ? 2 * f : f; ua.K = d; ua.x = b.x; ua.w = lw.w_up; ua.bias = lw.b_up;
+    ua.rank = r; ua.rows_per_copy = rpc; ua.act = swiglu ? -1 : c.act;
+    ua.out_kind = swiglu ? 2 : 0; ua.out = swiglu ? b.stage : b.u;
+    gemm(m, ua);
+    if (swiglu) launch_swiglu(st, c.dtype, b.stage, b.u, T, f);
+    LinearArgs wa{};
+    wa.dtype = c.dtype; wa.M = T; wa.N = d; wa.K = f; wa.x = b.u; wa.w = lw.w_down; wa.bias = lw.b_down;
+    wa.rank = r; wa.rows_per_copy = rpc; wa.act = -1; wa.residual = b.h; wa.out_kind = 1; wa.out = b.h;
+    gemm(m, wa);
+  }
+}
+
+// final norm, head and per-copy loss from the stacked residual stream h [T, d]
+void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t* labels, int E, int S, float* losses_out) {
+  const mpz_config& c = m->cfg;
+  hipStream_t st = m->stream;
+  Buffers b = m->buf;
+  b.h = const_cast<float*>(h);
+  const int n = 2 * m->q, rpc = E * S, T = n * rpc;
+  const int d = c.d_model;
+  launch_make_targets(st, c.loss_mode, tokens, labels, c.label_token[0], c.label_token[1], b.target, n, E, S);
+  if (c.loss_mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS) {
+    launch_norm(st, c.dtype, c.norm, c.norm_eps, b.h, d, m->w.lnf_g, m->w.lnf_b, b.x, T, d);
+    for (int r0 = 0; r0 < T; r0 += b.chunk_rows) {
+      int rows = T - r0 < b.chunk_rows ? T - r0 : b.chunk_rows;
+      LinearArgs la{};
+      la.dtype = c.dtype; la.M = rows; la.N = c.vocab; la.K = d;
+      la.x = (const unsigned char*)b.x + (size_t)r0 * d * elem_size(c.dtype);
+      la.w = m->w.lm_head; la.act = -1; la.rows_per_copy = rpc; la.out_kind = 1; la.out = b.logits;
+      gemm(m, la);
+      launch_ce_rows(st, c.dtype, b.logits, c.vocab, c.vocab, b.target + r0, b.ce + r0, rows);
+    }
+    launch_copy_mean(st, b.ce, rpc, E * (S - 1), losses_out, n);
+  } else {
+    const int rows_all = n * E;
+    launch_norm(st, c.dtype, c.norm, c.norm_eps, b.h + (size_t)(S - 1) * d, (int64_t)S * d, m->w.lnf_g, m->w.lnf_b, b.x,
+                rows_all, d);
+    if (c.loss_mode == MPZ_LOSS_LAST_POS_LABEL_SUBSET) {
+      launch_last_pos_subset_logits(st, c.dtype, b.x, m->w.lm_head, d, rows_all, c.label_token[0], c.label_token[1], b.logits);
+      launch_ce_rows(st, c.dtype, b.logits, 2, 2, b.target, b.ce, rows_all);
+    } else {
+      for (int r0 = 0; r0 < rows_all; r0 += b.chunk_rows) {
+        int rows = rows_all - r0 < b.chunk_rows ? rows_all - r0 : b.chunk_rows;
+        LinearArgs la{};
+        la.dtype = c.dtype; la.M = rows; la.N = c.vocab; la.K = d;
+        la.x = (const unsigned char*)b.x + (size_t)r0 * d * elem_size(c.dtype);
+        la.w = m->w.lm_head; la.act = -1; la.rows_per_copy = rpc; la.out_kind = 1; la.out = b.logits;
+        gemm(m, la);
+        launch_ce_rows(st, c.dtype, b.logits, c.vocab, c.vocab, b.target + r0, b.ce + r0, rows);
+      }
+    }
+    launch_copy_mean(st, b.ce, E, E, losses_out, n);
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t mpz_lora_numel(const mpz_config* cfg) {
+  if (!cfg || validate_config(cfg)) return 0;
+  std::vector<mpz_lora_tensor> lay; LoraLayerTable tab;
+  build_layout(cfg, lay, tab);
+  return (size_t)tab.per_layer * cfg->n_layers;
+}
+
+int32_t mpz_lora_tensor_count(const mpz_config* cfg) {
+  if (!cfg || validate_config(cfg)) return 0;
+  return 2 * count_targets(cfg->lora_targets) * cfg->n_layers;
+}
+
+mpz_status mpz_lora_tensor_info(const mpz_config* cfg, int32_t i, mpz_lora_tensor* out) {
+  if (!cfg || !out) return fail(nullptr, MPZ_ERR_NULL, "mpz_lora_tensor_info: NULL argument");
+  if (const char* e = validate_config(cfg)) return fail(nullptr, MPZ_ERR_CONFIG, e);
+  std::vector<mpz_lora_tensor> lay; LoraLayerTable tab;
+  build_layout(cfg, lay, tab);
+  if (i < 0 || i >= (int32_t)lay.size()) return fail(nullptr, MPZ_ERR_SHAPE, "tensor index out of range");
+  *out = lay[i];
+  return MPZ_OK;
+}
+
+size_t mpz_workspace_bytes(const mpz_config* cfg, int32_t q_max, int32_t E_max, int32_t S_max) {
+  if (!cfg || validate_config(cfg)) return 0;
+  if (q_max < 1 || q_max > 64 || E_max < 1 || S_max < 2 || S_max > cfg->max_seq) return 0;
+  return carve(cfg, q_max, E_max, S_max, nullptr, nullptr);
+}
+
+mpz_status mpz_init_model(const mpz_config* cfg, const mpz_weights* frozen, float* lora_masters, void* workspace,
+                          size_t workspace_bytes, int32_t q_max, int32_t E_max, int32_t S_max, void* hip_stream,
+                          mpz_model** out) {
+  if (!cfg || !frozen || !lora_masters || !workspace || !out) return fail(nullptr, MPZ_ERR_NULL, "mpz_init_model: NULL argument");
+  *out = nullptr;
+  if (const char* e = validate_config(cfg)) return fail(nullptr, MPZ_ERR_CONFIG, e);
+  if (q_max < 1 || q_max > 64) return fail(nullptr, MPZ_ERR_CONFIG, "q_max must be in [1, 64]");
+  if (E_max < 1 || S_max < 2 || S_max > cfg->max_seq) return fail(nullptr, MPZ_ERR_CONFIG, "E_max < 1 or S_max outside [2, max_seq]");
+  if ((int64_t)2 * q_max * E_max * S_max > (int64_t)1 << 24) return fail(nullptr, MPZ_ERR_CONFIG, "more than 2^24 stacked tokens");
+  if (!frozen->emb || !frozen->lm_head || !frozen->lnf_g || !frozen->layers)
+    return fail(nullptr, MPZ_ERR_NULL, "mpz_init_model: NULL frozen weight");
+  if (cfg->pos == MPZ_POS_LEARNED && !frozen->pos_emb) return fail(nullptr, MPZ_ERR_NULL, "learned positions need pos_emb");
+  if (cfg->norm == MPZ_NORM_LAYERNORM && !frozen->lnf_b) return fail(nullptr, MPZ_ERR_NULL, "LayerNorm needs lnf_b");
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const mpz_layer_weights& lw = frozen->layers[l];
+    if (!lw.ln1_g || !lw.ln2_g || !lw.w_qkv || !lw.w_o || !lw.w_up || !lw.w_down)
+      return fail(nullptr, MPZ_ERR_NULL, "mpz_init_model: NULL layer weight");
+    if (cfg->norm == MPZ_NORM_LAYERNORM && (!lw.ln1_b || !lw.ln2_b)) return fail(nullptr, MPZ_ERR_NULL, "LayerNorm needs biases");
+    if (cfg->has_bias && (!lw.b_qkv || !lw.b_o || !lw.b_up || !lw.b_down))
+      return fail(nullptr, MPZ_ERR_NULL, "has_bias set but a linear bias is NULL");
+  }
+  if (((uintptr_t)workspace & 255u) != 0) return fail(nullptr, MPZ_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  size_t need = carve(cfg, q_max, E_max, S_max, nullptr, nullptr);
+  if (workspace_bytes < need) {
+    char msg[128];
+    snprintf(msg, sizeof msg, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+    return fail(nullptr, MPZ_ERR_WORKSPACE, msg);
+  }
+  mpz_model* m = new (std::nothrow) mpz_model();
+  if (!m) return fail(nullptr, MPZ_ERR_DEVICE, "out of host memory");
+  m->cfg = *cfg;
+  m->layers.assign(frozen->layers, frozen->layers + cfg->n_layers);
+  if (!cfg->has_bias)
+    for (auto& lw : m->layers) lw.b_qkv = lw.b_o = lw.b_up = lw.b_down = nullptr;
+  if (cfg->norm == MPZ_NORM_RMSNORM)
+    for (auto& lw : m->layers) lw.ln1_b = lw.ln2_b = nullptr;
+  m->w = *frozen;
+  m->w.layers = m->layers.data();
+  if (cfg->norm == MPZ_NORM_RMSNORM) m->w.lnf_b = nullptr;
+  m->masters = lora_masters;
+  m->stream = (hipStream_t)hip_stream;
+  m->q_max = q_max; m->E_max = E_max; m->S_max = S_max;
+  build_layout(cfg, m->tensors, m->tab);
+  m->P = (int64_t)m->tab.per_layer * cfg->n_layers;
+  carve(cfg, q_max, E_max, S_max, workspace, &m->buf);
+  if (cfg->pos == MPZ_POS_ROPE) {
+    int dh = cfg->d_model / cfg->n_heads, half = dh / 2;
+    std::vector<float> cs((size_t)cfg->max_seq * half), sn((size_t)cfg->max_seq * half);
+    for (int i = 0; i < half; ++i) {
+      double inv = std::pow((double)cfg->rope_theta, -2.0 * i / dh);
+      for (int p = 0; p < cfg->max_seq; ++p) {
+        double ang = p * inv;
+        cs[(size_t)p * half + i] = (float)std::cos(ang);
+        sn[(size_t)p * half + i] = (float)std::sin(ang);
+      }
+    }
+    hipError_t e1 = hipMemcpyAsync(m->buf.rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice, m->stream);
+    hipError_t e2 = hipMemcpyAsync(m->buf.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice, m->stream);
+    hipError_t e3 = hipStreamSynchronize(m->stream);
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess) {
+      delete m;
+      return fail(nullptr, MPZ_ERR_DEVICE, "uploading the rotary tables failed");
+    }
+  }
+  *out = m;
+  return MPZ_OK;
+}
+
+mpz_status mpz_regen_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t q, float eps) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_regen_noise: NULL model");
+  if (q < 1 || q > m->q_max) return fail(m, MPZ_ERR_SHAPE, "q outside [1, q_max]");
+  if (!std::isfinite(eps) || eps < 0.f) return fail(m, MPZ_ERR_CONFIG, "eps must be finite and non-negative");
+  launch_perturb(m->stream, m->masters, m->buf.pert, m->P, m->tab, seed, step, q, eps, m->cfg.perturb_A);
+  m->have_noise = true; m->seed = seed; m->step = step; m->q = q; m->eps = eps;
+  return check_device(m, "mpz_regen_noise");
+}
+
+mpz_status mpz_forward_perturbed(mpz_model* m, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
+                                 float* losses_out) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_forward_perturbed: NULL model");
+  if (!tokens || !losses_out) return fail(m, MPZ_ERR_NULL, "mpz_forward_perturbed: NULL tokens or losses_out");
+  if (m->cfg.loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS && !labels) return fail(m, MPZ_ERR_NULL, "this loss mode needs labels");
+  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_forward_perturbed before mpz_regen_noise");
+  if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
+  run_embed(m, tokens, E, S, m->buf.h);
+  run_layers(m, m->buf.h, 0, m->cfg.n_layers, E, S);
+  run_head(m, m->buf.h, tokens, labels, E, S, losses_out);
+  return check_device(m, "mpz_forward_perturbed");
+}
+
+mpz_status mpz_debug_embed(mpz_model* m, const int32_t* tokens, int32_t E, int32_t S, float* h_out) {
+  if (!m || !tokens || !h_out) return fail(m, MPZ_ERR_NULL, "mpz_debug_embed: NULL argument");
+  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_debug_embed before mpz_regen_noise");
+  if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
+  run_embed(m, tokens, E, S, h_out);
+  return check_device(m, "mpz_debug_embed");
+}
+
+mpz_status mpz_debug_run_layers(mpz_model* m, float* h, int32_t layer_begin, int32_t layer_end, int32_t E, int32_t S) {
+  if (!m || !h) return fail(m, MPZ_ERR_NULL, "mpz_debug_run_layers: NULL argument");
+  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_debug_run_layers before mpz_regen_noise");
+  if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
+  if (layer_begin < 0 || layer_end > m->cfg.n_layers || layer_begin > layer_end) return fail(m, MPZ_ERR_SHAPE, "layer range outside the model");
+  run_layers(m, h, layer_begin, layer_end, E, S);
+  return check_device(m, "mpz_debug_run_layers");
+}
+
+mpz_status mpz_debug_head_loss(mpz_model* m, const float* h, const int32_t* tokens, const int32_t* labels, int32_t E,
+                               int32_t S, float* losses_out) {
+  if (!m || !h || !tokens || !losses_out) return fail(m, MPZ_ERR_NULL, "mpz_debug_head_loss: NULL argument");
+  if (m->cfg.loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS && !labels) return fail(m, MPZ_ERR_NULL, "this loss mode needs labels");
+  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_debug_head_loss before mpz_regen_noise");
+  if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
+  run_head(m, h, tokens, labels, E, S, losses_out);
+  return check_device(m, "mpz_debug_head_loss");
+}
+
+mpz_status mpz_zo_update(mpz_model* m, const float* losses, float lr, float* proj_grads_out) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_zo_update: NULL model");
+  if (!losses) return fail(m, MPZ_ERR_NULL, "mpz_zo_update: NULL losses");
+  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_zo_update before mpz_regen_noise");
+  if (!(m->eps > 0.f)) return fail(m, MPZ_ERR_CONFIG, "the last mpz_regen_noise used eps = 0: the two-point quotient is undefined");
+  if (!std::isfinite(lr)) return fail(m, MPZ_ERR_CONFIG, "lr must be finite");
+  launch_update(m->stream, m->masters, m->P, m->tab, m->seed, m->step, m->q, m->eps, lr, m->cfg.perturb_A, losses,
+                proj_grads_out);
+  m->have_noise = false;                       // the perturbed copies no longer match the masters
+  return check_device(m, "mpz_zo_update");
+}
+
+mpz_status mpz_debug_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t k, int32_t tensor_id, float* z_out) {
+  if (!m || !z_out) return fail(m, MPZ_ERR_NULL, "mpz_debug_noise: NULL argument");
+  if (k < 0) return fail(m, MPZ_ERR_SHAPE, "k must be non-negative");
+  for (const auto& t : m->tensors)
+    if (t.tensor_id == tensor_id) {
+      launch_debug_noise(m->stream, z_out, (int64_t)t.rows * t.cols, seed, step, k, tensor_id);
+      return check_device(m, "mpz_debug_noise");
+    }
+  return fail(m, MPZ_ERR_SHAPE, "no LoRA factor with this tensor_id");
+}
+
+mpz_status mpz_debug_normals_from_words(const uint32_t* words, size_t n4, float* normals_out, void* hip_stream) {
+  if (!words || !normals_out) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_normals_from_words: NULL argument");
+  if (n4 == 0) return MPZ_OK;
+  if (n4 > ((size_t)1 << 31)) return fail(nullptr, MPZ_ERR_SHAPE, "too many groups");
+  launch_normals_from_words((hipStream_t)hip_stream, words, n4, normals_out);
+  return check_device(nullptr, "mpz_debug_normals_from_words");
+}
+
+mpz_status mpz_debug_perturbed_copy(mpz_model* m, int32_t c, float* out) {
+  if (!m || !out) return fail(m, MPZ_ERR_NULL, "mpz_debug_perturbed_copy: NULL argument");
+  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "no perturbed copies: call mpz_regen_noise first");
+  if (c < 0 || c >= 2 * m->q) return fail(m, MPZ_ERR_SHAPE, "copy index outside [0, 2q)");
+  hipError_t e = hipMemcpyAsync(out, m->buf.pert + (int64_t)c * m->P, (size_t)m->P * 4, hipMemcpyDeviceToDevice, m->stream);
+  if (e != hipSuccess) return fail(m, MPZ_ERR_DEVICE, hipGetErrorString(e));
+  return MPZ_OK;
+}
+
+mpz_status mpz_profile_gemm_begin(mpz_model* m) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_profile_gemm_begin: NULL model");
+  m->prof_on = true; m->prof_used = 0; m->prof_flops = 0.0;
+  return MPZ_OK;
+}
+
+mpz_status mpz_profile_gemm_end(mpz_model* m, double* total_ms, int64_t* launches, double* flops) {
+  if (!m || !total_ms || !launches || !flops) return fail(m, MPZ_ERR_NULL, "mpz_profile_gemm_end: NULL argument");
+  if (!m->prof_on) return fail(m, MPZ_ERR_STATE, "mpz_profile_gemm_end without mpz_profile_gemm_begin");
+  m->prof_on = false;
+  if (hipStreamSynchronize(m->stream) != hipSuccess) return fail(m, MPZ_ERR_DEVICE, "stream synchronisation failed");
+  double ms = 0.0;
+  for (size_t i = 0; i + 1 < m->prof_used; i += 2) {
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, m->prof_ev[i], m->prof_ev[i + 1]) != hipSuccess) return fail(m, MPZ_ERR_DEVICE, "hipEventElapsedTime failed");
+    ms += t;
+  }
+  *total_ms = ms; *launches = (int64_t)(m->prof_used / 2); *flops = m->prof_flops;
+  return MPZ_OK;
+}
+
+void mpz_destroy(mpz_model* m) { delete m; }
+
+const char* mpz_last_error(const mpz_model* m) { return m ? m->err.c_str() : g_last_error.c_str(); }
+
+const char* mpz_status_string(mpz_status s) {
+  switch (s) {
+    case MPZ_OK: return "MPZ_OK";
+    case MPZ_ERR_NULL: return "MPZ_ERR_NULL";
+    case MPZ_ERR_CONFIG: return "MPZ_ERR_CONFIG";
+    case MPZ_ERR_SHAPE: return "MPZ_ERR_SHAPE";
+    case MPZ_ERR_WORKSPACE: return "MPZ_ERR_WORKSPACE";
+    case MPZ_ERR_STATE: return "MPZ_ERR_STATE";
+    case MPZ_ERR_DEVICE: return "MPZ_ERR_DEVICE";
+  }
+  return "MPZ_ERR_UNKNOWN";
+}
+
+}  // extern "C"

@@ -1,0 +1,326 @@
+"""ctypes binding of libmpz.so: argument marshalling only, every step runs in the HIP kernels.
+
+PyTorch is used for device memory and the stream handle.  The library is loaded from this
+package directory; if it has not been built (`python -m paper_2409_15520_amd.build`) loading
+raises - there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libmpz.so")
+_lib = None
+
+ACT = {"relu": 0, "gelu": 1, "swiglu": 2}
+NORM = {"layernorm": 0, "rmsnorm": 1}
+POS = {"learned": 0, "rope": 1}
+DTYPE = {"f32": 0, "bf16": 1}
+LOSS = {"last_pos_label_subset": 0, "last_pos_full_vocab": 1, "next_token_all_pos": 2}
+TARGET_BIT = {"q": 1, "k": 2, "v": 4, "o": 8}
+
+
+class MpzError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{mpz_status_string(status)}: {message}")
+        self.status = status
+
+
+class MpzConfig(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32),
+                ("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("d_ffn", C.c_int32), ("vocab", C.c_int32), ("max_seq", C.c_int32),
+                ("act", C.c_int32), ("norm", C.c_int32), ("norm_eps", C.c_float), ("pos", C.c_int32),
+                ("rope_theta", C.c_float), ("has_bias", C.c_int32), ("dtype", C.c_int32),
+                ("lora_rank", C.c_int32), ("lora_targets", C.c_uint32), ("lora_scale", C.c_float),
+                ("perturb_A", C.c_int32), ("loss_mode", C.c_int32), ("label_token", C.c_int32 * 2)]
+
+
+class MpzLayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b",
+                                          "w_up", "b_up", "w_down", "b_down")]
+
+
+class MpzWeights(C.Structure):
+    _fields_ = [("emb", C.c_void_p), ("pos_emb", C.c_void_p), ("lm_head", C.c_void_p), ("lnf_g", C.c_void_p),
+                ("lnf_b", C.c_void_p), ("layers", C.POINTER(MpzLayerWeights))]
+
+
+class MpzLoraTensor(C.Structure):
+    _fields_ = [("layer", C.c_int32), ("target", C.c_int32), ("factor", C.c_int32), ("tensor_id", C.c_int32),
+                ("offset", C.c_int64), ("rows", C.c_int32), ("cols", C.c_int32)]
+
+
+def load_library() -> C.CDLL:
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2409_15520_amd.build` "
+                          "(there is no fallback implementation)")
+    lib = C.CDLL(_LIB_PATH)
+    cfgp = C.POINTER(MpzConfig)
+    lib.mpz_lora_numel.restype = C.c_size_t
+    lib.mpz_lora_numel.argtypes = [cfgp]
+    lib.mpz_lora_tensor_count.restype = C.c_int32
+    lib.mpz_lora_tensor_count.argtypes = [cfgp]
+    lib.mpz_lora_tensor_info.restype = C.c_int
+    lib.mpz_lora_tensor_info.argtypes = [cfgp, C.c_int32, C.POINTER(MpzLoraTensor)]
+    lib.mpz_workspace_bytes.restype = C.c_size_t
+    lib.mpz_workspace_bytes.argtypes = [cfgp, C.c_int32, C.c_int32, C.c_int32]
+    lib.mpz_init_model.restype = C.c_int
+    lib.mpz_init_model.argtypes = [cfgp, C.POINTER(MpzWeights), C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32,
+                                   C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_void_p)]
+    lib.mpz_regen_noise.restype = C.c_int
+    lib.mpz_regen_noise.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_int32, C.c_float]
+    lib.mpz_forward_perturbed.restype = C.c_int
+    lib.mpz_forward_perturbed.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    lib.mpz_zo_update.restype = C.c_int
+    lib.mpz_zo_update.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]
+    lib.mpz_debug_noise.restype = C.c_int
+    lib.mpz_debug_noise.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_int32, C.c_int32, C.c_void_p]
+    lib.mpz_debug_normals_from_words.restype = C.c_int
+    lib.mpz_debug_normals_from_words.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.mpz_debug_perturbed_copy.restype = C.c_int
+    lib.mpz_debug_perturbed_copy.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+    lib.mpz_debug_embed.restype = C.c_int
+    lib.mpz_debug_embed.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    lib.mpz_debug_run_layers.restype = C.c_int
+    lib.mpz_debug_run_layers.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    lib.mpz_debug_head_loss.restype = C.c_int
+    lib.mpz_debug_head_loss.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    lib.mpz_profile_gemm_begin.restype = C.c_int
+    lib.mpz_profile_gemm_begin.argtypes = [C.c_void_p]
+    lib.mpz_profile_gemm_end.restype = C.c_int
+    lib.mpz_profile_gemm_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+    lib.mpz_destroy.restype = None
+    lib.mpz_destroy.argtypes = [C.c_void_p]
+    lib.mpz_last_error.restype = C.c_char_p
+    lib.mpz_last_error.argtypes = [C.c_void_p]
+    lib.mpz_status_string.restype = C.c_char_p
+    lib.mpz_status_string.argtypes = [C.c_int]
+    _lib = lib
+    return lib
+
+
+def _check(status: int, handle=None):
+    if status != 0:
+        raise MpzError(status, mpz_last_error(handle))
+
+
+# ---- the C entry points under their own names ----------------------------------------------------
+def mpz_status_string(status: int) -> str:
+    return load_library().mpz_status_string(int(status)).decode()
+
+
+def mpz_last_error(handle=None) -> str:
+    return load_library().mpz_last_error(handle).decode()
+
+
+def mpz_lora_numel(cfg: MpzConfig) -> int:
+    return int(load_library().mpz_lora_numel(C.byref(cfg)))
+
+
+def mpz_lora_tensor_count(cfg: MpzConfig) -> int:
+    return int(load_library().mpz_lora_tensor_count(C.byref(cfg)))
+
+
+def mpz_lora_tensor_info(cfg: MpzConfig, i: int) -> MpzLoraTensor:
+    out = MpzLoraTensor()
+    _check(load_library().mpz_lora_tensor_info(C.byref(cfg), i, C.byref(out)))
+    return out
+
+
+def mpz_workspace_bytes(cfg: MpzConfig, q_max: int, E_max: int, S_max: int) -> int:
+    return int(load_library().mpz_workspace_bytes(C.byref(cfg), q_max, E_max, S_max))
+
+
+def mpz_init_model(cfg: MpzConfig, weights: MpzWeights, lora_masters_ptr: int, workspace_ptr: int,
+                   workspace_bytes: int, q_max: int, E_max: int, S_max: int, stream_ptr: int):
+    handle = C.c_void_p()
+    _check(load_library().mpz_init_model(C.byref(cfg), C.byref(weights), lora_masters_ptr, workspace_ptr,
+                                         workspace_bytes, q_max, E_max, S_max, stream_ptr, C.byref(handle)))
+    return handle
+
+
+def mpz_regen_noise(handle, seed: int, step: int, q: int, eps: float):
+    _check(load_library().mpz_regen_noise(handle, seed, step, q, eps), handle)
+
+
+def mpz_forward_perturbed(handle, tokens_ptr: int, labels_ptr: Optional[int], E: int, S: int, losses_ptr: int):
+    _check(load_library().mpz_forward_perturbed(handle, tokens_ptr, labels_ptr, E, S, losses_ptr), handle)
+
+
+def mpz_zo_update(handle, losses_ptr: int, lr: float, proj_grads_ptr: Optional[int]):
+    _check(load_library().mpz_zo_update(handle, losses_ptr, lr, proj_grads_ptr), handle)
+
+
+def mpz_debug_noise(handle, seed: int, step: int, k: int, tensor_id: int, z_ptr: int):
+    _check(load_library().mpz_debug_noise(handle, seed, step, k, tensor_id, z_ptr), handle)
+
+
+def mpz_debug_normals_from_words(words_ptr: int, n4: int, out_ptr: int, stream_ptr: int):
+    _check(load_library().mpz_debug_normals_from_words(words_ptr, n4, out_ptr, stream_ptr))
+
+
+def mpz_debug_perturbed_copy(handle, c: int, out_ptr: int):
+    _check(load_library().mpz_debug_perturbed_copy(handle, c, out_ptr), handle)
+
+
+def mpz_debug_embed(handle, tokens_ptr: int, E: int, S: int, h_ptr: int):
+    _check(load_library().mpz_debug_embed(handle, tokens_ptr, E, S, h_ptr), handle)
+
+
+def mpz_debug_run_layers(handle, h_ptr: int, layer_begin: int, layer_end: int, E: int, S: int):
+    _check(load_library().mpz_debug_run_layers(handle, h_ptr, layer_begin, layer_end, E, S), handle)
+
+
+def mpz_debug_head_loss(handle, h_ptr: int, tokens_ptr: int, labels_ptr: Optional[int], E: int, S: int, losses_ptr: int):
+    _check(load_library().mpz_debug_head_loss(handle, h_ptr, tokens_ptr, labels_ptr, E, S, losses_ptr), handle)
+
+
+def mpz_profile_gemm_begin(handle):
+    _check(load_library().mpz_profile_gemm_begin(handle), handle)
+
+
+def mpz_profile_gemm_end(handle):
+    """Returns (total GEMM kernel ms, launches, algorithmic FLOPs) since mpz_profile_gemm_begin."""
+    ms, n, fl = C.c_double(), C.c_int64(), C.c_double()
+    _check(load_library().mpz_profile_gemm_end(handle, C.byref(ms), C.byref(n), C.byref(fl)), handle)
+    return ms.value, n.value, fl.value
+
+
+def mpz_destroy(handle):
+    load_library().mpz_destroy(handle)
+
+
+# ---- marshalling helpers ---------------------------------------------------------------------------
+def config_from_workload(w) -> MpzConfig:
+    cfg = MpzConfig()
+    cfg.struct_size = C.sizeof(MpzConfig)
+    cfg.n_layers, cfg.d_model, cfg.n_heads, cfg.n_kv_heads = w.n_layers, w.d_model, w.n_heads, w.n_kv_heads
+    cfg.d_ffn, cfg.vocab, cfg.max_seq = w.d_ffn, w.vocab, w.max_seq
+    cfg.act, cfg.norm, cfg.norm_eps, cfg.pos = ACT[w.act], NORM[w.norm], w.norm_eps, POS[w.pos]
+    cfg.rope_theta, cfg.has_bias, cfg.dtype = w.rope_theta, int(w.has_bias), DTYPE[w.dtype]
+    cfg.lora_rank = w.lora_rank
+    cfg.lora_targets = sum(TARGET_BIT[t] for t in w.lora_targets)
+    cfg.lora_scale, cfg.perturb_A, cfg.loss_mode = w.lora_scale, int(w.perturb_A), LOSS[w.loss_mode]
+    cfg.label_token[0], cfg.label_token[1] = w.label_tokens
+    return cfg
+
+
+class ZoModel:
+    """Device buffers + handle for one workload.  Holds the torch tensors the library borrows."""
+
+    def __init__(self, w, frozen: Dict[str, object], masters: np.ndarray, q_max: Optional[int] = None,
+                 E_max: Optional[int] = None, S_max: Optional[int] = None, device: str = "cuda:0"):
+        import torch
+        self.torch = torch
+        self.w = w
+        self.device = torch.device(device)
+        self.cfg = config_from_workload(w)
+        self.q_max, self.E_max, self.S_max = q_max or w.q, E_max or w.E, S_max or w.S
+        st = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+        self._keep = []
+
+        def dev(a, dtype, transpose=False):
+            if a is None:
+                return None
+            t = torch.from_numpy(np.ascontiguousarray(a.T if transpose else a))
+            t = t.to(self.device).to(dtype).contiguous()
+            self._keep.append(t)
+            return t.data_ptr()
+
+        L = len(frozen["layers"])
+        assert L == w.n_layers
+        layers = (MpzLayerWeights * L)()
+        for i, lw in enumerate(frozen["layers"]):
+            for name in ("ln1_g", "ln1_b", "b_qkv", "b_o", "ln2_g", "ln2_b", "b_up", "b_down"):
+                setattr(layers[i], name, dev(lw[name], torch.float32))
+            for name in ("w_qkv", "w_o", "w_up", "w_down"):          # [k_in, k_out] -> output-major
+                setattr(layers[i], name, dev(lw[name], st, transpose=True))
+        self._layers = layers
+        wt = MpzWeights()
+        wt.emb = dev(frozen["emb"], st)
+        wt.pos_emb = dev(frozen["pos_emb"], st)
+        wt.lm_head = wt.emb if frozen["lm_head"] is frozen["emb"] else dev(frozen["lm_head"], st)
+        wt.lnf_g = dev(frozen["lnf_g"], torch.float32)
+        wt.lnf_b = dev(frozen["lnf_b"], torch.float32)
+        wt.layers = layers
+        self._weights = wt
+        numel = mpz_lora_numel(self.cfg)
+        assert numel == masters.size, (numel, masters.size)
+        self.masters = torch.from_numpy(masters.astype(np.float32)).to(self.device)
+        ws_bytes = mpz_workspace_bytes(self.cfg, self.q_max, self.E_max, self.S_max)
+        if ws_bytes == 0:
+            raise MpzError(2, "invalid configuration for mpz_workspace_bytes")
+        self.workspace = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=self.device)
+        ws_ptr = (self.workspace.data_ptr() + 255) & ~255
+        self.stream = torch.cuda.current_stream(self.device)
+        self.handle = mpz_init_model(self.cfg, wt, self.masters.data_ptr(), ws_ptr, ws_bytes, self.q_max, self.E_max,
+                                     self.S_max, self.stream.cuda_stream)
+        self.losses = torch.zeros(2 * self.q_max, dtype=torch.float32, device=self.device)
+        self.grads = torch.zeros(self.q_max, dtype=torch.float32, device=self.device)
+        self.q = w.q
+
+    def regen_noise(self, seed: int, step: int, q: Optional[int] = None, eps: Optional[float] = None):
+        self.q = self.w.q if q is None else q
+        mpz_regen_noise(self.handle, seed, step, self.q, self.w.eps if eps is None else eps)
+
+    def forward_perturbed(self, tokens, labels=None):
+        """tokens: int32 device tensor [E, S]; labels: int32 device tensor [E] or None. Returns losses[2q] (device)."""
+        E, S = tokens.shape
+        mpz_forward_perturbed(self.handle, tokens.data_ptr(), None if labels is None else labels.data_ptr(), E, S,
+                              self.losses.data_ptr())
+        return self.losses[:2 * self.q]
+
+    def zo_update(self, lr: Optional[float] = None):
+        mpz_zo_update(self.handle, self.losses.data_ptr(), self.w.lr if lr is None else lr, self.grads.data_ptr())
+        return self.grads[:self.q]
+
+    def zo_step(self, tokens, labels, seed: int, step: int):
+        self.regen_noise(seed, step)
+        self.forward_perturbed(tokens, labels)
+        self.zo_update()
+
+    def debug_noise(self, seed: int, step: int, k: int, tensor_id: int, numel: int):
+        z = self.torch.empty(numel, dtype=self.torch.float32, device=self.device)
+        mpz_debug_noise(self.handle, seed, step, k, tensor_id, z.data_ptr())
+        return z
+
+    def perturbed_copy(self, c: int):
+        out = self.torch.empty(self.masters.numel(), dtype=self.torch.float32, device=self.device)
+        mpz_debug_perturbed_copy(self.handle, c, out.data_ptr())
+        return out
+
+    def embed(self, tokens):
+        E, S = tokens.shape
+        h = self.torch.empty((2 * self.q * E * S, self.w.d_model), dtype=self.torch.float32, device=self.device)
+        mpz_debug_embed(self.handle, tokens.data_ptr(), E, S, h.data_ptr())
+        return h
+
+    def run_layers(self, h, layer_begin: int, layer_end: int, E: int, S: int):
+        """In place on the fp32 device tensor h [2q*E*S, d]."""
+        mpz_debug_run_layers(self.handle, h.data_ptr(), layer_begin, layer_end, E, S)
+        return h
+
+    def head_loss(self, h, tokens, labels=None):
+        E, S = tokens.shape
+        mpz_debug_head_loss(self.handle, h.data_ptr(), tokens.data_ptr(), None if labels is None else labels.data_ptr(),
+                            E, S, self.losses.data_ptr())
+        return self.losses[:2 * self.q]
+
+    def close(self):
+        if getattr(self, "handle", None) is not None:
+            mpz_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

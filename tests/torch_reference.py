@@ -16,9 +16,10 @@ def _t(x):
 
 
 def _norm(h, g, b, w):
+    eps = float(torch.tensor(w.norm_eps, dtype=torch.float32))      # hyper-parameters are binary32 numbers
     if w.norm == "layernorm":
-        return F.layer_norm(h, (w.d_model,), _t(g), _t(b), w.norm_eps)
-    return F.rms_norm(h, (w.d_model,), _t(g), w.norm_eps)
+        return F.layer_norm(h, (w.d_model,), _t(g), _t(b), eps)
+    return F.rms_norm(h, (w.d_model,), _t(g), eps)
 
 
 def _rope_complex(x, S, dh, theta):
