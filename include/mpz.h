@@ -188,6 +188,11 @@ mpz_status mpz_debug_run_layers(mpz_model* m, float* h, int32_t layer_begin, int
 mpz_status mpz_debug_head_loss(mpz_model* m, const float* h, const int32_t* tokens, const int32_t* labels,
                                int32_t E, int32_t S, float* losses_out);
 
+/* Test hook: simple_only != 0 routes every stage through the shape-agnostic kernels (the only path of
+ * fp32 models); 0 restores the default (bf16 models use the MFMA kernels wherever a shape allows).
+ * Invalidates the perturbed copies: call mpz_regen_noise again. */
+mpz_status mpz_debug_set_kernel_path(mpz_model* m, int32_t simple_only);
+
 /* Measurement hook: between _begin and _end every base-weight GEMM launch (the shared-W term X W of the
  * MP-LoRA layer with its fused per-copy rank-r term, and the LM head) is bracketed by HIP events on the
  * model's stream.  _end synchronises the stream and returns the summed kernel time in milliseconds, the

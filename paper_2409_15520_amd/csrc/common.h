@@ -47,6 +47,14 @@ struct LoraSeg {              // one adapted column range of a linear
   int64_t copy_stride;
 };
 
+struct MfmaLoraSeg {
+  int32_t col_begin, col_end;   // adapted output columns, multiples of 128
+  const void* tp;               // [T, rp] bf16: [t | t | 0], t = OP(s x A_c)
+  const void* bp;               // packed B copies: copy c at bp + c*copy_stride, [k_out, rp] bf16 = [hi | lo | 0]
+  int32_t rp;                   // padded 2r, multiple of 16
+  int64_t copy_stride;          // elements
+};
+
 struct LinearArgs {
   int dtype;                  // MPZ_DTYPE_*
   int M, N, K;
@@ -54,6 +62,7 @@ struct LinearArgs {
   const void* w;              // [N, K] model dtype (output-major)
   const float* bias;          // [N] or null
   int n_seg; LoraSeg seg[3];
+  int mfma_lora; MfmaLoraSeg mseg[3];   // the same segments in the MFMA kernels' operand layouts (when prepared)
   int rank; int rows_per_copy;
   int act;                    // -1 none, else MPZ_ACT_RELU / MPZ_ACT_GELU_ERF
   const float* residual;      // [M, N] fp32 added before the store, or null
@@ -90,5 +99,32 @@ void launch_make_targets(hipStream_t st, int mode, const int32_t* tokens, const 
                          int32_t* target, int n_copies, int E, int S);
 void launch_copy_mean(hipStream_t st, const float* ce, int rows_per_copy, int count_per_copy, float* losses, int n_copies);
 void launch_fill_f32(hipStream_t st, float* p, float v, int64_t n);
+
+// ---- gemm_mfma.hip: bf16 MFMA kernels (gfx950) ------------------------------------------------
+struct MfmaGemmArgs {
+  int M, N, K;                  // out[M, N] = x[M, K] w[N, K]^T ; dual: N = columns of ONE of the two tiles
+  const void* x; const void* w;
+  const float* bias;            // [N] (dual: [dual_offset + N]) or null
+  int dual; int dual_offset;    // dual: second weight tile starts dual_offset rows below (SwiGLU gate | up)
+  int n_seg; MfmaLoraSeg seg[3];
+  int rows_per_copy;
+  int act;                      // -1 none, MPZ_ACT_RELU, MPZ_ACT_GELU_ERF (ignored when dual: SiLU(gate) * up)
+  const float* residual;        // [M, ldo] fp32 or null
+  int out_f32; void* out; int ldo;
+};
+bool mfma_gemm_supported(const MfmaGemmArgs& a);
+void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a);
+
+struct MfmaLoraDownArgs {
+  int T, K, rank, n_targets, rows_per_copy, rp;
+  const void* x; float scale;
+  const void* ap[3];            // packed A copies per target: copy c at ap[i] + c*copy_stride, [2][r][K] bf16 (hi rows, lo rows)
+  int64_t copy_stride;
+  void* tp[3];                  // per target [T, rp] bf16
+};
+bool mfma_lora_down_supported(const MfmaLoraDownArgs& a);
+void launch_lora_down_mfma(hipStream_t st, const MfmaLoraDownArgs& a);
+void launch_pack_factors(hipStream_t st, const float* pert, int64_t P, int n_copies, const LoraLayerTable& tab,
+                         int n_layers, int rank, int rp, void* packed, int64_t packed_per_copy);
 
 }  // namespace mpz

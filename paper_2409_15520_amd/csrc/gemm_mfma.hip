@@ -1,0 +1,366 @@
+// bf16 MFMA GEMM for the shared-weight term of the MP-LoRA layer (Section 3: Y = X W + (X A) (.) B):
+// the frozen weight tile is read once for all n = 2q stacked copies, and the per-copy rank-r term is
+// folded into the same fp32 accumulators as extra K-steps whose "weight" operand is that copy's packed
+// factor [B_hi | B_lo].  gfx950 only: v_mfma_f32_32x32x16_bf16, 64-lane waves, LDS-staged 128x128x64
+// tiles with register-staged double buffering.
+//
+// Orientation: the MFMA "A" operand is a W tile (rows = output features n), the "B" operand an X tile
+// (rows = tokens m), so every lane ends up with 4 consecutive n of one token: bias / residual / stores
+// are 8- or 16-byte accesses along the contiguous output dimension.
+#include "common.h"
+#include "../../include/mpz.h"
+
+namespace mpz {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int BM = 128;          // tokens per block
+constexpr int BN = 128;          // output features per block
+constexpr int BK = 64;           // K per stage
+constexpr int LDS_STRIDE = BK + 8;   // bf16 elements; +16 B per row keeps ds_read_b128 conflict-free
+
+__device__ __forceinline__ bf16x8 as_frag(const uint4& v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f)); }
+
+// DUAL: two weight tiles (rows n and n + dual_offset: SwiGLU gate and up) against the same X tile.
+template <bool DUAL>
+__global__ void __launch_bounds__(256) gemm_bf16_kernel(MfmaGemmArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int NW = DUAL ? 2 : 1;
+  constexpr int TILE = BM * LDS_STRIDE;                  // elements per operand tile per stage
+  uint16_t* sW = (uint16_t*)smem;                        // [2 stages][NW][BN][LDS_STRIDE]
+  uint16_t* sX = sW + 2 * NW * TILE;                     // [2 stages][BM][LDS_STRIDE]
+
+  // XCD-aware tile order: hardware deals consecutive workgroups round-robin to the 8 XCDs; give each XCD
+  // a contiguous range of tiles so that neighbours in its L2 share X rows and the whole (small) W.
+  const int tiles_n = (a.N + BN - 1) / BN, tiles_m = (a.M + BM - 1) / BM;
+  const int nblk = tiles_n * tiles_m;
+  int pid = blockIdx.x;
+  {
+    const int per = nblk / 8, rem = nblk % 8;              // XCD x owns per (+1 if x < rem) tiles
+    const int xcd = pid % 8, idx = pid / 8;
+    pid = xcd * per + (xcd < rem ? xcd : rem) + idx;
+  }
+  const int tile_m = pid / tiles_n, tile_n = pid % tiles_n;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wn = (wave >> 1) * 64, wm = (wave & 1) * 64;   // wave tile origin inside the block tile
+  const int lrow = lane & 31, lhalf = lane >> 5;
+
+  const uint16_t* W = (const uint16_t*)a.w;
+  const uint16_t* X = (const uint16_t*)a.x;
+
+  // global -> register staging: 4 chunks of 16 B per operand tile per thread
+  int ld_row[4], ld_kc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { int c = tid + 256 * i; ld_row[i] = c >> 3; ld_kc[i] = (c & 7) * 8; }
+  const uint16_t* wp[NW][4];
+  const uint16_t* xp[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int n = n0 + ld_row[i]; n = n < a.N ? n : a.N - 1;     // clamp: out-of-range rows are never stored
+    int m = m0 + ld_row[i]; m = m < a.M ? m : a.M - 1;
+    wp[0][i] = W + (size_t)n * a.K + ld_kc[i];
+    if (DUAL) wp[NW - 1][i] = W + (size_t)(n + a.dual_offset) * a.K + ld_kc[i];
+    xp[i] = X + (size_t)m * a.K + ld_kc[i];
+  }
+  uint4 rw[NW][4], rx[4];
+  auto load_global = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int d = 0; d < NW; ++d) rw[d][i] = *(const uint4*)(wp[d][i] + k0);
+      rx[i] = *(const uint4*)(xp[i] + k0);
+    }
+  };
+  auto store_lds = [&](int stage) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int off = ld_row[i] * LDS_STRIDE + ld_kc[i];
+#pragma unroll
+      for (int d = 0; d < NW; ++d) *(uint4*)(sW + (stage * NW + d) * TILE + off) = rw[d][i];
+      *(uint4*)(sX + stage * TILE + off) = rx[i];
+    }
+  };
+
+  f32x16 acc[NW][2][2];
+#pragma unroll
+  for (int d = 0; d < NW; ++d)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[d][i][j][e] = 0.f;
+
+  const int nk = a.K / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int stage = kt & 1;
+    if (kt + 1 < nk) load_global((kt + 1) * BK);
+    const uint16_t* cw = sW + stage * NW * TILE;
+    const uint16_t* cx = sX + stage * TILE;
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+      bf16x8 fw[NW][2], fx[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int d = 0; d < NW; ++d)
+          fw[d][i] = as_frag(*(const uint4*)(cw + d * TILE + (wn + i * 32 + lrow) * LDS_STRIDE + kk + lhalf * 8));
+        fx[i] = as_frag(*(const uint4*)(cx + (wm + i * 32 + lrow) * LDS_STRIDE + kk + lhalf * 8));
+      }
+#pragma unroll
+      for (int d = 0; d < NW; ++d)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[d][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[d][i], fx[j], acc[d][i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_lds(stage ^ 1);
+    __syncthreads();
+  }
+
+  // per-copy low-rank term: extra K-steps with the packed factor [B_hi | B_lo] of this block's copy against
+  // the duplicated bottleneck activations [t | t]  (block rows never straddle copies, segments are tile-aligned)
+  if (!DUAL) {
+    for (int s = 0; s < a.n_seg; ++s) {
+      const MfmaLoraSeg& sg = a.seg[s];
+      if (n0 < sg.col_begin || n0 >= sg.col_end) continue;
+      const int copy = m0 / a.rows_per_copy;
+      const uint16_t* bp = (const uint16_t*)sg.bp + (size_t)copy * sg.copy_stride;
+      const uint16_t* tp = (const uint16_t*)sg.tp;
+      for (int ks = 0; ks < sg.rp; ks += 16) {
+        bf16x8 fw[2], fx[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          int n = n0 + wn + i * 32 + lrow - sg.col_begin;
+          int m = m0 + wm + i * 32 + lrow;
+          fw[i] = as_frag(*(const uint4*)(bp + (size_t)n * sg.rp + ks + lhalf * 8));
+          fx[i] = as_frag(*(const uint4*)(tp + (size_t)m * sg.rp + ks + lhalf * 8));
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fx[j], acc[0][i][j], 0, 0, 0);
+      }
+    }
+  }
+
+  // epilogue: lane holds, for token m, features n = nb + g*8 + lhalf*4 + (0..3), g = 0..3
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int m = m0 + wm + j * 32 + lrow;
+    if (m >= a.M) continue;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = n0 + wn + i * 32 + g * 8 + lhalf * 4;
+        if (n >= a.N) continue;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[0][i][j][g * 4 + e];
+        if (a.bias != nullptr) {
+          float4 bb = *(const float4*)(a.bias + n);
+          v[0] += bb.x; v[1] += bb.y; v[2] += bb.z; v[3] += bb.w;
+        }
+        if (DUAL) {
+          float u[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) u[e] = acc[NW - 1][i][j][g * 4 + e];
+          if (a.bias != nullptr) {
+            float4 bb = *(const float4*)(a.bias + a.dual_offset + n);
+            u[0] += bb.x; u[1] += bb.y; u[2] += bb.z; u[3] += bb.w;
+          }
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = v[e] / (1.0f + expf(-v[e])) * u[e];      // SiLU(gate) * up
+        } else if (a.act == MPZ_ACT_RELU) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+        } else if (a.act == MPZ_ACT_GELU_ERF) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
+        }
+        const size_t o = (size_t)m * a.ldo + n;
+        if (a.residual != nullptr) {
+          float4 rr = *(const float4*)(a.residual + o);
+          v[0] += rr.x; v[1] += rr.y; v[2] += rr.z; v[3] += rr.w;
+        }
+        if (a.out_f32) {
+          *(float4*)((float*)a.out + o) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+          uint2 pk;
+          pk.x = (uint32_t)f32_to_bf16(v[0]).bits | ((uint32_t)f32_to_bf16(v[1]).bits << 16);
+          pk.y = (uint32_t)f32_to_bf16(v[2]).bits | ((uint32_t)f32_to_bf16(v[3]).bits << 16);
+          *(uint2*)((uint16_t*)a.out + o) = pk;
+        }
+      }
+    }
+  }
+}
+
+// ---- LoRA bottleneck: tp[m] = [t | t | 0], t = bf16(scale * x (A_hi + A_lo)) for the block's copy ----------
+// One wave per 32 tokens.  MFMA rows = bottleneck columns j of all targets that share the input x.
+template <int JT>   // number of 32-row MFMA tiles covering n_targets * r bottleneck columns
+__global__ void __launch_bounds__(64) lora_down_mfma_kernel(MfmaLoraDownArgs a) {
+  const int lane = threadIdx.x, lrow = lane & 31, lhalf = lane >> 5;
+  const int m0 = blockIdx.x * 32;
+  const int copy = m0 / a.rows_per_copy;
+  const int R = a.n_targets * a.rank;
+  const uint16_t* X = (const uint16_t*)a.x + (size_t)(m0 + lrow) * a.K + lhalf * 8;
+  // packed A: per copy [n_targets][2][rank][K]  (hi rows then lo rows), K contiguous
+  const uint16_t* Ah[JT];
+  const uint16_t* Al[JT];
+  bool valid[JT];
+#pragma unroll
+  for (int t = 0; t < JT; ++t) {
+    int j = t * 32 + lrow;
+    valid[t] = j < R;
+    int jj = valid[t] ? j : 0;
+    int tgt = jj / a.rank, jr = jj % a.rank;
+    const uint16_t* base = (const uint16_t*)a.ap[tgt] + (size_t)copy * a.copy_stride;
+    Ah[t] = base + (size_t)jr * a.K + lhalf * 8;
+    Al[t] = base + (size_t)(a.rank + jr) * a.K + lhalf * 8;
+  }
+  f32x16 acc[JT];
+#pragma unroll
+  for (int t = 0; t < JT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+  const uint4 zero = make_uint4(0, 0, 0, 0);
+#pragma unroll 4
+  for (int k = 0; k < a.K; k += 16) {
+    bf16x8 fx = as_frag(*(const uint4*)(X + k));
+#pragma unroll
+    for (int t = 0; t < JT; ++t) {
+      uint4 h = valid[t] ? *(const uint4*)(Ah[t] + k) : zero;
+      uint4 l = valid[t] ? *(const uint4*)(Al[t] + k) : zero;
+      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(h), fx, acc[t], 0, 0, 0);
+      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(l), fx, acc[t], 0, 0, 0);
+    }
+  }
+  // lane holds token m0 + lrow, bottleneck columns j = t*32 + g*8 + lhalf*4 + e
+  const int m = m0 + lrow;
+#pragma unroll
+  for (int t = 0; t < JT; ++t)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        int j = t * 32 + g * 8 + lhalf * 4 + e;
+        if (j >= R) continue;
+        int tgt = j / a.rank, jr = j % a.rank;
+        uint16_t v = f32_to_bf16(acc[t][g * 4 + e] * a.scale).bits;
+        uint16_t* row = (uint16_t*)a.tp[tgt] + (size_t)m * a.rp;
+        row[jr] = v;
+        row[a.rank + jr] = v;
+      }
+  // zero padding up to rp (done by lhalf 0 lanes; rp - 2 rank is 0 or 8)
+  if (lhalf == 0)
+    for (int tgt = 0; tgt < a.n_targets; ++tgt)
+      for (int c = 2 * a.rank; c < a.rp; ++c) ((uint16_t*)a.tp[tgt])[(size_t)m * a.rp + c] = 0;
+}
+
+// ---- pack the perturbed fp32 factors into the bf16 hi/lo operand layouts ---------------------------------
+// A [K, r] (master layout) -> ap [2][r][K];  B [r, k_out] -> bp [k_out][rp] = [hi(r) | lo(r) | 0]
+__global__ void __launch_bounds__(256) pack_factors_kernel(const float* __restrict__ pert, int64_t P, int n_copies,
+                                                           LoraLayerTable tab, int n_layers, int rank, int rp,
+                                                           uint16_t* __restrict__ packed, int64_t packed_per_copy) {
+  // one thread per master element
+  int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)n_copies * P) return;
+  int copy = (int)(idx / P);
+  int64_t e = idx % P;
+  int layer = (int)(e / tab.per_layer);
+  int rem = (int)(e % tab.per_layer);
+  int i = 0;
+  while (i + 1 < tab.n_tensors && rem >= tab.off[i + 1]) ++i;
+  int local = rem - tab.off[i];
+  float v = pert[idx];
+  uint16_t hi = f32_to_bf16(v).bits;
+  bf16_t hb; hb.bits = hi;
+  uint16_t lo = f32_to_bf16(v - bf16_to_f32(hb)).bits;
+  // packed offset of tensor i inside a layer: A tensors take 2*rows*cols, B tensors take cols*rp
+  int64_t poff = 0;
+  for (int t = 0; t < i; ++t) poff += (tab.local_id[t] & 1) ? (int64_t)tab.cols[t] * rp : (int64_t)2 * tab.rows[t] * tab.cols[t];
+  int64_t per_layer_packed = poff;
+  for (int t = i; t < tab.n_tensors; ++t)
+    per_layer_packed += (tab.local_id[t] & 1) ? (int64_t)tab.cols[t] * rp : (int64_t)2 * tab.rows[t] * tab.cols[t];
+  uint16_t* dst = packed + (int64_t)copy * packed_per_copy + (int64_t)layer * per_layer_packed + poff;
+  if ((tab.local_id[i] & 1) == 0) {              // A [K, r]: element (k, j) -> hi at [j][k], lo at [r + j][k]
+    int K = tab.rows[i];
+    int k = local / rank, j = local % rank;
+    dst[(int64_t)j * K + k] = hi;
+    dst[(int64_t)(rank + j) * K + k] = lo;
+  } else {                                        // B [r, k_out]: element (j, n) -> [n][j] hi, [n][r + j] lo
+    int kout = tab.cols[i];
+    int j = local / kout, n = local % kout;
+    dst[(int64_t)n * rp + j] = hi;
+    dst[(int64_t)n * rp + rank + j] = lo;
+    if (j == 0)
+      for (int c = 2 * rank; c < rp; ++c) dst[(int64_t)n * rp + c] = 0;
+  }
+}
+
+}  // namespace
+
+size_t mfma_gemm_lds_bytes(bool dual) { return (size_t)2 * ((dual ? 2 : 1) + 1) * BM * LDS_STRIDE * 2; }
+
+bool mfma_gemm_supported(const MfmaGemmArgs& a) {
+  if (a.K % BK || a.N % 4 || a.M < 1 || a.N < 1) return false;
+  if (a.n_seg > 0 && (a.rows_per_copy % BM || a.M % BM)) return false;
+  for (int s = 0; s < a.n_seg; ++s)
+    if (a.seg[s].col_begin % BN || a.seg[s].col_end % BN || a.seg[s].rp % 16) return false;
+  if (a.dual && a.n_seg) return false;
+  return true;
+}
+
+void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
+  const int tiles = ((a.N + BN - 1) / BN) * ((a.M + BM - 1) / BM);
+  if (a.dual) {
+    static bool attr_set = false;
+    if (!attr_set) {
+      (void)hipFuncSetAttribute((const void*)gemm_bf16_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)mfma_gemm_lds_bytes(true));
+      attr_set = true;
+    }
+    gemm_bf16_kernel<true><<<tiles, 256, mfma_gemm_lds_bytes(true), st>>>(a);
+  } else {
+    static bool attr_set = false;
+    if (!attr_set) {
+      (void)hipFuncSetAttribute((const void*)gemm_bf16_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)mfma_gemm_lds_bytes(false));
+      attr_set = true;
+    }
+    gemm_bf16_kernel<false><<<tiles, 256, mfma_gemm_lds_bytes(false), st>>>(a);
+  }
+}
+
+bool mfma_lora_down_supported(const MfmaLoraDownArgs& a) {
+  int R = a.n_targets * a.rank;
+  return a.K % 16 == 0 && a.T % 32 == 0 && a.rows_per_copy % 32 == 0 && R <= 64 && a.rp % 8 == 0;
+}
+
+void launch_lora_down_mfma(hipStream_t st, const MfmaLoraDownArgs& a) {
+  int R = a.n_targets * a.rank;
+  if (R <= 32) lora_down_mfma_kernel<1><<<a.T / 32, 64, 0, st>>>(a);
+  else lora_down_mfma_kernel<2><<<a.T / 32, 64, 0, st>>>(a);
+}
+
+void launch_pack_factors(hipStream_t st, const float* pert, int64_t P, int n_copies, const LoraLayerTable& tab,
+                         int n_layers, int rank, int rp, void* packed, int64_t packed_per_copy) {
+  int64_t total = (int64_t)n_copies * P;
+  pack_factors_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(pert, P, n_copies, tab, n_layers, rank, rp,
+                                                                       (uint16_t*)packed, packed_per_copy);
+}
+
+}  // namespace mpz

@@ -42,6 +42,8 @@ struct Buffers {
   float* ce = nullptr;        // [T] per-row losses
   int32_t* target = nullptr;  // [T]
   int chunk_rows = 0;
+  void* packed = nullptr;     // [2 q_max][packed_per_copy] bf16 hi/lo operand layouts of the perturbed factors
+  void* tp[3] = {nullptr, nullptr, nullptr};  // per target [T, rp] duplicated bottleneck activations
 };
 
 size_t elem_size(int dtype) { return dtype == MPZ_DTYPE_F32 ? 4 : 2; }
@@ -130,6 +132,14 @@ size_t carve(const mpz_config* c, int q_max, int E_max, int S_max, void* base, B
   }
   bb.ce = cv.take<float>((size_t)loss_rows);
   bb.target = cv.take<int32_t>((size_t)loss_rows);
+  if (c->dtype == MPZ_DTYPE_BF16) {
+    int rp = (2 * c->lora_rank + 15) / 16 * 16;
+    int64_t per_layer = 0;
+    for (int i = 0; i < tab.n_tensors; ++i)
+      per_layer += (tab.local_id[i] & 1) ? (int64_t)tab.cols[i] * rp : (int64_t)2 * tab.rows[i] * tab.cols[i];
+    bb.packed = cv.take<uint16_t>((size_t)(n * per_layer * c->n_layers));
+    for (int i = 0; i < 3; ++i) bb.tp[i] = cv.take<uint16_t>((size_t)T * rp);
+  }
   if (b) *b = bb;
   return (cv.off + 255) & ~(size_t)255;
 }
@@ -151,6 +161,11 @@ struct mpz_model {
   uint64_t seed = 0; uint32_t step = 0; int q = 0; float eps = 0.f;
   std::string err;
   // optional per-launch timing of the base-weight GEMMs (mpz_profile_gemm_begin / _end)
+  // bf16 MFMA path
+  bool use_mfma = false;
+  int rp = 0;                                   // padded 2r
+  int64_t packed_per_layer = 0, packed_per_copy = 0;
+  int64_t packed_off[8] = {0};                  // offset of tensor i inside a layer's packed block
   bool prof_on = false;
   std::vector<hipEvent_t> prof_ev;   // start/stop pairs
   size_t prof_used = 0;
@@ -193,8 +208,49 @@ void gemm(mpz_model* m, const LinearArgs& a) {
       (void)hipEventRecord(e0, m->stream);
     }
   }
-  launch_linear_simple(m->stream, a);
+  bool done = false;
+  if (m->use_mfma && a.dtype == MPZ_DTYPE_BF16 && (a.n_seg == 0 || a.mfma_lora)) {
+    MfmaGemmArgs g{};
+    g.M = a.M; g.N = a.N; g.K = a.K; g.x = a.x; g.w = a.w; g.bias = a.bias; g.dual = 0; g.dual_offset = 0;
+    g.n_seg = a.n_seg; g.rows_per_copy = a.rows_per_copy; g.act = a.act; g.residual = a.residual;
+    g.out_f32 = a.out_kind != 0; g.out = a.out; g.ldo = a.N;   // bf16 models stage in fp32
+    for (int i = 0; i < a.n_seg; ++i) g.seg[i] = a.mseg[i];
+    if (mfma_gemm_supported(g)) { launch_gemm_mfma(m->stream, g); done = true; }
+  }
+  if (!done) launch_linear_simple(m->stream, a);
   if (e1) (void)hipEventRecord(e1, m->stream);
+}
+
+// SwiGLU up-projection: gate and up tiles in one kernel, u = SiLU(gate) * up rounded once
+bool gemm_swiglu_mfma(mpz_model* m, const LinearArgs& a, int f, void* u_out) {
+  if (!m->use_mfma) return false;
+  MfmaGemmArgs g{};
+  g.M = a.M; g.N = f; g.K = a.K; g.x = a.x; g.w = a.w; g.bias = a.bias; g.dual = 1; g.dual_offset = f;
+  g.rows_per_copy = a.rows_per_copy; g.act = -1; g.out_f32 = 0; g.out = u_out; g.ldo = f;
+  if (!mfma_gemm_supported(g)) return false;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (m->prof_on) {
+    if (m->prof_used + 2 > m->prof_ev.size()) {
+      hipEvent_t x = nullptr, y = nullptr;
+      if (hipEventCreate(&x) == hipSuccess && hipEventCreate(&y) == hipSuccess) { m->prof_ev.push_back(x); m->prof_ev.push_back(y); }
+    }
+    if (m->prof_used + 2 <= m->prof_ev.size()) {
+      e0 = m->prof_ev[m->prof_used]; e1 = m->prof_ev[m->prof_used + 1];
+      m->prof_used += 2;
+      m->prof_flops += 2.0 * a.M * (double)(2 * f) * a.K;
+      (void)hipEventRecord(e0, m->stream);
+    }
+  }
+  launch_gemm_mfma(m->stream, g);
+  if (e1) (void)hipEventRecord(e1, m->stream);
+  return true;
+}
+
+// index of (target, factor) among one layer's LoRA tensors
+int tensor_slot(const mpz_model* m, int target, int factor) {
+  for (int i = 0; i < m->tab.n_tensors; ++i)
+    if (m->tab.local_id[i] == target * 2 + factor) return i;
+  return 0;
 }
 
 void run_embed(mpz_model* m, const int32_t* tokens, int E, int S, float* h) {
@@ -238,7 +294,31 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     }
     for (int i = 0; i < nt; ++i) qa.seg[i].t_stride = nt * r;
     da.n_targets = nt; qa.n_seg = nt;
-    if (nt) launch_lora_down_simple(st, da);
+    const char* packed_l = (const char*)b.packed + (size_t)l * m->packed_per_layer * 2;
+    bool lora_done = false;
+    if (nt && m->use_mfma) {
+      MfmaLoraDownArgs md{};
+      md.T = T; md.K = d; md.rank = r; md.n_targets = nt; md.rows_per_copy = rpc; md.rp = m->rp; md.x = b.x;
+      md.scale = c.lora_scale; md.copy_stride = m->packed_per_copy;
+      int i = 0;
+      for (int t = 0; t < 3; ++t) {
+        if (!(c.lora_targets & (1u << t))) continue;
+        int ia = tensor_slot(m, t, 0), ib = tensor_slot(m, t, 1);
+        md.ap[i] = packed_l + m->packed_off[ia] * 2; md.tp[i] = b.tp[i];
+        MfmaLoraSeg& ms = qa.mseg[i];
+        ms.col_begin = col0[t]; ms.col_end = col1[t]; ms.tp = b.tp[i]; ms.bp = packed_l + m->packed_off[ib] * 2;
+        ms.rp = m->rp; ms.copy_stride = m->packed_per_copy;
+        ++i;
+      }
+      MfmaGemmArgs probe{};
+      probe.M = T; probe.N = nqkv; probe.K = d; probe.n_seg = nt; probe.rows_per_copy = rpc;
+      for (int k = 0; k < nt; ++k) probe.seg[k] = qa.mseg[k];
+      if (mfma_lora_down_supported(md) && mfma_gemm_supported(probe)) {
+        launch_lora_down_mfma(st, md);
+        qa.mfma_lora = 1; lora_done = true;
+      }
+    }
+    if (nt && !lora_done) launch_lora_down_simple(st, da);
     qa.out_kind = rope ? 2 : 0; qa.out = rope ? b.stage : b.qkv;
     gemm(m, qa);
     if (rope) launch_rope_convert(st, c.dtype, b.stage, b.qkv, T, S, nqkv, dh, c.n_heads + c.n_kv_heads, b.rope_cos, b.rope_sin);
@@ -252,7 +332,23 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     if (c.lora_targets & MPZ_TARGET_O) {
       LoraDownArgs oda = da;
       oda.x = b.attn; oda.n_targets = 1; oda.Ac[0] = b.pert + find_tensor(m, l, 3, 0)->offset;
-      launch_lora_down_simple(st, oda);
+      bool o_done = false;
+      if (m->use_mfma) {
+        MfmaLoraDownArgs md{};
+        md.T = T; md.K = d; md.rank = r; md.n_targets = 1; md.rows_per_copy = rpc; md.rp = m->rp; md.x = b.attn;
+        md.scale = c.lora_scale; md.copy_stride = m->packed_per_copy;
+        md.ap[0] = packed_l + m->packed_off[tensor_slot(m, 3, 0)] * 2; md.tp[0] = b.tp[0];
+        MfmaLoraSeg& ms = oa.mseg[0];
+        ms.col_begin = 0; ms.col_end = d; ms.tp = b.tp[0]; ms.bp = packed_l + m->packed_off[tensor_slot(m, 3, 1)] * 2;
+        ms.rp = m->rp; ms.copy_stride = m->packed_per_copy;
+        MfmaGemmArgs probe{};
+        probe.M = T; probe.N = d; probe.K = d; probe.n_seg = 1; probe.rows_per_copy = rpc; probe.seg[0] = ms;
+        if (mfma_lora_down_supported(md) && mfma_gemm_supported(probe)) {
+          launch_lora_down_mfma(st, md);
+          oa.mfma_lora = 1; o_done = true;
+        }
+      }
+      if (!o_done) launch_lora_down_simple(st, oda);
       oa.n_seg = 1;
       oa.seg[0].col_begin = 0; oa.seg[0].col_end = d; oa.seg[0].t = b.t; oa.seg[0].t_stride = r; oa.seg[0].t_off = 0;
       oa.seg[0].Bc = b.pert + find_tensor(m, l, 3, 1)->offset; oa.seg[0].copy_stride = m->P;
@@ -265,8 +361,10 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     ua.dtype = c.dtype; ua.M = T; ua.N = swiglu ? 2 * f : f; ua.K = d; ua.x = b.x; ua.w = lw.w_up; ua.bias = lw.b_up;
     ua.rank = r; ua.rows_per_copy = rpc; ua.act = swiglu ? -1 : c.act;
     ua.out_kind = swiglu ? 2 : 0; ua.out = swiglu ? b.stage : b.u;
-    gemm(m, ua);
-    if (swiglu) launch_swiglu(st, c.dtype, b.stage, b.u, T, f);
+    if (!(swiglu && gemm_swiglu_mfma(m, ua, f, b.u))) {
+      gemm(m, ua);
+      if (swiglu) launch_swiglu(st, c.dtype, b.stage, b.u, T, f);
+    }
     LinearArgs wa{};
     wa.dtype = c.dtype; wa.M = T; wa.N = d; wa.K = f; wa.x = b.u; wa.w = lw.w_down; wa.bias = lw.b_down;
     wa.rank = r; wa.rows_per_copy = rpc; wa.act = -1; wa.residual = b.h; wa.out_kind = 1; wa.out = b.h;
@@ -394,6 +492,13 @@ mpz_status mpz_init_model(const mpz_config* cfg, const mpz_weights* frozen, floa
   build_layout(cfg, m->tensors, m->tab);
   m->P = (int64_t)m->tab.per_layer * cfg->n_layers;
   carve(cfg, q_max, E_max, S_max, workspace, &m->buf);
+  m->use_mfma = cfg->dtype == MPZ_DTYPE_BF16;
+  m->rp = (2 * cfg->lora_rank + 15) / 16 * 16;
+  for (int i = 0; i < m->tab.n_tensors; ++i) {
+    m->packed_off[i] = m->packed_per_layer;
+    m->packed_per_layer += (m->tab.local_id[i] & 1) ? (int64_t)m->tab.cols[i] * m->rp : (int64_t)2 * m->tab.rows[i] * m->tab.cols[i];
+  }
+  m->packed_per_copy = m->packed_per_layer * cfg->n_layers;
   if (cfg->pos == MPZ_POS_ROPE) {
     int dh = cfg->d_model / cfg->n_heads, half = dh / 2;
     std::vector<float> cs((size_t)cfg->max_seq * half), sn((size_t)cfg->max_seq * half);
@@ -422,6 +527,9 @@ mpz_status mpz_regen_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t q
   if (q < 1 || q > m->q_max) return fail(m, MPZ_ERR_SHAPE, "q outside [1, q_max]");
   if (!std::isfinite(eps) || eps < 0.f) return fail(m, MPZ_ERR_CONFIG, "eps must be finite and non-negative");
   launch_perturb(m->stream, m->masters, m->buf.pert, m->P, m->tab, seed, step, q, eps, m->cfg.perturb_A);
+  if (m->use_mfma)
+    launch_pack_factors(m->stream, m->buf.pert, m->P, 2 * q, m->tab, m->cfg.n_layers, m->cfg.lora_rank, m->rp, m->buf.packed,
+                        m->packed_per_copy);
   m->have_noise = true; m->seed = seed; m->step = step; m->q = q; m->eps = eps;
   return check_device(m, "mpz_regen_noise");
 }
@@ -503,6 +611,13 @@ mpz_status mpz_debug_perturbed_copy(mpz_model* m, int32_t c, float* out) {
   if (c < 0 || c >= 2 * m->q) return fail(m, MPZ_ERR_SHAPE, "copy index outside [0, 2q)");
   hipError_t e = hipMemcpyAsync(out, m->buf.pert + (int64_t)c * m->P, (size_t)m->P * 4, hipMemcpyDeviceToDevice, m->stream);
   if (e != hipSuccess) return fail(m, MPZ_ERR_DEVICE, hipGetErrorString(e));
+  return MPZ_OK;
+}
+
+mpz_status mpz_debug_set_kernel_path(mpz_model* m, int32_t simple_only) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_set_kernel_path: NULL model");
+  m->use_mfma = !simple_only && m->cfg.dtype == MPZ_DTYPE_BF16;
+  m->have_noise = false;                       // operand layouts differ between the paths: regenerate
   return MPZ_OK;
 }
 

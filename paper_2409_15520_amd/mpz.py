@@ -93,6 +93,8 @@ def load_library() -> C.CDLL:
     lib.mpz_debug_run_layers.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.mpz_debug_head_loss.restype = C.c_int
     lib.mpz_debug_head_loss.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    lib.mpz_debug_set_kernel_path.restype = C.c_int
+    lib.mpz_debug_set_kernel_path.argtypes = [C.c_void_p, C.c_int32]
     lib.mpz_profile_gemm_begin.restype = C.c_int
     lib.mpz_profile_gemm_begin.argtypes = [C.c_void_p]
     lib.mpz_profile_gemm_end.restype = C.c_int
@@ -181,6 +183,10 @@ def mpz_debug_run_layers(handle, h_ptr: int, layer_begin: int, layer_end: int, E
 
 def mpz_debug_head_loss(handle, h_ptr: int, tokens_ptr: int, labels_ptr: Optional[int], E: int, S: int, losses_ptr: int):
     _check(load_library().mpz_debug_head_loss(handle, h_ptr, tokens_ptr, labels_ptr, E, S, losses_ptr), handle)
+
+
+def mpz_debug_set_kernel_path(handle, simple_only: bool):
+    _check(load_library().mpz_debug_set_kernel_path(handle, int(simple_only)), handle)
 
 
 def mpz_profile_gemm_begin(handle):

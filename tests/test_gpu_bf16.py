@@ -20,11 +20,18 @@ CASES = {
     "mini_llama": MINI_LLAMA.with_(dtype="bf16"),
     "mini_opt": MINI_OPT.with_(dtype="bf16", loss_mode="next_token_all_pos"),
     "c2_2layers": W.get_workload("c2_opt125m").with_(n_layers=2),
+    # Llama-style shapes that the MFMA kernels accept: adapters on q, k, v, o with r = 16, grouped-query
+    # attention, rotary positions, SwiGLU (gate|up tiles fused), next-token loss over the whole vocabulary
+    "llama_mfma": W.Workload(
+        name="llama_mfma", n_layers=2, d_model=256, n_heads=4, n_kv_heads=2, d_ffn=384, vocab=1000, max_seq=64,
+        act="swiglu", norm="rmsnorm", pos="rope", has_bias=False, tie_embeddings=False, dtype="bf16",
+        lora_rank=16, lora_targets=("q", "k", "v", "o"), loss_mode="next_token_all_pos", q=2, E=2, S=64, steps=1),
 }
 
 
 @pytest.mark.parametrize("name,eps,b_std", [("mini_llama", 1e-3, 0.01), ("mini_opt", 1e-3, 0.01),
-                                            ("c2_2layers", 1e-3, 0.01), ("c2_2layers", 5e-2, 0.05)])
+                                            ("c2_2layers", 1e-3, 0.01), ("c2_2layers", 5e-2, 0.05),
+                                            ("llama_mfma", 1e-3, 0.01), ("llama_mfma", 5e-2, 0.05)])
 def test_each_stage_on_oracle_inputs(name, eps, b_std):
     """Second c2 case: perturbation and B large enough that the low-rank term moves the projections by
     O(10%), so a wrong or missing per-copy term cannot hide under the rounding tolerance."""
@@ -98,3 +105,25 @@ def test_same_widths_in_fp32_meet_the_fp32_bar():
     assert np.abs(Lg - Lo).max() <= 1e-6 * np.abs(Lo).max()
     assert all(rel_err(Gg[s], Go[s]) <= 1e-4 for s in range(2))
     assert rel_err(Mg, Mo) <= 1e-3
+
+
+@pytest.mark.parametrize("name", ["c2_2layers", "llama_mfma"])
+def test_mfma_path_agrees_with_shape_agnostic_path(name):
+    """Same rounding points, different kernels: one block on identical inputs, element by element."""
+    import torch
+    import paper_2409_15520_amd as M
+    w = CASES[name].with_(eps=5e-2)
+    b = make_bundle(w, b_std=0.05)
+    m = gpu_model(b)
+    tok = torch.from_numpy(b["tokens"]).cuda()
+    outs = []
+    for simple in (False, True):
+        M.mpz_debug_set_kernel_path(m.handle, simple)
+        m.regen_noise(3456, 0)
+        h = m.embed(tok)
+        m.run_layers(h, 0, 1, w.E, w.S)
+        outs.append(h.cpu().numpy().astype(np.float64))
+    rms = np.sqrt(np.mean(outs[1] ** 2))
+    d = np.abs(outs[0] - outs[1])
+    print(f"\n{name}: mfma vs simple: max|d|/rms {d.max() / rms:.3e} rms|d|/rms {np.sqrt(np.mean(d ** 2)) / rms:.3e}")
+    assert np.sqrt(np.mean(d ** 2)) <= 3e-3 * rms and d.max() <= 5e-2 * rms
