@@ -188,6 +188,14 @@ mpz_status mpz_debug_run_layers(mpz_model* m, float* h, int32_t layer_begin, int
 mpz_status mpz_debug_head_loss(mpz_model* m, const float* h, const int32_t* tokens, const int32_t* labels,
                                int32_t E, int32_t S, float* losses_out);
 
+/* Test hooks for single operations of a bf16 / any model on caller-provided operands:
+ * - the q/k/v projection of the MP-LoRA layer (Section 3: Y = X W + (X A)(.)B, plus bias) of block `layer` for all
+ *   stacked copies: x [dev] model dtype [2q*E*S, d] -> out [dev] fp32 [2q*E*S, d + 2 d_kv], before the rotary
+ *   embedding and before rounding to the operand type (bf16 models only);
+ * - causal attention: qkv [dev] model dtype [n_seq*S, d + 2 d_kv] (q | k | v) -> out [dev] model dtype [n_seq*S, d]. */
+mpz_status mpz_debug_qkv_projection(mpz_model* m, const void* x, int32_t layer, int32_t E, int32_t S, float* out);
+mpz_status mpz_debug_attention(mpz_model* m, const void* qkv, int32_t n_seq, int32_t S, void* out);
+
 /* Test hook: simple_only != 0 routes every stage through the shape-agnostic kernels (the only path of
  * fp32 models); 0 restores the default (bf16 models use the MFMA kernels wherever a shape allows).
  * Invalidates the perturbed copies: call mpz_regen_noise again. */

@@ -1,0 +1,205 @@
+// Causal self-attention for the stacked copies (every copy is an ordinary batch row here: Section 3,
+// the n copies of the input batch travel through the model side by side).  bf16 MFMA for Q K^T and P V,
+// fp32 softmax.  Two passes over the keys: the first finds each query's exact row maximum, the second
+// recomputes the scores (bit-identical), forms P = bf16(exp(s - max)) and accumulates P V and sum(P).
+// Rounding P against the exact maximum makes the result independent of the key tiling, which a running
+// ("online") maximum would not be.
+//
+// One block = one (sequence, head) and 128 queries, 4 waves x 32 queries.  MFMA orientation: rows = keys
+// (A operand), columns = queries (B operand): a lane owns ONE query, so max / sum are in-lane plus one
+// cross-half shuffle, and the score registers are directly the B operand of the P V product
+// D[dv, q] = sum_key Vt[dv, key] P[key, q] (the key order inside an MFMA K-step is permuted identically
+// on both operands).
+#include "common.h"
+
+namespace mpz {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int QB = 128;   // queries per block
+constexpr int KC = 64;    // keys per LDS chunk
+
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+  return (uint32_t)f32_to_bf16(a).bits | ((uint32_t)f32_to_bf16(b).bits << 16);
+}
+
+template <int DH>
+__global__ void __launch_bounds__(256) attention_mfma_kernel(const uint16_t* __restrict__ qkv, int qkv_stride,
+                                                             uint16_t* __restrict__ out, int S, int H, int Hkv,
+                                                             float scale) {
+  constexpr int KS = DH + 8;        // K chunk row stride (elements)
+  constexpr int VS = KC + 8;        // V^T chunk row stride
+  constexpr int NJ = DH / 16;       // MFMA K-steps over the head dimension
+  constexpr int NT = DH / 32;       // 32-row output tiles over the head dimension
+  __shared__ __align__(16) uint16_t sK[KC * KS];
+  __shared__ __align__(16) uint16_t sVt[DH * VS];
+
+  const int qblocks = (S + QB - 1) / QB;
+  const int qb = blockIdx.x % qblocks;
+  const int head = (blockIdx.x / qblocks) % H;
+  const int seq = blockIdx.x / (qblocks * H);
+  const int kvh = head / (H / Hkv);
+  const int d = H * DH, dkv = Hkv * DH;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lrow = lane & 31, lhalf = lane >> 5;
+
+  const int q0 = qb * QB + wave * 32;             // first query of this wave
+  const int qi = q0 + lrow;                       // this lane's query
+  const int qi_c = qi < S ? qi : S - 1;
+  const size_t row0 = (size_t)seq * S;
+  const uint16_t* kbase = qkv + row0 * qkv_stride + d + kvh * DH;
+  const uint16_t* vbase = qkv + row0 * qkv_stride + d + dkv + kvh * DH;
+
+  // Q fragments (B operand): query qi, head-dim elements j*16 + lhalf*8 .. +7
+  bf16x8 fq[NJ];
+  {
+    const uint16_t* qp = qkv + (row0 + qi_c) * qkv_stride + head * DH + lhalf * 8;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) fq[j] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qp + j * 16));
+  }
+
+  const int last_q_block = (qb * QB + QB - 1 < S ? qb * QB + QB - 1 : S - 1);
+  const int n_chunks = last_q_block / KC + 1;     // key chunks any query of the block can see
+  const int wave_last_q = q0 + 31;
+
+  auto load_k_chunk = [&](int c) {
+    constexpr int CPR = DH / 8;                   // 16-byte chunks per key row
+    for (int i = tid; i < KC * CPR; i += 256) {
+      int key = i / CPR, ch = i % CPR;
+      int kg = c * KC + key; kg = kg < S ? kg : S - 1;
+      *(u32x4*)(sK + key * KS + ch * 8) = *(const u32x4*)(kbase + (size_t)kg * qkv_stride + ch * 8);
+    }
+  };
+  auto load_v_chunk = [&](int c) {
+    constexpr int CPR = DH / 8;
+    for (int i = tid; i < KC * CPR; i += 256) {
+      int key = i / CPR, ch = i % CPR;
+      int kg = c * KC + key; kg = kg < S ? kg : S - 1;
+      u32x4 v = *(const u32x4*)(vbase + (size_t)kg * qkv_stride + ch * 8);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        sVt[(ch * 8 + 2 * e) * VS + key] = (uint16_t)(v[e] & 0xFFFFu);
+        sVt[(ch * 8 + 2 * e + 1) * VS + key] = (uint16_t)(v[e] >> 16);
+      }
+    }
+  };
+  // scores of one 32-key tile against this wave's 32 queries; lane: query qi, keys kt0 + (e/4)*8 + lhalf*4 + e%4
+  auto score_tile = [&](int kt_local, int kt0, float s[16]) {
+    f32x16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      bf16x8 fk = __builtin_bit_cast(bf16x8, *(const u32x4*)(sK + (kt_local * 32 + lrow) * KS + j * 16 + lhalf * 8));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk, fq[j], acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      int key = kt0 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
+      s[e] = key <= qi ? acc[e] * scale : -1e30f;
+    }
+  };
+
+  // ---- pass 1: exact row maximum ----
+  float mx = -1e30f;
+  for (int c = 0; c < n_chunks; ++c) {
+    __syncthreads();
+    load_k_chunk(c);
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < KC / 32; ++t) {
+      int kt0 = c * KC + t * 32;
+      if (kt0 > wave_last_q) continue;            // tile entirely in this wave's future
+      float s[16];
+      score_tile(t, kt0, s);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mx = s[e] > mx ? s[e] : mx;
+    }
+  }
+  {
+    float other = __shfl_xor(mx, 32, 64);
+    mx = other > mx ? other : mx;
+  }
+
+  // ---- pass 2: P = bf16(exp(s - max)), O^T += V^T P, l += P ----
+  f32x16 oacc[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[t][e] = 0.f;
+  float lsum = 0.f;
+  for (int c = 0; c < n_chunks; ++c) {
+    __syncthreads();
+    load_k_chunk(c);
+    load_v_chunk(c);
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < KC / 32; ++t) {
+      int kt0 = c * KC + t * 32;
+      if (kt0 > wave_last_q) continue;
+      float s[16];
+      score_tile(t, kt0, s);
+      uint32_t pw[8];                             // 16 probabilities as bf16 pairs
+#pragma unroll
+      for (int e = 0; e < 16; e += 2) {
+        float p0 = s[e] > -1e29f ? expf(s[e] - mx) : 0.f;
+        float p1 = s[e + 1] > -1e29f ? expf(s[e + 1] - mx) : 0.f;
+        bf16_t b0 = f32_to_bf16(p0), b1 = f32_to_bf16(p1);
+        lsum += bf16_to_f32(b0) + bf16_to_f32(b1);
+        pw[e >> 1] = (uint32_t)b0.bits | ((uint32_t)b1.bits << 16);
+      }
+      // two MFMA K-steps of 16 keys: step h uses score registers 8h .. 8h+7, i.e. keys
+      // kt0 + 16h + lhalf*4 + (0..3) and kt0 + 16h + 8 + lhalf*4 + (0..3)
+#pragma unroll
+      for (int hstep = 0; hstep < 2; ++hstep) {
+        u32x4 pfrag = {pw[hstep * 4], pw[hstep * 4 + 1], pw[hstep * 4 + 2], pw[hstep * 4 + 3]};
+        bf16x8 fp = __builtin_bit_cast(bf16x8, pfrag);
+        const int kl = t * 32 + hstep * 16 + lhalf * 4;   // key offset inside the chunk
+#pragma unroll
+        for (int vt = 0; vt < NT; ++vt) {
+          const uint16_t* vp = sVt + (vt * 32 + lrow) * VS + kl;
+          u32x2 a = *(const u32x2*)vp, b = *(const u32x2*)(vp + 8);
+          u32x4 vfrag = {a[0], a[1], b[0], b[1]};
+          oacc[vt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vfrag), fp, oacc[vt], 0, 0, 0);
+        }
+      }
+    }
+  }
+  lsum += __shfl_xor(lsum, 32, 64);
+
+  if (qi < S) {
+    uint16_t* op = out + (row0 + qi) * (size_t)d + head * DH;
+#pragma unroll
+    for (int vt = 0; vt < NT; ++vt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        int dv = vt * 32 + g * 8 + lhalf * 4;
+        u32x2 pk = {pack2(oacc[vt][g * 4] / lsum, oacc[vt][g * 4 + 1] / lsum),
+                    pack2(oacc[vt][g * 4 + 2] / lsum, oacc[vt][g * 4 + 3] / lsum)};
+        *(u32x2*)(op + dv) = pk;
+      }
+  }
+}
+
+}  // namespace
+
+bool attention_mfma_supported(int dh, int qkv_stride, int d) {
+  return (dh == 64 || dh == 128) && qkv_stride % 8 == 0 && d % 8 == 0;
+}
+
+void launch_attention_mfma(hipStream_t st, const void* qkv, int qkv_stride, void* out, int n_seq, int S, int H, int Hkv,
+                           int dh) {
+  const int qblocks = (S + QB - 1) / QB;
+  const unsigned blocks = (unsigned)((size_t)n_seq * H * qblocks);
+  const float scale = (float)(1.0 / sqrt((double)dh));
+  if (dh == 64)
+    attention_mfma_kernel<64><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale);
+  else
+    attention_mfma_kernel<128><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale);
+}
+
+}  // namespace mpz

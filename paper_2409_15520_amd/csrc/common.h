@@ -127,4 +127,10 @@ void launch_lora_down_mfma(hipStream_t st, const MfmaLoraDownArgs& a);
 void launch_pack_factors(hipStream_t st, const float* pert, int64_t P, int n_copies, const LoraLayerTable& tab,
                          int n_layers, int rank, int rp, void* packed, int64_t packed_per_copy);
 
+
+// ---- attention_mfma.hip ---------------------------------------------------------------------------
+bool attention_mfma_supported(int dh, int qkv_stride, int d);
+void launch_attention_mfma(hipStream_t st, const void* qkv, int qkv_stride, void* out, int n_seq, int S, int H, int Hkv,
+                           int dh);
+
 }  // namespace mpz

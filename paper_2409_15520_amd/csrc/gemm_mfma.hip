@@ -15,13 +15,14 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;     // 16-byte chunk in registers (native vector type)
 
 constexpr int BM = 128;          // tokens per block
 constexpr int BN = 128;          // output features per block
 constexpr int BK = 64;           // K per stage
 constexpr int LDS_STRIDE = BK + 8;   // bf16 elements; +16 B per row keeps ds_read_b128 conflict-free
 
-__device__ __forceinline__ bf16x8 as_frag(const uint4& v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ bf16x8 as_frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f)); }
 
@@ -68,24 +69,18 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(MfmaGemmArgs a) {
     if (DUAL) wp[NW - 1][i] = W + (size_t)(n + a.dual_offset) * a.K + ld_kc[i];
     xp[i] = X + (size_t)m * a.K + ld_kc[i];
   }
-  uint4 rw[NW][4], rx[4];
-  auto load_global = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-      for (int d = 0; d < NW; ++d) rw[d][i] = *(const uint4*)(wp[d][i] + k0);
-      rx[i] = *(const uint4*)(xp[i] + k0);
-    }
-  };
-  auto store_lds = [&](int stage) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int off = ld_row[i] * LDS_STRIDE + ld_kc[i];
-#pragma unroll
-      for (int d = 0; d < NW; ++d) *(uint4*)(sW + (stage * NW + d) * TILE + off) = rw[d][i];
-      *(uint4*)(sX + stage * TILE + off) = rx[i];
-    }
-  };
+  u32x4 rw[NW][4], rx[4];
+#define MPZ_LOAD_GLOBAL(k0)                                                        \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                  \
+    _Pragma("unroll") for (int d = 0; d < NW; ++d) rw[d][i] = *(const u32x4*)(wp[d][i] + (k0)); \
+    rx[i] = *(const u32x4*)(xp[i] + (k0));                                         \
+  }
+#define MPZ_STORE_LDS(stage)                                                       \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                  \
+    const int off = ld_row[i] * LDS_STRIDE + ld_kc[i];                             \
+    _Pragma("unroll") for (int d = 0; d < NW; ++d) *(u32x4*)(sW + ((stage) * NW + d) * TILE + off) = rw[d][i]; \
+    *(u32x4*)(sX + (stage) * TILE + off) = rx[i];                                  \
+  }
 
   f32x16 acc[NW][2][2];
 #pragma unroll
@@ -98,12 +93,12 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(MfmaGemmArgs a) {
         for (int e = 0; e < 16; ++e) acc[d][i][j][e] = 0.f;
 
   const int nk = a.K / BK;
-  load_global(0);
-  store_lds(0);
+  MPZ_LOAD_GLOBAL(0)
+  MPZ_STORE_LDS(0)
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const int stage = kt & 1;
-    if (kt + 1 < nk) load_global((kt + 1) * BK);
+    if (kt + 1 < nk) { MPZ_LOAD_GLOBAL((kt + 1) * BK) }
     const uint16_t* cw = sW + stage * NW * TILE;
     const uint16_t* cx = sX + stage * TILE;
 #pragma unroll
@@ -113,8 +108,8 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(MfmaGemmArgs a) {
       for (int i = 0; i < 2; ++i) {
 #pragma unroll
         for (int d = 0; d < NW; ++d)
-          fw[d][i] = as_frag(*(const uint4*)(cw + d * TILE + (wn + i * 32 + lrow) * LDS_STRIDE + kk + lhalf * 8));
-        fx[i] = as_frag(*(const uint4*)(cx + (wm + i * 32 + lrow) * LDS_STRIDE + kk + lhalf * 8));
+          fw[d][i] = as_frag(*(const u32x4*)(cw + d * TILE + (wn + i * 32 + lrow) * LDS_STRIDE + kk + lhalf * 8));
+        fx[i] = as_frag(*(const u32x4*)(cx + (wm + i * 32 + lrow) * LDS_STRIDE + kk + lhalf * 8));
       }
 #pragma unroll
       for (int d = 0; d < NW; ++d)
@@ -124,7 +119,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(MfmaGemmArgs a) {
           for (int j = 0; j < 2; ++j)
             acc[d][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[d][i], fx[j], acc[d][i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_lds(stage ^ 1);
+    if (kt + 1 < nk) { MPZ_STORE_LDS(stage ^ 1) }
     __syncthreads();
   }
 
@@ -143,8 +138,8 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(MfmaGemmArgs a) {
         for (int i = 0; i < 2; ++i) {
           int n = n0 + wn + i * 32 + lrow - sg.col_begin;
           int m = m0 + wm + i * 32 + lrow;
-          fw[i] = as_frag(*(const uint4*)(bp + (size_t)n * sg.rp + ks + lhalf * 8));
-          fx[i] = as_frag(*(const uint4*)(tp + (size_t)m * sg.rp + ks + lhalf * 8));
+          fw[i] = as_frag(*(const u32x4*)(bp + (size_t)n * sg.rp + ks + lhalf * 8));
+          fx[i] = as_frag(*(const u32x4*)(tp + (size_t)m * sg.rp + ks + lhalf * 8));
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -236,14 +231,14 @@ __global__ void __launch_bounds__(64) lora_down_mfma_kernel(MfmaLoraDownArgs a) 
   for (int t = 0; t < JT; ++t)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
-  const uint4 zero = make_uint4(0, 0, 0, 0);
+  const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll 4
   for (int k = 0; k < a.K; k += 16) {
-    bf16x8 fx = as_frag(*(const uint4*)(X + k));
+    bf16x8 fx = as_frag(*(const u32x4*)(X + k));
 #pragma unroll
     for (int t = 0; t < JT; ++t) {
-      uint4 h = valid[t] ? *(const uint4*)(Ah[t] + k) : zero;
-      uint4 l = valid[t] ? *(const uint4*)(Al[t] + k) : zero;
+      u32x4 h = valid[t] ? *(const u32x4*)(Ah[t] + k) : zero;
+      u32x4 l = valid[t] ? *(const u32x4*)(Al[t] + k) : zero;
       acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(h), fx, acc[t], 0, 0, 0);
       acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(l), fx, acc[t], 0, 0, 0);
     }

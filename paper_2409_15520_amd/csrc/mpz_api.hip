@@ -259,22 +259,15 @@ void run_embed(mpz_model* m, const int32_t* tokens, int E, int S, float* h) {
                c.d_model);
 }
 
-// Decoder blocks [l0, l1) on the stacked residual stream h [T, d]: per adapted linear an optional
-// bottleneck kernel, then the GEMM with the per-copy rank-r term.
-void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
+// q/k/v projections of the MP-LoRA layer for all stacked copies: x = b.x [T, d] -> out [T, d + 2 d_kv]
+void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, int out_kind, void* out) {
   const mpz_config& c = m->cfg;
   hipStream_t st = m->stream;
-  Buffers b = m->buf;
-  b.h = h;
+  const mpz_layer_weights& lw = m->layers[l];
   const int n = 2 * m->q, rpc = E * S, T = n * rpc;
-  const int d = c.d_model, dh = d / c.n_heads, dkv = c.n_kv_heads * dh, f = c.d_ffn, r = c.lora_rank;
+  const int d = c.d_model, dh = d / c.n_heads, dkv = c.n_kv_heads * dh, r = c.lora_rank;
   const int nqkv = d + 2 * dkv;
-  const bool rope = c.pos == MPZ_POS_ROPE, swiglu = c.act == MPZ_ACT_SWIGLU;
-
-  for (int l = l0; l < l1; ++l) {
-    const mpz_layer_weights& lw = m->layers[l];
-    launch_norm(st, c.dtype, c.norm, c.norm_eps, b.h, d, lw.ln1_g, lw.ln1_b, b.x, T, d);
-
+  {
     // q/k/v projections of the MP-LoRA layer: shared W, per-copy (A_c, B_c)
     LoraDownArgs da{};
     da.dtype = c.dtype; da.T = T; da.K = d; da.rank = r; da.rows_per_copy = rpc; da.x = b.x; da.scale = c.lora_scale;
@@ -319,13 +312,40 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
       }
     }
     if (nt && !lora_done) launch_lora_down_simple(st, da);
-    qa.out_kind = rope ? 2 : 0; qa.out = rope ? b.stage : b.qkv;
+    qa.out_kind = out_kind; qa.out = out;
     gemm(m, qa);
+  }
+}
+
+// Decoder blocks [l0, l1) on the stacked residual stream h [T, d]: per adapted linear an optional
+// bottleneck kernel, then the GEMM with the per-copy rank-r term.
+void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
+  const mpz_config& c = m->cfg;
+  hipStream_t st = m->stream;
+  Buffers b = m->buf;
+  b.h = h;
+  const int n = 2 * m->q, rpc = E * S, T = n * rpc;
+  const int d = c.d_model, dh = d / c.n_heads, dkv = c.n_kv_heads * dh, f = c.d_ffn, r = c.lora_rank;
+  const int nqkv = d + 2 * dkv;
+  const bool rope = c.pos == MPZ_POS_ROPE, swiglu = c.act == MPZ_ACT_SWIGLU;
+
+  for (int l = l0; l < l1; ++l) {
+    const mpz_layer_weights& lw = m->layers[l];
+    launch_norm(st, c.dtype, c.norm, c.norm_eps, b.h, d, lw.ln1_g, lw.ln1_b, b.x, T, d);
+
+    run_qkv(m, b, l, E, S, rope ? 2 : 0, rope ? b.stage : b.qkv);
     if (rope) launch_rope_convert(st, c.dtype, b.stage, b.qkv, T, S, nqkv, dh, c.n_heads + c.n_kv_heads, b.rope_cos, b.rope_sin);
 
-    launch_attention_simple(st, c.dtype, b.qkv, nqkv, b.attn, n * E, S, c.n_heads, c.n_kv_heads, dh);
+    if (m->use_mfma && attention_mfma_supported(dh, nqkv, d))
+      launch_attention_mfma(st, b.qkv, nqkv, b.attn, n * E, S, c.n_heads, c.n_kv_heads, dh);
+    else
+      launch_attention_simple(st, c.dtype, b.qkv, nqkv, b.attn, n * E, S, c.n_heads, c.n_kv_heads, dh);
 
     // output projection (+ adapter) added to the residual stream
+    const char* packed_l = (const char*)b.packed + (size_t)l * m->packed_per_layer * 2;
+    LoraDownArgs da{};
+    da.dtype = c.dtype; da.T = T; da.K = d; da.rank = r; da.rows_per_copy = rpc; da.scale = c.lora_scale;
+    da.copy_stride = m->P; da.t = b.t;
     LinearArgs oa{};
     oa.dtype = c.dtype; oa.M = T; oa.N = d; oa.K = d; oa.x = b.attn; oa.w = lw.w_o; oa.bias = lw.b_o;
     oa.rank = r; oa.rows_per_copy = rpc; oa.act = -1; oa.residual = b.h; oa.out_kind = 1; oa.out = b.h;
@@ -612,6 +632,30 @@ mpz_status mpz_debug_perturbed_copy(mpz_model* m, int32_t c, float* out) {
   hipError_t e = hipMemcpyAsync(out, m->buf.pert + (int64_t)c * m->P, (size_t)m->P * 4, hipMemcpyDeviceToDevice, m->stream);
   if (e != hipSuccess) return fail(m, MPZ_ERR_DEVICE, hipGetErrorString(e));
   return MPZ_OK;
+}
+
+mpz_status mpz_debug_qkv_projection(mpz_model* m, const void* x, int32_t layer, int32_t E, int32_t S, float* out) {
+  if (!m || !x || !out) return fail(m, MPZ_ERR_NULL, "mpz_debug_qkv_projection: NULL argument");
+  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_debug_qkv_projection before mpz_regen_noise");
+  if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
+  if (layer < 0 || layer >= m->cfg.n_layers) return fail(m, MPZ_ERR_SHAPE, "layer outside the model");
+  if (m->cfg.dtype != MPZ_DTYPE_BF16) return fail(m, MPZ_ERR_CONFIG, "mpz_debug_qkv_projection is for bf16 models");
+  Buffers b = m->buf;
+  b.x = const_cast<void*>(x);
+  run_qkv(m, b, layer, E, S, 1, out);
+  return check_device(m, "mpz_debug_qkv_projection");
+}
+
+mpz_status mpz_debug_attention(mpz_model* m, const void* qkv, int32_t n_seq, int32_t S, void* out) {
+  if (!m || !qkv || !out) return fail(m, MPZ_ERR_NULL, "mpz_debug_attention: NULL argument");
+  if (n_seq < 1 || S < 2) return fail(m, MPZ_ERR_SHAPE, "n_seq < 1 or S < 2");
+  const mpz_config& c = m->cfg;
+  const int d = c.d_model, dh = d / c.n_heads, nqkv = d + 2 * c.n_kv_heads * dh;
+  if (m->use_mfma && attention_mfma_supported(dh, nqkv, d))
+    launch_attention_mfma(m->stream, qkv, nqkv, out, n_seq, S, c.n_heads, c.n_kv_heads, dh);
+  else
+    launch_attention_simple(m->stream, c.dtype, qkv, nqkv, out, n_seq, S, c.n_heads, c.n_kv_heads, dh);
+  return check_device(m, "mpz_debug_attention");
 }
 
 mpz_status mpz_debug_set_kernel_path(mpz_model* m, int32_t simple_only) {

@@ -93,6 +93,10 @@ def load_library() -> C.CDLL:
     lib.mpz_debug_run_layers.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.mpz_debug_head_loss.restype = C.c_int
     lib.mpz_debug_head_loss.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    lib.mpz_debug_qkv_projection.restype = C.c_int
+    lib.mpz_debug_qkv_projection.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+    lib.mpz_debug_attention.restype = C.c_int
+    lib.mpz_debug_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
     lib.mpz_debug_set_kernel_path.restype = C.c_int
     lib.mpz_debug_set_kernel_path.argtypes = [C.c_void_p, C.c_int32]
     lib.mpz_profile_gemm_begin.restype = C.c_int
@@ -183,6 +187,14 @@ def mpz_debug_run_layers(handle, h_ptr: int, layer_begin: int, layer_end: int, E
 
 def mpz_debug_head_loss(handle, h_ptr: int, tokens_ptr: int, labels_ptr: Optional[int], E: int, S: int, losses_ptr: int):
     _check(load_library().mpz_debug_head_loss(handle, h_ptr, tokens_ptr, labels_ptr, E, S, losses_ptr), handle)
+
+
+def mpz_debug_qkv_projection(handle, x_ptr: int, layer: int, E: int, S: int, out_ptr: int):
+    _check(load_library().mpz_debug_qkv_projection(handle, x_ptr, layer, E, S, out_ptr), handle)
+
+
+def mpz_debug_attention(handle, qkv_ptr: int, n_seq: int, S: int, out_ptr: int):
+    _check(load_library().mpz_debug_attention(handle, qkv_ptr, n_seq, S, out_ptr), handle)
 
 
 def mpz_debug_set_kernel_path(handle, simple_only: bool):
