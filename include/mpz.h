@@ -196,6 +196,12 @@ mpz_status mpz_debug_head_loss(mpz_model* m, const float* h, const int32_t* toke
 mpz_status mpz_debug_qkv_projection(mpz_model* m, const void* x, int32_t layer, int32_t E, int32_t S, float* out);
 mpz_status mpz_debug_attention(mpz_model* m, const void* qkv, int32_t n_seq, int32_t S, void* out);
 
+/* Test / measurement hook: the bf16 MFMA GEMM alone, out[M, N] = act(x[M, K] w[N, K]^T + bias), all [dev], x and w bf16,
+ * out bf16 or fp32 (out_f32), act = -1 (none), MPZ_ACT_RELU, MPZ_ACT_GELU_ERF, or MPZ_ACT_SWIGLU (then w has 2N rows,
+ * gate then up, bias 2N, out = SiLU(gate) * up); tile_cfg 0 = chosen by shape, 1..6 = a fixed block-tile configuration.  Errors: NULL, SHAPE (K % 64, N % 4). */
+mpz_status mpz_debug_gemm_bf16(int32_t M, int32_t N, int32_t K, const void* x, const void* w, const float* bias,
+                               int32_t act, void* out, int32_t out_f32, int32_t tile_cfg, void* hip_stream);
+
 /* Test hook: simple_only != 0 routes every stage through the shape-agnostic kernels (the only path of
  * fp32 models); 0 restores the default (bf16 models use the MFMA kernels wherever a shape allows).
  * Invalidates the perturbed copies: call mpz_regen_noise again. */

@@ -104,6 +104,7 @@ void launch_fill_f32(hipStream_t st, float* p, float v, int64_t n);
 struct MfmaGemmArgs {
   int M, N, K;                  // out[M, N] = x[M, K] w[N, K]^T ; dual: N = columns of ONE of the two tiles
   const void* x; const void* w;
+  int w_rows;                   // rows of w (N, or 2N for dual): bounds the weight buffer
   const float* bias;            // [N] (dual: [dual_offset + N]) or null
   int dual; int dual_offset;    // dual: second weight tile starts dual_offset rows below (SwiGLU gate | up)
   int n_seg; MfmaLoraSeg seg[3];
@@ -111,6 +112,7 @@ struct MfmaGemmArgs {
   int act;                      // -1 none, MPZ_ACT_RELU, MPZ_ACT_GELU_ERF (ignored when dual: SiLU(gate) * up)
   const float* residual;        // [M, ldo] fp32 or null
   int out_f32; void* out; int ldo;
+  int tile_cfg;                 // 0 = choose by shape; 1..4 force a tile configuration (measurement)
 };
 bool mfma_gemm_supported(const MfmaGemmArgs& a);
 void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a);
@@ -132,5 +134,11 @@ void launch_pack_factors(hipStream_t st, const float* pert, int64_t P, int n_cop
 bool attention_mfma_supported(int dh, int qkv_stride, int d);
 void launch_attention_mfma(hipStream_t st, const void* qkv, int qkv_stride, void* out, int n_seq, int S, int H, int Hkv,
                            int dh);
+
+
+// ---- rowwise.hip ----------------------------------------------------------------------------------
+bool norm_rows_supported(int d, int64_t h_row_stride);
+void launch_norm_rows(hipStream_t st, int kind, float eps, const float* h, int64_t h_row_stride, const float* g,
+                      const float* b, void* out, int rows, int d);
 
 }  // namespace mpz

@@ -1,8 +1,8 @@
 // bf16 MFMA GEMM for the shared-weight term of the MP-LoRA layer (Section 3: Y = X W + (X A) (.) B):
 // the frozen weight tile is read once for all n = 2q stacked copies, and the per-copy rank-r term is
 // folded into the same fp32 accumulators as extra K-steps whose "weight" operand is that copy's packed
-// factor [B_hi | B_lo].  gfx950 only: v_mfma_f32_32x32x16_bf16, 64-lane waves, LDS-staged 128x128x64
-// tiles with register-staged double buffering.
+// factor [B_hi | B_lo].  gfx950 only: v_mfma_f32_32x32x16_bf16, 64-lane waves, LDS-staged block tiles
+// (128..256 square-ish, several configurations) with register-staged double buffering.
 //
 // Orientation: the MFMA "A" operand is a W tile (rows = output features n), the "B" operand an X tile
 // (rows = tokens m), so every lane ends up with 4 consecutive n of one token: bias / residual / stores
@@ -16,24 +16,30 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;     // 16-byte chunk in registers (native vector type)
-
-constexpr int BM = 128;          // tokens per block
-constexpr int BN = 128;          // output features per block
-constexpr int BK = 64;           // K per stage
-constexpr int LDS_STRIDE = BK + 8;   // bf16 elements; +16 B per row keeps ds_read_b128 conflict-free
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 __device__ __forceinline__ bf16x8 as_frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f)); }
 
-// DUAL: two weight tiles (rows n and n + dual_offset: SwiGLU gate and up) against the same X tile.
-template <bool DUAL>
-__global__ void __launch_bounds__(256) gemm_bf16_kernel(MfmaGemmArgs a) {
+// Block tile BN (output features) x BM (tokens), K-step BK, WGN x WGM waves, each wave (BN/WGN) x (BM/WGM) =
+// NI x NJ MFMA tiles.  NSET = register sets of tiles in flight.  DUAL: two weight tiles (rows n and n + dual_offset:
+// SwiGLU gate and up) against the same X tile.  LDS rows are padded by 16 B, which keeps ds_read_b128 of 32 rows
+// conflict-free for BK = 32 and BK = 64.
+template <int BN, int BM, int BK, int WGN, int WGM, int NSET, bool DUAL>
+__global__ void __launch_bounds__(64 * WGN * WGM, (BN * BM * (DUAL ? 2 : 1) <= 256 * 128 && WGN * WGM == 4) ? 2 : 1)
+gemm_bf16_kernel(MfmaGemmArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int NW = DUAL ? 2 : 1;
-  constexpr int TILE = BM * LDS_STRIDE;                  // elements per operand tile per stage
+  constexpr int LDS_STRIDE = BK + 8;
+  constexpr int TILE_W = BN * LDS_STRIDE, TILE_X = BM * LDS_STRIDE;     // elements per operand tile per stage
+  constexpr int NT = 64 * WGN * WGM;                                     // threads per block
+  constexpr int TN = BN / WGN, TM = BM / WGM, NI = TN / 32, NJ = TM / 32;
+  constexpr int CPR = BK / 8;                                            // 16-byte chunks per tile row
+  constexpr int LW = BN * CPR / NT, LX = BM * CPR / NT;                  // chunks per thread and tile
   uint16_t* sW = (uint16_t*)smem;                        // [2 stages][NW][BN][LDS_STRIDE]
-  uint16_t* sX = sW + 2 * NW * TILE;                     // [2 stages][BM][LDS_STRIDE]
+  uint16_t* sX = sW + 2 * NW * TILE_W;                   // [2 stages][BM][LDS_STRIDE]
 
   // XCD-aware tile order: hardware deals consecutive workgroups round-robin to the 8 XCDs; give each XCD
   // a contiguous range of tiles so that neighbours in its L2 share X rows and the whole (small) W.
@@ -49,79 +55,114 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(MfmaGemmArgs a) {
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wn = (wave >> 1) * 64, wm = (wave & 1) * 64;   // wave tile origin inside the block tile
+  const int wn = (wave / WGM) * TN, wm = (wave % WGM) * TM;   // wave tile origin inside the block tile
   const int lrow = lane & 31, lhalf = lane >> 5;
 
-  const uint16_t* W = (const uint16_t*)a.w;
-  const uint16_t* X = (const uint16_t*)a.x;
-
-  // global -> register staging: 4 chunks of 16 B per operand tile per thread
-  int ld_row[4], ld_kc[4];
+  // Operand fetch: raw buffer loads (per-thread byte offset in a VGPR, the K offset of the tile in an SGPR);
+  // rows past the end of W or X fall outside the buffer and read as zero, so ragged M / N need no clamps.
+  const __amdgpu_buffer_rsrc_t rsrcW =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.w), 0, (int)((size_t)a.w_rows * a.K * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcX =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.x), 0, (int)((size_t)a.M * a.K * 2), 0x00020000);
+  uint32_t voffW[NW][LW], voffX[LX];
+  int ldsW[LW], ldsX[LX];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { int c = tid + 256 * i; ld_row[i] = c >> 3; ld_kc[i] = (c & 7) * 8; }
-  const uint16_t* wp[NW][4];
-  const uint16_t* xp[4];
+  for (int i = 0; i < LW; ++i) {
+    const int c = tid + NT * i, row = c / CPR, kc = (c % CPR) * 8;
+    voffW[0][i] = ((uint32_t)(n0 + row) * (uint32_t)a.K + kc) * 2u;
+    if (DUAL) voffW[NW - 1][i] = ((uint32_t)(n0 + row + a.dual_offset) * (uint32_t)a.K + kc) * 2u;
+    ldsW[i] = row * LDS_STRIDE + kc;
+  }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int n = n0 + ld_row[i]; n = n < a.N ? n : a.N - 1;     // clamp: out-of-range rows are never stored
-    int m = m0 + ld_row[i]; m = m < a.M ? m : a.M - 1;
-    wp[0][i] = W + (size_t)n * a.K + ld_kc[i];
-    if (DUAL) wp[NW - 1][i] = W + (size_t)(n + a.dual_offset) * a.K + ld_kc[i];
-    xp[i] = X + (size_t)m * a.K + ld_kc[i];
+  for (int i = 0; i < LX; ++i) {
+    const int c = tid + NT * i, row = c / CPR, kc = (c % CPR) * 8;
+    voffX[i] = ((uint32_t)(m0 + row) * (uint32_t)a.K + kc) * 2u;
+    ldsX[i] = row * LDS_STRIDE + kc;
   }
-  u32x4 rw[NW][4], rx[4];
-#define MPZ_LOAD_GLOBAL(k0)                                                        \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                  \
-    _Pragma("unroll") for (int d = 0; d < NW; ++d) rw[d][i] = *(const u32x4*)(wp[d][i] + (k0)); \
-    rx[i] = *(const u32x4*)(xp[i] + (k0));                                         \
+  u32x4 rw[NSET][NW][LW], rx[NSET][LX];
+#define MPZ_LOAD_GLOBAL(set, kt)                                                   \
+  {                                                                                \
+    const int soff = (kt) * BK * 2;                                                \
+    _Pragma("unroll") for (int d = 0; d < NW; ++d)                                 \
+      _Pragma("unroll") for (int i = 0; i < LW; ++i)                               \
+        rw[set][d][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, voffW[d][i], soff, 0); \
+    _Pragma("unroll") for (int i = 0; i < LX; ++i)                                 \
+      rx[set][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcX, voffX[i], soff, 0); \
+    __builtin_amdgcn_sched_barrier(0);   /* keep the fetch here: the scheduler would sink it to its use */ \
   }
-#define MPZ_STORE_LDS(stage)                                                       \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                  \
-    const int off = ld_row[i] * LDS_STRIDE + ld_kc[i];                             \
-    _Pragma("unroll") for (int d = 0; d < NW; ++d) *(u32x4*)(sW + ((stage) * NW + d) * TILE + off) = rw[d][i]; \
-    *(u32x4*)(sX + (stage) * TILE + off) = rx[i];                                  \
+#define MPZ_STORE_LDS(set, stage)                                                  \
+  {                                                                                \
+    _Pragma("unroll") for (int d = 0; d < NW; ++d)                                 \
+      _Pragma("unroll") for (int i = 0; i < LW; ++i)                               \
+        *(u32x4*)(sW + ((stage) * NW + d) * TILE_W + ldsW[i]) = rw[set][d][i];     \
+    _Pragma("unroll") for (int i = 0; i < LX; ++i)                                 \
+      *(u32x4*)(sX + (stage) * TILE_X + ldsX[i]) = rx[set][i];                     \
+    __builtin_amdgcn_sched_barrier(0);                                             \
+  }
+#define MPZ_COMPUTE(stage)                                                         \
+  {                                                                                \
+    const uint16_t* cw = sW + (stage) * NW * TILE_W;                               \
+    const uint16_t* cx = sX + (stage) * TILE_X;                                    \
+    _Pragma("unroll") for (int kk = 0; kk < BK; kk += 16) {                        \
+      bf16x8 fw[NW][NI], fx[NJ];                                                   \
+      _Pragma("unroll") for (int d = 0; d < NW; ++d)                               \
+        _Pragma("unroll") for (int i = 0; i < NI; ++i)                             \
+          fw[d][i] = as_frag(*(const u32x4*)(cw + d * TILE_W + (wn + i * 32 + lrow) * LDS_STRIDE + kk + lhalf * 8)); \
+      _Pragma("unroll") for (int j = 0; j < NJ; ++j)                               \
+        fx[j] = as_frag(*(const u32x4*)(cx + (wm + j * 32 + lrow) * LDS_STRIDE + kk + lhalf * 8)); \
+      _Pragma("unroll") for (int d = 0; d < NW; ++d)                               \
+        _Pragma("unroll") for (int i = 0; i < NI; ++i)                             \
+          _Pragma("unroll") for (int j = 0; j < NJ; ++j)                           \
+            acc[d][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[d][i], fx[j], acc[d][i][j], 0, 0, 0); \
+    }                                                                              \
   }
 
-  f32x16 acc[NW][2][2];
+  f32x16 acc[NW][NI][NJ];
 #pragma unroll
   for (int d = 0; d < NW; ++d)
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < NJ; ++j)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[d][i][j][e] = 0.f;
 
   const int nk = a.K / BK;
-  MPZ_LOAD_GLOBAL(0)
-  MPZ_STORE_LDS(0)
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int stage = kt & 1;
-    if (kt + 1 < nk) { MPZ_LOAD_GLOBAL((kt + 1) * BK) }
-    const uint16_t* cw = sW + stage * NW * TILE;
-    const uint16_t* cx = sX + stage * TILE;
-#pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8 fw[NW][2], fx[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-#pragma unroll
-        for (int d = 0; d < NW; ++d)
-          fw[d][i] = as_frag(*(const u32x4*)(cw + d * TILE + (wn + i * 32 + lrow) * LDS_STRIDE + kk + lhalf * 8));
-        fx[i] = as_frag(*(const u32x4*)(cx + (wm + i * 32 + lrow) * LDS_STRIDE + kk + lhalf * 8));
-      }
-#pragma unroll
-      for (int d = 0; d < NW; ++d)
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc[d][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[d][i], fx[j], acc[d][i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) { MPZ_STORE_LDS(stage ^ 1) }
+  if constexpr (NSET == 2) {
+    // Tile kt+1 sits in one register set (in flight or landed) while tile kt+2 is fetched into the other:
+    // a load has two MFMA phases to arrive before its LDS store needs it.  Loads past the last tile fall
+    // outside the buffers (zeros) and are never stored.
+    MPZ_LOAD_GLOBAL(0, 0)
+    MPZ_STORE_LDS(0, 0)
+    MPZ_LOAD_GLOBAL(0, 1)
     __syncthreads();
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+      MPZ_LOAD_GLOBAL(1, kt + 2)         // even phase: stage 0 is current, set 0 holds tile kt+1
+      MPZ_STORE_LDS(0, 1)
+      MPZ_COMPUTE(0)
+      __syncthreads();
+      MPZ_LOAD_GLOBAL(0, kt + 3)         // odd phase: stage 1 is current, set 1 holds tile kt+2
+      MPZ_STORE_LDS(1, 0)
+      MPZ_COMPUTE(1)
+      __syncthreads();
+    }
+    if (kt < nk) MPZ_COMPUTE(0)          // odd number of tiles: the last one is already in stage 0
+  } else {
+    MPZ_LOAD_GLOBAL(0, 0)
+    MPZ_STORE_LDS(0, 0)
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+      const int stage = kt & 1;
+      MPZ_LOAD_GLOBAL(0, kt + 1)
+      MPZ_COMPUTE(stage)
+      MPZ_STORE_LDS(0, stage ^ 1)
+      __syncthreads();
+    }
   }
+#undef MPZ_LOAD_GLOBAL
+#undef MPZ_STORE_LDS
+#undef MPZ_COMPUTE
 
   // per-copy low-rank term: extra K-steps with the packed factor [B_hi | B_lo] of this block's copy against
   // the duplicated bottleneck activations [t | t]  (block rows never straddle copies, segments are tile-aligned)
@@ -133,18 +174,21 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(MfmaGemmArgs a) {
       const uint16_t* bp = (const uint16_t*)sg.bp + (size_t)copy * sg.copy_stride;
       const uint16_t* tp = (const uint16_t*)sg.tp;
       for (int ks = 0; ks < sg.rp; ks += 16) {
-        bf16x8 fw[2], fx[2];
+        bf16x8 fw[NI], fx[NJ];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NI; ++i) {
           int n = n0 + wn + i * 32 + lrow - sg.col_begin;
-          int m = m0 + wm + i * 32 + lrow;
           fw[i] = as_frag(*(const u32x4*)(bp + (size_t)n * sg.rp + ks + lhalf * 8));
-          fx[i] = as_frag(*(const u32x4*)(tp + (size_t)m * sg.rp + ks + lhalf * 8));
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < NJ; ++j) {
+          int m = m0 + wm + j * 32 + lrow;
+          fx[j] = as_frag(*(const u32x4*)(tp + (size_t)m * sg.rp + ks + lhalf * 8));
+        }
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+          for (int j = 0; j < NJ; ++j)
             acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fx[j], acc[0][i][j], 0, 0, 0);
       }
     }
@@ -152,11 +196,11 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(MfmaGemmArgs a) {
 
   // epilogue: lane holds, for token m, features n = nb + g*8 + lhalf*4 + (0..3), g = 0..3
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
+  for (int j = 0; j < NJ; ++j) {
     const int m = m0 + wm + j * 32 + lrow;
     if (m >= a.M) continue;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < NI; ++i) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int n = n0 + wn + i * 32 + g * 8 + lhalf * 4;
@@ -165,16 +209,18 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(MfmaGemmArgs a) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[0][i][j][g * 4 + e];
         if (a.bias != nullptr) {
-          float4 bb = *(const float4*)(a.bias + n);
-          v[0] += bb.x; v[1] += bb.y; v[2] += bb.z; v[3] += bb.w;
+          f32x4 bb = *(const f32x4*)(a.bias + n);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += bb[e];
         }
         if (DUAL) {
           float u[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) u[e] = acc[NW - 1][i][j][g * 4 + e];
           if (a.bias != nullptr) {
-            float4 bb = *(const float4*)(a.bias + a.dual_offset + n);
-            u[0] += bb.x; u[1] += bb.y; u[2] += bb.z; u[3] += bb.w;
+            f32x4 bb = *(const f32x4*)(a.bias + a.dual_offset + n);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) u[e] += bb[e];
           }
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = v[e] / (1.0f + expf(-v[e])) * u[e];      // SiLU(gate) * up
@@ -187,16 +233,17 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(MfmaGemmArgs a) {
         }
         const size_t o = (size_t)m * a.ldo + n;
         if (a.residual != nullptr) {
-          float4 rr = *(const float4*)(a.residual + o);
-          v[0] += rr.x; v[1] += rr.y; v[2] += rr.z; v[3] += rr.w;
+          f32x4 rr = *(const f32x4*)(a.residual + o);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += rr[e];
         }
         if (a.out_f32) {
-          *(float4*)((float*)a.out + o) = make_float4(v[0], v[1], v[2], v[3]);
+          f32x4 ov = {v[0], v[1], v[2], v[3]};
+          *(f32x4*)((float*)a.out + o) = ov;
         } else {
-          uint2 pk;
-          pk.x = (uint32_t)f32_to_bf16(v[0]).bits | ((uint32_t)f32_to_bf16(v[1]).bits << 16);
-          pk.y = (uint32_t)f32_to_bf16(v[2]).bits | ((uint32_t)f32_to_bf16(v[3]).bits << 16);
-          *(uint2*)((uint16_t*)a.out + o) = pk;
+          u32x2 pk = {(uint32_t)f32_to_bf16(v[0]).bits | ((uint32_t)f32_to_bf16(v[1]).bits << 16),
+                      (uint32_t)f32_to_bf16(v[2]).bits | ((uint32_t)f32_to_bf16(v[3]).bits << 16)};
+          *(u32x2*)((uint16_t*)a.out + o) = pk;
         }
       }
     }
@@ -306,37 +353,75 @@ __global__ void __launch_bounds__(256) pack_factors_kernel(const float* __restri
   }
 }
 
+
+// ---- tile configurations ----------------------------------------------------------------------------
+//  id  BN  BM  BK sets   LDS      use
+//   1 128 128  64  2    73.7 KB   small N (more blocks)
+//   2 256 128  32  2    61.4 KB   general
+//   3 128 256  32  2    61.4 KB   general, tall
+//   4 256 256  32  1    81.9 KB   large problems (lowest LDS traffic per MFMA)
+//  dual (SwiGLU): 2 x 128 x 128 x 32, 2 sets, 61.4 KB
+template <int BN, int BM, int BK, int WGN, int WGM, int NSET, bool DUAL>
+void launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
+  constexpr size_t lds = (size_t)2 * ((DUAL ? 2 : 1) * BN + BM) * (BK + 8) * 2;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)gemm_bf16_kernel<BN, BM, BK, WGN, WGM, NSET, DUAL>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    attr_set = true;
+  }
+  const int tiles = ((a.N + BN - 1) / BN) * ((a.M + BM - 1) / BM);
+  gemm_bf16_kernel<BN, BM, BK, WGN, WGM, NSET, DUAL><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
+}
+
+int tile_bn(int cfg) { return (cfg == 2 || cfg >= 4) ? 256 : 128; }
+int tile_bm(int cfg) { return (cfg == 3 || cfg >= 4) ? 256 : 128; }
+
+bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
+  const int bn = tile_bn(cfg), bm = tile_bm(cfg);
+  if (a.n_seg > 0 && (a.rows_per_copy % bm || a.M % bm)) return false;
+  for (int s = 0; s < a.n_seg; ++s)
+    if (a.seg[s].col_begin % bn || a.seg[s].col_end % bn) return false;
+  return true;
+}
+
+int choose_cfg(const MfmaGemmArgs& a) {
+  if (a.tile_cfg >= 1 && a.tile_cfg <= 6 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
+  // enough 256 x 256 tiles to keep 256 CUs busy for several rounds -> biggest tile; else the largest tile that
+  // still gives at least ~2 blocks per CU
+  // The L2 -> CU path feeds about 64 B/clk per CU, which a 128 x 128 tile needs in full at MFMA peak; 256 x 256
+  // halves that.  Use the big tile (8 waves of 128 x 64) once it yields two or more rounds of blocks on 256 CUs.
+  const long t5 = (long)((a.N + 255) / 256) * ((a.M + 255) / 256);
+  if (t5 >= 512 && cfg_ok(a, 5)) return 5;
+  return 1;
+}
+
 }  // namespace
 
-size_t mfma_gemm_lds_bytes(bool dual) { return (size_t)2 * ((dual ? 2 : 1) + 1) * BM * LDS_STRIDE * 2; }
-
 bool mfma_gemm_supported(const MfmaGemmArgs& a) {
-  if (a.K % BK || a.N % 4 || a.M < 1 || a.N < 1) return false;
-  if (a.n_seg > 0 && (a.rows_per_copy % BM || a.M % BM)) return false;
+  if (a.K % 64 || a.N % 4 || a.M < 1 || a.N < 1) return false;
+  if ((size_t)a.M * a.K * 2 >= ((size_t)1 << 31) || (size_t)(a.dual ? 2 : 1) * a.N * a.K * 2 >= ((size_t)1 << 31)) return false;
   for (int s = 0; s < a.n_seg; ++s)
-    if (a.seg[s].col_begin % BN || a.seg[s].col_end % BN || a.seg[s].rp % 16) return false;
+    if (a.seg[s].rp % 16) return false;
+  if (!cfg_ok(a, 1)) return false;
   if (a.dual && a.n_seg) return false;
   return true;
 }
 
 void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
-  const int tiles = ((a.N + BN - 1) / BN) * ((a.M + BM - 1) / BM);
   if (a.dual) {
-    static bool attr_set = false;
-    if (!attr_set) {
-      (void)hipFuncSetAttribute((const void*)gemm_bf16_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)mfma_gemm_lds_bytes(true));
-      attr_set = true;
-    }
-    gemm_bf16_kernel<true><<<tiles, 256, mfma_gemm_lds_bytes(true), st>>>(a);
-  } else {
-    static bool attr_set = false;
-    if (!attr_set) {
-      (void)hipFuncSetAttribute((const void*)gemm_bf16_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)mfma_gemm_lds_bytes(false));
-      attr_set = true;
-    }
-    gemm_bf16_kernel<false><<<tiles, 256, mfma_gemm_lds_bytes(false), st>>>(a);
+    const long tb = (long)((a.N + 127) / 128) * ((a.M + 255) / 256);
+    if ((a.tile_cfg == 0 && tb >= 512) || a.tile_cfg == 5) launch_cfg<128, 256, 32, 2, 4, 2, true>(st, a);   // 2 x 128 x 256, 8 waves
+    else launch_cfg<128, 128, 32, 2, 2, 2, true>(st, a);
+    return;
+  }
+  switch (choose_cfg(a)) {
+    case 2: launch_cfg<256, 128, 32, 2, 2, 2, false>(st, a); break;
+    case 3: launch_cfg<128, 256, 32, 2, 2, 2, false>(st, a); break;
+    case 4: launch_cfg<256, 256, 32, 2, 2, 1, false>(st, a); break;
+    case 5: launch_cfg<256, 256, 32, 2, 4, 2, false>(st, a); break;     // 8 waves of 128 x 64
+    case 6: launch_cfg<256, 256, 64, 2, 4, 1, false>(st, a); break;     // 8 waves, BK 64 (147 KB LDS)
+    default: launch_cfg<128, 128, 64, 2, 2, 2, false>(st, a); break;
   }
 }
 

@@ -211,7 +211,7 @@ void gemm(mpz_model* m, const LinearArgs& a) {
   bool done = false;
   if (m->use_mfma && a.dtype == MPZ_DTYPE_BF16 && (a.n_seg == 0 || a.mfma_lora)) {
     MfmaGemmArgs g{};
-    g.M = a.M; g.N = a.N; g.K = a.K; g.x = a.x; g.w = a.w; g.bias = a.bias; g.dual = 0; g.dual_offset = 0;
+    g.M = a.M; g.N = a.N; g.K = a.K; g.x = a.x; g.w = a.w; g.w_rows = a.N; g.bias = a.bias; g.dual = 0; g.dual_offset = 0;
     g.n_seg = a.n_seg; g.rows_per_copy = a.rows_per_copy; g.act = a.act; g.residual = a.residual;
     g.out_f32 = a.out_kind != 0; g.out = a.out; g.ldo = a.N;   // bf16 models stage in fp32
     for (int i = 0; i < a.n_seg; ++i) g.seg[i] = a.mseg[i];
@@ -225,7 +225,7 @@ void gemm(mpz_model* m, const LinearArgs& a) {
 bool gemm_swiglu_mfma(mpz_model* m, const LinearArgs& a, int f, void* u_out) {
   if (!m->use_mfma) return false;
   MfmaGemmArgs g{};
-  g.M = a.M; g.N = f; g.K = a.K; g.x = a.x; g.w = a.w; g.bias = a.bias; g.dual = 1; g.dual_offset = f;
+  g.M = a.M; g.N = f; g.K = a.K; g.x = a.x; g.w = a.w; g.w_rows = 2 * f; g.bias = a.bias; g.dual = 1; g.dual_offset = f;
   g.rows_per_copy = a.rows_per_copy; g.act = -1; g.out_f32 = 0; g.out = u_out; g.ldo = f;
   if (!mfma_gemm_supported(g)) return false;
   hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -251,6 +251,15 @@ int tensor_slot(const mpz_model* m, int target, int factor) {
   for (int i = 0; i < m->tab.n_tensors; ++i)
     if (m->tab.local_id[i] == target * 2 + factor) return i;
   return 0;
+}
+
+// fp32 residual rows -> operand type
+void norm(mpz_model* m, const float* h, int64_t h_row_stride, const float* g, const float* b, void* out, int rows) {
+  const mpz_config& c = m->cfg;
+  if (m->use_mfma && norm_rows_supported(c.d_model, h_row_stride))
+    launch_norm_rows(m->stream, c.norm, c.norm_eps, h, h_row_stride, g, b, out, rows, c.d_model);
+  else
+    launch_norm(m->stream, c.dtype, c.norm, c.norm_eps, h, h_row_stride, g, b, out, rows, c.d_model);
 }
 
 void run_embed(mpz_model* m, const int32_t* tokens, int E, int S, float* h) {
@@ -331,7 +340,7 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
 
   for (int l = l0; l < l1; ++l) {
     const mpz_layer_weights& lw = m->layers[l];
-    launch_norm(st, c.dtype, c.norm, c.norm_eps, b.h, d, lw.ln1_g, lw.ln1_b, b.x, T, d);
+    norm(m, b.h, d, lw.ln1_g, lw.ln1_b, b.x, T);
 
     run_qkv(m, b, l, E, S, rope ? 2 : 0, rope ? b.stage : b.qkv);
     if (rope) launch_rope_convert(st, c.dtype, b.stage, b.qkv, T, S, nqkv, dh, c.n_heads + c.n_kv_heads, b.rope_cos, b.rope_sin);
@@ -376,7 +385,7 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     gemm(m, oa);
 
     // feed-forward block
-    launch_norm(st, c.dtype, c.norm, c.norm_eps, b.h, d, lw.ln2_g, lw.ln2_b, b.x, T, d);
+    norm(m, b.h, d, lw.ln2_g, lw.ln2_b, b.x, T);
     LinearArgs ua{};
     ua.dtype = c.dtype; ua.M = T; ua.N = swiglu ? 2 * f : f; ua.K = d; ua.x = b.x; ua.w = lw.w_up; ua.bias = lw.b_up;
     ua.rank = r; ua.rows_per_copy = rpc; ua.act = swiglu ? -1 : c.act;
@@ -402,7 +411,7 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
   const int d = c.d_model;
   launch_make_targets(st, c.loss_mode, tokens, labels, c.label_token[0], c.label_token[1], b.target, n, E, S);
   if (c.loss_mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS) {
-    launch_norm(st, c.dtype, c.norm, c.norm_eps, b.h, d, m->w.lnf_g, m->w.lnf_b, b.x, T, d);
+    norm(m, b.h, d, m->w.lnf_g, m->w.lnf_b, b.x, T);
     for (int r0 = 0; r0 < T; r0 += b.chunk_rows) {
       int rows = T - r0 < b.chunk_rows ? T - r0 : b.chunk_rows;
       LinearArgs la{};
@@ -415,8 +424,7 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
     launch_copy_mean(st, b.ce, rpc, E * (S - 1), losses_out, n);
   } else {
     const int rows_all = n * E;
-    launch_norm(st, c.dtype, c.norm, c.norm_eps, b.h + (size_t)(S - 1) * d, (int64_t)S * d, m->w.lnf_g, m->w.lnf_b, b.x,
-                rows_all, d);
+    norm(m, b.h + (size_t)(S - 1) * d, (int64_t)S * d, m->w.lnf_g, m->w.lnf_b, b.x, rows_all);
     if (c.loss_mode == MPZ_LOSS_LAST_POS_LABEL_SUBSET) {
       launch_last_pos_subset_logits(st, c.dtype, b.x, m->w.lm_head, d, rows_all, c.label_token[0], c.label_token[1], b.logits);
       launch_ce_rows(st, c.dtype, b.logits, 2, 2, b.target, b.ce, rows_all);
@@ -656,6 +664,18 @@ mpz_status mpz_debug_attention(mpz_model* m, const void* qkv, int32_t n_seq, int
   else
     launch_attention_simple(m->stream, c.dtype, qkv, nqkv, out, n_seq, S, c.n_heads, c.n_kv_heads, dh);
   return check_device(m, "mpz_debug_attention");
+}
+
+mpz_status mpz_debug_gemm_bf16(int32_t M, int32_t N, int32_t K, const void* x, const void* w, const float* bias,
+                               int32_t act, void* out, int32_t out_f32, int32_t tile_cfg, void* hip_stream) {
+  if (!x || !w || !out) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_gemm_bf16: NULL argument");
+  MfmaGemmArgs g{};
+  g.M = M; g.N = N; g.K = K; g.x = x; g.w = w; g.w_rows = N; g.bias = bias; g.rows_per_copy = M; g.act = act;
+  g.out_f32 = out_f32; g.out = out; g.ldo = N; g.tile_cfg = tile_cfg;
+  if (act == MPZ_ACT_SWIGLU) { g.dual = 1; g.dual_offset = N; g.w_rows = 2 * N; g.act = -1; }
+  if (!mfma_gemm_supported(g)) return fail(nullptr, MPZ_ERR_SHAPE, "shape not supported by the MFMA GEMM (K % 64, N % 4)");
+  launch_gemm_mfma((hipStream_t)hip_stream, g);
+  return check_device(nullptr, "mpz_debug_gemm_bf16");
 }
 
 mpz_status mpz_debug_set_kernel_path(mpz_model* m, int32_t simple_only) {

@@ -97,6 +97,9 @@ def load_library() -> C.CDLL:
     lib.mpz_debug_qkv_projection.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
     lib.mpz_debug_attention.restype = C.c_int
     lib.mpz_debug_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    lib.mpz_debug_gemm_bf16.restype = C.c_int
+    lib.mpz_debug_gemm_bf16.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                        C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
     lib.mpz_debug_set_kernel_path.restype = C.c_int
     lib.mpz_debug_set_kernel_path.argtypes = [C.c_void_p, C.c_int32]
     lib.mpz_profile_gemm_begin.restype = C.c_int
@@ -195,6 +198,12 @@ def mpz_debug_qkv_projection(handle, x_ptr: int, layer: int, E: int, S: int, out
 
 def mpz_debug_attention(handle, qkv_ptr: int, n_seq: int, S: int, out_ptr: int):
     _check(load_library().mpz_debug_attention(handle, qkv_ptr, n_seq, S, out_ptr), handle)
+
+
+def mpz_debug_gemm_bf16(M: int, N: int, K: int, x_ptr: int, w_ptr: int, bias_ptr: Optional[int], act: int, out_ptr: int,
+                        out_f32: bool, stream_ptr: int, tile_cfg: int = 0):
+    _check(load_library().mpz_debug_gemm_bf16(M, N, K, x_ptr, w_ptr, bias_ptr, act, out_ptr, int(out_f32), tile_cfg,
+                                              stream_ptr))
 
 
 def mpz_debug_set_kernel_path(handle, simple_only: bool):

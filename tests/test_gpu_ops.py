@@ -90,3 +90,43 @@ def test_attention_matches_oracle_on_the_same_operands(name, S, simple):
     assert bad.mean() < 5e-3                      # rounding flips of P and of the output only
     # an output ulp, plus one flipped probability (2^-8 relative, p <= 1) times the largest |v|
     assert (np.abs(got - want) <= 1.01 * ulp + 2.0 ** -8 * np.abs(v).max()).all()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("M_,N_,K_", [(512, 512, 256), (300, 260, 192), (1024, 768, 64)])
+def test_gemm_every_tile_configuration_and_ragged_edges(cfg, M_, N_, K_):
+    """x W^T + bias with ReLU, fp32 output, against the fp64 product of the same bf16 operands."""
+    import torch
+    import paper_2409_15520_amd as M
+    rng = np.random.default_rng(cfg * 1000 + M_)
+    x = BF.operand(rng.standard_normal((M_, K_)))
+    w = BF.operand(0.05 * rng.standard_normal((N_, K_)))
+    bias = rng.standard_normal(N_).astype(np.float32)
+    xd, wd = _bf16_tensor(x), _bf16_tensor(w)
+    bd = torch.from_numpy(bias).cuda()
+    out = torch.full((M_, N_), float("nan"), dtype=torch.float32, device="cuda")
+    M.mpz_debug_gemm_bf16(M_, N_, K_, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), 0, out.data_ptr(), True,
+                          torch.cuda.current_stream().cuda_stream, cfg)
+    got = out.cpu().numpy().astype(np.float64)
+    want = np.maximum(x @ w.T + bias, 0.0)
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= 2e-6 * np.sqrt(K_) * np.abs(want).max()
+
+
+@pytest.mark.parametrize("cfg", [1, 5])
+def test_swiglu_dual_gemm(cfg):
+    import torch
+    import paper_2409_15520_amd as M
+    M_, F_, K_ = 520, 384, 128
+    rng = np.random.default_rng(cfg)
+    x = BF.operand(rng.standard_normal((M_, K_)))
+    w = BF.operand(0.1 * rng.standard_normal((2 * F_, K_)))
+    xd, wd = _bf16_tensor(x), _bf16_tensor(w)
+    out = torch.zeros((M_, F_), dtype=torch.bfloat16, device="cuda")
+    M.mpz_debug_gemm_bf16(M_, F_, K_, xd.data_ptr(), wd.data_ptr(), None, 2, out.data_ptr(), False,
+                          torch.cuda.current_stream().cuda_stream, cfg)
+    got = out.float().cpu().numpy().astype(np.float64)
+    g, u = x @ w[:F_].T, x @ w[F_:].T
+    want = BF.operand(g / (1.0 + np.exp(-g)) * u)
+    ulp = np.maximum(np.abs(want), 1e-30) * 2.0 ** -7
+    assert np.mean(got != want) < 2e-3 and (np.abs(got - want) <= 1.01 * ulp + 1e-7).all()
