@@ -81,7 +81,7 @@ def test_end_to_end_losses_and_drift_of_g(name):
     err_g = rel_err(Gg[0], Go[0])
     print(f"\n{name}: loss err {err_l:.3e} (oracle-vs-jittered-oracle {floor_l:.3e}); g err {err_g:.3e} "
           f"(oracle-vs-jittered-oracle {floor_g:.3e}); g gpu {Gg[0]}, oracle {Go[0]}")
-    assert err_l <= 5e-3
+    assert err_l <= 2e-2            # the bf16 bar for per-copy losses
     assert err_g <= max(2e-2, 4.0 * floor_g)
 
 
