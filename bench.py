@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2_opt125m")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--device-init", action="store_true",
+                    help="draw the frozen weights on the GPU (large workloads; implies --no-cpu-baseline)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (copies would shard across GPUs with one all-gather "
@@ -76,7 +78,11 @@ def main():
 
     w = W.get_workload(args.workload)
     seeds = {"weights": 1234, "lora": 99, "tokens": 2345, "noise": 3456}
-    frozen = W.make_frozen_weights(w, seeds["weights"])
+    if args.device_init:
+        args.no_cpu_baseline = True
+        frozen = M.device_random_weights(w, seeds["weights"])
+    else:
+        frozen = W.make_frozen_weights(w, seeds["weights"])
     masters = W.make_lora_masters(w, seeds["lora"])
     tokens, labels = W.make_tokens(w, seeds["tokens"]), W.make_labels(w, seeds["tokens"])
     m = M.ZoModel(w, frozen, masters, device="cuda:0")

@@ -1,5 +1,5 @@
 """MI355X-native MP-LoRA zeroth-order step: thin Python binding over the C-ABI library libmpz.so."""
-from .mpz import (MpzError, MpzConfig, load_library, config_from_workload, ZoModel,
+from .mpz import (MpzError, MpzConfig, load_library, config_from_workload, ZoModel, device_random_weights,
                   mpz_lora_numel, mpz_lora_tensor_count, mpz_lora_tensor_info, mpz_workspace_bytes,
                   mpz_init_model, mpz_regen_noise, mpz_forward_perturbed, mpz_zo_update, mpz_debug_noise,
                   mpz_debug_normals_from_words, mpz_debug_perturbed_copy, mpz_debug_embed,

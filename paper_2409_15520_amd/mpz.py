@@ -240,6 +240,38 @@ def config_from_workload(w) -> MpzConfig:
     return cfg
 
 
+def device_random_weights(w, seed: int, device: str = "cuda:0"):
+    """Frozen weights drawn on the GPU (N(0, 0.02^2), norm gains 1 / biases 0), already output-major and in the
+    model dtype: for benchmarks of the large workloads, where drawing and uploading host arrays would take minutes.
+    Same structure as workloads.make_frozen_weights; not bit-compatible with it."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    st = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    d, f = w.d_model, w.d_ffn
+    n_qkv, n_up = d + 2 * w.d_kv, (2 * f if w.act == "swiglu" else f)
+
+    def rnd(*shape, dtype=st):
+        return (torch.randn(*shape, generator=g, device=device, dtype=torch.float32) * 0.02).to(dtype)
+
+    ones = lambda n: torch.ones(n, device=device, dtype=torch.float32)
+    zeros = lambda n: torch.zeros(n, device=device, dtype=torch.float32)
+    ln = w.norm == "layernorm"
+    out = {"_device_output_major": True, "emb": rnd(w.vocab, d),
+           "pos_emb": rnd(w.max_seq, d) if w.pos == "learned" else None, "layers": []}
+    for _ in range(w.n_layers):
+        out["layers"].append({
+            "ln1_g": ones(d), "ln1_b": zeros(d) if ln else None,
+            "w_qkv": rnd(n_qkv, d), "b_qkv": rnd(n_qkv, dtype=torch.float32) if w.has_bias else None,
+            "w_o": rnd(d, d), "b_o": rnd(d, dtype=torch.float32) if w.has_bias else None,
+            "ln2_g": ones(d), "ln2_b": zeros(d) if ln else None,
+            "w_up": rnd(n_up, d), "b_up": rnd(n_up, dtype=torch.float32) if w.has_bias else None,
+            "w_down": rnd(d, f), "b_down": rnd(d, dtype=torch.float32) if w.has_bias else None})
+    out["lnf_g"], out["lnf_b"] = ones(d), (zeros(d) if ln else None)
+    out["lm_head"] = out["emb"] if w.tie_embeddings else rnd(w.vocab, d)
+    return out
+
+
 class ZoModel:
     """Device buffers + handle for one workload.  Holds the torch tensors the library borrows."""
 
@@ -254,11 +286,16 @@ class ZoModel:
         st = torch.bfloat16 if w.dtype == "bf16" else torch.float32
         self._keep = []
 
+        on_device = bool(frozen.get("_device_output_major", False))   # tensors already on the GPU, [k_out, k_in]
+
         def dev(a, dtype, transpose=False):
             if a is None:
                 return None
-            t = torch.from_numpy(np.ascontiguousarray(a.T if transpose else a))
-            t = t.to(self.device).to(dtype).contiguous()
+            if on_device:
+                t = a.to(dtype).contiguous()
+            else:
+                t = torch.from_numpy(np.ascontiguousarray(a.T if transpose else a))
+                t = t.to(self.device).to(dtype).contiguous()
             self._keep.append(t)
             return t.data_ptr()
 
