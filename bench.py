@@ -18,6 +18,9 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
 PEAK_FP64_VECTOR_TFLOPS = 78.6  # fp32-storage models accumulate in fp64 on the vector ALUs
+PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E
+# HBM bytes per GEMM launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
+GEMM_TRAFFIC = {}
 
 
 def gemm_flops_per_step(w):
@@ -103,19 +106,33 @@ def main():
     ms_per_step = 1e3 * dt / args.steps
     tokens_per_step = 2 * w.q * w.E * w.S
 
-    # second pass over the same number of steps with HIP events around every base-weight GEMM launch
-    M.mpz_profile_gemm_begin(m.handle)
+    # second pass over the same number of steps with HIP events around every kernel launch (the events add
+    # overhead, so they are kept out of the wall-clock region above)
+    M.mpz_profile_begin(m.handle)
     for _ in range(args.steps):
         m.zo_step(tok, lab, seeds["noise"], step)
         step += 1
-    gemm_ms, launches, flops = M.mpz_profile_gemm_end(m.handle)
+    prof = M.mpz_profile_end(m.handle)
     losses = m.losses[:2 * w.q].cpu().numpy()
     assert np.all(np.isfinite(losses)), losses
-    achieved = flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    gemm = prof["gemm"]
+    achieved = gemm["flops"] / (gemm["ms"] * 1e-3) / 1e12 if gemm["ms"] > 0 else 0.0
     alg = gemm_flops_per_step(w)
-    assert abs(flops / args.steps - alg) <= 1e-6 * alg, (flops / args.steps, alg)
+    assert abs(gemm["flops"] / args.steps - alg) <= 1e-6 * alg, (gemm["flops"] / args.steps, alg)
     bf16 = w.dtype == "bf16"
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP64_VECTOR_TFLOPS
+    kernels = {}
+    for name, e in prof.items():
+        if e["launches"] == 0:
+            continue
+        sec = e["ms"] * 1e-3
+        k = {"ms_per_step": e["ms"] / args.steps, "launches_per_step": e["launches"] / args.steps}
+        if e["flops"] > 0:
+            k["tflops"] = e["flops"] / sec / 1e12
+        if e["bytes"] > 0:
+            k["gbps"] = e["bytes"] / sec / 1e9
+            k["frac_hbm_peak"] = k["gbps"] / PEAK_HBM_GBPS
+        kernels[name] = k
     out = {
         "metric": "perturbed-copy tokens/sec", "value": tokens_per_step / (ms_per_step * 1e-3), "unit": "tokens/s",
         "zo_steps_per_sec": 1e3 / ms_per_step, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -125,10 +142,12 @@ def main():
                    "stacked_tokens": tokens_per_step, "layers": w.n_layers, "d_model": w.d_model,
                    "lora_rank": w.lora_rank, "eps": w.eps, "seeds": seeds},
         "roofline": {"bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": None, "kernel": "base-weight GEMMs (all launches of a step)",
-                     "launches_per_step": launches / args.steps, "gemm_ms_per_step": gemm_ms / args.steps,
+                     "frac": achieved / peak, "traffic": GEMM_TRAFFIC.get(w.name),
+                     "kernel": "base-weight GEMMs (all launches of a step)",
+                     "launches_per_step": gemm["launches"] / args.steps, "gemm_ms_per_step": gemm["ms"] / args.steps,
                      "algorithmic_flops_per_step": alg},
         "mfma_util_pct": 100.0 * achieved / peak if bf16 else None,
+        "kernels": kernels,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, frozen, masters, tokens, labels, seeds["noise"])

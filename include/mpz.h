@@ -207,14 +207,28 @@ mpz_status mpz_debug_gemm_bf16(int32_t M, int32_t N, int32_t K, const void* x, c
  * Invalidates the perturbed copies: call mpz_regen_noise again. */
 mpz_status mpz_debug_set_kernel_path(mpz_model* m, int32_t simple_only);
 
-/* Measurement hook: between _begin and _end every base-weight GEMM launch (the shared-W term X W of the
- * MP-LoRA layer with its fused per-copy rank-r term, and the LM head) is bracketed by HIP events on the
- * model's stream.  _end synchronises the stream and returns the summed kernel time in milliseconds, the
- * number of launches and the algorithmic FLOPs (2 M N K per launch).  Adds event overhead: do not enable
- * it inside a region whose wall-clock is reported.  Errors: NULL, STATE (end without begin), DEVICE. */
-mpz_status mpz_profile_gemm_begin(mpz_model* m);
-mpz_status mpz_profile_gemm_end(mpz_model* m, double* total_ms /*[host]*/, int64_t* launches /*[host]*/,
-                                double* flops /*[host]*/);
+/* Measurement hook: between _begin and _end every kernel launch of the three hot-path calls is bracketed by HIP
+ * events on the model's stream and booked under a category.  _end synchronises the stream and fills
+ * out[MPZ_PROF_COUNT] [host] with, per category, the summed kernel time (ms), the number of launches, the
+ * algorithmic FLOPs (GEMM: 2 M N K; attention: the causal-useful Q K^T and P V work) and the algorithmic bytes
+ * (one read of each input, one write of each output).  Adds event overhead: do not enable it inside a region
+ * whose wall-clock is reported.  Errors: NULL, STATE (end without begin), DEVICE. */
+enum {
+  MPZ_PROF_GEMM = 0,      /* base-weight GEMMs with the fused per-copy rank-r term, incl. the LM head */
+  MPZ_PROF_ATTENTION = 1,
+  MPZ_PROF_NORM = 2,
+  MPZ_PROF_LORA_DOWN = 3, /* bottleneck t = s x A_c */
+  MPZ_PROF_NOISE = 4,     /* regenerate noise, write the perturbed copies (and their bf16 operand layouts) */
+  MPZ_PROF_UPDATE = 5,    /* two-point estimate + seed-replayed update */
+  MPZ_PROF_EMBED = 6,
+  MPZ_PROF_ROPE = 7,
+  MPZ_PROF_LOSS = 8,      /* targets, per-row cross-entropy, per-copy mean */
+  MPZ_PROF_OTHER = 9,
+  MPZ_PROF_COUNT = 10
+};
+typedef struct { double ms; int64_t launches; double flops; double bytes; } mpz_profile_entry;
+mpz_status mpz_profile_begin(mpz_model* m);
+mpz_status mpz_profile_end(mpz_model* m, mpz_profile_entry* out /*[host] MPZ_PROF_COUNT entries*/);
 
 void mpz_destroy(mpz_model* m);
 const char* mpz_last_error(const mpz_model* m /* may be NULL */);

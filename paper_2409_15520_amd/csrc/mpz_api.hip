@@ -160,7 +160,7 @@ struct mpz_model {
   bool have_noise = false;
   uint64_t seed = 0; uint32_t step = 0; int q = 0; float eps = 0.f;
   std::string err;
-  // optional per-launch timing of the base-weight GEMMs (mpz_profile_gemm_begin / _end)
+  // optional per-launch timing by kernel category (mpz_profile_begin / _end)
   // bf16 MFMA path
   bool use_mfma = false;
   int rp = 0;                                   // padded 2r
@@ -168,8 +168,9 @@ struct mpz_model {
   int64_t packed_off[8] = {0};                  // offset of tensor i inside a layer's packed block
   bool prof_on = false;
   std::vector<hipEvent_t> prof_ev;   // start/stop pairs
+  std::vector<int> prof_cat;         // category of pair i
   size_t prof_used = 0;
-  double prof_flops = 0.0;
+  double prof_flops[MPZ_PROF_COUNT] = {0}, prof_bytes[MPZ_PROF_COUNT] = {0};
   ~mpz_model() { for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e); }
 };
 
@@ -193,32 +194,42 @@ const mpz_lora_tensor* find_tensor(const mpz_model* m, int layer, int target, in
   return nullptr;
 }
 
-// Every base-weight GEMM of the pass goes through here (kernel selection and optional timing).
-void gemm(mpz_model* m, const LinearArgs& a) {
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  if (m->prof_on) {
+// Brackets one launch with HIP events when profiling is on, and books its algorithmic work.
+struct ProfScope {
+  mpz_model* m; hipEvent_t e1 = nullptr;
+  ProfScope(mpz_model* m_, int cat, double flops, double bytes) : m(m_) {
+    if (!m->prof_on) return;
     if (m->prof_used + 2 > m->prof_ev.size()) {
       hipEvent_t x = nullptr, y = nullptr;
-      if (hipEventCreate(&x) == hipSuccess && hipEventCreate(&y) == hipSuccess) { m->prof_ev.push_back(x); m->prof_ev.push_back(y); }
+      if (hipEventCreate(&x) != hipSuccess || hipEventCreate(&y) != hipSuccess) return;
+      m->prof_ev.push_back(x); m->prof_ev.push_back(y);
     }
-    if (m->prof_used + 2 <= m->prof_ev.size()) {
-      e0 = m->prof_ev[m->prof_used]; e1 = m->prof_ev[m->prof_used + 1];
-      m->prof_used += 2;
-      m->prof_flops += 2.0 * a.M * (double)a.N * a.K;
-      (void)hipEventRecord(e0, m->stream);
-    }
+    hipEvent_t e0 = m->prof_ev[m->prof_used]; e1 = m->prof_ev[m->prof_used + 1];
+    if (m->prof_cat.size() < m->prof_ev.size() / 2) m->prof_cat.resize(m->prof_ev.size() / 2);
+    m->prof_cat[m->prof_used / 2] = cat;
+    m->prof_used += 2;
+    m->prof_flops[cat] += flops; m->prof_bytes[cat] += bytes;
+    (void)hipEventRecord(e0, m->stream);
   }
-  bool done = false;
+  ~ProfScope() { if (e1) (void)hipEventRecord(e1, m->stream); }
+};
+
+double esz(const mpz_model* m) { return m->cfg.dtype == MPZ_DTYPE_F32 ? 4.0 : 2.0; }
+
+// Every base-weight GEMM of the pass goes through here (kernel selection and optional timing).
+void gemm(mpz_model* m, const LinearArgs& a) {
+  ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)a.N * a.K,
+               esz(m) * ((double)a.M * a.K + (double)a.N * a.K) + (a.out_kind == 0 ? esz(m) : 4.0) * a.M * (double)a.N +
+                   (a.residual ? 4.0 * a.M * (double)a.N : 0.0));
   if (m->use_mfma && a.dtype == MPZ_DTYPE_BF16 && (a.n_seg == 0 || a.mfma_lora)) {
     MfmaGemmArgs g{};
     g.M = a.M; g.N = a.N; g.K = a.K; g.x = a.x; g.w = a.w; g.w_rows = a.N; g.bias = a.bias; g.dual = 0; g.dual_offset = 0;
     g.n_seg = a.n_seg; g.rows_per_copy = a.rows_per_copy; g.act = a.act; g.residual = a.residual;
     g.out_f32 = a.out_kind != 0; g.out = a.out; g.ldo = a.N;   // bf16 models stage in fp32
     for (int i = 0; i < a.n_seg; ++i) g.seg[i] = a.mseg[i];
-    if (mfma_gemm_supported(g)) { launch_gemm_mfma(m->stream, g); done = true; }
+    if (mfma_gemm_supported(g)) { launch_gemm_mfma(m->stream, g); return; }
   }
-  if (!done) launch_linear_simple(m->stream, a);
-  if (e1) (void)hipEventRecord(e1, m->stream);
+  launch_linear_simple(m->stream, a);
 }
 
 // SwiGLU up-projection: gate and up tiles in one kernel, u = SiLU(gate) * up rounded once
@@ -228,21 +239,9 @@ bool gemm_swiglu_mfma(mpz_model* m, const LinearArgs& a, int f, void* u_out) {
   g.M = a.M; g.N = f; g.K = a.K; g.x = a.x; g.w = a.w; g.w_rows = 2 * f; g.bias = a.bias; g.dual = 1; g.dual_offset = f;
   g.rows_per_copy = a.rows_per_copy; g.act = -1; g.out_f32 = 0; g.out = u_out; g.ldo = f;
   if (!mfma_gemm_supported(g)) return false;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  if (m->prof_on) {
-    if (m->prof_used + 2 > m->prof_ev.size()) {
-      hipEvent_t x = nullptr, y = nullptr;
-      if (hipEventCreate(&x) == hipSuccess && hipEventCreate(&y) == hipSuccess) { m->prof_ev.push_back(x); m->prof_ev.push_back(y); }
-    }
-    if (m->prof_used + 2 <= m->prof_ev.size()) {
-      e0 = m->prof_ev[m->prof_used]; e1 = m->prof_ev[m->prof_used + 1];
-      m->prof_used += 2;
-      m->prof_flops += 2.0 * a.M * (double)(2 * f) * a.K;
-      (void)hipEventRecord(e0, m->stream);
-    }
-  }
+  ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)(2 * f) * a.K,
+               2.0 * ((double)a.M * a.K + 2.0 * f * a.K + (double)a.M * f));
   launch_gemm_mfma(m->stream, g);
-  if (e1) (void)hipEventRecord(e1, m->stream);
   return true;
 }
 
@@ -256,6 +255,7 @@ int tensor_slot(const mpz_model* m, int target, int factor) {
 // fp32 residual rows -> operand type
 void norm(mpz_model* m, const float* h, int64_t h_row_stride, const float* g, const float* b, void* out, int rows) {
   const mpz_config& c = m->cfg;
+  ProfScope ps(m, MPZ_PROF_NORM, 0.0, (double)rows * c.d_model * (4.0 + esz(m)));
   if (m->use_mfma && norm_rows_supported(c.d_model, h_row_stride))
     launch_norm_rows(m->stream, c.norm, c.norm_eps, h, h_row_stride, g, b, out, rows, c.d_model);
   else
@@ -264,6 +264,7 @@ void norm(mpz_model* m, const float* h, int64_t h_row_stride, const float* g, co
 
 void run_embed(mpz_model* m, const int32_t* tokens, int E, int S, float* h) {
   const mpz_config& c = m->cfg;
+  ProfScope ps(m, MPZ_PROF_EMBED, 0.0, 2.0 * m->q * E * S * (double)c.d_model * (4.0 + esz(m)));
   launch_embed(m->stream, c.dtype, tokens, m->w.emb, c.pos == MPZ_POS_ROPE ? nullptr : m->w.pos_emb, h, 2 * m->q, E, S,
                c.d_model);
 }
@@ -316,11 +317,15 @@ void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, int out_kind, 
       probe.M = T; probe.N = nqkv; probe.K = d; probe.n_seg = nt; probe.rows_per_copy = rpc;
       for (int k = 0; k < nt; ++k) probe.seg[k] = qa.mseg[k];
       if (mfma_lora_down_supported(md) && mfma_gemm_supported(probe)) {
-        launch_lora_down_mfma(st, md);
+        { ProfScope ps(m, MPZ_PROF_LORA_DOWN, 4.0 * T * (double)d * nt * r, 2.0 * T * ((double)d + (double)nt * m->rp));
+          launch_lora_down_mfma(st, md); }
         qa.mfma_lora = 1; lora_done = true;
       }
     }
-    if (nt && !lora_done) launch_lora_down_simple(st, da);
+    if (nt && !lora_done) {
+      ProfScope ps(m, MPZ_PROF_LORA_DOWN, 2.0 * T * (double)d * nt * r, esz(m) * T * ((double)d + (double)nt * r));
+      launch_lora_down_simple(st, da);
+    }
     qa.out_kind = out_kind; qa.out = out;
     gemm(m, qa);
   }
@@ -343,12 +348,19 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     norm(m, b.h, d, lw.ln1_g, lw.ln1_b, b.x, T);
 
     run_qkv(m, b, l, E, S, rope ? 2 : 0, rope ? b.stage : b.qkv);
-    if (rope) launch_rope_convert(st, c.dtype, b.stage, b.qkv, T, S, nqkv, dh, c.n_heads + c.n_kv_heads, b.rope_cos, b.rope_sin);
+    if (rope) {
+      ProfScope ps(m, MPZ_PROF_ROPE, 0.0, (double)T * nqkv * (acc_size(c.dtype) + esz(m)));
+      launch_rope_convert(st, c.dtype, b.stage, b.qkv, T, S, nqkv, dh, c.n_heads + c.n_kv_heads, b.rope_cos, b.rope_sin);
+    }
 
-    if (m->use_mfma && attention_mfma_supported(dh, nqkv, d))
-      launch_attention_mfma(st, b.qkv, nqkv, b.attn, n * E, S, c.n_heads, c.n_kv_heads, dh);
-    else
-      launch_attention_simple(st, c.dtype, b.qkv, nqkv, b.attn, n * E, S, c.n_heads, c.n_kv_heads, dh);
+    {
+      // causal-useful work: Q K^T and P V over the S (S + 1) / 2 visible (query, key) pairs of every head
+      ProfScope ps(m, MPZ_PROF_ATTENTION, 2.0 * n * E * c.n_heads * (double)S * (S + 1) * dh, esz(m) * T * ((double)nqkv + d));
+      if (m->use_mfma && attention_mfma_supported(dh, nqkv, d))
+        launch_attention_mfma(st, b.qkv, nqkv, b.attn, n * E, S, c.n_heads, c.n_kv_heads, dh);
+      else
+        launch_attention_simple(st, c.dtype, b.qkv, nqkv, b.attn, n * E, S, c.n_heads, c.n_kv_heads, dh);
+    }
 
     // output projection (+ adapter) added to the residual stream
     const char* packed_l = (const char*)b.packed + (size_t)l * m->packed_per_layer * 2;
@@ -373,11 +385,15 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
         MfmaGemmArgs probe{};
         probe.M = T; probe.N = d; probe.K = d; probe.n_seg = 1; probe.rows_per_copy = rpc; probe.seg[0] = ms;
         if (mfma_lora_down_supported(md) && mfma_gemm_supported(probe)) {
-          launch_lora_down_mfma(st, md);
+          { ProfScope ps(m, MPZ_PROF_LORA_DOWN, 4.0 * T * (double)d * r, 2.0 * T * ((double)d + (double)m->rp));
+            launch_lora_down_mfma(st, md); }
           oa.mfma_lora = 1; o_done = true;
         }
       }
-      if (!o_done) launch_lora_down_simple(st, oda);
+      if (!o_done) {
+        ProfScope ps(m, MPZ_PROF_LORA_DOWN, 2.0 * T * (double)d * r, esz(m) * T * ((double)d + (double)r));
+        launch_lora_down_simple(st, oda);
+      }
       oa.n_seg = 1;
       oa.seg[0].col_begin = 0; oa.seg[0].col_end = d; oa.seg[0].t = b.t; oa.seg[0].t_stride = r; oa.seg[0].t_off = 0;
       oa.seg[0].Bc = b.pert + find_tensor(m, l, 3, 1)->offset; oa.seg[0].copy_stride = m->P;
@@ -392,7 +408,10 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     ua.out_kind = swiglu ? 2 : 0; ua.out = swiglu ? b.stage : b.u;
     if (!(swiglu && gemm_swiglu_mfma(m, ua, f, b.u))) {
       gemm(m, ua);
-      if (swiglu) launch_swiglu(st, c.dtype, b.stage, b.u, T, f);
+      if (swiglu) {
+        ProfScope ps(m, MPZ_PROF_OTHER, 0.0, (double)T * f * (2.0 * acc_size(c.dtype) + esz(m)));
+        launch_swiglu(st, c.dtype, b.stage, b.u, T, f);
+      }
     }
     LinearArgs wa{};
     wa.dtype = c.dtype; wa.M = T; wa.N = d; wa.K = f; wa.x = b.u; wa.w = lw.w_down; wa.bias = lw.b_down;
@@ -409,7 +428,8 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
   b.h = const_cast<float*>(h);
   const int n = 2 * m->q, rpc = E * S, T = n * rpc;
   const int d = c.d_model;
-  launch_make_targets(st, c.loss_mode, tokens, labels, c.label_token[0], c.label_token[1], b.target, n, E, S);
+  { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 0.0);
+    launch_make_targets(st, c.loss_mode, tokens, labels, c.label_token[0], c.label_token[1], b.target, n, E, S); }
   if (c.loss_mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS) {
     norm(m, b.h, d, m->w.lnf_g, m->w.lnf_b, b.x, T);
     for (int r0 = 0; r0 < T; r0 += b.chunk_rows) {
@@ -419,13 +439,16 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
       la.x = (const unsigned char*)b.x + (size_t)r0 * d * elem_size(c.dtype);
       la.w = m->w.lm_head; la.act = -1; la.rows_per_copy = rpc; la.out_kind = 1; la.out = b.logits;
       gemm(m, la);
-      launch_ce_rows(st, c.dtype, b.logits, c.vocab, c.vocab, b.target + r0, b.ce + r0, rows);
+      { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 4.0 * rows * (double)c.vocab);
+        launch_ce_rows(st, c.dtype, b.logits, c.vocab, c.vocab, b.target + r0, b.ce + r0, rows); }
     }
-    launch_copy_mean(st, b.ce, rpc, E * (S - 1), losses_out, n);
+    { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 4.0 * T);
+      launch_copy_mean(st, b.ce, rpc, E * (S - 1), losses_out, n); }
   } else {
     const int rows_all = n * E;
     norm(m, b.h + (size_t)(S - 1) * d, (int64_t)S * d, m->w.lnf_g, m->w.lnf_b, b.x, rows_all);
     if (c.loss_mode == MPZ_LOSS_LAST_POS_LABEL_SUBSET) {
+      ProfScope ps(m, MPZ_PROF_LOSS, 0.0, esz(m) * (double)d * (rows_all + 2));
       launch_last_pos_subset_logits(st, c.dtype, b.x, m->w.lm_head, d, rows_all, c.label_token[0], c.label_token[1], b.logits);
       launch_ce_rows(st, c.dtype, b.logits, 2, 2, b.target, b.ce, rows_all);
     } else {
@@ -436,10 +459,12 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
         la.x = (const unsigned char*)b.x + (size_t)r0 * d * elem_size(c.dtype);
         la.w = m->w.lm_head; la.act = -1; la.rows_per_copy = rpc; la.out_kind = 1; la.out = b.logits;
         gemm(m, la);
-        launch_ce_rows(st, c.dtype, b.logits, c.vocab, c.vocab, b.target + r0, b.ce + r0, rows);
+        { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 4.0 * rows * (double)c.vocab);
+        launch_ce_rows(st, c.dtype, b.logits, c.vocab, c.vocab, b.target + r0, b.ce + r0, rows); }
       }
     }
-    launch_copy_mean(st, b.ce, E, E, losses_out, n);
+    { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 4.0 * rows_all);
+      launch_copy_mean(st, b.ce, E, E, losses_out, n); }
   }
 }
 
@@ -554,7 +579,11 @@ mpz_status mpz_regen_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t q
   if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_regen_noise: NULL model");
   if (q < 1 || q > m->q_max) return fail(m, MPZ_ERR_SHAPE, "q outside [1, q_max]");
   if (!std::isfinite(eps) || eps < 0.f) return fail(m, MPZ_ERR_CONFIG, "eps must be finite and non-negative");
-  launch_perturb(m->stream, m->masters, m->buf.pert, m->P, m->tab, seed, step, q, eps, m->cfg.perturb_A);
+  {
+    ProfScope ps(m, MPZ_PROF_NOISE, 0.0, 4.0 * m->P * (1.0 + 2.0 * q));
+    launch_perturb(m->stream, m->masters, m->buf.pert, m->P, m->tab, seed, step, q, eps, m->cfg.perturb_A);
+  }
+  ProfScope ps_pack(m, MPZ_PROF_NOISE, 0.0, m->use_mfma ? 2.0 * q * (4.0 * m->P + 2.0 * m->packed_per_copy) : 0.0);
   if (m->use_mfma)
     launch_pack_factors(m->stream, m->buf.pert, m->P, 2 * q, m->tab, m->cfg.n_layers, m->cfg.lora_rank, m->rp, m->buf.packed,
                         m->packed_per_copy);
@@ -608,6 +637,7 @@ mpz_status mpz_zo_update(mpz_model* m, const float* losses, float lr, float* pro
   if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_zo_update before mpz_regen_noise");
   if (!(m->eps > 0.f)) return fail(m, MPZ_ERR_CONFIG, "the last mpz_regen_noise used eps = 0: the two-point quotient is undefined");
   if (!std::isfinite(lr)) return fail(m, MPZ_ERR_CONFIG, "lr must be finite");
+  ProfScope ps(m, MPZ_PROF_UPDATE, 0.0, 8.0 * m->P);
   launch_update(m->stream, m->masters, m->P, m->tab, m->seed, m->step, m->q, m->eps, lr, m->cfg.perturb_A, losses,
                 proj_grads_out);
   m->have_noise = false;                       // the perturbed copies no longer match the masters
@@ -685,24 +715,25 @@ mpz_status mpz_debug_set_kernel_path(mpz_model* m, int32_t simple_only) {
   return MPZ_OK;
 }
 
-mpz_status mpz_profile_gemm_begin(mpz_model* m) {
-  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_profile_gemm_begin: NULL model");
-  m->prof_on = true; m->prof_used = 0; m->prof_flops = 0.0;
+mpz_status mpz_profile_begin(mpz_model* m) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_profile_begin: NULL model");
+  m->prof_on = true; m->prof_used = 0;
+  for (int i = 0; i < MPZ_PROF_COUNT; ++i) m->prof_flops[i] = m->prof_bytes[i] = 0.0;
   return MPZ_OK;
 }
 
-mpz_status mpz_profile_gemm_end(mpz_model* m, double* total_ms, int64_t* launches, double* flops) {
-  if (!m || !total_ms || !launches || !flops) return fail(m, MPZ_ERR_NULL, "mpz_profile_gemm_end: NULL argument");
-  if (!m->prof_on) return fail(m, MPZ_ERR_STATE, "mpz_profile_gemm_end without mpz_profile_gemm_begin");
+mpz_status mpz_profile_end(mpz_model* m, mpz_profile_entry* out) {
+  if (!m || !out) return fail(m, MPZ_ERR_NULL, "mpz_profile_end: NULL argument");
+  if (!m->prof_on) return fail(m, MPZ_ERR_STATE, "mpz_profile_end without mpz_profile_begin");
   m->prof_on = false;
   if (hipStreamSynchronize(m->stream) != hipSuccess) return fail(m, MPZ_ERR_DEVICE, "stream synchronisation failed");
-  double ms = 0.0;
+  for (int i = 0; i < MPZ_PROF_COUNT; ++i) { out[i].ms = 0.0; out[i].launches = 0; out[i].flops = m->prof_flops[i]; out[i].bytes = m->prof_bytes[i]; }
   for (size_t i = 0; i + 1 < m->prof_used; i += 2) {
     float t = 0.f;
     if (hipEventElapsedTime(&t, m->prof_ev[i], m->prof_ev[i + 1]) != hipSuccess) return fail(m, MPZ_ERR_DEVICE, "hipEventElapsedTime failed");
-    ms += t;
+    const int cat = m->prof_cat[i / 2];
+    out[cat].ms += t; out[cat].launches += 1;
   }
-  *total_ms = ms; *launches = (int64_t)(m->prof_used / 2); *flops = m->prof_flops;
   return MPZ_OK;
 }
 

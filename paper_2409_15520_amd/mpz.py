@@ -50,6 +50,13 @@ class MpzWeights(C.Structure):
                 ("lnf_b", C.c_void_p), ("layers", C.POINTER(MpzLayerWeights))]
 
 
+PROF_CATEGORIES = ("gemm", "attention", "norm", "lora_down", "noise", "update", "embed", "rope", "loss", "other")
+
+
+class MpzProfileEntry(C.Structure):
+    _fields_ = [("ms", C.c_double), ("launches", C.c_int64), ("flops", C.c_double), ("bytes", C.c_double)]
+
+
 class MpzLoraTensor(C.Structure):
     _fields_ = [("layer", C.c_int32), ("target", C.c_int32), ("factor", C.c_int32), ("tensor_id", C.c_int32),
                 ("offset", C.c_int64), ("rows", C.c_int32), ("cols", C.c_int32)]
@@ -102,10 +109,10 @@ def load_library() -> C.CDLL:
                                         C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
     lib.mpz_debug_set_kernel_path.restype = C.c_int
     lib.mpz_debug_set_kernel_path.argtypes = [C.c_void_p, C.c_int32]
-    lib.mpz_profile_gemm_begin.restype = C.c_int
-    lib.mpz_profile_gemm_begin.argtypes = [C.c_void_p]
-    lib.mpz_profile_gemm_end.restype = C.c_int
-    lib.mpz_profile_gemm_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+    lib.mpz_profile_begin.restype = C.c_int
+    lib.mpz_profile_begin.argtypes = [C.c_void_p]
+    lib.mpz_profile_end.restype = C.c_int
+    lib.mpz_profile_end.argtypes = [C.c_void_p, C.POINTER(MpzProfileEntry)]
     lib.mpz_destroy.restype = None
     lib.mpz_destroy.argtypes = [C.c_void_p]
     lib.mpz_last_error.restype = C.c_char_p
@@ -210,15 +217,16 @@ def mpz_debug_set_kernel_path(handle, simple_only: bool):
     _check(load_library().mpz_debug_set_kernel_path(handle, int(simple_only)), handle)
 
 
-def mpz_profile_gemm_begin(handle):
-    _check(load_library().mpz_profile_gemm_begin(handle), handle)
+def mpz_profile_begin(handle):
+    _check(load_library().mpz_profile_begin(handle), handle)
 
 
-def mpz_profile_gemm_end(handle):
-    """Returns (total GEMM kernel ms, launches, algorithmic FLOPs) since mpz_profile_gemm_begin."""
-    ms, n, fl = C.c_double(), C.c_int64(), C.c_double()
-    _check(load_library().mpz_profile_gemm_end(handle, C.byref(ms), C.byref(n), C.byref(fl)), handle)
-    return ms.value, n.value, fl.value
+def mpz_profile_end(handle):
+    """Returns {category: dict(ms, launches, flops, bytes)} since mpz_profile_begin."""
+    arr = (MpzProfileEntry * len(PROF_CATEGORIES))()
+    _check(load_library().mpz_profile_end(handle, arr), handle)
+    return {name: dict(ms=arr[i].ms, launches=arr[i].launches, flops=arr[i].flops, bytes=arr[i].bytes)
+            for i, name in enumerate(PROF_CATEGORIES)}
 
 
 def mpz_destroy(handle):
