@@ -21,13 +21,23 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int QB = 128;   // queries per block
-constexpr int KC = 64;    // keys per LDS chunk
 
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
   return (uint32_t)f32_to_bf16(a).bits | ((uint32_t)f32_to_bf16(b).bits << 16);
 }
 
-template <int DH>
+// exp(x) for x <= 0 through the hardware exp2: x log2(e) is split into a rounded product t and its exact
+// remainder r (fma) plus the low part of log2(e), exp2(t + r) = exp2(t) (1 + r ln 2); relative error ~1e-7.
+__device__ __forceinline__ float exp_neg(float x) {
+  const float L2E = 1.4426950408889634f, L2E_LO = 1.925963033500011e-8f;
+  float t = x * L2E;
+  float r = fmaf(x, L2E, -t) + x * L2E_LO;
+  return __builtin_amdgcn_exp2f(t) * fmaf(r, 0.6931471805599453f, 1.0f);
+}
+
+// KC = keys per LDS chunk.  When every key the block can see fits one chunk, K and V are loaded once and both
+// passes run from LDS; otherwise each pass streams the chunks.
+template <int DH, int KC>
 __global__ void __launch_bounds__(256) attention_mfma_kernel(const uint16_t* __restrict__ qkv, int qkv_stride,
                                                              uint16_t* __restrict__ out, int S, int H, int Hkv,
                                                              float scale) {
@@ -65,57 +75,52 @@ __global__ void __launch_bounds__(256) attention_mfma_kernel(const uint16_t* __r
   const int last_q_block = (qb * QB + QB - 1 < S ? qb * QB + QB - 1 : S - 1);
   const int n_chunks = last_q_block / KC + 1;     // key chunks any query of the block can see
   const int wave_last_q = q0 + 31;
+  constexpr int CPR = DH / 8;                     // 16-byte chunks per key row
 
-  auto load_k_chunk = [&](int c) {
-    constexpr int CPR = DH / 8;                   // 16-byte chunks per key row
-    for (int i = tid; i < KC * CPR; i += 256) {
-      int key = i / CPR, ch = i % CPR;
-      int kg = c * KC + key; kg = kg < S ? kg : S - 1;
-      *(u32x4*)(sK + key * KS + ch * 8) = *(const u32x4*)(kbase + (size_t)kg * qkv_stride + ch * 8);
-    }
-  };
-  auto load_v_chunk = [&](int c) {
-    constexpr int CPR = DH / 8;
-    for (int i = tid; i < KC * CPR; i += 256) {
-      int key = i / CPR, ch = i % CPR;
-      int kg = c * KC + key; kg = kg < S ? kg : S - 1;
-      u32x4 v = *(const u32x4*)(vbase + (size_t)kg * qkv_stride + ch * 8);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        sVt[(ch * 8 + 2 * e) * VS + key] = (uint16_t)(v[e] & 0xFFFFu);
-        sVt[(ch * 8 + 2 * e + 1) * VS + key] = (uint16_t)(v[e] >> 16);
-      }
-    }
-  };
+#define MPZ_LOAD_K(c)                                                              \
+  for (int i = tid; i < KC * CPR; i += 256) {                                      \
+    int key = i / CPR, ch = i % CPR;                                               \
+    int kg = (c) * KC + key; kg = kg < S ? kg : S - 1;                             \
+    *(u32x4*)(sK + key * KS + ch * 8) = *(const u32x4*)(kbase + (size_t)kg * qkv_stride + ch * 8); \
+  }
+#define MPZ_LOAD_V(c)                                                              \
+  for (int i = tid; i < KC * CPR; i += 256) {                                      \
+    int key = i / CPR, ch = i % CPR;                                               \
+    int kg = (c) * KC + key; kg = kg < S ? kg : S - 1;                             \
+    u32x4 v = *(const u32x4*)(vbase + (size_t)kg * qkv_stride + ch * 8);           \
+    _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                \
+      sVt[(ch * 8 + 2 * e) * VS + key] = (uint16_t)(v[e] & 0xFFFFu);               \
+      sVt[(ch * 8 + 2 * e + 1) * VS + key] = (uint16_t)(v[e] >> 16);               \
+    }                                                                              \
+  }
   // scores of one 32-key tile against this wave's 32 queries; lane: query qi, keys kt0 + (e/4)*8 + lhalf*4 + e%4
-  auto score_tile = [&](int kt_local, int kt0, float s[16]) {
-    f32x16 acc;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-      bf16x8 fk = __builtin_bit_cast(bf16x8, *(const u32x4*)(sK + (kt_local * 32 + lrow) * KS + j * 16 + lhalf * 8));
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk, fq[j], acc, 0, 0, 0);
-    }
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      int key = kt0 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
-      s[e] = key <= qi ? acc[e] * scale : -1e30f;
-    }
-  };
+#define MPZ_SCORE_TILE(t_local, kt0, s)                                            \
+  {                                                                                \
+    f32x16 sacc;                                                                   \
+    _Pragma("unroll") for (int e = 0; e < 16; ++e) sacc[e] = 0.f;                  \
+    _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                               \
+      bf16x8 fk = __builtin_bit_cast(bf16x8, *(const u32x4*)(sK + ((t_local) * 32 + lrow) * KS + j * 16 + lhalf * 8)); \
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk, fq[j], sacc, 0, 0, 0);    \
+    }                                                                              \
+    _Pragma("unroll") for (int e = 0; e < 16; ++e) {                               \
+      int key = (kt0) + (e >> 2) * 8 + lhalf * 4 + (e & 3);                        \
+      s[e] = key <= qi ? sacc[e] * scale : -1e30f;                                 \
+    }                                                                              \
+  }
 
   // ---- pass 1: exact row maximum ----
   float mx = -1e30f;
   for (int c = 0; c < n_chunks; ++c) {
     __syncthreads();
-    load_k_chunk(c);
+    MPZ_LOAD_K(c)
+    if (n_chunks == 1) { MPZ_LOAD_V(c) }
     __syncthreads();
 #pragma unroll
     for (int t = 0; t < KC / 32; ++t) {
       int kt0 = c * KC + t * 32;
       if (kt0 > wave_last_q) continue;            // tile entirely in this wave's future
       float s[16];
-      score_tile(t, kt0, s);
+      MPZ_SCORE_TILE(t, kt0, s)
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = s[e] > mx ? s[e] : mx;
     }
@@ -133,22 +138,22 @@ __global__ void __launch_bounds__(256) attention_mfma_kernel(const uint16_t* __r
     for (int e = 0; e < 16; ++e) oacc[t][e] = 0.f;
   float lsum = 0.f;
   for (int c = 0; c < n_chunks; ++c) {
-    __syncthreads();
-    load_k_chunk(c);
-    load_v_chunk(c);
-    __syncthreads();
+    if (n_chunks > 1) {
+      __syncthreads();
+      MPZ_LOAD_K(c)
+      MPZ_LOAD_V(c)
+      __syncthreads();
+    }
 #pragma unroll
     for (int t = 0; t < KC / 32; ++t) {
       int kt0 = c * KC + t * 32;
       if (kt0 > wave_last_q) continue;
       float s[16];
-      score_tile(t, kt0, s);
+      MPZ_SCORE_TILE(t, kt0, s)
       uint32_t pw[8];                             // 16 probabilities as bf16 pairs
 #pragma unroll
       for (int e = 0; e < 16; e += 2) {
-        float p0 = s[e] > -1e29f ? expf(s[e] - mx) : 0.f;
-        float p1 = s[e + 1] > -1e29f ? expf(s[e + 1] - mx) : 0.f;
-        bf16_t b0 = f32_to_bf16(p0), b1 = f32_to_bf16(p1);
+        bf16_t b0 = f32_to_bf16(exp_neg(s[e] - mx)), b1 = f32_to_bf16(exp_neg(s[e + 1] - mx));
         lsum += bf16_to_f32(b0) + bf16_to_f32(b1);
         pw[e >> 1] = (uint32_t)b0.bits | ((uint32_t)b1.bits << 16);
       }
@@ -169,17 +174,21 @@ __global__ void __launch_bounds__(256) attention_mfma_kernel(const uint16_t* __r
       }
     }
   }
+#undef MPZ_LOAD_K
+#undef MPZ_LOAD_V
+#undef MPZ_SCORE_TILE
   lsum += __shfl_xor(lsum, 32, 64);
 
   if (qi < S) {
+    const float inv = 1.0f / lsum;
     uint16_t* op = out + (row0 + qi) * (size_t)d + head * DH;
 #pragma unroll
     for (int vt = 0; vt < NT; ++vt)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         int dv = vt * 32 + g * 8 + lhalf * 4;
-        u32x2 pk = {pack2(oacc[vt][g * 4] / lsum, oacc[vt][g * 4 + 1] / lsum),
-                    pack2(oacc[vt][g * 4 + 2] / lsum, oacc[vt][g * 4 + 3] / lsum)};
+        u32x2 pk = {pack2(oacc[vt][g * 4] * inv, oacc[vt][g * 4 + 1] * inv),
+                    pack2(oacc[vt][g * 4 + 2] * inv, oacc[vt][g * 4 + 3] * inv)};
         *(u32x2*)(op + dv) = pk;
       }
   }
@@ -197,9 +206,9 @@ void launch_attention_mfma(hipStream_t st, const void* qkv, int qkv_stride, void
   const unsigned blocks = (unsigned)((size_t)n_seq * H * qblocks);
   const float scale = (float)(1.0 / sqrt((double)dh));
   if (dh == 64)
-    attention_mfma_kernel<64><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale);
+    attention_mfma_kernel<64, 128><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale);
   else
-    attention_mfma_kernel<128><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale);
+    attention_mfma_kernel<128, 64><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale);
 }
 
 }  // namespace mpz

@@ -251,13 +251,17 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
 }
 
 // ---- LoRA bottleneck: tp[m] = [t | t | 0], t = bf16(scale * x (A_hi + A_lo)) for the block's copy ----------
-// One wave per 32 tokens.  MFMA rows = bottleneck columns j of all targets that share the input x.
+// One block = 32 tokens; its 4 waves each take a quarter of K (the kernel is latency-bound: short dependent
+// chains and many loads in flight matter, not MFMA count) and their partial sums meet in LDS in a fixed order.
+// MFMA rows = bottleneck columns j of all targets that share the input x.
 template <int JT>   // number of 32-row MFMA tiles covering n_targets * r bottleneck columns
-__global__ void __launch_bounds__(64) lora_down_mfma_kernel(MfmaLoraDownArgs a) {
-  const int lane = threadIdx.x, lrow = lane & 31, lhalf = lane >> 5;
+__global__ void __launch_bounds__(256) lora_down_mfma_kernel(MfmaLoraDownArgs a) {
+  __shared__ float part[3][JT][16][64];          // partial sums of waves 1..3
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lrow = lane & 31, lhalf = lane >> 5;
   const int m0 = blockIdx.x * 32;
   const int copy = m0 / a.rows_per_copy;
   const int R = a.n_targets * a.rank;
+  const int kq = a.K / 4, kbeg = wave * kq;
   const uint16_t* X = (const uint16_t*)a.x + (size_t)(m0 + lrow) * a.K + lhalf * 8;
   // packed A: per copy [n_targets][2][rank][K]  (hi rows then lo rows), K contiguous
   const uint16_t* Ah[JT];
@@ -280,7 +284,7 @@ __global__ void __launch_bounds__(64) lora_down_mfma_kernel(MfmaLoraDownArgs a) 
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
   const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll 4
-  for (int k = 0; k < a.K; k += 16) {
+  for (int k = kbeg; k < kbeg + kq; k += 16) {
     bf16x8 fx = as_frag(*(const u32x4*)(X + k));
 #pragma unroll
     for (int t = 0; t < JT; ++t) {
@@ -290,6 +294,18 @@ __global__ void __launch_bounds__(64) lora_down_mfma_kernel(MfmaLoraDownArgs a) 
       acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(l), fx, acc[t], 0, 0, 0);
     }
   }
+  if (wave > 0) {
+#pragma unroll
+    for (int t = 0; t < JT; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) part[wave - 1][t][e][lane] = acc[t][e];
+  }
+  __syncthreads();
+  if (wave != 0) return;
+#pragma unroll
+  for (int t = 0; t < JT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = ((acc[t][e] + part[0][t][e][lane]) + part[1][t][e][lane]) + part[2][t][e][lane];
   // lane holds token m0 + lrow, bottleneck columns j = t*32 + g*8 + lhalf*4 + e
   const int m = m0 + lrow;
 #pragma unroll
@@ -427,13 +443,13 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
 
 bool mfma_lora_down_supported(const MfmaLoraDownArgs& a) {
   int R = a.n_targets * a.rank;
-  return a.K % 16 == 0 && a.T % 32 == 0 && a.rows_per_copy % 32 == 0 && R <= 64 && a.rp % 8 == 0;
+  return a.K % 64 == 0 && a.T % 32 == 0 && a.rows_per_copy % 32 == 0 && R <= 64 && a.rp % 8 == 0;
 }
 
 void launch_lora_down_mfma(hipStream_t st, const MfmaLoraDownArgs& a) {
   int R = a.n_targets * a.rank;
-  if (R <= 32) lora_down_mfma_kernel<1><<<a.T / 32, 64, 0, st>>>(a);
-  else lora_down_mfma_kernel<2><<<a.T / 32, 64, 0, st>>>(a);
+  if (R <= 32) lora_down_mfma_kernel<1><<<a.T / 32, 256, 0, st>>>(a);
+  else lora_down_mfma_kernel<2><<<a.T / 32, 256, 0, st>>>(a);
 }
 
 void launch_pack_factors(hipStream_t st, const float* pert, int64_t P, int n_copies, const LoraLayerTable& tab,
