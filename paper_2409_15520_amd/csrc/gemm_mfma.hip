@@ -51,7 +51,14 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
     const int xcd = pid % 8, idx = pid / 8;
     pid = xcd * per + (xcd < rem ? xcd : rem) + idx;
   }
-  const int tile_m = pid / tiles_n, tile_n = pid % tiles_n;
+  // Inside that range, walk groups of GM token-tiles with the token-tile index fastest: the blocks running
+  // together on an XCD then form a compact patch of the output (few distinct X and W tiles per block), and a
+  // W tile is finished after GM consecutive blocks instead of having to survive in L2 until the next row of tiles.
+  constexpr int GM = 8;
+  const int group = pid / (GM * tiles_n), first_m = group * GM;
+  const int gsz = tiles_m - first_m < GM ? tiles_m - first_m : GM;
+  const int rr = pid - group * GM * tiles_n;
+  const int tile_m = first_m + rr % gsz, tile_n = rr / gsz;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -390,8 +397,8 @@ void launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
   gemm_bf16_kernel<BN, BM, BK, WGN, WGM, NSET, DUAL><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
 }
 
-int tile_bn(int cfg) { return (cfg == 2 || cfg >= 4) ? 256 : 128; }
-int tile_bm(int cfg) { return (cfg == 3 || cfg >= 4) ? 256 : 128; }
+int tile_bn(int cfg) { return (cfg == 2 || cfg >= 4) ? 256 : 128; }   // 7, 8: 256 x 128
+int tile_bm(int cfg) { return (cfg == 3 || (cfg >= 4 && cfg <= 6)) ? 256 : 128; }
 
 bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
   const int bn = tile_bn(cfg), bm = tile_bm(cfg);
@@ -402,7 +409,7 @@ bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
 }
 
 int choose_cfg(const MfmaGemmArgs& a) {
-  if (a.tile_cfg >= 1 && a.tile_cfg <= 6 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
+  if (a.tile_cfg >= 1 && a.tile_cfg <= 8 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
   // enough 256 x 256 tiles to keep 256 CUs busy for several rounds -> biggest tile; else the largest tile that
   // still gives at least ~2 blocks per CU
   // The L2 -> CU path feeds about 64 B/clk per CU, which a 128 x 128 tile needs in full at MFMA peak; 256 x 256
@@ -437,6 +444,8 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     case 4: launch_cfg<256, 256, 32, 2, 2, 1, false>(st, a); break;
     case 5: launch_cfg<256, 256, 32, 2, 4, 2, false>(st, a); break;     // 8 waves of 128 x 64
     case 6: launch_cfg<256, 256, 64, 2, 4, 1, false>(st, a); break;     // 8 waves, BK 64 (147 KB LDS)
+    case 7: launch_cfg<256, 128, 64, 4, 2, 2, false>(st, a); break;     // 8 waves of 64 x 64, 110 KB LDS
+    case 8: launch_cfg<256, 128, 32, 4, 2, 2, false>(st, a); break;     // 8 waves of 64 x 64, 61 KB LDS
     default: launch_cfg<128, 128, 64, 2, 2, 2, false>(st, a); break;
   }
 }
