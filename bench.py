@@ -67,6 +67,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2_opt125m")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mode", default="batched", choices=["batched", "inner", "sequential"],
+                    help="batched: all 2q copies in one pass (inner + outer loop parallel); inner: one query per pass, "
+                         "both signs together (inner-loop parallelisation only); sequential: one pass per copy "
+                         "(MeZO-style)")
+    ap.add_argument("--q", type=int, default=None, help="override the workload's number of queries")
+    ap.add_argument("--E", type=int, default=None, help="override the sequences per copy")
+    ap.add_argument("--S", type=int, default=None, help="override the sequence length")
     ap.add_argument("--device-init", action="store_true",
                     help="draw the frozen weights on the GPU (large workloads; implies --no-cpu-baseline)")
     args = ap.parse_args()
@@ -80,6 +87,9 @@ def main():
     import paper_2409_15520_amd as M
 
     w = W.get_workload(args.workload)
+    over = {k: v for k, v in (("q", args.q), ("E", args.E), ("S", args.S)) if v is not None}
+    if over:
+        w = w.with_(**over)
     seeds = {"weights": 1234, "lora": 99, "tokens": 2345, "noise": 3456}
     if args.device_init:
         args.no_cpu_baseline = True
@@ -92,14 +102,24 @@ def main():
     tok = torch.from_numpy(tokens).cuda()
     lab = torch.from_numpy(labels).cuda()
 
+    group = {"batched": 2 * w.q, "inner": 2, "sequential": 1}[args.mode]
+
+    def zo_step(step):
+        m.regen_noise(seeds["noise"], step)
+        if args.mode == "batched":
+            m.forward_perturbed(tok, lab)
+        else:
+            m.forward_sequential(tok, lab, group=group)
+        m.zo_update()
+
     step = 0
     for _ in range(args.warmup):
-        m.zo_step(tok, lab, seeds["noise"], step)
+        zo_step(step)
         step += 1
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        m.zo_step(tok, lab, seeds["noise"], step)
+        zo_step(step)
         step += 1
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -110,7 +130,7 @@ def main():
     # overhead, so they are kept out of the wall-clock region above)
     M.mpz_profile_begin(m.handle)
     for _ in range(args.steps):
-        m.zo_step(tok, lab, seeds["noise"], step)
+        zo_step(step)
         step += 1
     prof = M.mpz_profile_end(m.handle)
     losses = m.losses[:2 * w.q].cpu().numpy()
@@ -138,7 +158,7 @@ def main():
         "zo_steps_per_sec": 1e3 / ms_per_step, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f64", "data": "synthetic",
-        "config": {"workload": w.name, "q": w.q, "copies": 2 * w.q, "E": w.E, "S": w.S,
+        "config": {"workload": w.name, "mode": args.mode, "q": w.q, "copies": 2 * w.q, "E": w.E, "S": w.S,
                    "stacked_tokens": tokens_per_step, "layers": w.n_layers, "d_model": w.d_model,
                    "lora_rank": w.lora_rank, "eps": w.eps, "seeds": seeds},
         "roofline": {"bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",

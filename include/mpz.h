@@ -160,6 +160,15 @@ mpz_status mpz_regen_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t q
 mpz_status mpz_forward_perturbed(mpz_model* m, const int32_t* tokens, const int32_t* labels,
                                  int32_t E, int32_t S, float* losses_out);
 
+/* The same pass restricted to the copies [copy_begin, copy_begin + n_copies) of the last mpz_regen_noise; writes
+ * losses_out[copy_begin .. copy_begin + n_copies) and leaves the other entries untouched.  n_copies = 1 in a loop
+ * over all 2q copies is the sequential evaluation that Section 3 starts from (one forward pass per perturbed
+ * parameter vector, as in MeZO with q > 1, Appendix A); n_copies = q over the + copies and then the - copies is
+ * outer-loop parallelisation alone.  Every copy's loss is bit-identical to what mpz_forward_perturbed gives it.
+ * Errors as mpz_forward_perturbed, plus SHAPE for a range outside [0, 2q). */
+mpz_status mpz_forward_copies(mpz_model* m, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
+                              int32_t copy_begin, int32_t n_copies, float* losses_out);
+
 /* Algorithm 1, projected gradient and update: g_k = (l_{2k} - l_{2k+1}) / (2 eps) in fp64 from the fp32 losses, then
  * theta_l <- theta_l - lr (1/q) sum_k g_k z_k on the fp32 masters, z_k replayed from the (seed,
  * step, q, eps) of the last mpz_regen_noise.

@@ -159,6 +159,7 @@ struct mpz_model {
   int64_t P = 0;
   bool have_noise = false;
   uint64_t seed = 0; uint32_t step = 0; int q = 0; float eps = 0.f;
+  int cb = 0, nc = 0;                           // copies [cb, cb + nc) processed by the current pass
   std::string err;
   // optional per-launch timing by kernel category (mpz_profile_begin / _end)
   // bf16 MFMA path
@@ -216,6 +217,28 @@ struct ProfScope {
 
 double esz(const mpz_model* m) { return m->cfg.dtype == MPZ_DTYPE_F32 ? 4.0 : 2.0; }
 
+// Workspace pointers of the copies [m->cb, m->cb + m->nc): every activation buffer is row-major over the stacked
+// tokens, so a range of copies is a range of rows; staging and logits buffers are shared (one pass at a time).
+Buffers view(const mpz_model* m, int E, int S) {
+  Buffers b = m->buf;
+  const mpz_config& c = m->cfg;
+  const size_t row0 = (size_t)m->cb * E * S, es = elem_size(c.dtype);
+  const int d = c.d_model, dkv = c.n_kv_heads * (d / c.n_heads);
+  b.pert += (size_t)m->cb * m->P;
+  if (b.packed) b.packed = (uint16_t*)b.packed + (size_t)m->cb * m->packed_per_copy;
+  b.h += row0 * d;
+  b.x = (char*)b.x + row0 * d * es;
+  b.qkv = (char*)b.qkv + row0 * (d + 2 * dkv) * es;
+  b.attn = (char*)b.attn + row0 * d * es;
+  b.t = (char*)b.t + row0 * 4 * c.lora_rank * es;
+  b.u = (char*)b.u + row0 * c.d_ffn * es;
+  for (int i = 0; i < 3; ++i)
+    if (b.tp[i]) b.tp[i] = (uint16_t*)b.tp[i] + row0 * m->rp;
+  const size_t loss0 = c.loss_mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS ? row0 : (size_t)m->cb * E;
+  b.ce += loss0; b.target += loss0;
+  return b;
+}
+
 // Every base-weight GEMM of the pass goes through here (kernel selection and optional timing).
 void gemm(mpz_model* m, const LinearArgs& a) {
   ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)a.N * a.K,
@@ -264,8 +287,8 @@ void norm(mpz_model* m, const float* h, int64_t h_row_stride, const float* g, co
 
 void run_embed(mpz_model* m, const int32_t* tokens, int E, int S, float* h) {
   const mpz_config& c = m->cfg;
-  ProfScope ps(m, MPZ_PROF_EMBED, 0.0, 2.0 * m->q * E * S * (double)c.d_model * (4.0 + esz(m)));
-  launch_embed(m->stream, c.dtype, tokens, m->w.emb, c.pos == MPZ_POS_ROPE ? nullptr : m->w.pos_emb, h, 2 * m->q, E, S,
+  ProfScope ps(m, MPZ_PROF_EMBED, 0.0, (double)m->nc * E * S * (double)c.d_model * (4.0 + esz(m)));
+  launch_embed(m->stream, c.dtype, tokens, m->w.emb, c.pos == MPZ_POS_ROPE ? nullptr : m->w.pos_emb, h, m->nc, E, S,
                c.d_model);
 }
 
@@ -274,7 +297,7 @@ void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, int out_kind, 
   const mpz_config& c = m->cfg;
   hipStream_t st = m->stream;
   const mpz_layer_weights& lw = m->layers[l];
-  const int n = 2 * m->q, rpc = E * S, T = n * rpc;
+  const int n = m->nc, rpc = E * S, T = n * rpc;
   const int d = c.d_model, dh = d / c.n_heads, dkv = c.n_kv_heads * dh, r = c.lora_rank;
   const int nqkv = d + 2 * dkv;
   {
@@ -336,9 +359,9 @@ void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, int out_kind, 
 void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
   const mpz_config& c = m->cfg;
   hipStream_t st = m->stream;
-  Buffers b = m->buf;
+  Buffers b = view(m, E, S);
   b.h = h;
-  const int n = 2 * m->q, rpc = E * S, T = n * rpc;
+  const int n = m->nc, rpc = E * S, T = n * rpc;
   const int d = c.d_model, dh = d / c.n_heads, dkv = c.n_kv_heads * dh, f = c.d_ffn, r = c.lora_rank;
   const int nqkv = d + 2 * dkv;
   const bool rope = c.pos == MPZ_POS_ROPE, swiglu = c.act == MPZ_ACT_SWIGLU;
@@ -424,9 +447,9 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
 void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t* labels, int E, int S, float* losses_out) {
   const mpz_config& c = m->cfg;
   hipStream_t st = m->stream;
-  Buffers b = m->buf;
+  Buffers b = view(m, E, S);
   b.h = const_cast<float*>(h);
-  const int n = 2 * m->q, rpc = E * S, T = n * rpc;
+  const int n = m->nc, rpc = E * S, T = n * rpc;
   const int d = c.d_model;
   { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 0.0);
     launch_make_targets(st, c.loss_mode, tokens, labels, c.label_token[0], c.label_token[1], b.target, n, E, S); }
@@ -588,6 +611,7 @@ mpz_status mpz_regen_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t q
     launch_pack_factors(m->stream, m->buf.pert, m->P, 2 * q, m->tab, m->cfg.n_layers, m->cfg.lora_rank, m->rp, m->buf.packed,
                         m->packed_per_copy);
   m->have_noise = true; m->seed = seed; m->step = step; m->q = q; m->eps = eps;
+  m->cb = 0; m->nc = 2 * q;
   return check_device(m, "mpz_regen_noise");
 }
 
@@ -598,10 +622,28 @@ mpz_status mpz_forward_perturbed(mpz_model* m, const int32_t* tokens, const int3
   if (m->cfg.loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS && !labels) return fail(m, MPZ_ERR_NULL, "this loss mode needs labels");
   if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_forward_perturbed before mpz_regen_noise");
   if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
+  m->cb = 0; m->nc = 2 * m->q;
   run_embed(m, tokens, E, S, m->buf.h);
   run_layers(m, m->buf.h, 0, m->cfg.n_layers, E, S);
   run_head(m, m->buf.h, tokens, labels, E, S, losses_out);
   return check_device(m, "mpz_forward_perturbed");
+}
+
+mpz_status mpz_forward_copies(mpz_model* m, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
+                              int32_t copy_begin, int32_t n_copies, float* losses_out) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_forward_copies: NULL model");
+  if (!tokens || !losses_out) return fail(m, MPZ_ERR_NULL, "mpz_forward_copies: NULL tokens or losses_out");
+  if (m->cfg.loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS && !labels) return fail(m, MPZ_ERR_NULL, "this loss mode needs labels");
+  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_forward_copies before mpz_regen_noise");
+  if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
+  if (copy_begin < 0 || n_copies < 1 || copy_begin + n_copies > 2 * m->q) return fail(m, MPZ_ERR_SHAPE, "copy range outside [0, 2q)");
+  m->cb = copy_begin; m->nc = n_copies;
+  float* h = m->buf.h + (size_t)copy_begin * E * S * m->cfg.d_model;
+  run_embed(m, tokens, E, S, h);
+  run_layers(m, h, 0, m->cfg.n_layers, E, S);
+  run_head(m, h, tokens, labels, E, S, losses_out + copy_begin);
+  m->cb = 0; m->nc = 2 * m->q;
+  return check_device(m, "mpz_forward_copies");
 }
 
 mpz_status mpz_debug_embed(mpz_model* m, const int32_t* tokens, int32_t E, int32_t S, float* h_out) {

@@ -86,6 +86,9 @@ def load_library() -> C.CDLL:
     lib.mpz_regen_noise.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_int32, C.c_float]
     lib.mpz_forward_perturbed.restype = C.c_int
     lib.mpz_forward_perturbed.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    lib.mpz_forward_copies.restype = C.c_int
+    lib.mpz_forward_copies.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                       C.c_void_p]
     lib.mpz_zo_update.restype = C.c_int
     lib.mpz_zo_update.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]
     lib.mpz_debug_noise.restype = C.c_int
@@ -169,6 +172,12 @@ def mpz_regen_noise(handle, seed: int, step: int, q: int, eps: float):
 
 def mpz_forward_perturbed(handle, tokens_ptr: int, labels_ptr: Optional[int], E: int, S: int, losses_ptr: int):
     _check(load_library().mpz_forward_perturbed(handle, tokens_ptr, labels_ptr, E, S, losses_ptr), handle)
+
+
+def mpz_forward_copies(handle, tokens_ptr: int, labels_ptr: Optional[int], E: int, S: int, copy_begin: int,
+                       n_copies: int, losses_ptr: int):
+    _check(load_library().mpz_forward_copies(handle, tokens_ptr, labels_ptr, E, S, copy_begin, n_copies, losses_ptr),
+           handle)
 
 
 def mpz_zo_update(handle, losses_ptr: int, lr: float, proj_grads_ptr: Optional[int]):
@@ -348,6 +357,18 @@ class ZoModel:
         E, S = tokens.shape
         mpz_forward_perturbed(self.handle, tokens.data_ptr(), None if labels is None else labels.data_ptr(), E, S,
                               self.losses.data_ptr())
+        return self.losses[:2 * self.q]
+
+    def forward_copies(self, tokens, labels, copy_begin: int, n_copies: int):
+        E, S = tokens.shape
+        mpz_forward_copies(self.handle, tokens.data_ptr(), None if labels is None else labels.data_ptr(), E, S,
+                           copy_begin, n_copies, self.losses.data_ptr())
+        return self.losses[:2 * self.q]
+
+    def forward_sequential(self, tokens, labels=None, group: int = 1):
+        """All 2q copies in passes of `group` copies each (group = 1: one forward pass per perturbed copy)."""
+        for c in range(0, 2 * self.q, group):
+            self.forward_copies(tokens, labels, c, min(group, 2 * self.q - c))
         return self.losses[:2 * self.q]
 
     def zo_update(self, lr: Optional[float] = None):

@@ -1,0 +1,49 @@
+"""GPU: evaluating the copies one at a time (or in groups) gives each copy exactly the loss of the batched pass,
+for the fp32 path and for the bf16 MFMA path, so the batched MP-LoRA pass changes the schedule, not the numbers."""
+import numpy as np
+import pytest
+
+import workloads as W
+from gpu_helpers import make_bundle, gpu_model
+from small_workloads import MINI_LLAMA
+from test_gpu_bf16 import CASES
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("w", [W.get_workload("c1_tiny_fp32"), MINI_LLAMA, CASES["c2_2layers"], CASES["llama_mfma"]],
+                         ids=["c1", "mini_llama_f32", "c2_2layers", "llama_mfma"])
+def test_sequential_and_grouped_passes_are_bit_identical_to_the_batched_pass(w):
+    import torch
+    b = make_bundle(w, b_std=0.01)
+    m = gpu_model(b)
+    tok = torch.from_numpy(b["tokens"]).cuda()
+    lab = torch.from_numpy(b["labels"]).cuda()
+    m.regen_noise(3456, 0)
+    batched = m.forward_perturbed(tok, lab).cpu().numpy().copy()
+    m.losses.zero_()
+    seq = m.forward_sequential(tok, lab, group=1).cpu().numpy().copy()
+    m.losses.zero_()
+    outer = m.forward_sequential(tok, lab, group=2).cpu().numpy().copy()
+    assert np.array_equal(batched.view(np.uint32), seq.view(np.uint32))
+    assert np.array_equal(batched.view(np.uint32), outer.view(np.uint32))
+    assert len(set(batched.tolist())) == 2 * w.q              # copies really differ
+
+
+def test_copy_range_errors():
+    import torch
+    import paper_2409_15520_amd as M
+    w = W.get_workload("c1_tiny_fp32")
+    b = make_bundle(w)
+    m = gpu_model(b)
+    tok = torch.from_numpy(b["tokens"]).cuda()
+    lab = torch.from_numpy(b["labels"]).cuda()
+    with pytest.raises(M.MpzError) as e:
+        m.forward_copies(tok, lab, 0, 1)
+    assert e.value.status == 5
+    m.regen_noise(1, 0)
+    for cb, nc in ((-1, 1), (0, 0), (3, 2), (4, 1)):
+        with pytest.raises(M.MpzError) as e:
+            m.forward_copies(tok, lab, cb, nc)
+        assert e.value.status == 3
+    torch.cuda.synchronize()
