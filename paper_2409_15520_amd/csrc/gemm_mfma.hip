@@ -171,32 +171,29 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
 #undef MPZ_STORE_LDS
 #undef MPZ_COMPUTE
 
-  // per-copy low-rank term: extra K-steps with the packed factor [B_hi | B_lo] of this block's copy against
-  // the duplicated bottleneck activations [t | t]  (block rows never straddle copies, segments are tile-aligned)
+  // per-copy low-rank term: extra K-steps with the packed factor [B_hi | B_lo] of a copy against the duplicated
+  // bottleneck activations [t | t].  Copies are whole multiples of 32 rows, so every 32-row MFMA tile belongs to
+  // one copy (a block tile may span several); segments are aligned to the block tile.
   if (!DUAL) {
     for (int s = 0; s < a.n_seg; ++s) {
       const MfmaLoraSeg& sg = a.seg[s];
       if (n0 < sg.col_begin || n0 >= sg.col_end) continue;
-      const int copy = m0 / a.rows_per_copy;
-      const uint16_t* bp = (const uint16_t*)sg.bp + (size_t)copy * sg.copy_stride;
       const uint16_t* tp = (const uint16_t*)sg.tp;
       for (int ks = 0; ks < sg.rp; ks += 16) {
-        bf16x8 fw[NI], fx[NJ];
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-          int n = n0 + wn + i * 32 + lrow - sg.col_begin;
-          fw[i] = as_frag(*(const u32x4*)(bp + (size_t)n * sg.rp + ks + lhalf * 8));
-        }
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
-          int m = m0 + wm + j * 32 + lrow;
-          fx[j] = as_frag(*(const u32x4*)(tp + (size_t)m * sg.rp + ks + lhalf * 8));
+          int mt = m0 + wm + j * 32;                       // first row of this MFMA tile
+          mt = mt < a.M ? mt : a.M - 32;                   // tiles past the end compute discarded values in bounds
+          const int copy = mt / a.rows_per_copy;
+          const uint16_t* bp = (const uint16_t*)sg.bp + (size_t)copy * sg.copy_stride;
+          const bf16x8 fx = as_frag(*(const u32x4*)(tp + (size_t)(mt + lrow) * sg.rp + ks + lhalf * 8));
+#pragma unroll
+          for (int i = 0; i < NI; ++i) {
+            const int n = n0 + wn + i * 32 + lrow - sg.col_begin;
+            const bf16x8 fw = as_frag(*(const u32x4*)(bp + (size_t)n * sg.rp + ks + lhalf * 8));
+            acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fx, acc[0][i][j], 0, 0, 0);
+          }
         }
-#pragma unroll
-        for (int i = 0; i < NI; ++i)
-#pragma unroll
-          for (int j = 0; j < NJ; ++j)
-            acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fx[j], acc[0][i][j], 0, 0, 0);
       }
     }
   }
@@ -402,7 +399,8 @@ int tile_bm(int cfg) { return (cfg == 3 || (cfg >= 4 && cfg <= 6)) ? 256 : 128; 
 
 bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
   const int bn = tile_bn(cfg), bm = tile_bm(cfg);
-  if (a.n_seg > 0 && (a.rows_per_copy % bm || a.M % bm)) return false;
+  (void)bm;
+  if (a.n_seg > 0 && (a.rows_per_copy % 32 || a.M % 32)) return false;
   for (int s = 0; s < a.n_seg; ++s)
     if (a.seg[s].col_begin % bn || a.seg[s].col_end % bn) return false;
   return true;

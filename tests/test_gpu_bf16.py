@@ -20,6 +20,8 @@ CASES = {
     "mini_llama": MINI_LLAMA.with_(dtype="bf16"),
     "mini_opt": MINI_OPT.with_(dtype="bf16", loss_mode="next_token_all_pos"),
     "c2_2layers": W.get_workload("c2_opt125m").with_(n_layers=2),
+    # 96 rows per copy: block tiles of 128 rows span two copies, every 32-row MFMA tile still belongs to one
+    "c2_ragged_copies": W.get_workload("c2_opt125m").with_(n_layers=1, q=3, E=1, S=96),
     # Llama-style shapes that the MFMA kernels accept: adapters on q, k, v, o with r = 16, grouped-query
     # attention, rotary positions, SwiGLU (gate|up tiles fused), next-token loss over the whole vocabulary
     "llama_mfma": W.Workload(
@@ -31,7 +33,8 @@ CASES = {
 
 @pytest.mark.parametrize("name,eps,b_std", [("mini_llama", 1e-3, 0.01), ("mini_opt", 1e-3, 0.01),
                                             ("c2_2layers", 1e-3, 0.01), ("c2_2layers", 5e-2, 0.05),
-                                            ("llama_mfma", 1e-3, 0.01), ("llama_mfma", 5e-2, 0.05)])
+                                            ("llama_mfma", 1e-3, 0.01), ("llama_mfma", 5e-2, 0.05),
+                                            ("c2_ragged_copies", 5e-2, 0.05)])
 def test_each_stage_on_oracle_inputs(name, eps, b_std):
     """Second c2 case: perturbation and B large enough that the low-rank term moves the projections by
     O(10%), so a wrong or missing per-copy term cannot hide under the rounding tolerance."""

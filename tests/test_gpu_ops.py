@@ -19,7 +19,8 @@ def _bf16_tensor(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(torch.bfloat16).contiguous()
 
 
-@pytest.mark.parametrize("name,simple", [("c2_2layers", False), ("llama_mfma", False), ("c2_2layers", True)])
+@pytest.mark.parametrize("name,simple", [("c2_2layers", False), ("llama_mfma", False), ("c2_2layers", True),
+                                         ("c2_ragged_copies", False)])
 def test_qkv_projection_matches_the_mp_lora_layer_equation(name, simple):
     import torch
     import paper_2409_15520_amd as M
