@@ -216,6 +216,10 @@ mpz_status mpz_debug_gemm_bf16(int32_t M, int32_t N, int32_t K, const void* x, c
  * Invalidates the perturbed copies: call mpz_regen_noise again. */
 mpz_status mpz_debug_set_kernel_path(mpz_model* m, int32_t simple_only);
 
+/* Test hook: force one block-tile configuration (1..8; 0 = chosen by shape) for every MFMA GEMM of the model's
+ * passes, so that small test shapes can exercise the configurations large workloads select.  Errors: NULL, CONFIG. */
+mpz_status mpz_debug_set_tile_config(mpz_model* m, int32_t tile_cfg);
+
 /* Measurement hook: between _begin and _end every kernel launch of the three hot-path calls is bracketed by HIP
  * events on the model's stream and booked under a category.  _end synchronises the stream and fills
  * out[MPZ_PROF_COUNT] [host] with, per category, the summed kernel time (ms), the number of launches, the

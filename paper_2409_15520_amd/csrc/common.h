@@ -68,6 +68,8 @@ struct LinearArgs {
   const float* residual;      // [M, N] fp32 added before the store, or null
   int out_kind;               // 0: model dtype, 1: fp32, 2: accumulate type staging (double for f32 models, float for bf16)
   void* out;                  // [M, N]
+  // optional fused rotary embedding (MFMA path, model-dtype output): see MfmaGemmArgs
+  const float* rope_cos; const float* rope_sin; int rope_cols, rope_dh, S;
 };
 void launch_linear_simple(hipStream_t st, const LinearArgs& a);
 
@@ -112,7 +114,10 @@ struct MfmaGemmArgs {
   int act;                      // -1 none, MPZ_ACT_RELU, MPZ_ACT_GELU_ERF (ignored when dual: SiLU(gate) * up)
   const float* residual;        // [M, ldo] fp32 or null
   int out_f32; void* out; int ldo;
-  int tile_cfg;                 // 0 = choose by shape; 1..4 force a tile configuration (measurement)
+  int tile_cfg;                 // 0 = choose by shape; 1..8 force a tile configuration (measurement)
+  // fused rotary embedding (bf16 output only): columns [0, rope_cols) are heads of width rope_dh rotated by the
+  // position m % S with tables [max_seq, rope_dh / 2]
+  const float* rope_cos; const float* rope_sin; int rope_cols, rope_dh, S;
 };
 bool mfma_gemm_supported(const MfmaGemmArgs& a);
 void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a);

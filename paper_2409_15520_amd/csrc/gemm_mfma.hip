@@ -27,7 +27,9 @@ __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + e
 // NI x NJ MFMA tiles.  NSET = register sets of tiles in flight.  DUAL: two weight tiles (rows n and n + dual_offset:
 // SwiGLU gate and up) against the same X tile.  LDS rows are padded by 16 B, which keeps ds_read_b128 of 32 rows
 // conflict-free for BK = 32 and BK = 64.
-template <int BN, int BM, int BK, int WGN, int WGM, int NSET, bool DUAL>
+// HP > 0: rotary embedding fused into the epilogue for head width 64 * HP (the partner column d_head/2 away sits in
+// the same lane, HP MFMA tiles further), for output columns below rope_cols; the result is stored as bf16.
+template <int BN, int BM, int BK, int WGN, int WGM, int NSET, bool DUAL, int HP>
 __global__ void __launch_bounds__(64 * WGN * WGM, (BN * BM * (DUAL ? 2 : 1) <= 256 * 128 && WGN * WGM == 4) ? 2 : 1)
 gemm_bf16_kernel(MfmaGemmArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -195,6 +197,51 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
           }
         }
       }
+    }
+  }
+
+  if constexpr (HP > 0) {
+    static_assert(!DUAL && NI >= 2 * HP && NI % (2 * HP) == 0, "a wave tile must hold whole heads");
+    if (n0 < a.rope_cols) {
+      // q / k columns: y_lo = x_lo cos - x_hi sin, y_hi = x_hi cos + x_lo sin with (lo, hi) = columns (c, c + d_head/2)
+      const int half = 32 * HP;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const int m = m0 + wm + j * 32 + lrow;
+        if (m >= a.M) continue;
+        const int pos = m % a.S;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+          if ((i / HP) % 2 != 0) continue;                  // upper halves are written together with their lower half
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int n = n0 + wn + i * 32 + g * 8 + lhalf * 4;
+            if (n >= a.N) continue;
+            const int c = (i % HP) * 32 + g * 8 + lhalf * 4;  // column inside the lower half of the head
+            float lo[4], hi[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { lo[e] = acc[0][i][j][g * 4 + e]; hi[e] = acc[0][i + HP][j][g * 4 + e]; }
+            if (a.bias != nullptr) {
+              f32x4 b0 = *(const f32x4*)(a.bias + n), b1 = *(const f32x4*)(a.bias + n + half);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) { lo[e] += b0[e]; hi[e] += b1[e]; }
+            }
+            const f32x4 cs = *(const f32x4*)(a.rope_cos + (size_t)pos * half + c);
+            const f32x4 sn = *(const f32x4*)(a.rope_sin + (size_t)pos * half + c);
+            float ylo[4], yhi[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { ylo[e] = lo[e] * cs[e] - hi[e] * sn[e]; yhi[e] = hi[e] * cs[e] + lo[e] * sn[e]; }
+            const size_t o = (size_t)m * a.ldo + n;
+            u32x2 p0 = {(uint32_t)f32_to_bf16(ylo[0]).bits | ((uint32_t)f32_to_bf16(ylo[1]).bits << 16),
+                        (uint32_t)f32_to_bf16(ylo[2]).bits | ((uint32_t)f32_to_bf16(ylo[3]).bits << 16)};
+            u32x2 p1 = {(uint32_t)f32_to_bf16(yhi[0]).bits | ((uint32_t)f32_to_bf16(yhi[1]).bits << 16),
+                        (uint32_t)f32_to_bf16(yhi[2]).bits | ((uint32_t)f32_to_bf16(yhi[3]).bits << 16)};
+            *(u32x2*)((uint16_t*)a.out + o) = p0;
+            *(u32x2*)((uint16_t*)a.out + o + half) = p1;
+          }
+        }
+      }
+      return;
     }
   }
 
@@ -381,17 +428,17 @@ __global__ void __launch_bounds__(256) pack_factors_kernel(const float* __restri
 //   3 128 256  32  2    61.4 KB   general, tall
 //   4 256 256  32  1    81.9 KB   large problems (lowest LDS traffic per MFMA)
 //  dual (SwiGLU): 2 x 128 x 128 x 32, 2 sets, 61.4 KB
-template <int BN, int BM, int BK, int WGN, int WGM, int NSET, bool DUAL>
+template <int BN, int BM, int BK, int WGN, int WGM, int NSET, bool DUAL, int HP = 0>
 void launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
   constexpr size_t lds = (size_t)2 * ((DUAL ? 2 : 1) * BN + BM) * (BK + 8) * 2;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_bf16_kernel<BN, BM, BK, WGN, WGM, NSET, DUAL>,
+    (void)hipFuncSetAttribute((const void*)gemm_bf16_kernel<BN, BM, BK, WGN, WGM, NSET, DUAL, HP>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_set = true;
   }
   const int tiles = ((a.N + BN - 1) / BN) * ((a.M + BM - 1) / BM);
-  gemm_bf16_kernel<BN, BM, BK, WGN, WGM, NSET, DUAL><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
+  gemm_bf16_kernel<BN, BM, BK, WGN, WGM, NSET, DUAL, HP><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
 }
 
 int tile_bn(int cfg) { return (cfg == 2 || cfg >= 4) ? 256 : 128; }   // 7, 8: 256 x 128
@@ -426,6 +473,13 @@ bool mfma_gemm_supported(const MfmaGemmArgs& a) {
     if (a.seg[s].rp % 16) return false;
   if (!cfg_ok(a, 1)) return false;
   if (a.dual && a.n_seg) return false;
+  if (a.rope_cos != nullptr) {
+    // the rotated column range must end on a block-tile boundary, and a wave tile must hold whole heads
+    const int cfg = choose_cfg(a), bn = tile_bn(cfg), tn = cfg == 5 ? 128 : 64;
+    if (a.dual || a.out_f32 || a.act >= 0 || a.residual != nullptr || !a.rope_sin || a.S < 1) return false;
+    if ((cfg != 5 && cfg != 1) || (a.rope_dh != 64 && a.rope_dh != 128) || a.rope_dh > tn) return false;
+    if (a.rope_cols % bn || a.rope_cols > a.N || a.N % a.rope_dh) return false;
+  }
   return true;
 }
 
@@ -434,6 +488,15 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     const long tb = (long)((a.N + 127) / 128) * ((a.M + 255) / 256);
     if ((a.tile_cfg == 0 && tb >= 512) || a.tile_cfg == 5) launch_cfg<128, 256, 32, 2, 4, 2, true>(st, a);   // 2 x 128 x 256, 8 waves
     else launch_cfg<128, 128, 32, 2, 2, 2, true>(st, a);
+    return;
+  }
+  if (a.rope_cos != nullptr) {             // fused rotary epilogue: only the two configurations the model path uses
+    if (choose_cfg(a) == 5) {
+      if (a.rope_dh == 64) launch_cfg<256, 256, 32, 2, 4, 2, false, 1>(st, a);
+      else launch_cfg<256, 256, 32, 2, 4, 2, false, 2>(st, a);
+    } else {
+      launch_cfg<128, 128, 64, 2, 2, 2, false, 1>(st, a);
+    }
     return;
   }
   switch (choose_cfg(a)) {

@@ -160,6 +160,7 @@ struct mpz_model {
   bool have_noise = false;
   uint64_t seed = 0; uint32_t step = 0; int q = 0; float eps = 0.f;
   int cb = 0, nc = 0;                           // copies [cb, cb + nc) processed by the current pass
+  int force_tile_cfg = 0;                       // test hook: GEMM block-tile configuration (0 = by shape)
   std::string err;
   // optional per-launch timing by kernel category (mpz_profile_begin / _end)
   // bf16 MFMA path
@@ -239,8 +240,22 @@ Buffers view(const mpz_model* m, int E, int S) {
   return b;
 }
 
-// Every base-weight GEMM of the pass goes through here (kernel selection and optional timing).
-void gemm(mpz_model* m, const LinearArgs& a) {
+// Every base-weight GEMM of the pass goes through here (kernel selection and optional timing).  Returns false
+// (nothing launched) only when a fused rotary epilogue was requested and the shape does not allow it.
+bool gemm(mpz_model* m, const LinearArgs& a) {
+  if (a.rope_cos != nullptr) {
+    if (!(m->use_mfma && a.dtype == MPZ_DTYPE_BF16 && (a.n_seg == 0 || a.mfma_lora))) return false;
+    MfmaGemmArgs g{};
+    g.M = a.M; g.N = a.N; g.K = a.K; g.x = a.x; g.w = a.w; g.w_rows = a.N; g.bias = a.bias;
+    g.n_seg = a.n_seg; g.rows_per_copy = a.rows_per_copy; g.act = -1; g.out_f32 = 0; g.out = a.out; g.ldo = a.N;
+    for (int i = 0; i < a.n_seg; ++i) g.seg[i] = a.mseg[i];
+    g.rope_cos = a.rope_cos; g.rope_sin = a.rope_sin; g.rope_cols = a.rope_cols; g.rope_dh = a.rope_dh; g.S = a.S;
+    g.tile_cfg = m->force_tile_cfg;
+    if (!mfma_gemm_supported(g)) return false;
+    ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)a.N * a.K, 2.0 * ((double)a.M * a.K + (double)a.N * a.K + (double)a.M * a.N));
+    launch_gemm_mfma(m->stream, g);
+    return true;
+  }
   ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)a.N * a.K,
                esz(m) * ((double)a.M * a.K + (double)a.N * a.K) + (a.out_kind == 0 ? esz(m) : 4.0) * a.M * (double)a.N +
                    (a.residual ? 4.0 * a.M * (double)a.N : 0.0));
@@ -249,10 +264,12 @@ void gemm(mpz_model* m, const LinearArgs& a) {
     g.M = a.M; g.N = a.N; g.K = a.K; g.x = a.x; g.w = a.w; g.w_rows = a.N; g.bias = a.bias; g.dual = 0; g.dual_offset = 0;
     g.n_seg = a.n_seg; g.rows_per_copy = a.rows_per_copy; g.act = a.act; g.residual = a.residual;
     g.out_f32 = a.out_kind != 0; g.out = a.out; g.ldo = a.N;   // bf16 models stage in fp32
+    g.tile_cfg = m->force_tile_cfg;
     for (int i = 0; i < a.n_seg; ++i) g.seg[i] = a.mseg[i];
-    if (mfma_gemm_supported(g)) { launch_gemm_mfma(m->stream, g); return; }
+    if (mfma_gemm_supported(g)) { launch_gemm_mfma(m->stream, g); return true; }
   }
   launch_linear_simple(m->stream, a);
+  return true;
 }
 
 // SwiGLU up-projection: gate and up tiles in one kernel, u = SiLU(gate) * up rounded once
@@ -261,6 +278,7 @@ bool gemm_swiglu_mfma(mpz_model* m, const LinearArgs& a, int f, void* u_out) {
   MfmaGemmArgs g{};
   g.M = a.M; g.N = f; g.K = a.K; g.x = a.x; g.w = a.w; g.w_rows = 2 * f; g.bias = a.bias; g.dual = 1; g.dual_offset = f;
   g.rows_per_copy = a.rows_per_copy; g.act = -1; g.out_f32 = 0; g.out = u_out; g.ldo = f;
+  g.tile_cfg = m->force_tile_cfg;
   if (!mfma_gemm_supported(g)) return false;
   ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)(2 * f) * a.K,
                2.0 * ((double)a.M * a.K + 2.0 * f * a.K + (double)a.M * f));
@@ -293,7 +311,9 @@ void run_embed(mpz_model* m, const int32_t* tokens, int E, int S, float* h) {
 }
 
 // q/k/v projections of the MP-LoRA layer for all stacked copies: x = b.x [T, d] -> out [T, d + 2 d_kv]
-void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, int out_kind, void* out) {
+// rope: apply the rotary embedding to q and k and write the operand type to b.qkv (fused into the GEMM epilogue
+// where the shape allows, else through the accumulate-type staging buffer); otherwise write `out` as `out_kind` says.
+void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, bool rope, int out_kind, void* out) {
   const mpz_config& c = m->cfg;
   hipStream_t st = m->stream;
   const mpz_layer_weights& lw = m->layers[l];
@@ -349,6 +369,17 @@ void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, int out_kind, 
       ProfScope ps(m, MPZ_PROF_LORA_DOWN, 2.0 * T * (double)d * nt * r, esz(m) * T * ((double)d + (double)nt * r));
       launch_lora_down_simple(st, da);
     }
+    if (rope) {
+      qa.out_kind = 0; qa.out = b.qkv;
+      qa.rope_cos = b.rope_cos; qa.rope_sin = b.rope_sin; qa.rope_cols = d + dkv; qa.rope_dh = dh; qa.S = S;
+      if (gemm(m, qa)) return;
+      qa.rope_cos = qa.rope_sin = nullptr;
+      qa.out_kind = 2; qa.out = b.stage;
+      gemm(m, qa);
+      ProfScope ps(m, MPZ_PROF_ROPE, 0.0, (double)T * nqkv * (acc_size(c.dtype) + esz(m)));
+      launch_rope_convert(st, c.dtype, b.stage, b.qkv, T, S, nqkv, dh, c.n_heads + c.n_kv_heads, b.rope_cos, b.rope_sin);
+      return;
+    }
     qa.out_kind = out_kind; qa.out = out;
     gemm(m, qa);
   }
@@ -370,11 +401,7 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     const mpz_layer_weights& lw = m->layers[l];
     norm(m, b.h, d, lw.ln1_g, lw.ln1_b, b.x, T);
 
-    run_qkv(m, b, l, E, S, rope ? 2 : 0, rope ? b.stage : b.qkv);
-    if (rope) {
-      ProfScope ps(m, MPZ_PROF_ROPE, 0.0, (double)T * nqkv * (acc_size(c.dtype) + esz(m)));
-      launch_rope_convert(st, c.dtype, b.stage, b.qkv, T, S, nqkv, dh, c.n_heads + c.n_kv_heads, b.rope_cos, b.rope_sin);
-    }
+    run_qkv(m, b, l, E, S, rope, 0, b.qkv);
 
     {
       // causal-useful work: Q K^T and P V over the S (S + 1) / 2 visible (query, key) pairs of every head
@@ -722,7 +749,7 @@ mpz_status mpz_debug_qkv_projection(mpz_model* m, const void* x, int32_t layer, 
   if (m->cfg.dtype != MPZ_DTYPE_BF16) return fail(m, MPZ_ERR_CONFIG, "mpz_debug_qkv_projection is for bf16 models");
   Buffers b = m->buf;
   b.x = const_cast<void*>(x);
-  run_qkv(m, b, layer, E, S, 1, out);
+  run_qkv(m, b, layer, E, S, false, 1, out);
   return check_device(m, "mpz_debug_qkv_projection");
 }
 
@@ -748,6 +775,13 @@ mpz_status mpz_debug_gemm_bf16(int32_t M, int32_t N, int32_t K, const void* x, c
   if (!mfma_gemm_supported(g)) return fail(nullptr, MPZ_ERR_SHAPE, "shape not supported by the MFMA GEMM (K % 64, N % 4)");
   launch_gemm_mfma((hipStream_t)hip_stream, g);
   return check_device(nullptr, "mpz_debug_gemm_bf16");
+}
+
+mpz_status mpz_debug_set_tile_config(mpz_model* m, int32_t tile_cfg) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_set_tile_config: NULL model");
+  if (tile_cfg < 0 || tile_cfg > 8) return fail(m, MPZ_ERR_CONFIG, "tile configuration outside [0, 8]");
+  m->force_tile_cfg = tile_cfg;
+  return MPZ_OK;
 }
 
 mpz_status mpz_debug_set_kernel_path(mpz_model* m, int32_t simple_only) {

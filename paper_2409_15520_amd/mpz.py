@@ -110,6 +110,8 @@ def load_library() -> C.CDLL:
     lib.mpz_debug_gemm_bf16.restype = C.c_int
     lib.mpz_debug_gemm_bf16.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                         C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    lib.mpz_debug_set_tile_config.restype = C.c_int
+    lib.mpz_debug_set_tile_config.argtypes = [C.c_void_p, C.c_int32]
     lib.mpz_debug_set_kernel_path.restype = C.c_int
     lib.mpz_debug_set_kernel_path.argtypes = [C.c_void_p, C.c_int32]
     lib.mpz_profile_begin.restype = C.c_int
@@ -220,6 +222,10 @@ def mpz_debug_gemm_bf16(M: int, N: int, K: int, x_ptr: int, w_ptr: int, bias_ptr
                         out_f32: bool, stream_ptr: int, tile_cfg: int = 0):
     _check(load_library().mpz_debug_gemm_bf16(M, N, K, x_ptr, w_ptr, bias_ptr, act, out_ptr, int(out_f32), tile_cfg,
                                               stream_ptr))
+
+
+def mpz_debug_set_tile_config(handle, tile_cfg: int):
+    _check(load_library().mpz_debug_set_tile_config(handle, tile_cfg), handle)
 
 
 def mpz_debug_set_kernel_path(handle, simple_only: bool):

@@ -18,13 +18,27 @@ CASES = {
 }
 
 
-@pytest.mark.parametrize("name", list(CASES))
-def test_full_width_stages_and_losses(name):
+_ORACLE = {}
+
+
+def _oracle(name):
+    if name not in _ORACLE:
+        b = make_bundle(CASES[name], b_std=0.01)
+        _ORACLE[name] = (b,) + oracle_traces(b)
+    return _ORACLE[name]
+
+
+@pytest.mark.parametrize("name,tile_cfg", [("c3_width", 0), ("c4_width", 0), ("c5_width", 0),
+                                           ("c3_width", 5), ("c4_width", 5), ("c5_width", 5)])
+def test_full_width_stages_and_losses(name, tile_cfg):
+    """tile_cfg 5 forces the 256 x 256 eight-wave tiles (with the fused rotary epilogue for both head widths and the
+    eight-wave SwiGLU kernel) that the full-size workloads select."""
     import torch
+    import paper_2409_15520_amd as M
     w = CASES[name]
-    b = make_bundle(w, b_std=0.01)
-    H, losses = oracle_traces(b)
+    b, H, losses = _oracle(name)
     m = gpu_model(b)
+    M.mpz_debug_set_tile_config(m.handle, tile_cfg)
     m.regen_noise(3456, 0)
     tok = torch.from_numpy(b["tokens"]).cuda()
     lab = torch.from_numpy(b["labels"]).cuda()
