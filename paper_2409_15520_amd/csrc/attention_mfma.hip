@@ -22,18 +22,9 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int QB = 128;   // queries per block
 
-__device__ __forceinline__ uint32_t pack2(float a, float b) {
-  return (uint32_t)f32_to_bf16(a).bits | ((uint32_t)f32_to_bf16(b).bits << 16);
-}
-
-// exp(x) for x <= 0 through the hardware exp2: x log2(e) is split into a rounded product t and its exact
-// remainder r (fma) plus the low part of log2(e), exp2(t + r) = exp2(t) (1 + r ln 2); relative error ~1e-7.
-__device__ __forceinline__ float exp_neg(float x) {
-  const float L2E = 1.4426950408889634f, L2E_LO = 1.925963033500011e-8f;
-  float t = x * L2E;
-  float r = fmaf(x, L2E, -t) + x * L2E_LO;
-  return __builtin_amdgcn_exp2f(t) * fmaf(r, 0.6931471805599453f, 1.0f);
-}
+// The softmax is VALU-bound at these head sizes (16 scores per lane and tile against 12 MFMAs), so the score
+// path is kept to one fma and one hardware exp2 per element: exp(scale (s - max)) = exp2(s c - max c) with
+// c = scale log2(e); masking only on tiles that touch the diagonal; bf16 rounding in hardware.
 
 // KC = keys per LDS chunk.  When every key the block can see fits one chunk, K and V are loaded once and both
 // passes run from LDS; otherwise each pass streams the chunks.
@@ -83,28 +74,36 @@ __global__ void __launch_bounds__(256) attention_mfma_kernel(const uint16_t* __r
     int kg = (c) * KC + key; kg = kg < S ? kg : S - 1;                             \
     *(u32x4*)(sK + key * KS + ch * 8) = *(const u32x4*)(kbase + (size_t)kg * qkv_stride + ch * 8); \
   }
+  // V^T into LDS: a thread takes two consecutive keys and 8 head-dim elements and writes 8 words
+  // {V[key][dv], V[key+1][dv]}; consecutive lanes hold consecutive key pairs, so the 32-bit writes of a wave fall
+  // into consecutive banks (a per-element 16-bit scatter would serialise on a handful of banks).
 #define MPZ_LOAD_V(c)                                                              \
-  for (int i = tid; i < KC * CPR; i += 256) {                                      \
-    int key = i / CPR, ch = i % CPR;                                               \
-    int kg = (c) * KC + key; kg = kg < S ? kg : S - 1;                             \
-    u32x4 v = *(const u32x4*)(vbase + (size_t)kg * qkv_stride + ch * 8);           \
+  for (int i = tid; i < (KC / 2) * CPR; i += 256) {                                \
+    int kp = i % (KC / 2), ch = i / (KC / 2);                                      \
+    int k0 = (c) * KC + 2 * kp, k1 = k0 + 1;                                       \
+    k0 = k0 < S ? k0 : S - 1; k1 = k1 < S ? k1 : S - 1;                            \
+    u32x4 v0 = *(const u32x4*)(vbase + (size_t)k0 * qkv_stride + ch * 8);          \
+    u32x4 v1 = *(const u32x4*)(vbase + (size_t)k1 * qkv_stride + ch * 8);          \
+    uint32_t* dst = (uint32_t*)sVt + kp;                                           \
     _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                \
-      sVt[(ch * 8 + 2 * e) * VS + key] = (uint16_t)(v[e] & 0xFFFFu);               \
-      sVt[(ch * 8 + 2 * e + 1) * VS + key] = (uint16_t)(v[e] >> 16);               \
+      dst[(ch * 8 + 2 * e) * (VS / 2)] = (v0[e] & 0xFFFFu) | (v1[e] << 16);        \
+      dst[(ch * 8 + 2 * e + 1) * (VS / 2)] = (v0[e] >> 16) | (v1[e] & 0xFFFF0000u); \
     }                                                                              \
   }
-  // scores of one 32-key tile against this wave's 32 queries; lane: query qi, keys kt0 + (e/4)*8 + lhalf*4 + e%4
-#define MPZ_SCORE_TILE(t_local, kt0, s)                                            \
+  // raw scores (q . k, unscaled) of one 32-key tile against this wave's 32 queries; lane: query qi,
+  // keys kt0 + (e/4)*8 + lhalf*4 + e%4.  Tiles that reach past the diagonal get -inf on the masked entries.
+#define MPZ_SCORE_TILE(t_local, kt0, sacc)                                         \
   {                                                                                \
-    f32x16 sacc;                                                                   \
     _Pragma("unroll") for (int e = 0; e < 16; ++e) sacc[e] = 0.f;                  \
     _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                               \
       bf16x8 fk = __builtin_bit_cast(bf16x8, *(const u32x4*)(sK + ((t_local) * 32 + lrow) * KS + j * 16 + lhalf * 8)); \
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk, fq[j], sacc, 0, 0, 0);    \
     }                                                                              \
-    _Pragma("unroll") for (int e = 0; e < 16; ++e) {                               \
-      int key = (kt0) + (e >> 2) * 8 + lhalf * 4 + (e & 3);                        \
-      s[e] = key <= qi ? sacc[e] * scale : -1e30f;                                 \
+    if ((kt0) + 31 > q0) {                                                         \
+      _Pragma("unroll") for (int e = 0; e < 16; ++e) {                             \
+        int key = (kt0) + (e >> 2) * 8 + lhalf * 4 + (e & 3);                      \
+        sacc[e] = key <= qi ? sacc[e] : -INFINITY;                                 \
+      }                                                                            \
     }                                                                              \
   }
 
@@ -119,16 +118,15 @@ __global__ void __launch_bounds__(256) attention_mfma_kernel(const uint16_t* __r
     for (int t = 0; t < KC / 32; ++t) {
       int kt0 = c * KC + t * 32;
       if (kt0 > wave_last_q) continue;            // tile entirely in this wave's future
-      float s[16];
-      MPZ_SCORE_TILE(t, kt0, s)
+      f32x16 sc;
+      MPZ_SCORE_TILE(t, kt0, sc)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) mx = s[e] > mx ? s[e] : mx;
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[e]);
     }
   }
-  {
-    float other = __shfl_xor(mx, 32, 64);
-    mx = other > mx ? other : mx;
-  }
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float c1 = scale * 1.4426950408889634f;   // scale > 0: the maximum of the raw scores is the maximum
+  const float mx2 = mx * c1;
 
   // ---- pass 2: P = bf16(exp(s - max)), O^T += V^T P, l += P ----
   f32x16 oacc[NT];
@@ -148,14 +146,16 @@ __global__ void __launch_bounds__(256) attention_mfma_kernel(const uint16_t* __r
     for (int t = 0; t < KC / 32; ++t) {
       int kt0 = c * KC + t * 32;
       if (kt0 > wave_last_q) continue;
-      float s[16];
-      MPZ_SCORE_TILE(t, kt0, s)
+      f32x16 sc;
+      MPZ_SCORE_TILE(t, kt0, sc)
       uint32_t pw[8];                             // 16 probabilities as bf16 pairs
 #pragma unroll
       for (int e = 0; e < 16; e += 2) {
-        bf16_t b0 = f32_to_bf16(exp_neg(s[e] - mx)), b1 = f32_to_bf16(exp_neg(s[e + 1] - mx));
-        lsum += bf16_to_f32(b0) + bf16_to_f32(b1);
-        pw[e >> 1] = (uint32_t)b0.bits | ((uint32_t)b1.bits << 16);
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[e], c1, -mx2));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[e + 1], c1, -mx2));
+        const uint32_t w = pack_bf16x2(p0, p1);
+        pw[e >> 1] = w;
+        lsum += __uint_as_float(w << 16) + __uint_as_float(w & 0xFFFF0000u);   // the rounded values
       }
       // two MFMA K-steps of 16 keys: step h uses score registers 8h .. 8h+7, i.e. keys
       // kt0 + 16h + lhalf*4 + (0..3) and kt0 + 16h + 8 + lhalf*4 + (0..3)
@@ -187,8 +187,8 @@ __global__ void __launch_bounds__(256) attention_mfma_kernel(const uint16_t* __r
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         int dv = vt * 32 + g * 8 + lhalf * 4;
-        u32x2 pk = {pack2(oacc[vt][g * 4] * inv, oacc[vt][g * 4 + 1] * inv),
-                    pack2(oacc[vt][g * 4 + 2] * inv, oacc[vt][g * 4 + 3] * inv)};
+        u32x2 pk = {pack_bf16x2(oacc[vt][g * 4] * inv, oacc[vt][g * 4 + 1] * inv),
+                    pack_bf16x2(oacc[vt][g * 4 + 2] * inv, oacc[vt][g * 4 + 3] * inv)};
         *(u32x2*)(op + dv) = pk;
       }
   }

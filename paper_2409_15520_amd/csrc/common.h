@@ -19,6 +19,14 @@ __host__ __device__ inline bf16_t f32_to_bf16(float f) {
   bf16_t o; o.bits = (uint16_t)(r >> 16); return o;
 }
 
+// two binary32 values -> two bf16 in one word (low half = a), round-to-nearest-even in hardware (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+  f32x2_t v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
 // Position of the LoRA factors inside one layer's slice of the flat master vector.
 struct LoraLayerTable {
   int32_t n_tensors;          // 2 per adapted target
