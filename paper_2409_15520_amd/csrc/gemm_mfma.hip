@@ -232,10 +232,8 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) { ylo[e] = lo[e] * cs[e] - hi[e] * sn[e]; yhi[e] = hi[e] * cs[e] + lo[e] * sn[e]; }
             const size_t o = (size_t)m * a.ldo + n;
-            u32x2 p0 = {(uint32_t)f32_to_bf16(ylo[0]).bits | ((uint32_t)f32_to_bf16(ylo[1]).bits << 16),
-                        (uint32_t)f32_to_bf16(ylo[2]).bits | ((uint32_t)f32_to_bf16(ylo[3]).bits << 16)};
-            u32x2 p1 = {(uint32_t)f32_to_bf16(yhi[0]).bits | ((uint32_t)f32_to_bf16(yhi[1]).bits << 16),
-                        (uint32_t)f32_to_bf16(yhi[2]).bits | ((uint32_t)f32_to_bf16(yhi[3]).bits << 16)};
+            u32x2 p0 = {pack_bf16x2(ylo[0], ylo[1]), pack_bf16x2(ylo[2], ylo[3])};
+            u32x2 p1 = {pack_bf16x2(yhi[0], yhi[1]), pack_bf16x2(yhi[2], yhi[3])};
             *(u32x2*)((uint16_t*)a.out + o) = p0;
             *(u32x2*)((uint16_t*)a.out + o + half) = p1;
           }
@@ -292,8 +290,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
           f32x4 ov = {v[0], v[1], v[2], v[3]};
           *(f32x4*)((float*)a.out + o) = ov;
         } else {
-          u32x2 pk = {(uint32_t)f32_to_bf16(v[0]).bits | ((uint32_t)f32_to_bf16(v[1]).bits << 16),
-                      (uint32_t)f32_to_bf16(v[2]).bits | ((uint32_t)f32_to_bf16(v[3]).bits << 16)};
+          u32x2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
           *(u32x2*)((uint16_t*)a.out + o) = pk;
         }
       }
@@ -302,18 +299,21 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
 }
 
 // ---- LoRA bottleneck: tp[m] = [t | t | 0], t = bf16(scale * x (A_hi + A_lo)) for the block's copy ----------
-// One block = 32 tokens; its 4 waves each take a quarter of K (the kernel is latency-bound: short dependent
-// chains and many loads in flight matter, not MFMA count) and their partial sums meet in LDS in a fixed order.
-// MFMA rows = bottleneck columns j of all targets that share the input x.
+// HBM-bound (it reads x once).  One block = 32 tokens.  x streams through LDS in chunks of 256 K-elements with
+// fully coalesced 16-byte loads (a wave reads two whole 512-byte row pieces per instruction; reading MFMA
+// fragments straight from the row-major x would touch 32 rows per instruction), one chunk in flight in registers
+// while the previous one is consumed.  Inside a chunk the 4 waves split K; their partial sums meet in LDS in a
+// fixed order.  MFMA rows = bottleneck columns j of all targets that share the input x.
 template <int JT>   // number of 32-row MFMA tiles covering n_targets * r bottleneck columns
 __global__ void __launch_bounds__(256) lora_down_mfma_kernel(MfmaLoraDownArgs a) {
+  constexpr int KCH = 256, XS = KCH + 8;
+  __shared__ __align__(16) uint16_t sx[2][32 * XS];
   __shared__ float part[3][JT][16][64];          // partial sums of waves 1..3
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lrow = lane & 31, lhalf = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lrow = lane & 31, lhalf = lane >> 5;
   const int m0 = blockIdx.x * 32;
   const int copy = m0 / a.rows_per_copy;
   const int R = a.n_targets * a.rank;
-  const int kq = a.K / 4, kbeg = wave * kq;
-  const uint16_t* X = (const uint16_t*)a.x + (size_t)(m0 + lrow) * a.K + lhalf * 8;
+  const uint16_t* X = (const uint16_t*)a.x + (size_t)m0 * a.K;
   // packed A: per copy [n_targets][2][rank][K]  (hi rows then lo rows), K contiguous
   const uint16_t* Ah[JT];
   const uint16_t* Al[JT];
@@ -325,8 +325,8 @@ __global__ void __launch_bounds__(256) lora_down_mfma_kernel(MfmaLoraDownArgs a)
     int jj = valid[t] ? j : 0;
     int tgt = jj / a.rank, jr = jj % a.rank;
     const uint16_t* base = (const uint16_t*)a.ap[tgt] + (size_t)copy * a.copy_stride;
-    Ah[t] = base + (size_t)jr * a.K + lhalf * 8;
-    Al[t] = base + (size_t)(a.rank + jr) * a.K + lhalf * 8;
+    Ah[t] = base + (size_t)jr * a.K + wave * 64 + lhalf * 8;
+    Al[t] = base + (size_t)(a.rank + jr) * a.K + wave * 64 + lhalf * 8;
   }
   f32x16 acc[JT];
 #pragma unroll
@@ -334,15 +334,35 @@ __global__ void __launch_bounds__(256) lora_down_mfma_kernel(MfmaLoraDownArgs a)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
   const u32x4 zero = {0u, 0u, 0u, 0u};
-#pragma unroll 4
-  for (int k = kbeg; k < kbeg + kq; k += 16) {
-    bf16x8 fx = as_frag(*(const u32x4*)(X + k));
+
+  // chunk staging: piece p = tid + 256 i of the 32 x 256 chunk: row p / 32, 16-byte column p % 32
+  int grow[4], gcol[4];
 #pragma unroll
-    for (int t = 0; t < JT; ++t) {
-      u32x4 h = valid[t] ? *(const u32x4*)(Ah[t] + k) : zero;
-      u32x4 l = valid[t] ? *(const u32x4*)(Al[t] + k) : zero;
-      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(h), fx, acc[t], 0, 0, 0);
-      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(l), fx, acc[t], 0, 0, 0);
+  for (int i = 0; i < 4; ++i) { int p = tid + 256 * i; grow[i] = p >> 5; gcol[i] = (p & 31) * 8; }
+  u32x4 st[4];
+  const int nch = a.K / KCH;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) st[i] = *(const u32x4*)(X + (size_t)grow[i] * a.K + gcol[i]);
+  for (int ch = 0; ch < nch; ++ch) {
+    uint16_t* buf = sx[ch & 1];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *(u32x4*)(buf + grow[i] * XS + gcol[i]) = st[i];
+    if (ch + 1 < nch) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) st[i] = *(const u32x4*)(X + (size_t)grow[i] * a.K + (ch + 1) * KCH + gcol[i]);
+    }
+    __syncthreads();                             // chunk ch visible; buffer (ch+1)&1 was last read two chunks ago
+    const int kg = ch * KCH;
+#pragma unroll
+    for (int kk = 0; kk < 64; kk += 16) {
+      bf16x8 fx = as_frag(*(const u32x4*)(buf + lrow * XS + wave * 64 + kk + lhalf * 8));
+#pragma unroll
+      for (int t = 0; t < JT; ++t) {
+        u32x4 h = valid[t] ? *(const u32x4*)(Ah[t] + kg + kk) : zero;
+        u32x4 l = valid[t] ? *(const u32x4*)(Al[t] + kg + kk) : zero;
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(h), fx, acc[t], 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(l), fx, acc[t], 0, 0, 0);
+      }
     }
   }
   if (wave > 0) {
@@ -513,7 +533,7 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
 
 bool mfma_lora_down_supported(const MfmaLoraDownArgs& a) {
   int R = a.n_targets * a.rank;
-  return a.K % 64 == 0 && a.T % 32 == 0 && a.rows_per_copy % 32 == 0 && R <= 64 && a.rp % 8 == 0;
+  return a.K % 256 == 0 && a.T % 32 == 0 && a.rows_per_copy % 32 == 0 && R <= 64 && a.rp % 8 == 0;
 }
 
 void launch_lora_down_mfma(hipStream_t st, const MfmaLoraDownArgs& a) {

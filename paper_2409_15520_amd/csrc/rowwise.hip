@@ -54,8 +54,7 @@ __global__ void __launch_bounds__(256) norm_rows_kernel(int kind, float eps, con
 #pragma unroll
       for (int e = 0; e < 4; ++e) y[e] += bb[e];
     }
-    u32x2 pk = {(uint32_t)f32_to_bf16(y[0]).bits | ((uint32_t)f32_to_bf16(y[1]).bits << 16),
-                (uint32_t)f32_to_bf16(y[2]).bits | ((uint32_t)f32_to_bf16(y[3]).bits << 16)};
+    u32x2 pk = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
     orow[i * 64 + lane] = pk;
   }
 }
