@@ -20,7 +20,7 @@ PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
 PEAK_FP64_VECTOR_TFLOPS = 78.6  # fp32-storage models accumulate in fp64 on the vector ALUs
 PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E
 # HBM bytes per GEMM launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
-GEMM_TRAFFIC = {}
+GEMM_TRAFFIC = {"c2_opt125m": 116.6e6}   # bytes per launch, profiles/hbm_traffic_gemm_c2_opt125m.md
 
 
 def gemm_flops_per_step(w):
