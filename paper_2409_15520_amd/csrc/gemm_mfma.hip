@@ -136,23 +136,62 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[d][i][j][e] = 0.f;
 
+  // Short-K GEMMs spend a visible share of a block's life in the epilogue, waiting for bias, residual and the
+  // low-rank operands: small tiles fetch them now, behind the main loop (they are issued first, so they have
+  // landed long before any tile load the loop waits for).
+  constexpr bool PREF = !DUAL && HP == 0 && NI * NJ <= 4;
+  f32x4 pre_res[PREF ? NJ : 1][PREF ? NI : 1][4];
+  bf16x8 pre_fw[PREF ? NJ : 1][PREF ? NI : 1], pre_fx[PREF ? NJ : 1];     // one K-step (rank <= 8)
+  int pre_seg = -1;
+  if constexpr (PREF) {
+    const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = n0 + wn + i * 32 + g * 8 + lhalf * 4;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          const int m = m0 + wm + j * 32 + lrow;
+          pre_res[j][i][g] = (a.residual != nullptr && n < a.N && m < a.M) ? *(const f32x4*)(a.residual + (size_t)m * a.ldo + n) : z4;
+        }
+      }
+    for (int s = 0; s < a.n_seg; ++s)
+      if (n0 >= a.seg[s].col_begin && n0 < a.seg[s].col_end && a.seg[s].rp == 16) pre_seg = s;
+    if (pre_seg >= 0) {
+      const MfmaLoraSeg& sg = a.seg[pre_seg];
+      const uint16_t* tp = (const uint16_t*)sg.tp;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        int mt = m0 + wm + j * 32;
+        mt = mt < a.M ? mt : a.M - 32;
+        const uint16_t* bp = (const uint16_t*)sg.bp + (size_t)(mt / a.rows_per_copy) * sg.copy_stride;
+        pre_fx[j] = as_frag(*(const u32x4*)(tp + (size_t)(mt + lrow) * sg.rp + lhalf * 8));
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+          pre_fw[j][i] = as_frag(*(const u32x4*)(bp + (size_t)(n0 + wn + i * 32 + lrow - sg.col_begin) * sg.rp + lhalf * 8));
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
   const int nk = a.K / BK;
   if constexpr (NSET == 2) {
     // Tile kt+1 sits in one register set (in flight or landed) while tile kt+2 is fetched into the other:
     // a load has two MFMA phases to arrive before its LDS store needs it.  Loads past the last tile fall
     // outside the buffers (zeros) and are never stored.
     MPZ_LOAD_GLOBAL(0, 0)
+    MPZ_LOAD_GLOBAL(1, 1)                // both in flight before the first wait
     MPZ_STORE_LDS(0, 0)
-    MPZ_LOAD_GLOBAL(0, 1)
     __syncthreads();
     int kt = 0;
     for (; kt + 1 < nk; kt += 2) {
-      MPZ_LOAD_GLOBAL(1, kt + 2)         // even phase: stage 0 is current, set 0 holds tile kt+1
-      MPZ_STORE_LDS(0, 1)
+      MPZ_LOAD_GLOBAL(0, kt + 2)         // even phase: stage 0 is current, set 1 holds tile kt+1
+      MPZ_STORE_LDS(1, 1)
       MPZ_COMPUTE(0)
       __syncthreads();
-      MPZ_LOAD_GLOBAL(0, kt + 3)         // odd phase: stage 1 is current, set 1 holds tile kt+2
-      MPZ_STORE_LDS(1, 0)
+      MPZ_LOAD_GLOBAL(1, kt + 3)         // odd phase: stage 1 is current, set 0 holds tile kt+2
+      MPZ_STORE_LDS(0, 0)
       MPZ_COMPUTE(1)
       __syncthreads();
     }
@@ -176,7 +215,13 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   // per-copy low-rank term: extra K-steps with the packed factor [B_hi | B_lo] of a copy against the duplicated
   // bottleneck activations [t | t].  Copies are whole multiples of 32 rows, so every 32-row MFMA tile belongs to
   // one copy (a block tile may span several); segments are aligned to the block tile.
-  if (!DUAL) {
+  if (PREF && pre_seg >= 0) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+        acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pre_fw[j][i], pre_fx[j], acc[0][i][j], 0, 0, 0);
+  } else if (!DUAL) {
     for (int s = 0; s < a.n_seg; ++s) {
       const MfmaLoraSeg& sg = a.seg[s];
       if (n0 < sg.col_begin || n0 >= sg.col_end) continue;
@@ -281,7 +326,10 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
           for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
         }
         const size_t o = (size_t)m * a.ldo + n;
-        if (a.residual != nullptr) {
+        if constexpr (PREF) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += pre_res[j][i][g][e];
+        } else if (a.residual != nullptr) {
           f32x4 rr = *(const f32x4*)(a.residual + o);
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] += rr[e];
@@ -462,7 +510,7 @@ void launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
 }
 
 int tile_bn(int cfg) { return (cfg == 2 || cfg >= 4) ? 256 : 128; }   // 7, 8: 256 x 128
-int tile_bm(int cfg) { return (cfg == 3 || (cfg >= 4 && cfg <= 6)) ? 256 : 128; }
+int tile_bm(int cfg) { return cfg == 9 ? 64 : (cfg == 3 || (cfg >= 4 && cfg <= 6)) ? 256 : 128; }
 
 bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
   const int bn = tile_bn(cfg), bm = tile_bm(cfg);
@@ -474,7 +522,7 @@ bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
 }
 
 int choose_cfg(const MfmaGemmArgs& a) {
-  if (a.tile_cfg >= 1 && a.tile_cfg <= 8 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
+  if (a.tile_cfg >= 1 && a.tile_cfg <= 9 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
   // enough 256 x 256 tiles to keep 256 CUs busy for several rounds -> biggest tile; else the largest tile that
   // still gives at least ~2 blocks per CU
   // The L2 -> CU path feeds about 64 B/clk per CU, which a 128 x 128 tile needs in full at MFMA peak; 256 x 256
@@ -527,6 +575,7 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     case 6: launch_cfg<256, 256, 64, 2, 4, 1, false>(st, a); break;     // 8 waves, BK 64 (147 KB LDS)
     case 7: launch_cfg<256, 128, 64, 4, 2, 2, false>(st, a); break;     // 8 waves of 64 x 64, 110 KB LDS
     case 8: launch_cfg<256, 128, 32, 4, 2, 2, false>(st, a); break;     // 8 waves of 64 x 64, 61 KB LDS
+    case 9: launch_cfg<128, 64, 64, 2, 2, 2, false>(st, a); break;      // 4 waves of 64 x 32: more, smaller blocks
     default: launch_cfg<128, 128, 64, 2, 2, 2, false>(st, a); break;
   }
 }
