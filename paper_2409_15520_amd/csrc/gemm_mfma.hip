@@ -23,13 +23,57 @@ __device__ __forceinline__ bf16x8 as_frag(u32x4 v) { return __builtin_bit_cast(b
 
 __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f)); }
 
+// Instruction interleave of one main-loop phase.  Issued as a burst, the tile's global loads occupy the address
+// path for ~16 cycles each and its LDS stores for ~8, during which the issuing wave cannot feed the matrix core:
+// spread them (and the fragment reads of the next K-step) between the MFMAs instead.
+template <int MASK>
+__device__ __forceinline__ void sched_one() { __builtin_amdgcn_sched_group_barrier(MASK, 1, 0); }
+
+// entries I..HI-1 of a K-step's list of non-MFMA instructions: NDSR fragment reads first (the next step needs
+// them soonest), then global loads and LDS stores alternating
+template <int I, int HI, int NDSR, int NVM, int NDSW>
+__device__ __forceinline__ void sched_others() {
+  if constexpr (I < HI) {
+    if constexpr (I < NDSR) sched_one<0x100>();
+    else {
+      constexpr int j = I - NDSR, pairs = NVM < NDSW ? NVM : NDSW;
+      if constexpr (j < 2 * pairs) { if constexpr (j % 2 == 0) sched_one<0x020>(); else sched_one<0x200>(); }
+      else if constexpr (NVM > NDSW) sched_one<0x020>();
+      else sched_one<0x200>();
+    }
+    sched_others<I + 1, HI, NDSR, NVM, NDSW>();
+  }
+}
+
+template <int NM, int NDSR, int NVM, int NDSW, int C = 0>
+__device__ __forceinline__ void sched_step() {
+  if constexpr (C < NM) {
+    sched_one<0x008>();
+    constexpr int NO = NDSR + NVM + NDSW;
+    sched_others<C * NO / NM, (C + 1) * NO / NM, NDSR, NVM, NDSW>();
+    sched_step<NM, NDSR, NVM, NDSW, C + 1>();
+  }
+}
+
+// one phase: NF fragment reads of K-step 0, then KS steps of NM MFMAs, each carrying the next step's NF reads
+// and its share of the NV global loads and NV LDS stores
+template <int NM, int NF, int NV, int KS, int S = 0>
+__device__ __forceinline__ void sched_phase() {
+  if constexpr (S == 0) __builtin_amdgcn_sched_group_barrier(0x100, NF, 0);
+  if constexpr (S < KS) {
+    constexpr int nv = ((S + 1) * NV + KS - 1) / KS - (S * NV + KS - 1) / KS;   // this step's share of the tile
+    sched_step<NM, (S + 1 < KS ? NF : 0), nv, nv>();
+    sched_phase<NM, NF, NV, KS, S + 1>();
+  }
+}
+
 // Block tile BN (output features) x BM (tokens), K-step BK, WGN x WGM waves, each wave (BN/WGN) x (BM/WGM) =
-// NI x NJ MFMA tiles.  NSET = register sets of tiles in flight.  DUAL: two weight tiles (rows n and n + dual_offset:
+// NI x NJ MFMA tiles; two register sets of tiles in flight.  DUAL: two weight tiles (rows n and n + dual_offset:
 // SwiGLU gate and up) against the same X tile.  LDS rows are padded by 16 B, which keeps ds_read_b128 of 32 rows
 // conflict-free for BK = 32 and BK = 64.
 // HP > 0: rotary embedding fused into the epilogue for head width 64 * HP (the partner column d_head/2 away sits in
 // the same lane, HP MFMA tiles further), for output columns below rope_cols; the result is stored as bf16.
-template <int BN, int BM, int BK, int WGN, int WGM, int NSET, bool DUAL, int HP>
+template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP>
 __global__ void __launch_bounds__(64 * WGN * WGM, (BN * BM * (DUAL ? 2 : 1) <= 256 * 128 && WGN * WGM == 4) ? 2 : 1)
 gemm_bf16_kernel(MfmaGemmArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -88,7 +132,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
     voffX[i] = ((uint32_t)(m0 + row) * (uint32_t)a.K + kc) * 2u;
     ldsX[i] = row * LDS_STRIDE + kc;
   }
-  u32x4 rw[NSET][NW][LW], rx[NSET][LX];
+  u32x4 rw[2][NW][LW], rx[2][LX];
 #define MPZ_LOAD_GLOBAL(set, kt)                                                   \
   {                                                                                \
     const int soff = (kt) * BK * 2;                                                \
@@ -108,22 +152,61 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
       *(u32x4*)(sX + (stage) * TILE_X + ldsX[i]) = rx[set][i];                     \
     __builtin_amdgcn_sched_barrier(0);                                             \
   }
+#define MPZ_READ_FRAGS(buf, cw, cx, kk)                                           \
+  {                                                                                \
+    _Pragma("unroll") for (int d = 0; d < NW; ++d)                                 \
+      _Pragma("unroll") for (int i = 0; i < NI; ++i)                               \
+        fw[buf][d][i] = as_frag(*(const u32x4*)((cw) + d * TILE_W + (wn + i * 32 + lrow) * LDS_STRIDE + (kk) + lhalf * 8)); \
+    _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                 \
+      fx[buf][j] = as_frag(*(const u32x4*)((cx) + (wm + j * 32 + lrow) * LDS_STRIDE + (kk) + lhalf * 8)); \
+  }
+#define MPZ_MFMAS(buf)                                                             \
+  {                                                                                \
+    _Pragma("unroll") for (int d = 0; d < NW; ++d)                                 \
+      _Pragma("unroll") for (int i = 0; i < NI; ++i)                               \
+        _Pragma("unroll") for (int j = 0; j < NJ; ++j)                             \
+          acc[d][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][d][i], fx[buf][j], acc[d][i][j], 0, 0, 0); \
+  }
+// last tile(s): nothing left to fetch or store
 #define MPZ_COMPUTE(stage)                                                         \
   {                                                                                \
     const uint16_t* cw = sW + (stage) * NW * TILE_W;                               \
     const uint16_t* cx = sX + (stage) * TILE_X;                                    \
+    bf16x8 fw[1][NW][NI], fx[1][NJ];                                               \
     _Pragma("unroll") for (int kk = 0; kk < BK; kk += 16) {                        \
-      bf16x8 fw[NW][NI], fx[NJ];                                                   \
-      _Pragma("unroll") for (int d = 0; d < NW; ++d)                               \
-        _Pragma("unroll") for (int i = 0; i < NI; ++i)                             \
-          fw[d][i] = as_frag(*(const u32x4*)(cw + d * TILE_W + (wn + i * 32 + lrow) * LDS_STRIDE + kk + lhalf * 8)); \
-      _Pragma("unroll") for (int j = 0; j < NJ; ++j)                               \
-        fx[j] = as_frag(*(const u32x4*)(cx + (wm + j * 32 + lrow) * LDS_STRIDE + kk + lhalf * 8)); \
-      _Pragma("unroll") for (int d = 0; d < NW; ++d)                               \
-        _Pragma("unroll") for (int i = 0; i < NI; ++i)                             \
-          _Pragma("unroll") for (int j = 0; j < NJ; ++j)                           \
-            acc[d][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[d][i], fx[j], acc[d][i][j], 0, 0, 0); \
+      MPZ_READ_FRAGS(0, cw, cx, kk)                                                \
+      MPZ_MFMAS(0)                                                                 \
     }                                                                              \
+  }
+// One steady-state phase: MFMAs on LDS stage `cur` (tile kt) while tile kt+1 moves from register set `sset` into
+// stage `nxt` and tile `ktl` = kt+2 is fetched into set `lset`.  LDS accesses keep their program order (the
+// compiler cannot tell the stages apart), so that order is the intended one: the fragment reads of K-step s+1,
+// then step s's share of the stores; sched_phase spreads them and the global loads between the MFMAs of step s.
+#define MPZ_PHASE(cur, nxt, lset, sset, ktl)                                       \
+  {                                                                                \
+    const uint16_t* cw = sW + (cur) * NW * TILE_W;                                 \
+    const uint16_t* cx = sX + (cur) * TILE_X;                                      \
+    const int soff = (ktl) * BK * 2;                                               \
+    bf16x8 fw[2][NW][NI], fx[2][NJ];                                               \
+    MPZ_READ_FRAGS(0, cw, cx, 0)                                                   \
+    _Pragma("unroll") for (int s = 0; s < KS; ++s) {                               \
+      if (s + 1 < KS) MPZ_READ_FRAGS((s + 1) & 1, cw, cx, (s + 1) * 16)            \
+      _Pragma("unroll") for (int c = 0; c < NV; ++c) {                             \
+        if (c >= (s * NV + KS - 1) / KS && c < ((s + 1) * NV + KS - 1) / KS) {     \
+          if (c < NW * LW) {                                                       \
+            const int d = c / LW, i = c % LW;                                      \
+            *(u32x4*)(sW + ((nxt) * NW + d) * TILE_W + ldsW[i]) = rw[sset][d][i];  \
+            rw[lset][d][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, voffW[d][i], soff, 0); \
+          } else {                                                                 \
+            const int i = c - NW * LW;                                             \
+            *(u32x4*)(sX + (nxt) * TILE_X + ldsX[i]) = rx[sset][i];                \
+            rx[lset][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcX, voffX[i], soff, 0); \
+          }                                                                        \
+        }                                                                          \
+      }                                                                            \
+      MPZ_MFMAS(s & 1)                                                             \
+    }                                                                              \
+    sched_phase<NM, NF, NV, KS>();                                                 \
   }
 
   f32x16 acc[NW][NI][NJ];
@@ -176,39 +259,26 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   }
 
   const int nk = a.K / BK;
-  if constexpr (NSET == 2) {
-    // Tile kt+1 sits in one register set (in flight or landed) while tile kt+2 is fetched into the other:
-    // a load has two MFMA phases to arrive before its LDS store needs it.  Loads past the last tile fall
-    // outside the buffers (zeros) and are never stored.
-    MPZ_LOAD_GLOBAL(0, 0)
-    MPZ_LOAD_GLOBAL(1, 1)                // both in flight before the first wait
-    MPZ_STORE_LDS(0, 0)
+  constexpr int NM = NW * NI * NJ, NF = NW * NI + NJ, NV = NW * LW + LX, KS = BK / 16;
+  // Tile kt+1 sits in one register set (in flight or landed) while tile kt+2 is fetched into the other: a load
+  // has two MFMA phases to arrive before its LDS store needs it.  Loads past the last tile fall outside the
+  // buffers (zeros); what they put into the idle LDS stage is never read.
+  MPZ_LOAD_GLOBAL(0, 0)
+  MPZ_LOAD_GLOBAL(1, 1)                  // both in flight before the first wait
+  MPZ_STORE_LDS(0, 0)
+  __syncthreads();
+  int kt = 0;
+  for (; kt + 1 < nk; kt += 2) {
+    MPZ_PHASE(0, 1, 0, 1, kt + 2)        // even phase: stage 0 is current, set 1 holds tile kt+1
     __syncthreads();
-    int kt = 0;
-    for (; kt + 1 < nk; kt += 2) {
-      MPZ_LOAD_GLOBAL(0, kt + 2)         // even phase: stage 0 is current, set 1 holds tile kt+1
-      MPZ_STORE_LDS(1, 1)
-      MPZ_COMPUTE(0)
-      __syncthreads();
-      MPZ_LOAD_GLOBAL(1, kt + 3)         // odd phase: stage 1 is current, set 0 holds tile kt+2
-      MPZ_STORE_LDS(0, 0)
-      MPZ_COMPUTE(1)
-      __syncthreads();
-    }
-    if (kt < nk) MPZ_COMPUTE(0)          // odd number of tiles: the last one is already in stage 0
-  } else {
-    MPZ_LOAD_GLOBAL(0, 0)
-    MPZ_STORE_LDS(0, 0)
+    MPZ_PHASE(1, 0, 1, 0, kt + 3)        // odd phase: stage 1 is current, set 0 holds tile kt+2
     __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-      const int stage = kt & 1;
-      MPZ_LOAD_GLOBAL(0, kt + 1)
-      MPZ_COMPUTE(stage)
-      MPZ_STORE_LDS(0, stage ^ 1)
-      __syncthreads();
-    }
   }
+  if (kt < nk) MPZ_COMPUTE(0)            // odd number of tiles: the last one is already in stage 0
 #undef MPZ_LOAD_GLOBAL
+#undef MPZ_READ_FRAGS
+#undef MPZ_MFMAS
+#undef MPZ_PHASE
 #undef MPZ_STORE_LDS
 #undef MPZ_COMPUTE
 
@@ -496,21 +566,21 @@ __global__ void __launch_bounds__(256) pack_factors_kernel(const float* __restri
 //   3 128 256  32  2    61.4 KB   general, tall
 //   4 256 256  32  1    81.9 KB   large problems (lowest LDS traffic per MFMA)
 //  dual (SwiGLU): 2 x 128 x 128 x 32, 2 sets, 61.4 KB
-template <int BN, int BM, int BK, int WGN, int WGM, int NSET, bool DUAL, int HP = 0>
+template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP = 0>
 void launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
   constexpr size_t lds = (size_t)2 * ((DUAL ? 2 : 1) * BN + BM) * (BK + 8) * 2;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_bf16_kernel<BN, BM, BK, WGN, WGM, NSET, DUAL, HP>,
+    (void)hipFuncSetAttribute((const void*)gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_set = true;
   }
   const int tiles = ((a.N + BN - 1) / BN) * ((a.M + BM - 1) / BM);
-  gemm_bf16_kernel<BN, BM, BK, WGN, WGM, NSET, DUAL, HP><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
+  gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
 }
 
-int tile_bn(int cfg) { return (cfg == 2 || cfg >= 4) ? 256 : 128; }   // 7, 8: 256 x 128
-int tile_bm(int cfg) { return cfg == 9 ? 64 : (cfg == 3 || (cfg >= 4 && cfg <= 6)) ? 256 : 128; }
+int tile_bn(int cfg) { return (cfg == 2 || cfg >= 5) ? 256 : 128; }   // 7, 8: 256 x 128 (4 is unused)
+int tile_bm(int cfg) { return cfg == 9 ? 64 : (cfg == 3 || cfg == 5 || cfg == 6) ? 256 : 128; }
 
 bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
   const int bn = tile_bn(cfg), bm = tile_bm(cfg);
@@ -522,13 +592,13 @@ bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
 }
 
 int choose_cfg(const MfmaGemmArgs& a) {
-  if (a.tile_cfg >= 1 && a.tile_cfg <= 9 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
+  if (a.tile_cfg >= 1 && a.tile_cfg <= 9 && a.tile_cfg != 4 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
   // enough 256 x 256 tiles to keep 256 CUs busy for several rounds -> biggest tile; else the largest tile that
   // still gives at least ~2 blocks per CU
   // The L2 -> CU path feeds about 64 B/clk per CU, which a 128 x 128 tile needs in full at MFMA peak; 256 x 256
   // halves that.  Use the big tile (8 waves of 128 x 64) once it yields two or more rounds of blocks on 256 CUs.
   const long t5 = (long)((a.N + 255) / 256) * ((a.M + 255) / 256);
-  if (t5 >= 512 && cfg_ok(a, 5)) return 5;
+  if (t5 >= 512 && cfg_ok(a, 6)) return 6;   // BK 64 with two tiles in flight: 128 KB of loads outstanding per CU
   return 1;
 }
 
@@ -543,9 +613,9 @@ bool mfma_gemm_supported(const MfmaGemmArgs& a) {
   if (a.dual && a.n_seg) return false;
   if (a.rope_cos != nullptr) {
     // the rotated column range must end on a block-tile boundary, and a wave tile must hold whole heads
-    const int cfg = choose_cfg(a), bn = tile_bn(cfg), tn = cfg == 5 ? 128 : 64;
+    const int cfg = choose_cfg(a), bn = tile_bn(cfg), tn = (cfg == 5 || cfg == 6) ? 128 : 64;
     if (a.dual || a.out_f32 || a.act >= 0 || a.residual != nullptr || !a.rope_sin || a.S < 1) return false;
-    if ((cfg != 5 && cfg != 1) || (a.rope_dh != 64 && a.rope_dh != 128) || a.rope_dh > tn) return false;
+    if ((cfg != 5 && cfg != 6 && cfg != 1) || (a.rope_dh != 64 && a.rope_dh != 128) || a.rope_dh > tn) return false;
     if (a.rope_cols % bn || a.rope_cols > a.N || a.N % a.rope_dh) return false;
   }
   return true;
@@ -554,29 +624,30 @@ bool mfma_gemm_supported(const MfmaGemmArgs& a) {
 void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
   if (a.dual) {
     const long tb = (long)((a.N + 127) / 128) * ((a.M + 255) / 256);
-    if ((a.tile_cfg == 0 && tb >= 512) || a.tile_cfg == 5) launch_cfg<128, 256, 32, 2, 4, 2, true>(st, a);   // 2 x 128 x 256, 8 waves
-    else launch_cfg<128, 128, 32, 2, 2, 2, true>(st, a);
+    if ((a.tile_cfg == 0 && tb >= 512) || a.tile_cfg == 6) launch_cfg<128, 256, 64, 2, 4, true>(st, a);   // 2 x 128 x 256, 8 waves
+    else if (a.tile_cfg == 5) launch_cfg<128, 256, 32, 2, 4, true>(st, a);
+    else launch_cfg<128, 128, 32, 2, 2, true>(st, a);
     return;
   }
   if (a.rope_cos != nullptr) {             // fused rotary epilogue: only the two configurations the model path uses
-    if (choose_cfg(a) == 5) {
-      if (a.rope_dh == 64) launch_cfg<256, 256, 32, 2, 4, 2, false, 1>(st, a);
-      else launch_cfg<256, 256, 32, 2, 4, 2, false, 2>(st, a);
+    const int cfg = choose_cfg(a);
+    if (cfg == 5 || cfg == 6) {
+      if (a.rope_dh == 64) launch_cfg<256, 256, 64, 2, 4, false, 1>(st, a);
+      else launch_cfg<256, 256, 64, 2, 4, false, 2>(st, a);
     } else {
-      launch_cfg<128, 128, 64, 2, 2, 2, false, 1>(st, a);
+      launch_cfg<128, 128, 64, 2, 2, false, 1>(st, a);
     }
     return;
   }
   switch (choose_cfg(a)) {
-    case 2: launch_cfg<256, 128, 32, 2, 2, 2, false>(st, a); break;
-    case 3: launch_cfg<128, 256, 32, 2, 2, 2, false>(st, a); break;
-    case 4: launch_cfg<256, 256, 32, 2, 2, 1, false>(st, a); break;
-    case 5: launch_cfg<256, 256, 32, 2, 4, 2, false>(st, a); break;     // 8 waves of 128 x 64
-    case 6: launch_cfg<256, 256, 64, 2, 4, 1, false>(st, a); break;     // 8 waves, BK 64 (147 KB LDS)
-    case 7: launch_cfg<256, 128, 64, 4, 2, 2, false>(st, a); break;     // 8 waves of 64 x 64, 110 KB LDS
-    case 8: launch_cfg<256, 128, 32, 4, 2, 2, false>(st, a); break;     // 8 waves of 64 x 64, 61 KB LDS
-    case 9: launch_cfg<128, 64, 64, 2, 2, 2, false>(st, a); break;      // 4 waves of 64 x 32: more, smaller blocks
-    default: launch_cfg<128, 128, 64, 2, 2, 2, false>(st, a); break;
+    case 2: launch_cfg<256, 128, 32, 2, 2, false>(st, a); break;
+    case 3: launch_cfg<128, 256, 32, 2, 2, false>(st, a); break;
+    case 5: launch_cfg<256, 256, 32, 2, 4, false>(st, a); break;     // 8 waves of 128 x 64
+    case 6: launch_cfg<256, 256, 64, 2, 4, false>(st, a); break;     // 8 waves, BK 64 (147 KB LDS), 128 KB in flight
+    case 7: launch_cfg<256, 128, 64, 4, 2, false>(st, a); break;     // 8 waves of 64 x 64, 110 KB LDS
+    case 8: launch_cfg<256, 128, 32, 4, 2, false>(st, a); break;     // 8 waves of 64 x 64, 61 KB LDS
+    case 9: launch_cfg<128, 64, 64, 2, 2, false>(st, a); break;      // 4 waves of 64 x 32: more, smaller blocks
+    default: launch_cfg<128, 128, 64, 2, 2, false>(st, a); break;
   }
 }
 
