@@ -74,7 +74,7 @@ __device__ __forceinline__ void sched_phase() {
 // HP > 0: rotary embedding fused into the epilogue for head width 64 * HP (the partner column d_head/2 away sits in
 // the same lane, HP MFMA tiles further), for output columns below rope_cols; the result is stored as bf16.
 template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP>
-__global__ void __launch_bounds__(64 * WGN * WGM, (BN * BM * (DUAL ? 2 : 1) <= 256 * 128 && WGN * WGM == 4) ? 2 : 1)
+__global__ void __launch_bounds__(64 * WGN * WGM, (BN == 192 && BK == 32) ? 3 : (BN * BM * (DUAL ? 2 : 1) <= 256 * 128 && WGN * WGM == 4 && !(BN == 192 && BK == 64)) ? 2 : 1)
 gemm_bf16_kernel(MfmaGemmArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int NW = DUAL ? 2 : 1;
@@ -219,45 +219,6 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[d][i][j][e] = 0.f;
 
-  // Short-K GEMMs spend a visible share of a block's life in the epilogue, waiting for bias, residual and the
-  // low-rank operands: small tiles fetch them now, behind the main loop (they are issued first, so they have
-  // landed long before any tile load the loop waits for).
-  constexpr bool PREF = !DUAL && HP == 0 && NI * NJ <= 4;
-  f32x4 pre_res[PREF ? NJ : 1][PREF ? NI : 1][4];
-  bf16x8 pre_fw[PREF ? NJ : 1][PREF ? NI : 1], pre_fx[PREF ? NJ : 1];     // one K-step (rank <= 8)
-  int pre_seg = -1;
-  if constexpr (PREF) {
-    const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < NI; ++i)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n = n0 + wn + i * 32 + g * 8 + lhalf * 4;
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-          const int m = m0 + wm + j * 32 + lrow;
-          pre_res[j][i][g] = (a.residual != nullptr && n < a.N && m < a.M) ? *(const f32x4*)(a.residual + (size_t)m * a.ldo + n) : z4;
-        }
-      }
-    for (int s = 0; s < a.n_seg; ++s)
-      if (n0 >= a.seg[s].col_begin && n0 < a.seg[s].col_end && a.seg[s].rp == 16) pre_seg = s;
-    if (pre_seg >= 0) {
-      const MfmaLoraSeg& sg = a.seg[pre_seg];
-      const uint16_t* tp = (const uint16_t*)sg.tp;
-#pragma unroll
-      for (int j = 0; j < NJ; ++j) {
-        int mt = m0 + wm + j * 32;
-        mt = mt < a.M ? mt : a.M - 32;
-        const uint16_t* bp = (const uint16_t*)sg.bp + (size_t)(mt / a.rows_per_copy) * sg.copy_stride;
-        pre_fx[j] = as_frag(*(const u32x4*)(tp + (size_t)(mt + lrow) * sg.rp + lhalf * 8));
-#pragma unroll
-        for (int i = 0; i < NI; ++i)
-          pre_fw[j][i] = as_frag(*(const u32x4*)(bp + (size_t)(n0 + wn + i * 32 + lrow - sg.col_begin) * sg.rp + lhalf * 8));
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  }
-
   const int nk = a.K / BK;
   constexpr int NM = NW * NI * NJ, NF = NW * NI + NJ, NV = NW * LW + LX, KS = BK / 16;
   // Tile kt+1 sits in one register set (in flight or landed) while tile kt+2 is fetched into the other: a load
@@ -285,13 +246,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   // per-copy low-rank term: extra K-steps with the packed factor [B_hi | B_lo] of a copy against the duplicated
   // bottleneck activations [t | t].  Copies are whole multiples of 32 rows, so every 32-row MFMA tile belongs to
   // one copy (a block tile may span several); segments are aligned to the block tile.
-  if (PREF && pre_seg >= 0) {
-#pragma unroll
-    for (int j = 0; j < NJ; ++j)
-#pragma unroll
-      for (int i = 0; i < NI; ++i)
-        acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pre_fw[j][i], pre_fx[j], acc[0][i][j], 0, 0, 0);
-  } else if (!DUAL) {
+  if constexpr (!DUAL) {
     for (int s = 0; s < a.n_seg; ++s) {
       const MfmaLoraSeg& sg = a.seg[s];
       if (n0 < sg.col_begin || n0 >= sg.col_end) continue;
@@ -315,6 +270,36 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
     }
   }
 
+  // Epilogue, part 1 (accumulator layout: a lane holds, for token m = lrow, features nb + g*8 + lhalf*4 + (0..3),
+  // g = 0..3, of every MFMA tile): bias, activation or gating, rotary embedding -- everything that needs no
+  // other token's data -- written back into acc[0].
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      int n = n0 + wn + i * 32 + g * 8 + lhalf * 4;
+      n = n < a.N ? n : 0;                                 // columns past N are never stored
+      f32x4 bg = {0.f, 0.f, 0.f, 0.f}, bu = bg;
+      if (a.bias != nullptr) {
+        bg = *(const f32x4*)(a.bias + n);
+        if (DUAL) bu = *(const f32x4*)(a.bias + a.dual_offset + n);
+      }
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float v = acc[0][i][j][g * 4 + e] + bg[e];
+          if (DUAL) {
+            const float u = acc[NW - 1][i][j][g * 4 + e] + bu[e];
+            v = v / (1.0f + expf(-v)) * u;                 // SiLU(gate) * up
+          } else if (a.act == MPZ_ACT_RELU) {
+            v = v > 0.f ? v : 0.f;
+          } else if (a.act == MPZ_ACT_GELU_ERF) {
+            v = gelu_erf(v);
+          }
+          acc[0][i][j][g * 4 + e] = v;
+        }
+    }
   if constexpr (HP > 0) {
     static_assert(!DUAL && NI >= 2 * HP && NI % (2 * HP) == 0, "a wave tile must hold whole heads");
     if (n0 < a.rope_cols) {
@@ -322,95 +307,59 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
       const int half = 32 * HP;
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
-        const int m = m0 + wm + j * 32 + lrow;
-        if (m >= a.M) continue;
+        int m = m0 + wm + j * 32 + lrow;
+        m = m < a.M ? m : a.M - 1;
         const int pos = m % a.S;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-          if ((i / HP) % 2 != 0) continue;                  // upper halves are written together with their lower half
+          if ((i / HP) % 2 != 0) continue;                  // upper halves are rotated together with their lower half
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
-            const int n = n0 + wn + i * 32 + g * 8 + lhalf * 4;
-            if (n >= a.N) continue;
             const int c = (i % HP) * 32 + g * 8 + lhalf * 4;  // column inside the lower half of the head
-            float lo[4], hi[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { lo[e] = acc[0][i][j][g * 4 + e]; hi[e] = acc[0][i + HP][j][g * 4 + e]; }
-            if (a.bias != nullptr) {
-              f32x4 b0 = *(const f32x4*)(a.bias + n), b1 = *(const f32x4*)(a.bias + n + half);
-#pragma unroll
-              for (int e = 0; e < 4; ++e) { lo[e] += b0[e]; hi[e] += b1[e]; }
-            }
             const f32x4 cs = *(const f32x4*)(a.rope_cos + (size_t)pos * half + c);
             const f32x4 sn = *(const f32x4*)(a.rope_sin + (size_t)pos * half + c);
-            float ylo[4], yhi[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { ylo[e] = lo[e] * cs[e] - hi[e] * sn[e]; yhi[e] = hi[e] * cs[e] + lo[e] * sn[e]; }
-            const size_t o = (size_t)m * a.ldo + n;
-            u32x2 p0 = {pack_bf16x2(ylo[0], ylo[1]), pack_bf16x2(ylo[2], ylo[3])};
-            u32x2 p1 = {pack_bf16x2(yhi[0], yhi[1]), pack_bf16x2(yhi[2], yhi[3])};
-            *(u32x2*)((uint16_t*)a.out + o) = p0;
-            *(u32x2*)((uint16_t*)a.out + o + half) = p1;
+            for (int e = 0; e < 4; ++e) {
+              const float lo = acc[0][i][j][g * 4 + e], hi = acc[0][i + HP][j][g * 4 + e];
+              acc[0][i][j][g * 4 + e] = lo * cs[e] - hi * sn[e];
+              acc[0][i + HP][j][g * 4 + e] = hi * cs[e] + lo * sn[e];
+            }
           }
         }
       }
-      return;
     }
   }
 
-  // epilogue: lane holds, for token m, features n = nb + g*8 + lhalf*4 + (0..3), g = 0..3
+  // Epilogue, part 2: each wave turns its tile around in a private LDS strip, 32 tokens at a time, so that a lane
+  // ends up with 4 consecutive features of a token and consecutive lanes with consecutive features: residual reads
+  // and output stores then cover whole 128-byte lines (straight from the accumulator layout a store instruction
+  // would touch 32 token rows with 16 bytes each).
+  constexpr int EPS = TN + 4;                              // strip row stride in floats: conflict-free 16-byte columns
+  constexpr int LPR = TN / 4;                              // lanes per token row on the way out
+  float* ep = (float*)smem + wave * 32 * EPS;
+  __syncthreads();                                         // every wave is done with the operand stages
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
-    const int m = m0 + wm + j * 32 + lrow;
-    if (m >= a.M) continue;
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int n = n0 + wn + i * 32 + g * 8 + lhalf * 4;
-        if (n >= a.N) continue;
-        float v[4];
+        const f32x4 v = {acc[0][i][j][g * 4], acc[0][i][j][g * 4 + 1], acc[0][i][j][g * 4 + 2], acc[0][i][j][g * 4 + 3]};
+        *(f32x4*)(ep + lrow * EPS + i * 32 + g * 8 + lhalf * 4) = v;
+      }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[0][i][j][g * 4 + e];
-        if (a.bias != nullptr) {
-          f32x4 bb = *(const f32x4*)(a.bias + n);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += bb[e];
-        }
-        if (DUAL) {
-          float u[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) u[e] = acc[NW - 1][i][j][g * 4 + e];
-          if (a.bias != nullptr) {
-            f32x4 bb = *(const f32x4*)(a.bias + a.dual_offset + n);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) u[e] += bb[e];
-          }
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = v[e] / (1.0f + expf(-v[e])) * u[e];      // SiLU(gate) * up
-        } else if (a.act == MPZ_ACT_RELU) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
-        } else if (a.act == MPZ_ACT_GELU_ERF) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
-        }
-        const size_t o = (size_t)m * a.ldo + n;
-        if constexpr (PREF) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += pre_res[j][i][g][e];
-        } else if (a.residual != nullptr) {
-          f32x4 rr = *(const f32x4*)(a.residual + o);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += rr[e];
-        }
-        if (a.out_f32) {
-          f32x4 ov = {v[0], v[1], v[2], v[3]};
-          *(f32x4*)((float*)a.out + o) = ov;
-        } else {
-          u32x2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-          *(u32x2*)((uint16_t*)a.out + o) = pk;
-        }
+    for (int r = 0; r < 32 * LPR / 64; ++r) {
+      const int idx = r * 64 + lane, row = idx / LPR, c4 = idx % LPR;
+      const int m = m0 + wm + j * 32 + row, n = n0 + wn + c4 * 4;
+      f32x4 v = *(const f32x4*)(ep + row * EPS + c4 * 4);
+      if (m >= a.M || n >= a.N) continue;
+      const size_t o = (size_t)m * a.ldo + n;
+      if (a.residual != nullptr) v += *(const f32x4*)(a.residual + o);
+      if (a.out_f32) {
+        *(f32x4*)((float*)a.out + o) = v;
+      } else {
+        u32x2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+        *(u32x2*)((uint16_t*)a.out + o) = pk;
       }
     }
   }
@@ -568,7 +517,9 @@ __global__ void __launch_bounds__(256) pack_factors_kernel(const float* __restri
 //  dual (SwiGLU): 2 x 128 x 128 x 32, 2 sets, 61.4 KB
 template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP = 0>
 void launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
-  constexpr size_t lds = (size_t)2 * ((DUAL ? 2 : 1) * BN + BM) * (BK + 8) * 2;
+  constexpr size_t lds_stages = (size_t)2 * ((DUAL ? 2 : 1) * BN + BM) * (BK + 8) * 2;
+  constexpr size_t lds_strips = (size_t)WGN * WGM * 32 * (BN / WGN + 4) * 4;          // epilogue: one strip per wave
+  constexpr size_t lds = lds_stages > lds_strips ? lds_stages : lds_strips;
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void*)gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP>,
@@ -579,7 +530,7 @@ void launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
   gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
 }
 
-int tile_bn(int cfg) { return (cfg == 2 || cfg >= 5) ? 256 : 128; }   // 7, 8: 256 x 128 (4 is unused)
+int tile_bn(int cfg) { return (cfg == 10 || cfg == 11) ? 192 : (cfg == 2 || (cfg >= 5 && cfg <= 8)) ? 256 : 128; }   // 7, 8: 256 x 128 (4 is unused)
 int tile_bm(int cfg) { return cfg == 9 ? 64 : (cfg == 3 || cfg == 5 || cfg == 6) ? 256 : 128; }
 
 bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
@@ -592,13 +543,17 @@ bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
 }
 
 int choose_cfg(const MfmaGemmArgs& a) {
-  if (a.tile_cfg >= 1 && a.tile_cfg <= 9 && a.tile_cfg != 4 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
+  if (a.tile_cfg >= 1 && a.tile_cfg <= 11 && a.tile_cfg != 4 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
   // enough 256 x 256 tiles to keep 256 CUs busy for several rounds -> biggest tile; else the largest tile that
   // still gives at least ~2 blocks per CU
   // The L2 -> CU path feeds about 64 B/clk per CU, which a 128 x 128 tile needs in full at MFMA peak; 256 x 256
   // halves that.  Use the big tile (8 waves of 128 x 64) once it yields two or more rounds of blocks on 256 CUs.
   const long t5 = (long)((a.N + 255) / 256) * ((a.M + 255) / 256);
   if (t5 >= 512 && cfg_ok(a, 6)) return 6;   // BK 64 with two tiles in flight: 128 KB of loads outstanding per CU
+  // 128 x 128 tiles that fill between one and two blocks per CU leave half the chip with twice the work of the
+  // other half; 192 x 128 tiles, one per CU, balance it (N = 768 projections of the 125M-class models)
+  const long t1 = (long)((a.N + 127) / 128) * ((a.M + 127) / 128), t11 = (long)((a.N + 191) / 192) * ((a.M + 127) / 128);
+  if (t1 > 256 && t1 < 512 && t11 <= 256 && a.N % 192 == 0 && a.K >= 1536 && a.rope_cos == nullptr && cfg_ok(a, 11)) return 11;
   return 1;
 }
 
@@ -647,6 +602,8 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     case 7: launch_cfg<256, 128, 64, 4, 2, false>(st, a); break;     // 8 waves of 64 x 64, 110 KB LDS
     case 8: launch_cfg<256, 128, 32, 4, 2, false>(st, a); break;     // 8 waves of 64 x 64, 61 KB LDS
     case 9: launch_cfg<128, 64, 64, 2, 2, false>(st, a); break;      // 4 waves of 64 x 32: more, smaller blocks
+    case 10: launch_cfg<192, 128, 32, 2, 2, false>(st, a); break;    // 4 waves of 96 x 64, 51 KB LDS: 3 blocks per CU
+    case 11: launch_cfg<192, 128, 64, 2, 2, false>(st, a); break;    // 4 waves of 96 x 64, 92 KB LDS: 1 block per CU
     default: launch_cfg<128, 128, 64, 2, 2, false>(st, a); break;
   }
 }
