@@ -74,7 +74,7 @@ __device__ __forceinline__ void sched_phase() {
 // HP > 0: rotary embedding fused into the epilogue for head width 64 * HP (the partner column d_head/2 away sits in
 // the same lane, HP MFMA tiles further), for output columns below rope_cols; the result is stored as bf16.
 template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP>
-__global__ void __launch_bounds__(64 * WGN * WGM, (BN == 192 && BK == 32) ? 3 : (BN * BM * (DUAL ? 2 : 1) <= 256 * 128 && WGN * WGM == 4 && !(BN == 192 && BK == 64)) ? 2 : 1)
+__global__ void __launch_bounds__(64 * WGN * WGM, (BN * BM * (DUAL ? 2 : 1) <= 256 * 128 && WGN * WGM == 4 && !(BN == 192 && BK == 64)) ? 2 : 1)
 gemm_bf16_kernel(MfmaGemmArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int NW = DUAL ? 2 : 1;
@@ -219,6 +219,32 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[d][i][j][e] = 0.f;
 
+  // Short-K GEMMs spend a visible share of a block's life after the main loop waiting for the low-rank operands:
+  // small tiles fetch the fragments of a one-step segment (rank <= 8) now, behind the main loop (they are issued
+  // first, so they have landed long before any tile load the loop waits for).
+  constexpr bool PREF = !DUAL && NI * NJ <= 4;
+  bf16x8 pre_fw[PREF ? NJ : 1][PREF ? NI : 1], pre_fx[PREF ? NJ : 1];
+  int pre_seg = -1;
+  if constexpr (PREF) {
+    for (int s = 0; s < a.n_seg; ++s)
+      if (n0 >= a.seg[s].col_begin && n0 < a.seg[s].col_end && a.seg[s].rp == 16) pre_seg = s;
+    if (pre_seg >= 0) {
+      const MfmaLoraSeg& sg = a.seg[pre_seg];
+      const uint16_t* tp = (const uint16_t*)sg.tp;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        int mt = m0 + wm + j * 32;
+        mt = mt < a.M ? mt : a.M - 32;
+        const uint16_t* bp = (const uint16_t*)sg.bp + (size_t)(mt / a.rows_per_copy) * sg.copy_stride;
+        pre_fx[j] = as_frag(*(const u32x4*)(tp + (size_t)(mt + lrow) * sg.rp + lhalf * 8));
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+          pre_fw[j][i] = as_frag(*(const u32x4*)(bp + (size_t)(n0 + wn + i * 32 + lrow - sg.col_begin) * sg.rp + lhalf * 8));
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
   const int nk = a.K / BK;
   constexpr int NM = NW * NI * NJ, NF = NW * NI + NJ, NV = NW * LW + LX, KS = BK / 16;
   // Tile kt+1 sits in one register set (in flight or landed) while tile kt+2 is fetched into the other: a load
@@ -246,7 +272,13 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   // per-copy low-rank term: extra K-steps with the packed factor [B_hi | B_lo] of a copy against the duplicated
   // bottleneck activations [t | t].  Copies are whole multiples of 32 rows, so every 32-row MFMA tile belongs to
   // one copy (a block tile may span several); segments are aligned to the block tile.
-  if constexpr (!DUAL) {
+  if (PREF && pre_seg >= 0) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+        acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pre_fw[j][i], pre_fx[j], acc[0][i][j], 0, 0, 0);
+  } else if constexpr (!DUAL) {
     for (int s = 0; s < a.n_seg; ++s) {
       const MfmaLoraSeg& sg = a.seg[s];
       if (n0 < sg.col_begin || n0 >= sg.col_end) continue;
@@ -530,7 +562,7 @@ void launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
   gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
 }
 
-int tile_bn(int cfg) { return (cfg == 10 || cfg == 11) ? 192 : (cfg == 2 || (cfg >= 5 && cfg <= 8)) ? 256 : 128; }   // 7, 8: 256 x 128 (4 is unused)
+int tile_bn(int cfg) { return cfg == 11 ? 192 : (cfg == 2 || (cfg >= 5 && cfg <= 8)) ? 256 : 128; }   // 7, 8: 256 x 128 (4 is unused)
 int tile_bm(int cfg) { return cfg == 9 ? 64 : (cfg == 3 || cfg == 5 || cfg == 6) ? 256 : 128; }
 
 bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
@@ -543,7 +575,7 @@ bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
 }
 
 int choose_cfg(const MfmaGemmArgs& a) {
-  if (a.tile_cfg >= 1 && a.tile_cfg <= 11 && a.tile_cfg != 4 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
+  if (a.tile_cfg >= 1 && a.tile_cfg <= 11 && a.tile_cfg != 4 && a.tile_cfg != 10 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
   // enough 256 x 256 tiles to keep 256 CUs busy for several rounds -> biggest tile; else the largest tile that
   // still gives at least ~2 blocks per CU
   // The L2 -> CU path feeds about 64 B/clk per CU, which a 128 x 128 tile needs in full at MFMA peak; 256 x 256
@@ -602,7 +634,6 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     case 7: launch_cfg<256, 128, 64, 4, 2, false>(st, a); break;     // 8 waves of 64 x 64, 110 KB LDS
     case 8: launch_cfg<256, 128, 32, 4, 2, false>(st, a); break;     // 8 waves of 64 x 64, 61 KB LDS
     case 9: launch_cfg<128, 64, 64, 2, 2, false>(st, a); break;      // 4 waves of 64 x 32: more, smaller blocks
-    case 10: launch_cfg<192, 128, 32, 2, 2, false>(st, a); break;    // 4 waves of 96 x 64, 51 KB LDS: 3 blocks per CU
     case 11: launch_cfg<192, 128, 64, 2, 2, false>(st, a); break;    // 4 waves of 96 x 64, 92 KB LDS: 1 block per CU
     default: launch_cfg<128, 128, 64, 2, 2, false>(st, a); break;
   }

@@ -779,7 +779,7 @@ mpz_status mpz_debug_gemm_bf16(int32_t M, int32_t N, int32_t K, const void* x, c
 
 mpz_status mpz_debug_set_tile_config(mpz_model* m, int32_t tile_cfg) {
   if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_set_tile_config: NULL model");
-  if (tile_cfg < 0 || tile_cfg > 8) return fail(m, MPZ_ERR_CONFIG, "tile configuration outside [0, 8]");
+  if (tile_cfg < 0 || tile_cfg > 11) return fail(m, MPZ_ERR_CONFIG, "tile configuration outside [0, 11]");
   m->force_tile_cfg = tile_cfg;
   return MPZ_OK;
 }
