@@ -126,8 +126,16 @@ struct MfmaGemmArgs {
   // fused rotary embedding (bf16 output only): columns [0, rope_cols) are heads of width rope_dh rotated by the
   // position m % S with tables [max_seq, rope_dh / 2]
   const float* rope_cos; const float* rope_sin; int rope_cols, rope_dh, S;
+  // fused cross-entropy (LM head): when ce_max is set nothing is stored to `out`; every wave tile writes, per token
+  // row, the maximum and the sum of exp(logit - maximum) over its columns to slot [tile_n * waves_n + wave_n][M] of
+  // ce_max / ce_sum, and the wave holding column ce_target[m] writes that logit to ce_tlogit[m]
+  float* ce_max; float* ce_sum; float* ce_tlogit; const int32_t* ce_target;
 };
 bool mfma_gemm_supported(const MfmaGemmArgs& a);
+int mfma_gemm_ce_slots(const MfmaGemmArgs& a);      // partial slots per row the launch will write (depends on the tile)
+// ce[m] = logsumexp over the slots - target logit (0 where ce_target[m] < 0)
+void launch_ce_combine(hipStream_t st, int slots, int M, const float* ce_max, const float* ce_sum, const float* ce_tlogit,
+                       const int32_t* ce_target, float* ce);
 void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a);
 
 struct MfmaLoraDownArgs {

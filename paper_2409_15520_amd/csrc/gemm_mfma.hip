@@ -362,6 +362,53 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
     }
   }
 
+  // Fused cross-entropy: the logits never leave the registers.  A lane holds NI * 16 columns of token row lrow
+  // (the other half of the row's columns sits in lane ^ 32): row maximum, sum of exponentials against it, and
+  // the target's logit if it falls into this wave tile.
+  if (a.ce_max != nullptr) {
+    constexpr float LOG2E = 1.4426950408889634f;
+    const int slot = (n0 / BN) * WGN + wave / WGM;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int m = m0 + wm + j * 32 + lrow;
+      const int tg = m < a.M ? a.ce_target[m] : -1;
+      float mx = -1e30f, tl = 0.f;
+      bool has = false;
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int n = n0 + wn + i * 32 + g * 8 + lhalf * 4 + e;
+            const float v = acc[0][i][j][g * 4 + e];
+            if (n < a.N) mx = v > mx ? v : mx;
+            if (n == tg) { tl = v; has = true; }
+          }
+      const float other = __shfl_xor(mx, 32);
+      mx = other > mx ? other : mx;
+      float sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int n = n0 + wn + i * 32 + g * 8 + lhalf * 4 + e;
+            if (n < a.N) sum += __builtin_amdgcn_exp2f((acc[0][i][j][g * 4 + e] - mx) * LOG2E);
+          }
+      sum += __shfl_xor(sum, 32);
+      if (m < a.M) {
+        if (lhalf == 0) {
+          a.ce_max[(size_t)slot * a.M + m] = mx;
+          a.ce_sum[(size_t)slot * a.M + m] = sum;
+        }
+        if (has) a.ce_tlogit[m] = tl;
+      }
+    }
+    return;
+  }
+
   // Epilogue, part 2: each wave turns its tile around in a private LDS strip, 32 tokens at a time, so that a lane
   // ends up with 4 consecutive features of a token and consecutive lanes with consecutive features: residual reads
   // and output stores then cover whole 128-byte lines (straight from the accumulator layout a store instruction
@@ -589,7 +636,47 @@ int choose_cfg(const MfmaGemmArgs& a) {
   return 1;
 }
 
+int wave_cols(int cfg) { return cfg == 11 ? 96 : (cfg == 2 || cfg == 5 || cfg == 6) ? 128 : 64; }   // BN / WGN of launch_gemm_mfma's table
+
+// 64 token rows per block, the slots dealt to 4 waves: logsumexp over the per-wave-tile partials (online
+// maximum / rescaled sum per thread, merged through LDS), minus the target's logit
+__global__ void __launch_bounds__(256) ce_combine_kernel(int slots, int M, const float* __restrict__ ce_max,
+                                                         const float* __restrict__ ce_sum,
+                                                         const float* __restrict__ ce_tlogit,
+                                                         const int32_t* __restrict__ ce_target, float* __restrict__ ce) {
+  __shared__ float pm[4][64], psum[4][64];
+  const int r = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const int m = blockIdx.x * 64 + r;
+  float mx = -1e30f, s = 0.f;
+  if (m < M) {
+    for (int t = part; t < slots; t += 4) {
+      const float v = ce_max[(size_t)t * M + m], sv = ce_sum[(size_t)t * M + m];
+      if (v > mx) { s = s * expf(mx - v) + sv; mx = v; }
+      else s += sv * expf(v - mx);
+    }
+  }
+  pm[part][r] = mx; psum[part][r] = s;
+  __syncthreads();
+  if (part != 0 || m >= M) return;
+  if (ce_target[m] < 0) { ce[m] = 0.f; return; }
+  float gm = pm[0][r];
+  for (int p = 1; p < 4; ++p) gm = pm[p][r] > gm ? pm[p][r] : gm;
+  float gs = 0.f;
+  for (int p = 0; p < 4; ++p) gs += psum[p][r] * expf(pm[p][r] - gm);
+  ce[m] = gm + logf(gs) - ce_tlogit[m];
+}
+
 }  // namespace
+
+int mfma_gemm_ce_slots(const MfmaGemmArgs& a) {
+  const int cfg = choose_cfg(a);
+  return ((a.N + tile_bn(cfg) - 1) / tile_bn(cfg)) * (tile_bn(cfg) / wave_cols(cfg));
+}
+
+void launch_ce_combine(hipStream_t st, int slots, int M, const float* ce_max, const float* ce_sum, const float* ce_tlogit,
+                       const int32_t* ce_target, float* ce) {
+  ce_combine_kernel<<<(M + 63) / 64, 256, 0, st>>>(slots, M, ce_max, ce_sum, ce_tlogit, ce_target, ce);
+}
 
 bool mfma_gemm_supported(const MfmaGemmArgs& a) {
   if (a.K % 64 || a.N % 4 || a.M < 1 || a.N < 1) return false;
@@ -598,6 +685,7 @@ bool mfma_gemm_supported(const MfmaGemmArgs& a) {
     if (a.seg[s].rp % 16) return false;
   if (!cfg_ok(a, 1)) return false;
   if (a.dual && a.n_seg) return false;
+  if (a.ce_max != nullptr && (a.dual || a.rope_cos != nullptr || !a.ce_sum || !a.ce_tlogit || !a.ce_target)) return false;
   if (a.rope_cos != nullptr) {
     // the rotated column range must end on a block-tile boundary, and a wave tile must hold whole heads
     const int cfg = choose_cfg(a), bn = tile_bn(cfg), tn = (cfg == 5 || cfg == 6) ? 128 : 64;

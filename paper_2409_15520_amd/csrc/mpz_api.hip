@@ -471,6 +471,31 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
 }
 
 // final norm, head and per-copy loss from the stacked residual stream h [T, d]
+// LM head and cross-entropy in one pass (bf16 MFMA path): the GEMM keeps the logits in its accumulators and
+// leaves, per token row and wave tile, a running maximum and sum of exponentials in the buffer that the unfused
+// path uses for a chunk of logits; a second small kernel folds them into the row's loss.  Returns false (nothing
+// launched) when the shape or the workspace does not allow it.
+bool head_ce_fused(mpz_model* m, const Buffers& b, const void* x, int rows, int vocab, int d, int rpc,
+                   const int32_t* target, float* ce) {
+  const mpz_config& c = m->cfg;
+  if (!(m->use_mfma && c.dtype == MPZ_DTYPE_BF16)) return false;
+  MfmaGemmArgs g{};
+  g.M = rows; g.N = vocab; g.K = d; g.x = x; g.w = m->w.lm_head; g.w_rows = vocab; g.rows_per_copy = rpc; g.act = -1;
+  g.out_f32 = 1; g.out = b.logits; g.ldo = vocab; g.tile_cfg = m->force_tile_cfg;
+  const int slots = mfma_gemm_ce_slots(g);
+  const size_t need = ((size_t)2 * slots + 1) * rows, have = (size_t)b.chunk_rows * vocab;
+  if (need > have) return false;
+  g.ce_max = b.logits; g.ce_sum = b.logits + (size_t)slots * rows; g.ce_tlogit = b.logits + (size_t)2 * slots * rows;
+  g.ce_target = target;
+  if (!mfma_gemm_supported(g)) return false;
+  { ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * rows * (double)vocab * d,
+                 2.0 * ((double)rows * d + (double)vocab * d) + 8.0 * slots * (double)rows);
+    launch_gemm_mfma(m->stream, g); }
+  { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 8.0 * slots * (double)rows);
+    launch_ce_combine(m->stream, slots, rows, g.ce_max, g.ce_sum, g.ce_tlogit, target, ce); }
+  return true;
+}
+
 void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t* labels, int E, int S, float* losses_out) {
   const mpz_config& c = m->cfg;
   hipStream_t st = m->stream;
@@ -482,6 +507,11 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
     launch_make_targets(st, c.loss_mode, tokens, labels, c.label_token[0], c.label_token[1], b.target, n, E, S); }
   if (c.loss_mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS) {
     norm(m, b.h, d, m->w.lnf_g, m->w.lnf_b, b.x, T);
+    if (head_ce_fused(m, b, b.x, T, c.vocab, d, rpc, b.target, b.ce)) {
+      ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 4.0 * T);
+      launch_copy_mean(st, b.ce, rpc, E * (S - 1), losses_out, n);
+      return;
+    }
     for (int r0 = 0; r0 < T; r0 += b.chunk_rows) {
       int rows = T - r0 < b.chunk_rows ? T - r0 : b.chunk_rows;
       LinearArgs la{};
@@ -502,7 +532,8 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
       launch_last_pos_subset_logits(st, c.dtype, b.x, m->w.lm_head, d, rows_all, c.label_token[0], c.label_token[1], b.logits);
       launch_ce_rows(st, c.dtype, b.logits, 2, 2, b.target, b.ce, rows_all);
     } else {
-      for (int r0 = 0; r0 < rows_all; r0 += b.chunk_rows) {
+      const bool fused = head_ce_fused(m, b, b.x, rows_all, c.vocab, d, rpc, b.target, b.ce);
+      for (int r0 = 0; r0 < rows_all && !fused; r0 += b.chunk_rows) {
         int rows = rows_all - r0 < b.chunk_rows ? rows_all - r0 : b.chunk_rows;
         LinearArgs la{};
         la.dtype = c.dtype; la.M = rows; la.N = c.vocab; la.K = d;

@@ -131,3 +131,32 @@ def test_swiglu_dual_gemm(cfg):
     want = BF.operand(g / (1.0 + np.exp(-g)) * u)
     ulp = np.maximum(np.abs(want), 1e-30) * 2.0 ** -7
     assert np.mean(got != want) < 2e-3 and (np.abs(got - want) <= 1.01 * ulp + 1e-7).all()
+
+
+@pytest.mark.parametrize("tile_cfg", [0, 1, 2, 6, 11])
+@pytest.mark.parametrize("loss_mode", ["next_token_all_pos", "last_pos_full_vocab"])
+def test_fused_head_cross_entropy(tile_cfg, loss_mode):
+    """LM head with the cross-entropy folded into the GEMM (logits stay in the accumulators, per-tile maximum /
+    sum of exponentials combined afterwards), for every wave-tile width, on a vocabulary that ends inside a tile:
+    against the oracle's head on the same residual stream."""
+    import torch
+    import paper_2409_15520_amd as M
+    from oracle.model import head_loss
+    from oracle.precision import Precision
+    w = W.Workload(name="head_ce", n_layers=1, d_model=256, n_heads=4, n_kv_heads=4, d_ffn=512, vocab=1000, max_seq=64,
+                   act="relu", norm="layernorm", pos="learned", has_bias=True, tie_embeddings=False, dtype="bf16",
+                   lora_rank=8, lora_targets=("q", "v"), loss_mode=loss_mode, label_tokens=(7, 993), q=2, E=3, S=64, steps=1)
+    b = make_bundle(w, b_std=0.01)
+    m = gpu_model(b)
+    M.mpz_debug_set_tile_config(m.handle, tile_cfg)
+    m.regen_noise(3456, 0)
+    rng = np.random.default_rng(5)
+    n = 2 * w.q
+    h = (3.0 * rng.standard_normal((n, w.E, w.S, w.d_model))).astype(np.float32)
+    tok = torch.from_numpy(b["tokens"]).cuda()
+    lab = torch.from_numpy(b["labels"]).cuda()
+    got = m.head_loss(torch.from_numpy(h.reshape(-1, w.d_model)).cuda(), tok, lab).cpu().numpy().astype(np.float64)
+    prec = Precision("bf16")
+    want = np.array([head_loss(w, b["frozen"], h[c].astype(np.float64), b["tokens"], b["labels"], prec) for c in range(n)])
+    print(f"\nfused head {loss_mode} cfg {tile_cfg}: {got} vs {want}")
+    assert np.abs(got - want).max() <= 2e-5 * np.abs(want).max()
