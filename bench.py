@@ -67,10 +67,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2_opt125m")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--mode", default="batched", choices=["batched", "inner", "sequential"],
+    ap.add_argument("--mode", default="batched", choices=["batched", "inner", "sequential", "stateful"],
                     help="batched: all 2q copies in one pass (inner + outer loop parallel); inner: one query per pass, "
                          "both signs together (inner-loop parallelisation only); sequential: one pass per copy "
-                         "(MeZO-style)")
+                         "(MeZO-style); stateful: batched pass, then update + re-perturbation in one kernel from the "
+                         "stored pairs (Algorithm 2) instead of regenerate + replay")
     ap.add_argument("--q", type=int, default=None, help="override the workload's number of queries")
     ap.add_argument("--E", type=int, default=None, help="override the sequences per copy")
     ap.add_argument("--S", type=int, default=None, help="override the sequence length")
@@ -102,9 +103,15 @@ def main():
     tok = torch.from_numpy(tokens).cuda()
     lab = torch.from_numpy(labels).cuda()
 
-    group = {"batched": 2 * w.q, "inner": 2, "sequential": 1}[args.mode]
+    group = {"batched": 2 * w.q, "inner": 2, "sequential": 1, "stateful": 2 * w.q}[args.mode]
+    if args.mode == "stateful":
+        m.regen_noise(seeds["noise"], 0)          # the only stand-alone noise pass of the run
 
     def zo_step(step):
+        if args.mode == "stateful":
+            m.forward_perturbed(tok, lab)
+            m.zo_update_regen(step + 1)
+            return
         m.regen_noise(seeds["noise"], step)
         if args.mode == "batched":
             m.forward_perturbed(tok, lab)

@@ -178,6 +178,20 @@ mpz_status mpz_forward_copies(mpz_model* m, const int32_t* tokens, const int32_t
  * two-point quotient is undefined; lr not finite). */
 mpz_status mpz_zo_update(mpz_model* m, const float* losses, float lr, float* proj_grads_out);
 
+/* Stateful variant of the step (Algorithm 2, the "mobile" module, here for q queries and both factors): the
+ * perturbed copies of the last mpz_regen_noise / mpz_zo_update_regen are still in the workspace, so the direction of
+ * pair k is read back from them, diff_k = (theta_k(+) - theta_k(-)) / 2, instead of being regenerated:
+ *   theta_l <- theta_l - sum_k (lr g_k / q) diff_k / eps,    g_k as in mpz_zo_update,
+ * and, in the same pass over the factors, the pairs are re-centred on the new masters with fresh noise,
+ * theta_l +- eps z'_k, z'_k drawn from (seed, next_step, k) with the seed, q and eps of the stored pairs.  One noise
+ * generation per step instead of two; the model is left ready for the next mpz_forward_perturbed (no
+ * mpz_regen_noise in between).  Up to the rounding of theta +- eps z, diff_k / eps is z_k and the result is that of
+ * mpz_zo_update followed by mpz_regen_noise(seed, next_step, q, eps).
+ *   losses           [dev] fp32[2q], proj_grads_out [dev] fp32[q] or NULL
+ * Errors: NULL, STATE (no stored pairs: no mpz_regen_noise yet, or mpz_zo_update since), CONFIG (pairs made with
+ * eps = 0; lr not finite). */
+mpz_status mpz_zo_update_regen(mpz_model* m, const float* losses, float lr, uint32_t next_step, float* proj_grads_out);
+
 /* Test hooks (not on the hot path). */
 /* z for one LoRA factor of one query: z_out [dev] fp32[rows*cols], row-major. */
 mpz_status mpz_debug_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t k, int32_t tensor_id,

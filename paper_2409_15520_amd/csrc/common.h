@@ -42,6 +42,10 @@ void launch_perturb(hipStream_t st, const float* masters, float* pert /*[2q][P]*
 void launch_update(hipStream_t st, float* masters, int64_t P, const LoraLayerTable& tab, uint64_t seed,
                    uint32_t step, int q, float eps, float lr, int perturb_A, const float* losses,
                    float* proj_grads_out);
+// update from the stored perturbed pairs, then re-perturb with the noise of next_step (stateful variant, Algorithm 2)
+void launch_update_regen(hipStream_t st, float* masters, float* pert, int64_t P, const LoraLayerTable& tab, uint64_t seed,
+                         uint32_t next_step, int q, float eps, float lr, int perturb_A, const float* losses,
+                         float* proj_grads_out);
 void launch_debug_noise(hipStream_t st, float* z_out, int64_t numel, uint64_t seed, uint32_t step, int k,
                         int tensor_id);
 void launch_normals_from_words(hipStream_t st, const uint32_t* words, size_t n4, float* out);

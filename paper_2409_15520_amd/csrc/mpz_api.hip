@@ -744,6 +744,26 @@ mpz_status mpz_zo_update(mpz_model* m, const float* losses, float lr, float* pro
   return check_device(m, "mpz_zo_update");
 }
 
+mpz_status mpz_zo_update_regen(mpz_model* m, const float* losses, float lr, uint32_t next_step, float* proj_grads_out) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_zo_update_regen: NULL model");
+  if (!losses) return fail(m, MPZ_ERR_NULL, "mpz_zo_update_regen: NULL losses");
+  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_zo_update_regen before mpz_regen_noise");
+  if (!(m->eps > 0.f)) return fail(m, MPZ_ERR_CONFIG, "the stored pairs were made with eps = 0: the two-point quotient is undefined");
+  if (!std::isfinite(lr)) return fail(m, MPZ_ERR_CONFIG, "lr must be finite");
+  {
+    ProfScope ps(m, MPZ_PROF_UPDATE, 0.0, 8.0 * m->P * (1.0 + 2.0 * m->q));
+    launch_update_regen(m->stream, m->masters, m->buf.pert, m->P, m->tab, m->seed, next_step, m->q, m->eps, lr,
+                        m->cfg.perturb_A, losses, proj_grads_out);
+  }
+  ProfScope ps_pack(m, MPZ_PROF_NOISE, 0.0, m->use_mfma ? 2.0 * m->q * (4.0 * m->P + 2.0 * m->packed_per_copy) : 0.0);
+  if (m->use_mfma)
+    launch_pack_factors(m->stream, m->buf.pert, m->P, 2 * m->q, m->tab, m->cfg.n_layers, m->cfg.lora_rank, m->rp,
+                        m->buf.packed, m->packed_per_copy);
+  m->step = next_step;                          // the stored copies now belong to next_step and match the masters
+  m->cb = 0; m->nc = 2 * m->q;
+  return check_device(m, "mpz_zo_update_regen");
+}
+
 mpz_status mpz_debug_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t k, int32_t tensor_id, float* z_out) {
   if (!m || !z_out) return fail(m, MPZ_ERR_NULL, "mpz_debug_noise: NULL argument");
   if (k < 0) return fail(m, MPZ_ERR_SHAPE, "k must be non-negative");

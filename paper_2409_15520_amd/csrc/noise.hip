@@ -164,6 +164,50 @@ __global__ void __launch_bounds__(256) update_kernel(float4* __restrict__ master
   masters[g] = make_float4(m.x - a0, m.y - a1, m.z - a2, m.w - a3);
 }
 
+// Stateful variant (Algorithm 2, q queries, explicit master): the noise of the finished step is read back from
+// the stored pair, diff_k = (theta_k(+) - theta_k(-)) / 2, update = sum_k (lr g_k / q) diff_k / eps, and the pair
+// is re-centred on the new master with the noise of `next_step` - one noise generation per step instead of
+// generate + replay.
+__global__ void __launch_bounds__(256) update_regen_kernel(float4* __restrict__ masters, float4* __restrict__ pert,
+                                                           int64_t n_groups, LoraLayerTable tab, uint32_t k0, uint32_t k1,
+                                                           uint32_t next_step, int q, float eps, float lr, int perturb_A,
+                                                           const float* __restrict__ losses,
+                                                           float* __restrict__ proj_grads_out) {
+  __shared__ float coef[MAX_Q];
+  if ((int)threadIdx.x < q) {
+    int k = threadIdx.x;
+    double g = ((double)losses[2 * k] - (double)losses[2 * k + 1]) / (2.0 * (double)eps);
+    float g32 = (float)g;
+    coef[k] = (float)((double)lr * (double)g32 / (double)q);
+    if (proj_grads_out != nullptr && blockIdx.x == 0) proj_grads_out[k] = g32;
+  }
+  __syncthreads();
+  int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= n_groups) return;
+  uint32_t tid, j; bool is_A;
+  locate(tab, g, tid, j, is_A);
+  if (is_A && !perturb_A) return;               // the copies of a frozen factor already equal its master
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  for (int k = 0; k < q; ++k) {
+    const float4 pl = pert[(int64_t)(2 * k) * n_groups + g], mi = pert[(int64_t)(2 * k + 1) * n_groups + g];
+    const float d0 = (pl.x - mi.x) * 0.5f, d1 = (pl.y - mi.y) * 0.5f, d2 = (pl.z - mi.z) * 0.5f, d3 = (pl.w - mi.w) * 0.5f;
+    const float z0 = d0 / eps, z1 = d1 / eps, z2 = d2 / eps, z3 = d3 / eps;
+    const float c = coef[k];
+    const float t0 = c * z0, t1 = c * z1, t2 = c * z2, t3 = c * z3;
+    a0 = a0 + t0; a1 = a1 + t1; a2 = a2 + t2; a3 = a3 + t3;
+  }
+  float4 m = masters[g];
+  m = make_float4(m.x - a0, m.y - a1, m.z - a2, m.w - a3);
+  masters[g] = m;
+  for (int k = 0; k < q; ++k) {
+    float z[4];
+    normals4(philox4x32_10(j, tid, next_step, (uint32_t)k, k0, k1), z);
+    const float p0 = eps * z[0], p1 = eps * z[1], p2 = eps * z[2], p3 = eps * z[3];
+    pert[(int64_t)(2 * k) * n_groups + g] = make_float4(m.x + p0, m.y + p1, m.z + p2, m.w + p3);
+    pert[(int64_t)(2 * k + 1) * n_groups + g] = make_float4(m.x - p0, m.y - p1, m.z - p2, m.w - p3);
+  }
+}
+
 __global__ void __launch_bounds__(256) debug_noise_kernel(float4* __restrict__ z_out, int64_t n_groups, uint32_t k0,
                                                           uint32_t k1, uint32_t step, uint32_t k, uint32_t tensor_id) {
   int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -199,6 +243,15 @@ void launch_update(hipStream_t st, float* masters, int64_t P, const LoraLayerTab
   int64_t ng = P / 4;
   update_kernel<<<blocks_for(ng, 256), 256, 0, st>>>((float4*)masters, ng, tab, (uint32_t)seed, (uint32_t)(seed >> 32),
                                                      step, q, eps, lr, perturb_A, losses, proj_grads_out);
+}
+
+void launch_update_regen(hipStream_t st, float* masters, float* pert, int64_t P, const LoraLayerTable& tab, uint64_t seed,
+                         uint32_t next_step, int q, float eps, float lr, int perturb_A, const float* losses,
+                         float* proj_grads_out) {
+  int64_t ng = P / 4;
+  update_regen_kernel<<<blocks_for(ng, 256), 256, 0, st>>>((float4*)masters, (float4*)pert, ng, tab, (uint32_t)seed,
+                                                           (uint32_t)(seed >> 32), next_step, q, eps, lr, perturb_A, losses,
+                                                           proj_grads_out);
 }
 
 void launch_debug_noise(hipStream_t st, float* z_out, int64_t numel, uint64_t seed, uint32_t step, int k, int tensor_id) {

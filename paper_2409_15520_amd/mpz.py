@@ -91,6 +91,8 @@ def load_library() -> C.CDLL:
                                        C.c_void_p]
     lib.mpz_zo_update.restype = C.c_int
     lib.mpz_zo_update.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]
+    lib.mpz_zo_update_regen.restype = C.c_int
+    lib.mpz_zo_update_regen.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_uint32, C.c_void_p]
     lib.mpz_debug_noise.restype = C.c_int
     lib.mpz_debug_noise.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_int32, C.c_int32, C.c_void_p]
     lib.mpz_debug_normals_from_words.restype = C.c_int
@@ -184,6 +186,10 @@ def mpz_forward_copies(handle, tokens_ptr: int, labels_ptr: Optional[int], E: in
 
 def mpz_zo_update(handle, losses_ptr: int, lr: float, proj_grads_ptr: Optional[int]):
     _check(load_library().mpz_zo_update(handle, losses_ptr, lr, proj_grads_ptr), handle)
+
+
+def mpz_zo_update_regen(handle, losses_ptr: int, lr: float, next_step: int, proj_grads_ptr: Optional[int]):
+    _check(load_library().mpz_zo_update_regen(handle, losses_ptr, lr, next_step, proj_grads_ptr), handle)
 
 
 def mpz_debug_noise(handle, seed: int, step: int, k: int, tensor_id: int, z_ptr: int):
@@ -379,6 +385,12 @@ class ZoModel:
 
     def zo_update(self, lr: Optional[float] = None):
         mpz_zo_update(self.handle, self.losses.data_ptr(), self.w.lr if lr is None else lr, self.grads.data_ptr())
+        return self.grads[:self.q]
+
+    def zo_update_regen(self, next_step: int, lr: Optional[float] = None):
+        """Stateful variant: update from the stored pairs and re-perturb for `next_step` in one pass."""
+        mpz_zo_update_regen(self.handle, self.losses.data_ptr(), self.w.lr if lr is None else lr, next_step,
+                            self.grads.data_ptr())
         return self.grads[:self.q]
 
     def zo_step(self, tokens, labels, seed: int, step: int):
