@@ -587,6 +587,84 @@ __global__ void __launch_bounds__(256) pack_factors_kernel(const float* __restri
 }
 
 
+// The same packing with 16-byte accesses on the side that matters.  Work items per (copy, layer): for an A factor
+// one thread per 8 consecutive k (reads 8 whole rows of A, contiguous; writes one 16-byte chunk of each of the 2r
+// K-contiguous output rows, contiguous across lanes); for a B factor one thread per output feature n (reads
+// column n of B, contiguous across lanes; writes its whole packed row [hi | lo | 0]).
+template <int RANK>
+__global__ void __launch_bounds__(256) pack_factors_vec_kernel(const float* __restrict__ pert, int64_t P, int n_copies,
+                                                               LoraLayerTable tab, int n_layers, int rp,
+                                                               uint16_t* __restrict__ packed, int64_t packed_per_copy,
+                                                               int items_per_layer) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t per_copy = (int64_t)items_per_layer * n_layers;
+  if (idx >= per_copy * n_copies) return;
+  const int copy = (int)(idx / per_copy);
+  const int64_t r0 = idx % per_copy;
+  const int layer = (int)(r0 / items_per_layer);
+  int item = (int)(r0 % items_per_layer);
+  int i = 0;
+  int64_t poff = 0;
+  for (;; ++i) {                                   // which factor of the layer, and where its packed form starts
+    const bool isB = tab.local_id[i] & 1;
+    const int cnt = isB ? tab.cols[i] : tab.rows[i] / 8;
+    if (item < cnt) break;
+    item -= cnt;
+    poff += isB ? (int64_t)tab.cols[i] * rp : (int64_t)2 * tab.rows[i] * tab.cols[i];
+  }
+  int64_t per_layer_packed = 0;
+  for (int t = 0; t < tab.n_tensors; ++t)
+    per_layer_packed += (tab.local_id[t] & 1) ? (int64_t)tab.cols[t] * rp : (int64_t)2 * tab.rows[t] * tab.cols[t];
+  const float* src = pert + (int64_t)copy * P + (int64_t)layer * tab.per_layer + tab.off[i];
+  uint16_t* dst = packed + (int64_t)copy * packed_per_copy + (int64_t)layer * per_layer_packed + poff;
+  if ((tab.local_id[i] & 1) == 0) {                // A [K, r]: rows k0..k0+7 -> chunk k0 of rows j (hi) and r + j (lo)
+    const int K = tab.rows[i], k0 = item * 8;
+    float v[8][RANK];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+#pragma unroll
+      for (int c = 0; c < RANK / 4; ++c) {
+        const f32x4 t = *(const f32x4*)(src + (int64_t)(k0 + e) * RANK + c * 4);
+        v[e][c * 4] = t[0]; v[e][c * 4 + 1] = t[1]; v[e][c * 4 + 2] = t[2]; v[e][c * 4 + 3] = t[3];
+      }
+#pragma unroll
+    for (int j = 0; j < RANK; ++j) {
+      uint32_t hi[4], lo[4];
+#pragma unroll
+      for (int e = 0; e < 8; e += 2) {
+        const bf16_t h0 = f32_to_bf16(v[e][j]), h1 = f32_to_bf16(v[e + 1][j]);
+        const bf16_t l0 = f32_to_bf16(v[e][j] - bf16_to_f32(h0)), l1 = f32_to_bf16(v[e + 1][j] - bf16_to_f32(h1));
+        hi[e / 2] = (uint32_t)h0.bits | ((uint32_t)h1.bits << 16);
+        lo[e / 2] = (uint32_t)l0.bits | ((uint32_t)l1.bits << 16);
+      }
+      const u32x4 hv = {hi[0], hi[1], hi[2], hi[3]}, lv = {lo[0], lo[1], lo[2], lo[3]};
+      *(u32x4*)(dst + (int64_t)j * K + k0) = hv;
+      *(u32x4*)(dst + (int64_t)(RANK + j) * K + k0) = lv;
+    }
+  } else {                                         // B [r, k_out]: column n -> packed row n = [hi(r) | lo(r) | 0]
+    const int kout = tab.cols[i], n = item;
+    uint16_t* row = dst + (int64_t)n * rp;
+    uint16_t hb[RANK], lb[RANK];
+#pragma unroll
+    for (int j = 0; j < RANK; ++j) {
+      const float x = src[(int64_t)j * kout + n];
+      const bf16_t h = f32_to_bf16(x);
+      hb[j] = h.bits;
+      lb[j] = f32_to_bf16(x - bf16_to_f32(h)).bits;
+    }
+    if constexpr (RANK % 4 == 0) {
+#pragma unroll
+      for (int j = 0; j < RANK; j += 4) {
+        const u32x2 hv = {(uint32_t)hb[j] | ((uint32_t)hb[j + 1] << 16), (uint32_t)hb[j + 2] | ((uint32_t)hb[j + 3] << 16)};
+        const u32x2 lv = {(uint32_t)lb[j] | ((uint32_t)lb[j + 1] << 16), (uint32_t)lb[j + 2] | ((uint32_t)lb[j + 3] << 16)};
+        *(u32x2*)(row + j) = hv;
+        *(u32x2*)(row + RANK + j) = lv;
+      }
+    }
+    for (int c = 2 * RANK; c < rp; ++c) row[c] = 0;
+  }
+}
+
 // ---- tile configurations ----------------------------------------------------------------------------
 //  id  BN  BM  BK sets   LDS      use
 //   1 128 128  64  2    73.7 KB   small N (more blocks)
@@ -740,6 +818,22 @@ void launch_lora_down_mfma(hipStream_t st, const MfmaLoraDownArgs& a) {
 
 void launch_pack_factors(hipStream_t st, const float* pert, int64_t P, int n_copies, const LoraLayerTable& tab,
                          int n_layers, int rank, int rp, void* packed, int64_t packed_per_copy) {
+  // vectorised variant: ranks 4 / 8 / 16 with every A factor's K a multiple of 8 and 8-byte-aligned packed rows
+  bool vec = (rank == 4 || rank == 8 || rank == 16) && rp % 4 == 0;
+  int items = 0;
+  for (int t = 0; t < tab.n_tensors; ++t) {
+    const bool isB = tab.local_id[t] & 1;
+    if (!isB && tab.rows[t] % 8) vec = false;
+    items += isB ? tab.cols[t] : tab.rows[t] / 8;
+  }
+  if (vec) {
+    const int64_t total = (int64_t)items * n_layers * n_copies;
+    const unsigned nb = (unsigned)((total + 255) / 256);
+    if (rank == 4) pack_factors_vec_kernel<4><<<nb, 256, 0, st>>>(pert, P, n_copies, tab, n_layers, rp, (uint16_t*)packed, packed_per_copy, items);
+    else if (rank == 8) pack_factors_vec_kernel<8><<<nb, 256, 0, st>>>(pert, P, n_copies, tab, n_layers, rp, (uint16_t*)packed, packed_per_copy, items);
+    else pack_factors_vec_kernel<16><<<nb, 256, 0, st>>>(pert, P, n_copies, tab, n_layers, rp, (uint16_t*)packed, packed_per_copy, items);
+    return;
+  }
   int64_t total = (int64_t)n_copies * P;
   pack_factors_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(pert, P, n_copies, tab, n_layers, rank, rp,
                                                                        (uint16_t*)packed, packed_per_copy);
