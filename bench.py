@@ -20,7 +20,7 @@ PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
 PEAK_FP64_VECTOR_TFLOPS = 78.6  # fp32-storage models accumulate in fp64 on the vector ALUs
 PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E
 # HBM bytes per GEMM launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
-GEMM_TRAFFIC = {"c2_opt125m": 116.6e6}   # bytes per launch, profiles/hbm_traffic_gemm_c2_opt125m.md
+GEMM_TRAFFIC = {"c2_opt125m": 107.3e6}   # bytes per launch, profiles/hbm_traffic_gemm_c2_opt125m.md
 
 
 def gemm_flops_per_step(w):
@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--S", type=int, default=None, help="override the sequence length")
     ap.add_argument("--device-init", action="store_true",
                     help="draw the frozen weights on the GPU (large workloads; implies --no-cpu-baseline)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 256 MiB device-to-device copies first (a kernel of known traffic, to "
+                         "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (copies would shard across GPUs with one all-gather "
@@ -87,6 +90,13 @@ def main():
     import workloads as W
     import paper_2409_15520_amd as M
 
+    if args.calibrate_copy:
+        a = torch.empty(256 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda").normal_()
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     w = W.get_workload(args.workload)
     over = {k: v for k, v in (("q", args.q), ("E", args.E), ("S", args.S)) if v is not None}
     if over:
