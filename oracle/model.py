@@ -136,17 +136,26 @@ def decoder_layer(w, lw, li: int, h, lora, prec: Precision):
     return prec.stream(h + _linear(u, lw["w_down"], lw["b_down"]))
 
 
-def head_loss(w, frozen, h, tokens: np.ndarray, labels, prec: Precision) -> float:
-    """Final norm, LM head and the mean cross-entropy of this copy in the configured loss mode."""
+def head_loss(w, frozen, h, tokens: np.ndarray, labels, prec: Precision, lengths=None) -> float:
+    """Final norm, LM head and the mean cross-entropy of this copy in the configured loss mode.
+
+    `lengths` (optional, one per sequence, 2 <= length <= S): sequences are right-padded to S as in the paper's batches
+    (Section 3 discusses the padding that batching sequences of unequal length brings); only real tokens carry a loss.
+    Next-token mode: positions p < length - 1; last-position modes: position length - 1.  The mean runs over the
+    copy's loss positions."""
     E, S, d = h.shape
     norm_eps = float(np.float32(w.norm_eps))
     head = np.asarray(frozen["lm_head"], dtype=np.float64)                       # [V, d]
+    lengths = np.full(E, S, dtype=np.int64) if lengths is None else np.asarray(lengths, dtype=np.int64)
     if w.loss_mode == "next_token_all_pos":
         xf = prec.operand(_norm(h[:, :S - 1], frozen["lnf_g"], frozen["lnf_b"], w.norm, norm_eps))
         logits = prec.stream(xf.reshape(-1, d) @ head.T)
-        ce = _cross_entropy(logits, tokens[:, 1:].reshape(-1))
+        ce = _cross_entropy(logits, tokens[:, 1:].reshape(-1)).reshape(E, S - 1)
+        valid = np.arange(S - 1)[None, :] < (lengths[:, None] - 1)
+        ce = ce[valid]                                                           # row-major: sequence, then position
     else:
-        xf = prec.operand(_norm(h[:, S - 1], frozen["lnf_g"], frozen["lnf_b"], w.norm, norm_eps))
+        last = h[np.arange(E), lengths - 1]
+        xf = prec.operand(_norm(last, frozen["lnf_g"], frozen["lnf_b"], w.norm, norm_eps))
         labels = np.asarray(labels)
         if w.loss_mode == "last_pos_label_subset":
             logits = prec.stream(xf @ head[list(w.label_tokens)].T)              # [E, 2]
@@ -158,7 +167,7 @@ def head_loss(w, frozen, h, tokens: np.ndarray, labels, prec: Precision) -> floa
 
 
 def copy_loss(w, frozen: Dict[str, object], lora: Dict[Tuple[int, int], Tuple[np.ndarray, np.ndarray]],
-              tokens: np.ndarray, labels, prec: Precision, trace=None) -> float:
+              tokens: np.ndarray, labels, prec: Precision, trace=None, lengths=None) -> float:
     """Loss of one copy.  `lora[(layer, target_index)] = (A_c, B_c)` are that copy's factors.
     If `trace` is a list, the residual stream after the embedding and after every block is appended."""
     h = embed(w, frozen, tokens, prec)
@@ -168,4 +177,4 @@ def copy_loss(w, frozen: Dict[str, object], lora: Dict[Tuple[int, int], Tuple[np
         h = decoder_layer(w, lw, li, h, lora, prec)
         if trace is not None:
             trace.append(h)
-    return head_loss(w, frozen, h, tokens, labels, prec)
+    return head_loss(w, frozen, h, tokens, labels, prec, lengths)

@@ -46,7 +46,7 @@ def split_factors(layout, flat) -> Dict[Tuple[int, int], Tuple[np.ndarray, np.nd
 
 
 def perturbed_losses(w, layout, frozen, masters, tokens, labels, seed: int, step: int,
-                     prec: Precision, q=None, eps=None) -> np.ndarray:
+                     prec: Precision, q=None, eps=None, lengths=None) -> np.ndarray:
     """l_c for c = 0..2q-1 (Algorithm 1, outer and inner loops)."""
     q = w.q if q is None else q
     eps = w.eps if eps is None else eps
@@ -55,7 +55,7 @@ def perturbed_losses(w, layout, frozen, masters, tokens, labels, seed: int, step
         z = draw_z(layout, seed, step, k, masters.size, w.perturb_A)
         for s, sign in enumerate((+1, -1)):
             theta = perturb(masters, z, sign, eps, prec)
-            losses[2 * k + s] = copy_loss(w, frozen, split_factors(layout, theta), tokens, labels, prec)
+            losses[2 * k + s] = copy_loss(w, frozen, split_factors(layout, theta), tokens, labels, prec, lengths=lengths)
     return losses
 
 
