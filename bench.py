@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--S", type=int, default=None, help="override the sequence length")
     ap.add_argument("--device-init", action="store_true",
                     help="draw the frozen weights on the GPU (large workloads; implies --no-cpu-baseline)")
+    ap.add_argument("--pad-fraction", type=float, default=None,
+                    help="right-padded batch of unequal lengths (seeded; about this fraction of the E*S slots is padding): "
+                         "the loss runs over real tokens only (mpz_forward_perturbed_varlen)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device-to-device copies first (a kernel of known traffic, to "
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -112,6 +115,12 @@ def main():
     m = M.ZoModel(w, frozen, masters, device="cuda:0")
     tok = torch.from_numpy(tokens).cuda()
     lab = torch.from_numpy(labels).cuda()
+    lengths = None
+    if args.pad_fraction is not None:
+        if args.mode not in ("batched", "stateful"):
+            sys.exit("bench.py: --pad-fraction needs --mode batched or stateful")
+        lengths_host = W.make_lengths(w, seeds["tokens"], pad_fraction=args.pad_fraction)
+        lengths = torch.from_numpy(lengths_host).cuda()
 
     group = {"batched": 2 * w.q, "inner": 2, "sequential": 1, "stateful": 2 * w.q}[args.mode]
     if args.mode == "stateful":
@@ -119,12 +128,12 @@ def main():
 
     def zo_step(step):
         if args.mode == "stateful":
-            m.forward_perturbed(tok, lab)
+            m.forward_perturbed(tok, lab, lengths)
             m.zo_update_regen(step + 1)
             return
         m.regen_noise(seeds["noise"], step)
         if args.mode == "batched":
-            m.forward_perturbed(tok, lab)
+            m.forward_perturbed(tok, lab, lengths)
         else:
             m.forward_sequential(tok, lab, group=group)
         m.zo_update()
@@ -177,7 +186,8 @@ def main():
         "dtype": "bf16" if bf16 else "f64", "data": "synthetic",
         "config": {"workload": w.name, "mode": args.mode, "q": w.q, "copies": 2 * w.q, "E": w.E, "S": w.S,
                    "stacked_tokens": tokens_per_step, "layers": w.n_layers, "d_model": w.d_model,
-                   "lora_rank": w.lora_rank, "eps": w.eps, "seeds": seeds},
+                   "lora_rank": w.lora_rank, "eps": w.eps, "seeds": seeds,
+                   "real_tokens_per_copy": int(lengths_host.sum()) if lengths is not None else w.E * w.S},
         "roofline": {"bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": GEMM_TRAFFIC.get(w.name),
                      "kernel": "base-weight GEMMs (all launches of a step)",

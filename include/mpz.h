@@ -169,6 +169,18 @@ mpz_status mpz_forward_perturbed(mpz_model* m, const int32_t* tokens, const int3
 mpz_status mpz_forward_copies(mpz_model* m, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
                               int32_t copy_begin, int32_t n_copies, float* losses_out);
 
+/* mpz_forward_perturbed on a right-padded batch of sequences of unequal length (Section 3 argues that spending the
+ * batch on q queries of E = B / q sequences shortens the padding that batching brings): sequence e has lengths[e] real
+ * tokens, 2 <= lengths[e] <= S (values outside are clamped), followed by padding whose token ids are arbitrary but
+ * inside the vocabulary.  Attention is causal, so no real token ever sees the padding; the loss is taken over real
+ * tokens only: next-token mode averages over the positions p < lengths[e] - 1 of all sequences, the last-position
+ * modes read position lengths[e] - 1.  With lengths[e] = S for all e the losses are bit-identical to
+ * mpz_forward_perturbed.
+ *   lengths   [dev] int32[E]
+ * Errors as mpz_forward_perturbed, plus NULL for lengths and SHAPE for d_ffn < 2 d_model / element size. */
+mpz_status mpz_forward_perturbed_varlen(mpz_model* m, const int32_t* tokens, const int32_t* labels, const int32_t* lengths,
+                                        int32_t E, int32_t S, float* losses_out);
+
 /* Algorithm 1, projected gradient and update: g_k = (l_{2k} - l_{2k+1}) / (2 eps) in fp64 from the fp32 losses, then
  * theta_l <- theta_l - lr (1/q) sum_k g_k z_k on the fp32 masters, z_k replayed from the (seed,
  * step, q, eps) of the last mpz_regen_noise.
@@ -205,11 +217,12 @@ mpz_status mpz_debug_perturbed_copy(mpz_model* m, int32_t c, float* out);
 /* The three stages of mpz_forward_perturbed, run separately on a caller-held stacked residual
  * stream h [dev] fp32[2q*E*S, d_model] (rows in copy-major order), so that each stage can be checked
  * on given inputs: embedding -> h_out; decoder blocks [layer_begin, layer_end) in place on h; final
- * norm + head + per-copy mean loss from h.  Same preconditions and errors as mpz_forward_perturbed. */
+ * norm + head + per-copy mean loss from h (lengths: [dev] int32[E] as in mpz_forward_perturbed_varlen, or NULL).
+ * Same preconditions and errors as mpz_forward_perturbed. */
 mpz_status mpz_debug_embed(mpz_model* m, const int32_t* tokens, int32_t E, int32_t S, float* h_out);
 mpz_status mpz_debug_run_layers(mpz_model* m, float* h, int32_t layer_begin, int32_t layer_end, int32_t E, int32_t S);
 mpz_status mpz_debug_head_loss(mpz_model* m, const float* h, const int32_t* tokens, const int32_t* labels,
-                               int32_t E, int32_t S, float* losses_out);
+                               const int32_t* lengths, int32_t E, int32_t S, float* losses_out);
 
 /* Test hooks for single operations of a bf16 / any model on caller-provided operands:
  * - the q/k/v projection of the MP-LoRA layer (Section 3: Y = X W + (X A)(.)B, plus bias) of block `layer` for all

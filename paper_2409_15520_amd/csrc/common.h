@@ -109,9 +109,12 @@ void launch_ce_rows(hipStream_t st, int dtype, const float* logits, int64_t row_
                     float* ce, int rows);
 void launch_last_pos_subset_logits(hipStream_t st, int dtype, const void* xf, const void* head, int d, int rows,
                                    int tok0, int tok1, float* logits2);
-void launch_make_targets(hipStream_t st, int mode, const int32_t* tokens, const int32_t* labels, int tok0, int tok1,
-                         int32_t* target, int n_copies, int E, int S);
-void launch_copy_mean(hipStream_t st, const float* ce, int rows_per_copy, int count_per_copy, float* losses, int n_copies);
+void launch_make_targets(hipStream_t st, int mode, const int32_t* tokens, const int32_t* labels, const int32_t* lengths,
+                         int tok0, int tok1, int32_t* target, int n_copies, int E, int S);
+void launch_gather_last_rows(hipStream_t st, const float* h, const int32_t* lengths, int n_copies, int E, int S, int d,
+                             float* out);
+void launch_copy_mean(hipStream_t st, const float* ce, int rows_per_copy, int count_per_copy, const int32_t* lengths, int E,
+                      int S, float* losses, int n_copies);
 void launch_fill_f32(hipStream_t st, float* p, float v, int64_t n);
 
 // ---- gemm_mfma.hip: bf16 MFMA kernels (gfx950) ------------------------------------------------

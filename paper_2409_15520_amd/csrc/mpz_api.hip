@@ -161,6 +161,7 @@ struct mpz_model {
   uint64_t seed = 0; uint32_t step = 0; int q = 0; float eps = 0.f;
   int cb = 0, nc = 0;                           // copies [cb, cb + nc) processed by the current pass
   int force_tile_cfg = 0;                       // test hook: GEMM block-tile configuration (0 = by shape)
+  const int32_t* lengths = nullptr;             // [dev] per-sequence lengths of the pass in flight (right-padded batch), or null
   std::string err;
   // optional per-launch timing by kernel category (mpz_profile_begin / _end)
   // bf16 MFMA path
@@ -504,12 +505,12 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
   const int n = m->nc, rpc = E * S, T = n * rpc;
   const int d = c.d_model;
   { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 0.0);
-    launch_make_targets(st, c.loss_mode, tokens, labels, c.label_token[0], c.label_token[1], b.target, n, E, S); }
+    launch_make_targets(st, c.loss_mode, tokens, labels, m->lengths, c.label_token[0], c.label_token[1], b.target, n, E, S); }
   if (c.loss_mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS) {
     norm(m, b.h, d, m->w.lnf_g, m->w.lnf_b, b.x, T);
     if (head_ce_fused(m, b, b.x, T, c.vocab, d, rpc, b.target, b.ce)) {
       ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 4.0 * T);
-      launch_copy_mean(st, b.ce, rpc, E * (S - 1), losses_out, n);
+      launch_copy_mean(st, b.ce, rpc, E * (S - 1), m->lengths, E, S, losses_out, n);
       return;
     }
     for (int r0 = 0; r0 < T; r0 += b.chunk_rows) {
@@ -523,10 +524,17 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
         launch_ce_rows(st, c.dtype, b.logits, c.vocab, c.vocab, b.target + r0, b.ce + r0, rows); }
     }
     { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 4.0 * T);
-      launch_copy_mean(st, b.ce, rpc, E * (S - 1), losses_out, n); }
+      launch_copy_mean(st, b.ce, rpc, E * (S - 1), m->lengths, E, S, losses_out, n); }
   } else {
     const int rows_all = n * E;
-    norm(m, b.h + (size_t)(S - 1) * d, (int64_t)S * d, m->w.lnf_g, m->w.lnf_b, b.x, rows_all);
+    if (m->lengths != nullptr) {                 // last real token of every sequence, gathered into the (idle) FFN buffer
+      float* last = (float*)b.u;
+      { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 8.0 * rows_all * d);
+        launch_gather_last_rows(st, b.h, m->lengths, n, E, S, d, last); }
+      norm(m, last, d, m->w.lnf_g, m->w.lnf_b, b.x, rows_all);
+    } else {
+      norm(m, b.h + (size_t)(S - 1) * d, (int64_t)S * d, m->w.lnf_g, m->w.lnf_b, b.x, rows_all);
+    }
     if (c.loss_mode == MPZ_LOSS_LAST_POS_LABEL_SUBSET) {
       ProfScope ps(m, MPZ_PROF_LOSS, 0.0, esz(m) * (double)d * (rows_all + 2));
       launch_last_pos_subset_logits(st, c.dtype, b.x, m->w.lm_head, d, rows_all, c.label_token[0], c.label_token[1], b.logits);
@@ -545,7 +553,7 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
       }
     }
     { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 4.0 * rows_all);
-      launch_copy_mean(st, b.ce, E, E, losses_out, n); }
+      launch_copy_mean(st, b.ce, E, E, nullptr, E, S, losses_out, n); }
   }
 }
 
@@ -687,6 +695,18 @@ mpz_status mpz_forward_perturbed(mpz_model* m, const int32_t* tokens, const int3
   return check_device(m, "mpz_forward_perturbed");
 }
 
+mpz_status mpz_forward_perturbed_varlen(mpz_model* m, const int32_t* tokens, const int32_t* labels, const int32_t* lengths,
+                                        int32_t E, int32_t S, float* losses_out) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_forward_perturbed_varlen: NULL model");
+  if (!lengths) return fail(m, MPZ_ERR_NULL, "mpz_forward_perturbed_varlen: NULL lengths");
+  if ((size_t)2 * m->cfg.d_ffn * elem_size(m->cfg.dtype) < (size_t)4 * m->cfg.d_model)
+    return fail(m, MPZ_ERR_SHAPE, "mpz_forward_perturbed_varlen: d_ffn too small to stage the last-token rows");
+  m->lengths = lengths;
+  const mpz_status st = mpz_forward_perturbed(m, tokens, labels, E, S, losses_out);
+  m->lengths = nullptr;
+  return st;
+}
+
 mpz_status mpz_forward_copies(mpz_model* m, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
                               int32_t copy_begin, int32_t n_copies, float* losses_out) {
   if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_forward_copies: NULL model");
@@ -721,13 +741,15 @@ mpz_status mpz_debug_run_layers(mpz_model* m, float* h, int32_t layer_begin, int
   return check_device(m, "mpz_debug_run_layers");
 }
 
-mpz_status mpz_debug_head_loss(mpz_model* m, const float* h, const int32_t* tokens, const int32_t* labels, int32_t E,
-                               int32_t S, float* losses_out) {
+mpz_status mpz_debug_head_loss(mpz_model* m, const float* h, const int32_t* tokens, const int32_t* labels,
+                               const int32_t* lengths, int32_t E, int32_t S, float* losses_out) {
   if (!m || !h || !tokens || !losses_out) return fail(m, MPZ_ERR_NULL, "mpz_debug_head_loss: NULL argument");
   if (m->cfg.loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS && !labels) return fail(m, MPZ_ERR_NULL, "this loss mode needs labels");
   if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_debug_head_loss before mpz_regen_noise");
   if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
+  m->lengths = lengths;
   run_head(m, h, tokens, labels, E, S, losses_out);
+  m->lengths = nullptr;
   return check_device(m, "mpz_debug_head_loss");
 }
 

@@ -317,13 +317,21 @@ __global__ void __launch_bounds__(64) subset_logits_kernel(const ST* __restrict_
   if (threadIdx.x == 0) { logits2[2 * r] = (float)a0; logits2[2 * r + 1] = (float)a1; }
 }
 
+// lengths (optional): sequences are right-padded to S; only real tokens carry a loss.  Values are clamped to [2, S].
+__device__ __forceinline__ int seq_len(const int32_t* lengths, int e, int S) {
+  if (lengths == nullptr) return S;
+  int L = lengths[e];
+  return L < 2 ? 2 : (L > S ? S : L);
+}
+
 __global__ void make_targets_kernel(int mode, const int32_t* __restrict__ tokens, const int32_t* __restrict__ labels,
-                                    int tok0, int tok1, int32_t* __restrict__ target, int n_copies, int E, int S) {
+                                    const int32_t* __restrict__ lengths, int tok0, int tok1,
+                                    int32_t* __restrict__ target, int n_copies, int E, int S) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS) {
     if (idx >= (int64_t)n_copies * E * S) return;
     int p = (int)(idx % S), e = (int)((idx / S) % E);
-    target[idx] = (p < S - 1) ? tokens[e * S + p + 1] : -1;
+    target[idx] = (p < seq_len(lengths, e, S) - 1) ? tokens[e * S + p + 1] : -1;
   } else {
     if (idx >= (int64_t)n_copies * E) return;
     int e = (int)(idx % E);
@@ -332,15 +340,32 @@ __global__ void make_targets_kernel(int mode, const int32_t* __restrict__ tokens
   }
 }
 
-// mean of a copy's per-row losses: fp64, fixed summation order
+// residual rows of the last real token of every sequence, gathered into a dense [n_copies * E, d] block
+__global__ void __launch_bounds__(256) gather_last_rows_kernel(const float* __restrict__ h,
+                                                               const int32_t* __restrict__ lengths, int E, int S, int d,
+                                                               float* __restrict__ out) {
+  const int r = blockIdx.x, e = r % E;
+  const float* src = h + ((int64_t)r * S + seq_len(lengths, e, S) - 1) * d;
+  for (int i = threadIdx.x; i < d; i += 256) out[(int64_t)r * d + i] = src[i];
+}
+
+// mean of a copy's per-row losses: fp64, fixed summation order.  With lengths the divisor is the number of
+// next-token positions of the padded batch, sum_e (length_e - 1).
 __global__ void __launch_bounds__(256) copy_mean_kernel(const float* __restrict__ ce, int rows_per_copy, int count,
+                                                        const int32_t* __restrict__ lengths, int E, int S,
                                                         float* __restrict__ losses) {
   __shared__ double red[4];
   const float* p = ce + (int64_t)blockIdx.x * rows_per_copy;
   double s = 0;
   for (int i = threadIdx.x; i < rows_per_copy; i += 256) s += (double)p[i];
   s = block_sum(s, red);
-  if (threadIdx.x == 0) losses[blockIdx.x] = (float)(s / (double)count);
+  if (threadIdx.x == 0) {
+    if (lengths != nullptr) {
+      count = 0;
+      for (int e = 0; e < E; ++e) count += seq_len(lengths, e, S) - 1;
+    }
+    losses[blockIdx.x] = (float)(s / (double)count);
+  }
 }
 
 __global__ void fill_kernel(float* p, float v, int64_t n) {
@@ -409,14 +434,20 @@ void launch_last_pos_subset_logits(hipStream_t st, int dtype, const void* xf, co
   MPZ_DISPATCH(dtype, (subset_logits_kernel<ST><<<rows, 64, 0, st>>>((const ST*)xf, (const ST*)head, d, tok0, tok1, logits2)));
 }
 
-void launch_make_targets(hipStream_t st, int mode, const int32_t* tokens, const int32_t* labels, int tok0, int tok1,
-                         int32_t* target, int n_copies, int E, int S) {
+void launch_make_targets(hipStream_t st, int mode, const int32_t* tokens, const int32_t* labels, const int32_t* lengths,
+                         int tok0, int tok1, int32_t* target, int n_copies, int E, int S) {
   int64_t n = (mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS) ? (int64_t)n_copies * E * S : (int64_t)n_copies * E;
-  make_targets_kernel<<<nblk(n, 256), 256, 0, st>>>(mode, tokens, labels, tok0, tok1, target, n_copies, E, S);
+  make_targets_kernel<<<nblk(n, 256), 256, 0, st>>>(mode, tokens, labels, lengths, tok0, tok1, target, n_copies, E, S);
 }
 
-void launch_copy_mean(hipStream_t st, const float* ce, int rows_per_copy, int count_per_copy, float* losses, int n_copies) {
-  copy_mean_kernel<<<n_copies, 256, 0, st>>>(ce, rows_per_copy, count_per_copy, losses);
+void launch_gather_last_rows(hipStream_t st, const float* h, const int32_t* lengths, int n_copies, int E, int S, int d,
+                             float* out) {
+  gather_last_rows_kernel<<<n_copies * E, 256, 0, st>>>(h, lengths, E, S, d, out);
+}
+
+void launch_copy_mean(hipStream_t st, const float* ce, int rows_per_copy, int count_per_copy, const int32_t* lengths, int E,
+                      int S, float* losses, int n_copies) {
+  copy_mean_kernel<<<n_copies, 256, 0, st>>>(ce, rows_per_copy, count_per_copy, lengths, E, S, losses);
 }
 
 void launch_fill_f32(hipStream_t st, float* p, float v, int64_t n) {

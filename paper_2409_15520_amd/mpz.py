@@ -86,6 +86,9 @@ def load_library() -> C.CDLL:
     lib.mpz_regen_noise.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_int32, C.c_float]
     lib.mpz_forward_perturbed.restype = C.c_int
     lib.mpz_forward_perturbed.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    lib.mpz_forward_perturbed_varlen.restype = C.c_int
+    lib.mpz_forward_perturbed_varlen.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                                 C.c_void_p]
     lib.mpz_forward_copies.restype = C.c_int
     lib.mpz_forward_copies.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                        C.c_void_p]
@@ -104,7 +107,8 @@ def load_library() -> C.CDLL:
     lib.mpz_debug_run_layers.restype = C.c_int
     lib.mpz_debug_run_layers.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.mpz_debug_head_loss.restype = C.c_int
-    lib.mpz_debug_head_loss.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    lib.mpz_debug_head_loss.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                        C.c_void_p]
     lib.mpz_debug_qkv_projection.restype = C.c_int
     lib.mpz_debug_qkv_projection.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
     lib.mpz_debug_attention.restype = C.c_int
@@ -178,6 +182,12 @@ def mpz_forward_perturbed(handle, tokens_ptr: int, labels_ptr: Optional[int], E:
     _check(load_library().mpz_forward_perturbed(handle, tokens_ptr, labels_ptr, E, S, losses_ptr), handle)
 
 
+def mpz_forward_perturbed_varlen(handle, tokens_ptr: int, labels_ptr: Optional[int], lengths_ptr: int, E: int, S: int,
+                                 losses_ptr: int):
+    _check(load_library().mpz_forward_perturbed_varlen(handle, tokens_ptr, labels_ptr, lengths_ptr, E, S, losses_ptr),
+           handle)
+
+
 def mpz_forward_copies(handle, tokens_ptr: int, labels_ptr: Optional[int], E: int, S: int, copy_begin: int,
                        n_copies: int, losses_ptr: int):
     _check(load_library().mpz_forward_copies(handle, tokens_ptr, labels_ptr, E, S, copy_begin, n_copies, losses_ptr),
@@ -212,8 +222,9 @@ def mpz_debug_run_layers(handle, h_ptr: int, layer_begin: int, layer_end: int, E
     _check(load_library().mpz_debug_run_layers(handle, h_ptr, layer_begin, layer_end, E, S), handle)
 
 
-def mpz_debug_head_loss(handle, h_ptr: int, tokens_ptr: int, labels_ptr: Optional[int], E: int, S: int, losses_ptr: int):
-    _check(load_library().mpz_debug_head_loss(handle, h_ptr, tokens_ptr, labels_ptr, E, S, losses_ptr), handle)
+def mpz_debug_head_loss(handle, h_ptr: int, tokens_ptr: int, labels_ptr: Optional[int], lengths_ptr: Optional[int], E: int,
+                        S: int, losses_ptr: int):
+    _check(load_library().mpz_debug_head_loss(handle, h_ptr, tokens_ptr, labels_ptr, lengths_ptr, E, S, losses_ptr), handle)
 
 
 def mpz_debug_qkv_projection(handle, x_ptr: int, layer: int, E: int, S: int, out_ptr: int):
@@ -364,9 +375,14 @@ class ZoModel:
         self.q = self.w.q if q is None else q
         mpz_regen_noise(self.handle, seed, step, self.q, self.w.eps if eps is None else eps)
 
-    def forward_perturbed(self, tokens, labels=None):
-        """tokens: int32 device tensor [E, S]; labels: int32 device tensor [E] or None. Returns losses[2q] (device)."""
+    def forward_perturbed(self, tokens, labels=None, lengths=None):
+        """tokens: int32 device tensor [E, S]; labels: int32 device tensor [E] or None; lengths: int32 device tensor [E]
+        for a right-padded batch, or None.  Returns losses[2q] (device)."""
         E, S = tokens.shape
+        if lengths is not None:
+            mpz_forward_perturbed_varlen(self.handle, tokens.data_ptr(), None if labels is None else labels.data_ptr(),
+                                         lengths.data_ptr(), E, S, self.losses.data_ptr())
+            return self.losses[:2 * self.q]
         mpz_forward_perturbed(self.handle, tokens.data_ptr(), None if labels is None else labels.data_ptr(), E, S,
                               self.losses.data_ptr())
         return self.losses[:2 * self.q]
@@ -419,10 +435,10 @@ class ZoModel:
         mpz_debug_run_layers(self.handle, h.data_ptr(), layer_begin, layer_end, E, S)
         return h
 
-    def head_loss(self, h, tokens, labels=None):
+    def head_loss(self, h, tokens, labels=None, lengths=None):
         E, S = tokens.shape
         mpz_debug_head_loss(self.handle, h.data_ptr(), tokens.data_ptr(), None if labels is None else labels.data_ptr(),
-                            E, S, self.losses.data_ptr())
+                            None if lengths is None else lengths.data_ptr(), E, S, self.losses.data_ptr())
         return self.losses[:2 * self.q]
 
     def close(self):

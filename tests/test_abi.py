@@ -106,6 +106,8 @@ def test_init_rejects_null_and_small_workspace_without_touching_the_device():
     assert lib.mpz_zo_update(h, 0x1000, 1e-4, None) == 5
     assert lib.mpz_zo_update_regen(h, 0x1000, 1e-4, 1, None) == 5                     # no stored pairs yet
     assert lib.mpz_zo_update_regen(None, None, 1e-4, 1, None) == 1
+    assert lib.mpz_forward_perturbed_varlen(h, 0x1000, 0x1000, None, 2, 32, 0x1000) == 1     # NULL lengths
+    assert lib.mpz_forward_perturbed_varlen(h, 0x1000, 0x1000, 0x1000, 2, 32, 0x1000) == 5   # before regen_noise
     assert lib.mpz_regen_noise(h, 1, 0, 3, 1e-3) == 3                                # q > q_max
     assert lib.mpz_regen_noise(h, 1, 0, 2, -1.0) == 2
     assert "eps" in M.mpz_last_error(h)
