@@ -59,6 +59,18 @@ def _lora_delta(x, lora, layer: int, target: str, scale: float, prec: Precision)
     return t @ prec.lora_factor(B)
 
 
+def _weight(lw, name: str) -> np.ndarray:
+    """Frozen weight [k_in, k_out] of a block in binary64.  With weight-only 8-bit quantisation (Appendix D,
+    "MobiZO with weight-only quantization": weights are stored in a low-bit format and dequantised for the forward
+    pass) the stored form is an int8 code per element and a scale per output channel; the weight is their exact
+    product (reading: no rounding to the 16-bit operand type on the way)."""
+    W = np.asarray(lw["w_" + name])
+    s = lw.get("s_" + name)
+    if s is None:
+        return W.astype(np.float64)
+    return W.astype(np.float64) * np.asarray(s, dtype=np.float64)[None, :]
+
+
 def _linear(x, W, b, delta=None):
     y = x @ np.asarray(W, dtype=np.float64)
     if b is not None:
@@ -107,7 +119,7 @@ def decoder_layer(w, lw, li: int, h, lora, prec: Precision):
     norm_eps = float(np.float32(w.norm_eps))            # hyper-parameters are binary32 numbers
     scale = float(np.float32(w.lora_scale))
     x = prec.operand(_norm(h, lw["ln1_g"], lw["ln1_b"], w.norm, norm_eps))
-    Wqkv, bqkv = lw["w_qkv"], lw["b_qkv"]
+    Wqkv, bqkv = _weight(lw, "qkv"), lw["b_qkv"]
     cols = {"q": (0, d), "k": (d, d + w.d_kv), "v": (d + w.d_kv, d + 2 * w.d_kv)}
     proj = {}
     for name, (c0, c1) in cols.items():
@@ -121,10 +133,10 @@ def decoder_layer(w, lw, li: int, h, lora, prec: Precision):
         qh, kh = _rope(qh, cos, sin), _rope(kh, cos, sin)
     qh, kh, vh = prec.operand(qh), prec.operand(kh), prec.operand(vh)
     attn = prec.operand(_attention(qh, kh, vh, H, Hkv, prec))
-    h = prec.stream(h + _linear(attn, lw["w_o"], lw["b_o"], _lora_delta(attn, lora, li, "o", scale, prec)))
+    h = prec.stream(h + _linear(attn, _weight(lw, "o"), lw["b_o"], _lora_delta(attn, lora, li, "o", scale, prec)))
 
     x = prec.operand(_norm(h, lw["ln2_g"], lw["ln2_b"], w.norm, norm_eps))
-    up = _linear(x, lw["w_up"], lw["b_up"])
+    up = _linear(x, _weight(lw, "up"), lw["b_up"])
     if w.act == "relu":
         u = np.maximum(up, 0.0)
     elif w.act == "gelu":
@@ -133,7 +145,7 @@ def decoder_layer(w, lw, li: int, h, lora, prec: Precision):
         gate, lin = up[..., :w.d_ffn], up[..., w.d_ffn:]
         u = gate / (1.0 + np.exp(-gate)) * lin
     u = prec.operand(u)
-    return prec.stream(h + _linear(u, lw["w_down"], lw["b_down"]))
+    return prec.stream(h + _linear(u, _weight(lw, "down"), lw["b_down"]))
 
 
 def head_loss(w, frozen, h, tokens: np.ndarray, labels, prec: Precision, lengths=None) -> float:

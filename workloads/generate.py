@@ -30,13 +30,23 @@ def _normal(rng: np.random.Generator, shape, std: float, bf16: bool) -> np.ndarr
     return to_bf16_values(x) if bf16 else x
 
 
+def _int8_weight(rng: np.random.Generator, shape):
+    """Synthetic weight-only int8 linear [k_in, k_out]: codes ~ round(N(0, 32^2)) clipped to [-127, 127] and one
+    float32 scale per output channel, 0.02/32 times a factor in [0.75, 1.25] (so the product is ~ N(0, 0.02^2) and
+    a per-channel mix-up is visible)."""
+    q = np.clip(np.rint(rng.standard_normal(shape, dtype=np.float32) * np.float32(32.0)), -127, 127).astype(np.int8)
+    s = (np.float32(0.02 / 32.0) * (np.float32(0.75) + np.float32(0.5) * rng.random(shape[1], dtype=np.float32)))
+    return q, s.astype(np.float32)
+
+
 def make_frozen_weights(w: Workload, seed: int, n_layers: Optional[int] = None) -> Dict[str, object]:
     """Frozen parameters as float32 arrays (bf16-representable when w.dtype == 'bf16').
 
     Layout: every linear is [k_in, k_out] row-major so that y = x W.  `w_qkv` is the column
     concatenation [W_q | W_k | W_v]; for SwiGLU `w_up` is [W_gate | W_up].  `emb` is
     [vocab, d]; `lm_head` is [vocab, d] (the same array as `emb` when embeddings are tied).
-    Norm gains/biases are float32.
+    Norm gains/biases are float32.  With w.weight_quant == "int8" the four linears of a block are int8 codes
+    `w_*` [k_in, k_out] with float32 scales `s_*` [k_out] (embeddings and the head stay in the model dtype).
     """
     L = w.n_layers if n_layers is None else n_layers
     bf = w.dtype == "bf16"
@@ -63,6 +73,11 @@ def make_frozen_weights(w: Workload, seed: int, n_layers: Optional[int] = None) 
             "w_down": _normal(rng, (f, d), 0.02, bf),
             "b_down": _normal(rng, (d,), 0.02, False) if w.has_bias else None,
         }
+        if w.weight_quant == "int8":
+            for name in ("qkv", "o", "up", "down"):
+                lw["w_" + name], lw["s_" + name] = _int8_weight(rng, lw["w_" + name].shape)
+        elif w.weight_quant != "none":
+            raise ValueError(f"unknown weight_quant {w.weight_quant!r}")
         layers.append(lw)
     out["layers"] = layers
     out["lnf_g"] = np.ones(d, np.float32)
