@@ -52,6 +52,7 @@ enum { MPZ_ACT_RELU = 0, MPZ_ACT_GELU_ERF = 1, MPZ_ACT_SWIGLU = 2 };
 enum { MPZ_NORM_LAYERNORM = 0, MPZ_NORM_RMSNORM = 1 };
 enum { MPZ_POS_LEARNED = 0, MPZ_POS_ROPE = 1 };
 enum { MPZ_DTYPE_F32 = 0, MPZ_DTYPE_BF16 = 1 };
+enum { MPZ_WEIGHT_QUANT_NONE = 0, MPZ_WEIGHT_QUANT_INT8 = 1 };
 enum { MPZ_TARGET_Q = 1, MPZ_TARGET_K = 2, MPZ_TARGET_V = 4, MPZ_TARGET_O = 8 };
 enum {
   MPZ_LOSS_LAST_POS_LABEL_SUBSET = 0, /* 2-way CE over two label-token logits at the last position */
@@ -78,6 +79,11 @@ typedef struct {
                              A frozen and shared by all copies, only B perturbed and updated */
   int32_t loss_mode;      /* MPZ_LOSS_* */
   int32_t label_token[2]; /* vocabulary ids of the two label words (last-position modes) */
+  int32_t weight_quant;   /* MPZ_WEIGHT_QUANT_*: weight-only quantisation of the four linears of every block
+                             (Appendix D, "MobiZO with weight-only quantization").  INT8: w_* hold int8 codes and
+                             s_* one fp32 scale per output channel, W = code * scale exactly; needs dtype BF16,
+                             d_model and d_ffn multiples of 64 and E*S a multiple of 32 (MFMA path only).  The codes
+                             are widened once per step for all 2q copies, inside the GEMM's operand load. */
 } mpz_config;
 
 /* Frozen parameters theta_f of one decoder block (Algorithm 1, input line).  All [dev], borrowed. */
@@ -94,6 +100,12 @@ typedef struct {
   const float* b_up;  /* [d_ffn] (SwiGLU: [2*d_ffn]) or NULL */
   const void* w_down; /* [d, d_ffn] */
   const float* b_down;/* [d] or NULL */
+  /* weight_quant = INT8 only (else ignored): per-output-channel scales, 16-byte aligned; the w_* above are then int8
+   * with the same [k_out, k_in] shapes */
+  const float* s_qkv; /* [d + 2*d_kv] */
+  const float* s_o;   /* [d] */
+  const float* s_up;  /* [d_ffn] (SwiGLU: [2*d_ffn]) */
+  const float* s_down;/* [d] */
 } mpz_layer_weights;
 
 typedef struct {
@@ -237,6 +249,12 @@ mpz_status mpz_debug_attention(mpz_model* m, const void* qkv, int32_t n_seq, int
  * gate then up, bias 2N, out = SiLU(gate) * up); tile_cfg 0 = chosen by shape, 1..11 = a fixed block-tile configuration (unsupported numbers fall back to the choice by shape).  Errors: NULL, SHAPE (K % 64, N % 4). */
 mpz_status mpz_debug_gemm_bf16(int32_t M, int32_t N, int32_t K, const void* x, const void* w, const float* bias,
                                int32_t act, void* out, int32_t out_f32, int32_t tile_cfg, void* hip_stream);
+/* The same with weight-only int8 weights: w_codes [dev] int8 [N, K] (SwiGLU: [2N, K]), w_scale [dev] fp32 [N] ([2N]),
+ * 16-byte aligned; out = act(x (codes * scale)^T + bias).  Tile configurations 1, 6 and 11 only (others fall back to
+ * the choice by shape). */
+mpz_status mpz_debug_gemm_int8(int32_t M, int32_t N, int32_t K, const void* x, const void* w_codes, const float* w_scale,
+                               const float* bias, int32_t act, void* out, int32_t out_f32, int32_t tile_cfg,
+                               void* hip_stream);
 
 /* Test hook: simple_only != 0 routes every stage through the shape-agnostic kernels (the only path of
  * fp32 models); 0 restores the default (bf16 models use the MFMA kernels wherever a shape allows).

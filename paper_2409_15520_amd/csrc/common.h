@@ -71,7 +71,8 @@ struct LinearArgs {
   int dtype;                  // MPZ_DTYPE_*
   int M, N, K;
   const void* x;              // [M, K] model dtype
-  const void* w;              // [N, K] model dtype (output-major)
+  const void* w;              // [N, K] model dtype (output-major); int8 codes when w_scale is set
+  const float* w_scale;       // [N] per-output-channel scales of int8 weights, or null
   const float* bias;          // [N] or null
   int n_seg; LoraSeg seg[3];
   int mfma_lora; MfmaLoraSeg mseg[3];   // the same segments in the MFMA kernels' operand layouts (when prepared)
@@ -121,6 +122,8 @@ void launch_fill_f32(hipStream_t st, float* p, float v, int64_t n);
 struct MfmaGemmArgs {
   int M, N, K;                  // out[M, N] = x[M, K] w[N, K]^T ; dual: N = columns of ONE of the two tiles
   const void* x; const void* w;
+  const float* w_scale;         // null: w is bf16.  Else w holds int8 codes [w_rows, K] and w_scale [w_rows] the
+                                // per-output-channel scales: the product is x . (code * scale)
   int w_rows;                   // rows of w (N, or 2N for dual): bounds the weight buffer
   const float* bias;            // [N] (dual: [dual_offset + N]) or null
   int dual; int dual_offset;    // dual: second weight tile starts dual_offset rows below (SwiGLU gate | up)

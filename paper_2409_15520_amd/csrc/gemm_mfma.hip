@@ -56,15 +56,33 @@ __device__ __forceinline__ void sched_step() {
 }
 
 // one phase: NF fragment reads of K-step 0, then KS steps of NM MFMAs, each carrying the next step's NF reads
-// and its share of the NV global loads and NV LDS stores
-template <int NM, int NF, int NV, int KS, int S = 0>
+// and its share of the tile's NUW + NUX fetch units (one global load each; WPU LDS stores per W unit, one per X unit)
+template <int NM, int NF, int NUW, int NUX, int WPU, int KS, int S = 0>
 __device__ __forceinline__ void sched_phase() {
   if constexpr (S == 0) __builtin_amdgcn_sched_group_barrier(0x100, NF, 0);
   if constexpr (S < KS) {
-    constexpr int nv = ((S + 1) * NV + KS - 1) / KS - (S * NV + KS - 1) / KS;   // this step's share of the tile
-    sched_step<NM, (S + 1 < KS ? NF : 0), nv, nv>();
-    sched_phase<NM, NF, NV, KS, S + 1>();
+    constexpr int NU = NUW + NUX;
+    constexpr int lo = (S * NU + KS - 1) / KS, hi = ((S + 1) * NU + KS - 1) / KS;   // this step's units
+    constexpr int wlo = lo < NUW ? lo : NUW, whi = hi < NUW ? hi : NUW;
+    constexpr int nvm = hi - lo, ndsw = (whi - wlo) * WPU + (hi - lo) - (whi - wlo);
+    sched_step<NM, (S + 1 < KS ? NF : 0), nvm, ndsw>();
+    sched_phase<NM, NF, NUW, NUX, WPU, KS, S + 1>();
   }
+}
+
+// 16 int8 codes (one 16-byte chunk along K) -> 16 bf16, exact: |code| <= 127 has 7 significant bits
+__device__ __forceinline__ void i8x16_to_bf16(u32x4 in, u32x4& lo8, u32x4& hi8) {
+  uint32_t o[8];
+#pragma unroll
+  for (int wd = 0; wd < 4; ++wd) {
+    const uint32_t v = in[wd];
+    const float f0 = (float)(int8_t)(v & 0xff), f1 = (float)(int8_t)((v >> 8) & 0xff);
+    const float f2 = (float)(int8_t)((v >> 16) & 0xff), f3 = (float)(int8_t)(v >> 24);
+    o[2 * wd] = pack_bf16x2(f0, f1);
+    o[2 * wd + 1] = pack_bf16x2(f2, f3);
+  }
+  lo8 = u32x4{o[0], o[1], o[2], o[3]};
+  hi8 = u32x4{o[4], o[5], o[6], o[7]};
 }
 
 // Block tile BN (output features) x BM (tokens), K-step BK, WGN x WGM waves, each wave (BN/WGN) x (BM/WGM) =
@@ -73,7 +91,7 @@ __device__ __forceinline__ void sched_phase() {
 // conflict-free for BK = 32 and BK = 64.
 // HP > 0: rotary embedding fused into the epilogue for head width 64 * HP (the partner column d_head/2 away sits in
 // the same lane, HP MFMA tiles further), for output columns below rope_cols; the result is stored as bf16.
-template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP>
+template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP, bool WQ>
 __global__ void __launch_bounds__(64 * WGN * WGM, (BN * BM * (DUAL ? 2 : 1) <= 256 * 128 && WGN * WGM == 4 && !(BN == 192 && BK == 64)) ? 2 : 1)
 gemm_bf16_kernel(MfmaGemmArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -82,8 +100,10 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   constexpr int TILE_W = BN * LDS_STRIDE, TILE_X = BM * LDS_STRIDE;     // elements per operand tile per stage
   constexpr int NT = 64 * WGN * WGM;                                     // threads per block
   constexpr int TN = BN / WGN, TM = BM / WGM, NI = TN / 32, NJ = TM / 32;
-  constexpr int CPR = BK / 8;                                            // 16-byte chunks per tile row
-  constexpr int LW = BN * CPR / NT, LX = BM * CPR / NT;                  // chunks per thread and tile
+  constexpr int CPR = BK / 8;                                            // 16-byte chunks per bf16 tile row
+  constexpr int WCH = WQ ? BK / 16 : CPR;                                // 16-byte chunks per W tile row (int8: 16 codes each)
+  constexpr int LW = BN * WCH / NT, LX = BM * CPR / NT;                  // chunks per thread and tile
+  static_assert(BN * WCH % NT == 0 && BM * CPR % NT == 0, "tile rows must deal out evenly to the threads");
   uint16_t* sW = (uint16_t*)smem;                        // [2 stages][NW][BN][LDS_STRIDE]
   uint16_t* sX = sW + 2 * NW * TILE_W;                   // [2 stages][BM][LDS_STRIDE]
 
@@ -114,16 +134,16 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   // Operand fetch: raw buffer loads (per-thread byte offset in a VGPR, the K offset of the tile in an SGPR);
   // rows past the end of W or X fall outside the buffer and read as zero, so ragged M / N need no clamps.
   const __amdgpu_buffer_rsrc_t rsrcW =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.w), 0, (int)((size_t)a.w_rows * a.K * 2), 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.w), 0, (int)((size_t)a.w_rows * a.K * (WQ ? 1 : 2)), 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrcX =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.x), 0, (int)((size_t)a.M * a.K * 2), 0x00020000);
   uint32_t voffW[NW][LW], voffX[LX];
   int ldsW[LW], ldsX[LX];
 #pragma unroll
   for (int i = 0; i < LW; ++i) {
-    const int c = tid + NT * i, row = c / CPR, kc = (c % CPR) * 8;
-    voffW[0][i] = ((uint32_t)(n0 + row) * (uint32_t)a.K + kc) * 2u;
-    if (DUAL) voffW[NW - 1][i] = ((uint32_t)(n0 + row + a.dual_offset) * (uint32_t)a.K + kc) * 2u;
+    const int c = tid + NT * i, row = c / WCH, kc = (c % WCH) * (WQ ? 16 : 8);
+    voffW[0][i] = ((uint32_t)(n0 + row) * (uint32_t)a.K + kc) * (WQ ? 1u : 2u);
+    if (DUAL) voffW[NW - 1][i] = ((uint32_t)(n0 + row + a.dual_offset) * (uint32_t)a.K + kc) * (WQ ? 1u : 2u);
     ldsW[i] = row * LDS_STRIDE + kc;
   }
 #pragma unroll
@@ -133,12 +153,24 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
     ldsX[i] = row * LDS_STRIDE + kc;
   }
   u32x4 rw[2][NW][LW], rx[2][LX];
+  // int8 weights: a fetched chunk is 16 codes; it becomes two 16-byte chunks of bf16 on its way into LDS
+#define MPZ_PUT_W(ptr, v)                                                          \
+  {                                                                                \
+    if constexpr (WQ) {                                                            \
+      u32x4 lo8_, hi8_;                                                            \
+      i8x16_to_bf16(v, lo8_, hi8_);                                                \
+      *(u32x4*)(ptr) = lo8_;                                                       \
+      *(u32x4*)((ptr) + 8) = hi8_;                                                 \
+    } else {                                                                       \
+      *(u32x4*)(ptr) = v;                                                          \
+    }                                                                              \
+  }
 #define MPZ_LOAD_GLOBAL(set, kt)                                                   \
   {                                                                                \
     const int soff = (kt) * BK * 2;                                                \
     _Pragma("unroll") for (int d = 0; d < NW; ++d)                                 \
       _Pragma("unroll") for (int i = 0; i < LW; ++i)                               \
-        rw[set][d][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, voffW[d][i], soff, 0); \
+        rw[set][d][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, voffW[d][i], WQ ? soff / 2 : soff, 0); \
     _Pragma("unroll") for (int i = 0; i < LX; ++i)                                 \
       rx[set][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcX, voffX[i], soff, 0); \
     __builtin_amdgcn_sched_barrier(0);   /* keep the fetch here: the scheduler would sink it to its use */ \
@@ -147,7 +179,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   {                                                                                \
     _Pragma("unroll") for (int d = 0; d < NW; ++d)                                 \
       _Pragma("unroll") for (int i = 0; i < LW; ++i)                               \
-        *(u32x4*)(sW + ((stage) * NW + d) * TILE_W + ldsW[i]) = rw[set][d][i];     \
+        MPZ_PUT_W(sW + ((stage) * NW + d) * TILE_W + ldsW[i], rw[set][d][i])       \
     _Pragma("unroll") for (int i = 0; i < LX; ++i)                                 \
       *(u32x4*)(sX + (stage) * TILE_X + ldsX[i]) = rx[set][i];                     \
     __builtin_amdgcn_sched_barrier(0);                                             \
@@ -195,8 +227,8 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
         if (c >= (s * NV + KS - 1) / KS && c < ((s + 1) * NV + KS - 1) / KS) {     \
           if (c < NW * LW) {                                                       \
             const int d = c / LW, i = c % LW;                                      \
-            *(u32x4*)(sW + ((nxt) * NW + d) * TILE_W + ldsW[i]) = rw[sset][d][i];  \
-            rw[lset][d][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, voffW[d][i], soff, 0); \
+            MPZ_PUT_W(sW + ((nxt) * NW + d) * TILE_W + ldsW[i], rw[sset][d][i])    \
+            rw[lset][d][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, voffW[d][i], WQ ? soff / 2 : soff, 0); \
           } else {                                                                 \
             const int i = c - NW * LW;                                             \
             *(u32x4*)(sX + (nxt) * TILE_X + ldsX[i]) = rx[sset][i];                \
@@ -206,7 +238,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
       }                                                                            \
       MPZ_MFMAS(s & 1)                                                             \
     }                                                                              \
-    sched_phase<NM, NF, NV, KS>();                                                 \
+    sched_phase<NM, NF, NW * LW, LX, WQ ? 2 : 1, KS>();                            \
   }
 
   f32x16 acc[NW][NI][NJ];
@@ -263,11 +295,31 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   }
   if (kt < nk) MPZ_COMPUTE(0)            // odd number of tiles: the last one is already in stage 0
 #undef MPZ_LOAD_GLOBAL
+#undef MPZ_PUT_W
 #undef MPZ_READ_FRAGS
 #undef MPZ_MFMAS
 #undef MPZ_PHASE
 #undef MPZ_STORE_LDS
 #undef MPZ_COMPUTE
+
+  // int8 weights: the accumulators hold x . codes; the per-output-channel scale turns them into x . W before
+  // anything else (low-rank term, bias) is added
+  if constexpr (WQ) {
+#pragma unroll
+    for (int d = 0; d < NW; ++d)
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          int n = n0 + wn + i * 32 + g * 8 + lhalf * 4;
+          n = n < a.N ? n : 0;
+          const f32x4 sc = *(const f32x4*)(a.w_scale + (d == 0 ? 0 : a.dual_offset) + n);
+#pragma unroll
+          for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[d][i][j][g * 4 + e] *= sc[e];
+        }
+  }
 
   // per-copy low-rank term: extra K-steps with the packed factor [B_hi | B_lo] of a copy against the duplicated
   // bottleneck activations [t | t].  Copies are whole multiples of 32 rows, so every 32-row MFMA tile belongs to
@@ -672,19 +724,19 @@ __global__ void __launch_bounds__(256) pack_factors_vec_kernel(const float* __re
 //   3 128 256  32  2    61.4 KB   general, tall
 //   4 256 256  32  1    81.9 KB   large problems (lowest LDS traffic per MFMA)
 //  dual (SwiGLU): 2 x 128 x 128 x 32, 2 sets, 61.4 KB
-template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP = 0>
+template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP = 0, bool WQ = false>
 void launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
   constexpr size_t lds_stages = (size_t)2 * ((DUAL ? 2 : 1) * BN + BM) * (BK + 8) * 2;
   constexpr size_t lds_strips = (size_t)WGN * WGM * 32 * (BN / WGN + 4) * 4;          // epilogue: one strip per wave
   constexpr size_t lds = lds_stages > lds_strips ? lds_stages : lds_strips;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP>,
+    (void)hipFuncSetAttribute((const void*)gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP, WQ>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_set = true;
   }
   const int tiles = ((a.N + BN - 1) / BN) * ((a.M + BM - 1) / BM);
-  gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
+  gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP, WQ><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
 }
 
 int tile_bn(int cfg) { return cfg == 11 ? 192 : (cfg == 2 || (cfg >= 5 && cfg <= 8)) ? 256 : 128; }   // 7, 8: 256 x 128 (4 is unused)
@@ -700,7 +752,8 @@ bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
 }
 
 int choose_cfg(const MfmaGemmArgs& a) {
-  if (a.tile_cfg >= 1 && a.tile_cfg <= 11 && a.tile_cfg != 4 && a.tile_cfg != 10 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
+  const bool forced_ok = a.w_scale == nullptr || a.tile_cfg == 1 || a.tile_cfg == 6 || a.tile_cfg == 11;   // int8: fewer instances
+  if (forced_ok && a.tile_cfg >= 1 && a.tile_cfg <= 11 && a.tile_cfg != 4 && a.tile_cfg != 10 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
   // enough 256 x 256 tiles to keep 256 CUs busy for several rounds -> biggest tile; else the largest tile that
   // still gives at least ~2 blocks per CU
   // The L2 -> CU path feeds about 64 B/clk per CU, which a 128 x 128 tile needs in full at MFMA peak; 256 x 256
@@ -759,6 +812,7 @@ void launch_ce_combine(hipStream_t st, int slots, int M, const float* ce_max, co
 bool mfma_gemm_supported(const MfmaGemmArgs& a) {
   if (a.K % 64 || a.N % 4 || a.M < 1 || a.N < 1) return false;
   if ((size_t)a.M * a.K * 2 >= ((size_t)1 << 31) || (size_t)(a.dual ? 2 : 1) * a.N * a.K * 2 >= ((size_t)1 << 31)) return false;
+  if (a.w_scale != nullptr && (a.K % 16 || ((uintptr_t)a.w_scale & 15))) return false;
   for (int s = 0; s < a.n_seg; ++s)
     if (a.seg[s].rp % 16) return false;
   if (!cfg_ok(a, 1)) return false;
@@ -775,20 +829,33 @@ bool mfma_gemm_supported(const MfmaGemmArgs& a) {
 }
 
 void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
+  const bool q8 = a.w_scale != nullptr;      // int8 weights: the configurations the model path uses
   if (a.dual) {
     const long tb = (long)((a.N + 127) / 128) * ((a.M + 255) / 256);
-    if ((a.tile_cfg == 0 && tb >= 512) || a.tile_cfg == 6) launch_cfg<128, 256, 64, 2, 4, true>(st, a);   // 2 x 128 x 256, 8 waves
-    else if (a.tile_cfg == 5) launch_cfg<128, 256, 32, 2, 4, true>(st, a);
-    else launch_cfg<128, 128, 32, 2, 2, true>(st, a);
+    if ((a.tile_cfg == 0 && tb >= 512) || a.tile_cfg == 6) {               // 2 x 128 x 256, 8 waves
+      if (q8) launch_cfg<128, 256, 64, 2, 4, true, 0, true>(st, a); else launch_cfg<128, 256, 64, 2, 4, true>(st, a);
+    } else if (a.tile_cfg == 5 && !q8) {
+      launch_cfg<128, 256, 32, 2, 4, true>(st, a);
+    } else {
+      if (q8) launch_cfg<128, 128, 32, 2, 2, true, 0, true>(st, a); else launch_cfg<128, 128, 32, 2, 2, true>(st, a);
+    }
     return;
   }
   if (a.rope_cos != nullptr) {             // fused rotary epilogue: only the two configurations the model path uses
     const int cfg = choose_cfg(a);
     if (cfg == 5 || cfg == 6) {
-      if (a.rope_dh == 64) launch_cfg<256, 256, 64, 2, 4, false, 1>(st, a);
-      else launch_cfg<256, 256, 64, 2, 4, false, 2>(st, a);
+      if (a.rope_dh == 64) { if (q8) launch_cfg<256, 256, 64, 2, 4, false, 1, true>(st, a); else launch_cfg<256, 256, 64, 2, 4, false, 1>(st, a); }
+      else { if (q8) launch_cfg<256, 256, 64, 2, 4, false, 2, true>(st, a); else launch_cfg<256, 256, 64, 2, 4, false, 2>(st, a); }
     } else {
-      launch_cfg<128, 128, 64, 2, 2, false, 1>(st, a);
+      if (q8) launch_cfg<128, 128, 64, 2, 2, false, 1, true>(st, a); else launch_cfg<128, 128, 64, 2, 2, false, 1>(st, a);
+    }
+    return;
+  }
+  if (q8) {
+    switch (choose_cfg(a)) {
+      case 6: launch_cfg<256, 256, 64, 2, 4, false, 0, true>(st, a); break;
+      case 11: launch_cfg<192, 128, 64, 2, 2, false, 0, true>(st, a); break;
+      default: launch_cfg<128, 128, 64, 2, 2, false, 0, true>(st, a); break;
     }
     return;
   }

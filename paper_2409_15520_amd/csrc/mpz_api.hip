@@ -66,6 +66,10 @@ const char* validate_config(const mpz_config* c) {
   if (c->d_model % 4) return "d_model must be a multiple of 4";
   if (!(c->norm_eps > 0.f) || !std::isfinite(c->lora_scale)) return "norm_eps must be positive and lora_scale finite";
   if (c->loss_mode < 0 || c->loss_mode > 2) return "unknown loss_mode";
+  if (c->weight_quant != MPZ_WEIGHT_QUANT_NONE && c->weight_quant != MPZ_WEIGHT_QUANT_INT8) return "unknown weight_quant";
+  if (c->weight_quant == MPZ_WEIGHT_QUANT_INT8 && (c->dtype != MPZ_DTYPE_BF16 || c->d_model % 64 || c->d_ffn % 64 ||
+                                                   (c->n_kv_heads * (c->d_model / c->n_heads)) % 2))
+    return "int8 weights need dtype BF16 and d_model, d_ffn multiples of 64";
   if (c->loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS) {
     for (int i = 0; i < 2; ++i)
       if (c->label_token[i] < 0 || c->label_token[i] >= c->vocab) return "label token id outside the vocabulary";
@@ -162,6 +166,7 @@ struct mpz_model {
   int cb = 0, nc = 0;                           // copies [cb, cb + nc) processed by the current pass
   int force_tile_cfg = 0;                       // test hook: GEMM block-tile configuration (0 = by shape)
   const int32_t* lengths = nullptr;             // [dev] per-sequence lengths of the pass in flight (right-padded batch), or null
+  const char* deferred = nullptr;               // set by a launch helper that had to refuse; reported by check_device
   std::string err;
   // optional per-launch timing by kernel category (mpz_profile_begin / _end)
   // bf16 MFMA path
@@ -186,6 +191,11 @@ mpz_status fail(mpz_model* m, mpz_status s, const std::string& msg) {
 }
 
 mpz_status check_device(mpz_model* m, const char* where) {
+  if (m && m->deferred) {                       // a launch helper refused (nothing was enqueued for that operation)
+    const char* msg = m->deferred;
+    m->deferred = nullptr;
+    return fail(m, MPZ_ERR_SHAPE, std::string(where) + ": " + msg);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(m, MPZ_ERR_DEVICE, std::string(where) + ": " + hipGetErrorString(e));
   return MPZ_OK;
@@ -247,7 +257,7 @@ bool gemm(mpz_model* m, const LinearArgs& a) {
   if (a.rope_cos != nullptr) {
     if (!(m->use_mfma && a.dtype == MPZ_DTYPE_BF16 && (a.n_seg == 0 || a.mfma_lora))) return false;
     MfmaGemmArgs g{};
-    g.M = a.M; g.N = a.N; g.K = a.K; g.x = a.x; g.w = a.w; g.w_rows = a.N; g.bias = a.bias;
+    g.M = a.M; g.N = a.N; g.K = a.K; g.x = a.x; g.w = a.w; g.w_scale = a.w_scale; g.w_rows = a.N; g.bias = a.bias;
     g.n_seg = a.n_seg; g.rows_per_copy = a.rows_per_copy; g.act = -1; g.out_f32 = 0; g.out = a.out; g.ldo = a.N;
     for (int i = 0; i < a.n_seg; ++i) g.seg[i] = a.mseg[i];
     g.rope_cos = a.rope_cos; g.rope_sin = a.rope_sin; g.rope_cols = a.rope_cols; g.rope_dh = a.rope_dh; g.S = a.S;
@@ -262,12 +272,16 @@ bool gemm(mpz_model* m, const LinearArgs& a) {
                    (a.residual ? 4.0 * a.M * (double)a.N : 0.0));
   if (m->use_mfma && a.dtype == MPZ_DTYPE_BF16 && (a.n_seg == 0 || a.mfma_lora)) {
     MfmaGemmArgs g{};
-    g.M = a.M; g.N = a.N; g.K = a.K; g.x = a.x; g.w = a.w; g.w_rows = a.N; g.bias = a.bias; g.dual = 0; g.dual_offset = 0;
+    g.M = a.M; g.N = a.N; g.K = a.K; g.x = a.x; g.w = a.w; g.w_scale = a.w_scale; g.w_rows = a.N; g.bias = a.bias; g.dual = 0; g.dual_offset = 0;
     g.n_seg = a.n_seg; g.rows_per_copy = a.rows_per_copy; g.act = a.act; g.residual = a.residual;
     g.out_f32 = a.out_kind != 0; g.out = a.out; g.ldo = a.N;   // bf16 models stage in fp32
     g.tile_cfg = m->force_tile_cfg;
     for (int i = 0; i < a.n_seg; ++i) g.seg[i] = a.mseg[i];
     if (mfma_gemm_supported(g)) { launch_gemm_mfma(m->stream, g); return true; }
+  }
+  if (a.w_scale != nullptr) {                  // no shape-agnostic kernel reads int8 weights: refuse, loudly
+    m->deferred = "int8 weights: a GEMM of this pass has a shape the MFMA kernel does not take";
+    return true;
   }
   launch_linear_simple(m->stream, a);
   return true;
@@ -277,7 +291,7 @@ bool gemm(mpz_model* m, const LinearArgs& a) {
 bool gemm_swiglu_mfma(mpz_model* m, const LinearArgs& a, int f, void* u_out) {
   if (!m->use_mfma) return false;
   MfmaGemmArgs g{};
-  g.M = a.M; g.N = f; g.K = a.K; g.x = a.x; g.w = a.w; g.w_rows = 2 * f; g.bias = a.bias; g.dual = 1; g.dual_offset = f;
+  g.M = a.M; g.N = f; g.K = a.K; g.x = a.x; g.w = a.w; g.w_scale = a.w_scale; g.w_rows = 2 * f; g.bias = a.bias; g.dual = 1; g.dual_offset = f;
   g.rows_per_copy = a.rows_per_copy; g.act = -1; g.out_f32 = 0; g.out = u_out; g.ldo = f;
   g.tile_cfg = m->force_tile_cfg;
   if (!mfma_gemm_supported(g)) return false;
@@ -327,7 +341,7 @@ void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, bool rope, int
     da.dtype = c.dtype; da.T = T; da.K = d; da.rank = r; da.rows_per_copy = rpc; da.x = b.x; da.scale = c.lora_scale;
     da.copy_stride = m->P; da.t = b.t;
     LinearArgs qa{};
-    qa.dtype = c.dtype; qa.M = T; qa.N = nqkv; qa.K = d; qa.x = b.x; qa.w = lw.w_qkv; qa.bias = lw.b_qkv;
+    qa.dtype = c.dtype; qa.M = T; qa.N = nqkv; qa.K = d; qa.x = b.x; qa.w = lw.w_qkv; qa.w_scale = lw.s_qkv; qa.bias = lw.b_qkv;
     qa.rank = r; qa.rows_per_copy = rpc; qa.act = -1; qa.residual = nullptr;
     const int col0[3] = {0, d, d + dkv}, col1[3] = {d, d + dkv, nqkv};
     int nt = 0;
@@ -419,7 +433,7 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     da.dtype = c.dtype; da.T = T; da.K = d; da.rank = r; da.rows_per_copy = rpc; da.scale = c.lora_scale;
     da.copy_stride = m->P; da.t = b.t;
     LinearArgs oa{};
-    oa.dtype = c.dtype; oa.M = T; oa.N = d; oa.K = d; oa.x = b.attn; oa.w = lw.w_o; oa.bias = lw.b_o;
+    oa.dtype = c.dtype; oa.M = T; oa.N = d; oa.K = d; oa.x = b.attn; oa.w = lw.w_o; oa.w_scale = lw.s_o; oa.bias = lw.b_o;
     oa.rank = r; oa.rows_per_copy = rpc; oa.act = -1; oa.residual = b.h; oa.out_kind = 1; oa.out = b.h;
     if (c.lora_targets & MPZ_TARGET_O) {
       LoraDownArgs oda = da;
@@ -454,7 +468,7 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     // feed-forward block
     norm(m, b.h, d, lw.ln2_g, lw.ln2_b, b.x, T);
     LinearArgs ua{};
-    ua.dtype = c.dtype; ua.M = T; ua.N = swiglu ? 2 * f : f; ua.K = d; ua.x = b.x; ua.w = lw.w_up; ua.bias = lw.b_up;
+    ua.dtype = c.dtype; ua.M = T; ua.N = swiglu ? 2 * f : f; ua.K = d; ua.x = b.x; ua.w = lw.w_up; ua.w_scale = lw.s_up; ua.bias = lw.b_up;
     ua.rank = r; ua.rows_per_copy = rpc; ua.act = swiglu ? -1 : c.act;
     ua.out_kind = swiglu ? 2 : 0; ua.out = swiglu ? b.stage : b.u;
     if (!(swiglu && gemm_swiglu_mfma(m, ua, f, b.u))) {
@@ -465,7 +479,7 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
       }
     }
     LinearArgs wa{};
-    wa.dtype = c.dtype; wa.M = T; wa.N = d; wa.K = f; wa.x = b.u; wa.w = lw.w_down; wa.bias = lw.b_down;
+    wa.dtype = c.dtype; wa.M = T; wa.N = d; wa.K = f; wa.x = b.u; wa.w = lw.w_down; wa.w_scale = lw.s_down; wa.bias = lw.b_down;
     wa.rank = r; wa.rows_per_copy = rpc; wa.act = -1; wa.residual = b.h; wa.out_kind = 1; wa.out = b.h;
     gemm(m, wa);
   }
@@ -609,6 +623,11 @@ mpz_status mpz_init_model(const mpz_config* cfg, const mpz_weights* frozen, floa
     if (cfg->norm == MPZ_NORM_LAYERNORM && (!lw.ln1_b || !lw.ln2_b)) return fail(nullptr, MPZ_ERR_NULL, "LayerNorm needs biases");
     if (cfg->has_bias && (!lw.b_qkv || !lw.b_o || !lw.b_up || !lw.b_down))
       return fail(nullptr, MPZ_ERR_NULL, "has_bias set but a linear bias is NULL");
+    if (cfg->weight_quant == MPZ_WEIGHT_QUANT_INT8) {
+      if (!lw.s_qkv || !lw.s_o || !lw.s_up || !lw.s_down) return fail(nullptr, MPZ_ERR_NULL, "int8 weights need their scales");
+      if ((((uintptr_t)lw.s_qkv | (uintptr_t)lw.s_o | (uintptr_t)lw.s_up | (uintptr_t)lw.s_down) & 15u) != 0)
+        return fail(nullptr, MPZ_ERR_CONFIG, "int8 weight scales must be 16-byte aligned");
+    }
   }
   if (((uintptr_t)workspace & 255u) != 0) return fail(nullptr, MPZ_ERR_WORKSPACE, "workspace is not 256-byte aligned");
   size_t need = carve(cfg, q_max, E_max, S_max, nullptr, nullptr);
@@ -625,6 +644,8 @@ mpz_status mpz_init_model(const mpz_config* cfg, const mpz_weights* frozen, floa
     for (auto& lw : m->layers) lw.b_qkv = lw.b_o = lw.b_up = lw.b_down = nullptr;
   if (cfg->norm == MPZ_NORM_RMSNORM)
     for (auto& lw : m->layers) lw.ln1_b = lw.ln2_b = nullptr;
+  if (cfg->weight_quant != MPZ_WEIGHT_QUANT_INT8)
+    for (auto& lw : m->layers) lw.s_qkv = lw.s_o = lw.s_up = lw.s_down = nullptr;
   m->w = *frozen;
   m->w.layers = m->layers.data();
   if (cfg->norm == MPZ_NORM_RMSNORM) m->w.lnf_b = nullptr;
@@ -688,6 +709,8 @@ mpz_status mpz_forward_perturbed(mpz_model* m, const int32_t* tokens, const int3
   if (m->cfg.loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS && !labels) return fail(m, MPZ_ERR_NULL, "this loss mode needs labels");
   if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_forward_perturbed before mpz_regen_noise");
   if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
+  if (m->cfg.weight_quant == MPZ_WEIGHT_QUANT_INT8 && ((E * S) % 32 || !m->use_mfma))
+    return fail(m, MPZ_ERR_SHAPE, "int8 weights: E*S must be a multiple of 32 (MFMA kernels only)");
   m->cb = 0; m->nc = 2 * m->q;
   run_embed(m, tokens, E, S, m->buf.h);
   run_layers(m, m->buf.h, 0, m->cfg.n_layers, E, S);
@@ -848,6 +871,19 @@ mpz_status mpz_debug_gemm_bf16(int32_t M, int32_t N, int32_t K, const void* x, c
   if (!mfma_gemm_supported(g)) return fail(nullptr, MPZ_ERR_SHAPE, "shape not supported by the MFMA GEMM (K % 64, N % 4)");
   launch_gemm_mfma((hipStream_t)hip_stream, g);
   return check_device(nullptr, "mpz_debug_gemm_bf16");
+}
+
+mpz_status mpz_debug_gemm_int8(int32_t M, int32_t N, int32_t K, const void* x, const void* w_codes, const float* w_scale,
+                               const float* bias, int32_t act, void* out, int32_t out_f32, int32_t tile_cfg,
+                               void* hip_stream) {
+  if (!x || !w_codes || !w_scale || !out) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_gemm_int8: NULL argument");
+  MfmaGemmArgs g{};
+  g.M = M; g.N = N; g.K = K; g.x = x; g.w = w_codes; g.w_scale = w_scale; g.w_rows = N; g.bias = bias; g.rows_per_copy = M;
+  g.act = act; g.out_f32 = out_f32; g.out = out; g.ldo = N; g.tile_cfg = tile_cfg;
+  if (act == MPZ_ACT_SWIGLU) { g.dual = 1; g.dual_offset = N; g.w_rows = 2 * N; g.act = -1; }
+  if (!mfma_gemm_supported(g)) return fail(nullptr, MPZ_ERR_SHAPE, "shape not supported by the MFMA GEMM (K % 64, N % 4, scale alignment)");
+  launch_gemm_mfma((hipStream_t)hip_stream, g);
+  return check_device(nullptr, "mpz_debug_gemm_int8");
 }
 
 mpz_status mpz_debug_set_tile_config(mpz_model* m, int32_t tile_cfg) {

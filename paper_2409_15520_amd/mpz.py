@@ -37,12 +37,13 @@ class MpzConfig(C.Structure):
                 ("act", C.c_int32), ("norm", C.c_int32), ("norm_eps", C.c_float), ("pos", C.c_int32),
                 ("rope_theta", C.c_float), ("has_bias", C.c_int32), ("dtype", C.c_int32),
                 ("lora_rank", C.c_int32), ("lora_targets", C.c_uint32), ("lora_scale", C.c_float),
-                ("perturb_A", C.c_int32), ("loss_mode", C.c_int32), ("label_token", C.c_int32 * 2)]
+                ("perturb_A", C.c_int32), ("loss_mode", C.c_int32), ("label_token", C.c_int32 * 2),
+                ("weight_quant", C.c_int32)]
 
 
 class MpzLayerWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b",
-                                          "w_up", "b_up", "w_down", "b_down")]
+                                          "w_up", "b_up", "w_down", "b_down", "s_qkv", "s_o", "s_up", "s_down")]
 
 
 class MpzWeights(C.Structure):
@@ -241,6 +242,16 @@ def mpz_debug_gemm_bf16(M: int, N: int, K: int, x_ptr: int, w_ptr: int, bias_ptr
                                               stream_ptr))
 
 
+def mpz_debug_gemm_int8(M: int, N: int, K: int, x_ptr: int, w_ptr: int, scale_ptr: int, bias_ptr: Optional[int], act: int,
+                        out_ptr: int, out_f32: bool, stream_ptr: int, tile_cfg: int = 0):
+    lib = load_library()
+    lib.mpz_debug_gemm_int8.restype = C.c_int
+    lib.mpz_debug_gemm_int8.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    _check(lib.mpz_debug_gemm_int8(M, N, K, x_ptr, w_ptr, scale_ptr, bias_ptr, act, out_ptr, int(out_f32), tile_cfg,
+                                   stream_ptr))
+
+
 def mpz_debug_set_tile_config(handle, tile_cfg: int):
     _check(load_library().mpz_debug_set_tile_config(handle, tile_cfg), handle)
 
@@ -277,6 +288,7 @@ def config_from_workload(w) -> MpzConfig:
     cfg.lora_targets = sum(TARGET_BIT[t] for t in w.lora_targets)
     cfg.lora_scale, cfg.perturb_A, cfg.loss_mode = w.lora_scale, int(w.perturb_A), LOSS[w.loss_mode]
     cfg.label_token[0], cfg.label_token[1] = w.label_tokens
+    cfg.weight_quant = {"none": 0, "int8": 1}[getattr(w, "weight_quant", "none")]
     return cfg
 
 
@@ -345,8 +357,11 @@ class ZoModel:
         for i, lw in enumerate(frozen["layers"]):
             for name in ("ln1_g", "ln1_b", "b_qkv", "b_o", "ln2_g", "ln2_b", "b_up", "b_down"):
                 setattr(layers[i], name, dev(lw[name], torch.float32))
+            q8 = getattr(w, "weight_quant", "none") == "int8"
             for name in ("w_qkv", "w_o", "w_up", "w_down"):          # [k_in, k_out] -> output-major
-                setattr(layers[i], name, dev(lw[name], st, transpose=True))
+                setattr(layers[i], name, dev(lw[name], torch.int8 if q8 else st, transpose=True))
+            for name in ("s_qkv", "s_o", "s_up", "s_down"):
+                setattr(layers[i], name, dev(lw.get(name), torch.float32) if q8 else None)
         self._layers = layers
         wt = MpzWeights()
         wt.emb = dev(frozen["emb"], st)

@@ -29,12 +29,17 @@ CASES = {
         act="swiglu", norm="rmsnorm", pos="rope", has_bias=False, tie_embeddings=False, dtype="bf16",
         lora_rank=16, lora_targets=("q", "k", "v", "o"), loss_mode="next_token_all_pos", q=2, E=2, S=64, steps=1),
 }
+# weight-only int8 block linears (codes widened in the GEMM's operand load, scale on the accumulator)
+CASES["c2_int8"] = CASES["c2_2layers"].with_(weight_quant="int8")
+CASES["llama_mfma_int8"] = CASES["llama_mfma"].with_(weight_quant="int8")
 
 
 @pytest.mark.parametrize("name,eps,b_std", [("mini_llama", 1e-3, 0.01), ("mini_opt", 1e-3, 0.01),
                                             ("c2_2layers", 1e-3, 0.01), ("c2_2layers", 5e-2, 0.05),
                                             ("llama_mfma", 1e-3, 0.01), ("llama_mfma", 5e-2, 0.05),
-                                            ("c2_ragged_copies", 5e-2, 0.05)])
+                                            ("c2_ragged_copies", 5e-2, 0.05),
+                                            ("c2_int8", 1e-3, 0.01), ("c2_int8", 5e-2, 0.05),
+                                            ("llama_mfma_int8", 1e-3, 0.01), ("llama_mfma_int8", 5e-2, 0.05)])
 def test_each_stage_on_oracle_inputs(name, eps, b_std):
     """Second c2 case: perturbation and B large enough that the low-rank term moves the projections by
     O(10%), so a wrong or missing per-copy term cannot hide under the rounding tolerance."""

@@ -160,3 +160,47 @@ def test_fused_head_cross_entropy(tile_cfg, loss_mode):
     want = np.array([head_loss(w, b["frozen"], h[c].astype(np.float64), b["tokens"], b["labels"], prec) for c in range(n)])
     print(f"\nfused head {loss_mode} cfg {tile_cfg}: {got} vs {want}")
     assert np.abs(got - want).max() <= 2e-5 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("cfg", [1, 6, 11])
+@pytest.mark.parametrize("M_,N_,K_", [(512, 768, 256), (300, 260, 192), (1024, 384, 64)])
+def test_gemm_int8_weights(cfg, M_, N_, K_):
+    """x (codes * scale)^T + bias with ReLU, fp32 output, against the fp64 product: the codes are widened to bf16
+    exactly and the per-output-channel scale multiplies the fp32 accumulator, so only accumulation order differs."""
+    import torch
+    import paper_2409_15520_amd as M
+    rng = np.random.default_rng(cfg * 1000 + M_)
+    x = BF.operand(rng.standard_normal((M_, K_)))
+    codes = rng.integers(-127, 128, size=(N_, K_), dtype=np.int8)
+    scale = (0.02 / 32 * (0.75 + 0.5 * rng.random(N_))).astype(np.float32)
+    bias = rng.standard_normal(N_).astype(np.float32)
+    xd = _bf16_tensor(x)
+    cd, sd, bd = torch.from_numpy(codes).cuda(), torch.from_numpy(scale).cuda(), torch.from_numpy(bias).cuda()
+    out = torch.full((M_, N_), float("nan"), dtype=torch.float32, device="cuda")
+    M.mpz_debug_gemm_int8(M_, N_, K_, xd.data_ptr(), cd.data_ptr(), sd.data_ptr(), bd.data_ptr(), 0, out.data_ptr(), True,
+                          torch.cuda.current_stream().cuda_stream, cfg)
+    got = out.cpu().numpy().astype(np.float64)
+    want = np.maximum(x @ (codes.astype(np.float64) * scale.astype(np.float64)[:, None]).T + bias, 0.0)
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= 2e-6 * np.sqrt(K_) * np.abs(want).max()
+
+
+@pytest.mark.parametrize("cfg", [1, 6])
+def test_swiglu_dual_gemm_int8_weights(cfg):
+    import torch
+    import paper_2409_15520_amd as M
+    Mr, F, K = 512, 384, 256
+    rng = np.random.default_rng(cfg + 40)
+    x = BF.operand(rng.standard_normal((Mr, K)))
+    codes = rng.integers(-127, 128, size=(2 * F, K), dtype=np.int8)
+    scale = (0.05 / 32 * (0.75 + 0.5 * rng.random(2 * F))).astype(np.float32)
+    xd = _bf16_tensor(x)
+    cd, sd = torch.from_numpy(codes).cuda(), torch.from_numpy(scale).cuda()
+    out = torch.full((Mr, F), float("nan"), dtype=torch.float32, device="cuda")
+    M.mpz_debug_gemm_int8(Mr, F, K, xd.data_ptr(), cd.data_ptr(), sd.data_ptr(), None, 2, out.data_ptr(), True,
+                          torch.cuda.current_stream().cuda_stream, cfg)
+    got = out.cpu().numpy().astype(np.float64)
+    wd = codes.astype(np.float64) * scale.astype(np.float64)[:, None]
+    gate, up = x @ wd[:F].T, x @ wd[F:].T
+    want = gate / (1.0 + np.exp(-gate)) * up
+    assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max()
