@@ -80,6 +80,8 @@ def main():
     ap.add_argument("--pad-fraction", type=float, default=None,
                     help="right-padded batch of unequal lengths (seeded; about this fraction of the E*S slots is padding): "
                          "the loss runs over real tokens only (mpz_forward_perturbed_varlen)")
+    ap.add_argument("--weight-quant", default=None, choices=["none", "int8"],
+                    help="weight-only quantisation of the block linears (int8 codes + per-channel scales)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device-to-device copies first (a kernel of known traffic, to "
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -101,7 +103,8 @@ def main():
         torch.cuda.synchronize()
         del a, b
     w = W.get_workload(args.workload)
-    over = {k: v for k, v in (("q", args.q), ("E", args.E), ("S", args.S)) if v is not None}
+    over = {k: v for k, v in (("q", args.q), ("E", args.E), ("S", args.S), ("weight_quant", args.weight_quant))
+            if v is not None}
     if over:
         w = w.with_(**over)
     seeds = {"weights": 1234, "lora": 99, "tokens": 2345, "noise": 3456}
@@ -186,7 +189,7 @@ def main():
         "dtype": "bf16" if bf16 else "f64", "data": "synthetic",
         "config": {"workload": w.name, "mode": args.mode, "q": w.q, "copies": 2 * w.q, "E": w.E, "S": w.S,
                    "stacked_tokens": tokens_per_step, "layers": w.n_layers, "d_model": w.d_model,
-                   "lora_rank": w.lora_rank, "eps": w.eps, "seeds": seeds,
+                   "lora_rank": w.lora_rank, "eps": w.eps, "seeds": seeds, "weight_quant": w.weight_quant,
                    "real_tokens_per_copy": int(lengths_host.sum()) if lengths is not None else w.E * w.S},
         "roofline": {"bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": GEMM_TRAFFIC.get(w.name),

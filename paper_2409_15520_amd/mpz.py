@@ -309,16 +309,27 @@ def device_random_weights(w, seed: int, device: str = "cuda:0"):
     ones = lambda n: torch.ones(n, device=device, dtype=torch.float32)
     zeros = lambda n: torch.zeros(n, device=device, dtype=torch.float32)
     ln = w.norm == "layernorm"
+    q8 = getattr(w, "weight_quant", "none") == "int8"
+
+    def lin(n_out, n_in):
+        """A block linear [k_out, k_in]: model dtype, or (int8 codes, per-output-channel scales)."""
+        if not q8:
+            return rnd(n_out, n_in), None
+        codes = (torch.randn(n_out, n_in, generator=g, device=device, dtype=torch.float32) * 32.0).round_().clamp_(-127, 127)
+        scale = (0.02 / 32.0) * (0.75 + 0.5 * torch.rand(n_out, generator=g, device=device, dtype=torch.float32))
+        return codes.to(torch.int8), scale
+
     out = {"_device_output_major": True, "emb": rnd(w.vocab, d),
            "pos_emb": rnd(w.max_seq, d) if w.pos == "learned" else None, "layers": []}
     for _ in range(w.n_layers):
+        (wq, sq), (wo, so), (wu, su), (wd, sd) = lin(n_qkv, d), lin(d, d), lin(n_up, d), lin(d, f)
         out["layers"].append({
             "ln1_g": ones(d), "ln1_b": zeros(d) if ln else None,
-            "w_qkv": rnd(n_qkv, d), "b_qkv": rnd(n_qkv, dtype=torch.float32) if w.has_bias else None,
-            "w_o": rnd(d, d), "b_o": rnd(d, dtype=torch.float32) if w.has_bias else None,
+            "w_qkv": wq, "s_qkv": sq, "b_qkv": rnd(n_qkv, dtype=torch.float32) if w.has_bias else None,
+            "w_o": wo, "s_o": so, "b_o": rnd(d, dtype=torch.float32) if w.has_bias else None,
             "ln2_g": ones(d), "ln2_b": zeros(d) if ln else None,
-            "w_up": rnd(n_up, d), "b_up": rnd(n_up, dtype=torch.float32) if w.has_bias else None,
-            "w_down": rnd(d, f), "b_down": rnd(d, dtype=torch.float32) if w.has_bias else None})
+            "w_up": wu, "s_up": su, "b_up": rnd(n_up, dtype=torch.float32) if w.has_bias else None,
+            "w_down": wd, "s_down": sd, "b_down": rnd(d, dtype=torch.float32) if w.has_bias else None})
     out["lnf_g"], out["lnf_b"] = ones(d), (zeros(d) if ln else None)
     out["lm_head"] = out["emb"] if w.tie_embeddings else rnd(w.vocab, d)
     return out
