@@ -29,7 +29,7 @@ constexpr int QB = 128;   // queries per block
 // KC = keys per LDS chunk.  When every key the block can see fits one chunk, K and V are loaded once and both
 // passes run from LDS; otherwise each pass streams the chunks.
 template <int DH, int KC>
-__global__ void __launch_bounds__(256) attention_mfma_kernel(const uint16_t* __restrict__ qkv, int qkv_stride,
+__global__ void __launch_bounds__(256, 2) attention_mfma_kernel(const uint16_t* __restrict__ qkv, int qkv_stride,
                                                              uint16_t* __restrict__ out, int S, int H, int Hkv,
                                                              float scale) {
   constexpr int KS = DH + 8;        // K chunk row stride (elements)

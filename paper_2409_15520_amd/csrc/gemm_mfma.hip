@@ -503,7 +503,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
 // while the previous one is consumed.  Inside a chunk the 4 waves split K; their partial sums meet in LDS in a
 // fixed order.  MFMA rows = bottleneck columns j of all targets that share the input x.
 template <int JT>   // number of 32-row MFMA tiles covering n_targets * r bottleneck columns
-__global__ void __launch_bounds__(256) lora_down_mfma_kernel(MfmaLoraDownArgs a) {
+__global__ void __launch_bounds__(256, 2) lora_down_mfma_kernel(MfmaLoraDownArgs a) {
   constexpr int KCH = 256, XS = KCH + 8;
   __shared__ __align__(16) uint16_t sx[2][32 * XS];
   __shared__ float part[3][JT][16][64];          // partial sums of waves 1..3
