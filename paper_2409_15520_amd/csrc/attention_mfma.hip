@@ -19,6 +19,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 constexpr int QB = 128;   // queries per block
 
@@ -68,26 +69,41 @@ __global__ void __launch_bounds__(256, 2) attention_mfma_kernel(const uint16_t* 
   const int wave_last_q = q0 + 31;
   constexpr int CPR = DH / 8;                     // 16-byte chunks per key row
 
-#define MPZ_LOAD_K(c)                                                              \
-  for (int i = tid; i < KC * CPR; i += 256) {                                      \
-    int key = i / CPR, ch = i % CPR;                                               \
+  // K / V chunks travel global -> registers -> LDS: the fetch of chunk c + 1 is issued right after chunk c has
+  // been published, so its latency hides behind the MFMAs on chunk c.
+  constexpr int KL = KC * CPR / 256;              // 16-byte pieces of a K chunk per thread
+  constexpr int VL = (KC / 2) * CPR / 256;        // key pairs x 8 head-dim elements per thread
+  static_assert(KC * CPR % 256 == 0 && (KC / 2) * CPR % 256 == 0, "chunks must deal out evenly");
+  u32x4 rk[KL], rv0[VL], rv1[VL];
+#define MPZ_FETCH_K(c)                                                             \
+  _Pragma("unroll") for (int it = 0; it < KL; ++it) {                              \
+    const int i = tid + 256 * it, key = i / CPR, ch = i % CPR;                     \
     int kg = (c) * KC + key; kg = kg < S ? kg : S - 1;                             \
-    *(u32x4*)(sK + key * KS + ch * 8) = *(const u32x4*)(kbase + (size_t)kg * qkv_stride + ch * 8); \
+    rk[it] = *(const u32x4*)(kbase + (size_t)kg * qkv_stride + ch * 8);            \
+  }
+#define MPZ_PUT_K()                                                                \
+  _Pragma("unroll") for (int it = 0; it < KL; ++it) {                              \
+    const int i = tid + 256 * it, key = i / CPR, ch = i % CPR;                     \
+    *(u32x4*)(sK + key * KS + ch * 8) = rk[it];                                    \
   }
   // V^T into LDS: a thread takes two consecutive keys and 8 head-dim elements and writes 8 words
   // {V[key][dv], V[key+1][dv]}; consecutive lanes hold consecutive key pairs, so the 32-bit writes of a wave fall
   // into consecutive banks (a per-element 16-bit scatter would serialise on a handful of banks).
-#define MPZ_LOAD_V(c)                                                              \
-  for (int i = tid; i < (KC / 2) * CPR; i += 256) {                                \
-    int kp = i % (KC / 2), ch = i / (KC / 2);                                      \
+#define MPZ_FETCH_V(c)                                                             \
+  _Pragma("unroll") for (int it = 0; it < VL; ++it) {                              \
+    const int i = tid + 256 * it, kp = i % (KC / 2), ch = i / (KC / 2);            \
     int k0 = (c) * KC + 2 * kp, k1 = k0 + 1;                                       \
     k0 = k0 < S ? k0 : S - 1; k1 = k1 < S ? k1 : S - 1;                            \
-    u32x4 v0 = *(const u32x4*)(vbase + (size_t)k0 * qkv_stride + ch * 8);          \
-    u32x4 v1 = *(const u32x4*)(vbase + (size_t)k1 * qkv_stride + ch * 8);          \
+    rv0[it] = *(const u32x4*)(vbase + (size_t)k0 * qkv_stride + ch * 8);           \
+    rv1[it] = *(const u32x4*)(vbase + (size_t)k1 * qkv_stride + ch * 8);           \
+  }
+#define MPZ_PUT_V()                                                                \
+  _Pragma("unroll") for (int it = 0; it < VL; ++it) {                              \
+    const int i = tid + 256 * it, kp = i % (KC / 2), ch = i / (KC / 2);            \
     uint32_t* dst = (uint32_t*)sVt + kp;                                           \
     _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                \
-      dst[(ch * 8 + 2 * e) * (VS / 2)] = (v0[e] & 0xFFFFu) | (v1[e] << 16);        \
-      dst[(ch * 8 + 2 * e + 1) * (VS / 2)] = (v0[e] >> 16) | (v1[e] & 0xFFFF0000u); \
+      dst[(ch * 8 + 2 * e) * (VS / 2)] = (rv0[it][e] & 0xFFFFu) | (rv1[it][e] << 16);        \
+      dst[(ch * 8 + 2 * e + 1) * (VS / 2)] = (rv0[it][e] >> 16) | (rv1[it][e] & 0xFFFF0000u); \
     }                                                                              \
   }
   // raw scores (q . k, unscaled) of one 32-key tile against this wave's 32 queries; lane: query qi,
@@ -109,11 +125,16 @@ __global__ void __launch_bounds__(256, 2) attention_mfma_kernel(const uint16_t* 
 
   // ---- pass 1: exact row maximum ----
   float mx = -1e30f;
+  MPZ_FETCH_K(0)
+  if (n_chunks == 1) { MPZ_FETCH_V(0) }
   for (int c = 0; c < n_chunks; ++c) {
+    __syncthreads();                              // every wave is done with the previous chunk
+    MPZ_PUT_K()
+    if (n_chunks == 1) { MPZ_PUT_V() }
     __syncthreads();
-    MPZ_LOAD_K(c)
-    if (n_chunks == 1) { MPZ_LOAD_V(c) }
-    __syncthreads();
+    if (n_chunks > 1) {                           // next chunk of this pass, or the first one of pass 2
+      if (c + 1 < n_chunks) { MPZ_FETCH_K(c + 1) } else { MPZ_FETCH_K(0) MPZ_FETCH_V(0) }
+    }
 #pragma unroll
     for (int t = 0; t < KC / 32; ++t) {
       int kt0 = c * KC + t * 32;
@@ -135,12 +156,14 @@ __global__ void __launch_bounds__(256, 2) attention_mfma_kernel(const uint16_t* 
 #pragma unroll
     for (int e = 0; e < 16; ++e) oacc[t][e] = 0.f;
   float lsum = 0.f;
+  const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
   for (int c = 0; c < n_chunks; ++c) {
     if (n_chunks > 1) {
       __syncthreads();
-      MPZ_LOAD_K(c)
-      MPZ_LOAD_V(c)
+      MPZ_PUT_K()
+      MPZ_PUT_V()
       __syncthreads();
+      if (c + 1 < n_chunks) { MPZ_FETCH_K(c + 1) MPZ_FETCH_V(c + 1) }
     }
 #pragma unroll
     for (int t = 0; t < KC / 32; ++t) {
@@ -155,7 +178,7 @@ __global__ void __launch_bounds__(256, 2) attention_mfma_kernel(const uint16_t* 
         const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[e + 1], c1, -mx2));
         const uint32_t w = pack_bf16x2(p0, p1);
         pw[e >> 1] = w;
-        lsum += __uint_as_float(w << 16) + __uint_as_float(w & 0xFFFF0000u);   // the rounded values
+        lsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, lsum, false);   // the rounded values
       }
       // two MFMA K-steps of 16 keys: step h uses score registers 8h .. 8h+7, i.e. keys
       // kt0 + 16h + lhalf*4 + (0..3) and kt0 + 16h + 8 + lhalf*4 + (0..3)
@@ -174,8 +197,10 @@ __global__ void __launch_bounds__(256, 2) attention_mfma_kernel(const uint16_t* 
       }
     }
   }
-#undef MPZ_LOAD_K
-#undef MPZ_LOAD_V
+#undef MPZ_FETCH_K
+#undef MPZ_PUT_K
+#undef MPZ_FETCH_V
+#undef MPZ_PUT_V
 #undef MPZ_SCORE_TILE
   lsum += __shfl_xor(lsum, 32, 64);
 
