@@ -182,6 +182,28 @@ def main():
             k["gbps"] = e["bytes"] / sec / 1e9
             k["frac_hbm_peak"] = k["gbps"] / PEAK_HBM_GBPS
         kernels[name] = k
+    # noise kernels: normals per second against the generator's own arithmetic ceiling (a kernel that makes the same
+    # Philox + Box-Muller calls and moves no data), next to their GB/s against HBM
+    n_groups = masters.size // 4
+    n_normals = masters.size * w.q                      # per pass over the factors (perturb, and again in the update)
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    st_ptr = torch.cuda.current_stream().cuda_stream
+    for _ in range(2):
+        M.mpz_debug_noise_alu_probe(n_groups, w.q, sink.data_ptr(), st_ptr)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 20
+    e0.record()
+    for _ in range(reps):
+        M.mpz_debug_noise_alu_probe(n_groups, w.q, sink.data_ptr(), st_ptr)
+    e1.record()
+    torch.cuda.synchronize()
+    ceiling = n_normals / (e0.elapsed_time(e1) * 1e-3 / reps)
+    for name in ("noise", "update"):
+        if name in kernels and prof[name]["ms"] > 0:
+            rate = n_normals * prof[name]["launches"] / (prof[name]["ms"] * 1e-3)
+            kernels[name]["normals_per_s"] = rate
+            kernels[name]["alu_ceiling_normals_per_s"] = ceiling
+            kernels[name]["frac_alu_ceiling"] = rate / ceiling
     out = {
         "metric": "perturbed-copy tokens/sec", "value": tokens_per_step / (ms_per_step * 1e-3), "unit": "tokens/s",
         "zo_steps_per_sec": 1e3 / ms_per_step, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -220,6 +220,11 @@ mpz_status mpz_zo_update_regen(mpz_model* m, const float* losses, float lr, uint
 /* z for one LoRA factor of one query: z_out [dev] fp32[rows*cols], row-major. */
 mpz_status mpz_debug_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t k, int32_t tensor_id,
                            float* z_out);
+/* Measurement aid for the noise kernels: generates q normals-quadruples for each of n_groups counter values exactly
+ * as mpz_regen_noise does (Philox call + Box-Muller transform), keeps them in registers and writes nothing (one
+ * word per thread is stored only if a checksum hits an impossible value): the arithmetic ceiling of the generator,
+ * against which the rate of the kernels that also move the factors is reported.  sink [dev] fp32[1]. */
+mpz_status mpz_debug_noise_alu_probe(int64_t n_groups, int32_t q, float* sink, void* hip_stream);
 /* The binary32 normal transform alone: words [dev] uint32[4*n4] -> normals [dev] fp32[4*n4]
  * (group j: words 4j..4j+3 -> Box-Muller pairs (0,1) and (2,3)).  hip_stream as in init. */
 mpz_status mpz_debug_normals_from_words(const uint32_t* words, size_t n4, float* normals_out, void* hip_stream);
@@ -276,13 +281,14 @@ enum {
   MPZ_PROF_ATTENTION = 1,
   MPZ_PROF_NORM = 2,
   MPZ_PROF_LORA_DOWN = 3, /* bottleneck t = s x A_c */
-  MPZ_PROF_NOISE = 4,     /* regenerate noise, write the perturbed copies (and their bf16 operand layouts) */
+  MPZ_PROF_NOISE = 4,     /* regenerate noise, write the perturbed copies */
   MPZ_PROF_UPDATE = 5,    /* two-point estimate + seed-replayed update */
   MPZ_PROF_EMBED = 6,
   MPZ_PROF_ROPE = 7,
   MPZ_PROF_LOSS = 8,      /* targets, per-row cross-entropy, per-copy mean */
   MPZ_PROF_OTHER = 9,
-  MPZ_PROF_COUNT = 10
+  MPZ_PROF_PACK = 10,     /* perturbed copies -> bf16 hi/lo MFMA operand layouts */
+  MPZ_PROF_COUNT = 11
 };
 typedef struct { double ms; int64_t launches; double flops; double bytes; } mpz_profile_entry;
 mpz_status mpz_profile_begin(mpz_model* m);

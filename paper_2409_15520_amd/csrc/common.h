@@ -43,6 +43,7 @@ void launch_update(hipStream_t st, float* masters, int64_t P, const LoraLayerTab
                    uint32_t step, int q, float eps, float lr, int perturb_A, const float* losses,
                    float* proj_grads_out);
 // update from the stored perturbed pairs, then re-perturb with the noise of next_step (stateful variant, Algorithm 2)
+void launch_noise_alu_probe(hipStream_t st, int64_t n_groups, int q, float* sink);
 void launch_update_regen(hipStream_t st, float* masters, float* pert, int64_t P, const LoraLayerTable& tab, uint64_t seed,
                          uint32_t next_step, int q, float eps, float lr, int perturb_A, const float* losses,
                          float* proj_grads_out);

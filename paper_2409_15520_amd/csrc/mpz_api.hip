@@ -693,7 +693,7 @@ mpz_status mpz_regen_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t q
     ProfScope ps(m, MPZ_PROF_NOISE, 0.0, 4.0 * m->P * (1.0 + 2.0 * q));
     launch_perturb(m->stream, m->masters, m->buf.pert, m->P, m->tab, seed, step, q, eps, m->cfg.perturb_A);
   }
-  ProfScope ps_pack(m, MPZ_PROF_NOISE, 0.0, m->use_mfma ? 2.0 * q * (4.0 * m->P + 2.0 * m->packed_per_copy) : 0.0);
+  ProfScope ps_pack(m, MPZ_PROF_PACK, 0.0, m->use_mfma ? 2.0 * q * (4.0 * m->P + 2.0 * m->packed_per_copy) : 0.0);
   if (m->use_mfma)
     launch_pack_factors(m->stream, m->buf.pert, m->P, 2 * q, m->tab, m->cfg.n_layers, m->cfg.lora_rank, m->rp, m->buf.packed,
                         m->packed_per_copy);
@@ -800,13 +800,20 @@ mpz_status mpz_zo_update_regen(mpz_model* m, const float* losses, float lr, uint
     launch_update_regen(m->stream, m->masters, m->buf.pert, m->P, m->tab, m->seed, next_step, m->q, m->eps, lr,
                         m->cfg.perturb_A, losses, proj_grads_out);
   }
-  ProfScope ps_pack(m, MPZ_PROF_NOISE, 0.0, m->use_mfma ? 2.0 * m->q * (4.0 * m->P + 2.0 * m->packed_per_copy) : 0.0);
+  ProfScope ps_pack(m, MPZ_PROF_PACK, 0.0, m->use_mfma ? 2.0 * m->q * (4.0 * m->P + 2.0 * m->packed_per_copy) : 0.0);
   if (m->use_mfma)
     launch_pack_factors(m->stream, m->buf.pert, m->P, 2 * m->q, m->tab, m->cfg.n_layers, m->cfg.lora_rank, m->rp,
                         m->buf.packed, m->packed_per_copy);
   m->step = next_step;                          // the stored copies now belong to next_step and match the masters
   m->cb = 0; m->nc = 2 * m->q;
   return check_device(m, "mpz_zo_update_regen");
+}
+
+mpz_status mpz_debug_noise_alu_probe(int64_t n_groups, int32_t q, float* sink, void* hip_stream) {
+  if (!sink) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_noise_alu_probe: NULL sink");
+  if (n_groups < 1 || n_groups > ((int64_t)1 << 31) || q < 1 || q > 64) return fail(nullptr, MPZ_ERR_SHAPE, "n_groups or q out of range");
+  launch_noise_alu_probe((hipStream_t)hip_stream, n_groups, q, sink);
+  return check_device(nullptr, "mpz_debug_noise_alu_probe");
 }
 
 mpz_status mpz_debug_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t k, int32_t tensor_id, float* z_out) {

@@ -208,6 +208,19 @@ __global__ void __launch_bounds__(256) update_regen_kernel(float4* __restrict__ 
   }
 }
 
+// the generator alone: same calls as perturb_kernel, no memory traffic
+__global__ void __launch_bounds__(256) noise_alu_probe_kernel(int64_t n_groups, int q, float* __restrict__ sink) {
+  int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= n_groups) return;
+  float acc = 0.f;
+  for (int k = 0; k < q; ++k) {
+    float z[4];
+    normals4(philox4x32_10((uint32_t)g, 7u, 3u, (uint32_t)k, 0x12345678u, 0x9abcdef0u), z);
+    acc += z[0] + z[1] + z[2] + z[3];
+  }
+  if (acc == 1.2345e30f) sink[0] = acc;
+}
+
 __global__ void __launch_bounds__(256) debug_noise_kernel(float4* __restrict__ z_out, int64_t n_groups, uint32_t k0,
                                                           uint32_t k1, uint32_t step, uint32_t k, uint32_t tensor_id) {
   int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -252,6 +265,10 @@ void launch_update_regen(hipStream_t st, float* masters, float* pert, int64_t P,
   update_regen_kernel<<<blocks_for(ng, 256), 256, 0, st>>>((float4*)masters, (float4*)pert, ng, tab, (uint32_t)seed,
                                                            (uint32_t)(seed >> 32), next_step, q, eps, lr, perturb_A, losses,
                                                            proj_grads_out);
+}
+
+void launch_noise_alu_probe(hipStream_t st, int64_t n_groups, int q, float* sink) {
+  noise_alu_probe_kernel<<<blocks_for(n_groups, 256), 256, 0, st>>>(n_groups, q, sink);
 }
 
 void launch_debug_noise(hipStream_t st, float* z_out, int64_t numel, uint64_t seed, uint32_t step, int k, int tensor_id) {

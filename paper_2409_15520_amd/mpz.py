@@ -51,7 +51,7 @@ class MpzWeights(C.Structure):
                 ("lnf_b", C.c_void_p), ("layers", C.POINTER(MpzLayerWeights))]
 
 
-PROF_CATEGORIES = ("gemm", "attention", "norm", "lora_down", "noise", "update", "embed", "rope", "loss", "other")
+PROF_CATEGORIES = ("gemm", "attention", "norm", "lora_down", "noise", "update", "embed", "rope", "loss", "other", "pack")
 
 
 class MpzProfileEntry(C.Structure):
@@ -250,6 +250,13 @@ def mpz_debug_gemm_int8(M: int, N: int, K: int, x_ptr: int, w_ptr: int, scale_pt
                                         C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
     _check(lib.mpz_debug_gemm_int8(M, N, K, x_ptr, w_ptr, scale_ptr, bias_ptr, act, out_ptr, int(out_f32), tile_cfg,
                                    stream_ptr))
+
+
+def mpz_debug_noise_alu_probe(n_groups: int, q: int, sink_ptr: int, stream_ptr: int):
+    lib = load_library()
+    lib.mpz_debug_noise_alu_probe.restype = C.c_int
+    lib.mpz_debug_noise_alu_probe.argtypes = [C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+    _check(lib.mpz_debug_noise_alu_probe(n_groups, q, sink_ptr, stream_ptr))
 
 
 def mpz_debug_set_tile_config(handle, tile_cfg: int):
