@@ -405,8 +405,10 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const float lo = acc[0][i][j][g * 4 + e], hi = acc[0][i + HP][j][g * 4 + e];
-              acc[0][i][j][g * 4 + e] = lo * cs[e] - hi * sn[e];
-              acc[0][i + HP][j][g * 4 + e] = hi * cs[e] + lo * sn[e];
+              // one rounded product, one fma: the same two operations as the stand-alone rotary kernel, so a pass
+              // that takes that kernel (tile too narrow for a whole head) gives the same bits
+              acc[0][i][j][g * 4 + e] = fmaf(lo, cs[e], -__fmul_rn(hi, sn[e]));
+              acc[0][i + HP][j][g * 4 + e] = fmaf(hi, cs[e], __fmul_rn(lo, sn[e]));
             }
           }
         }

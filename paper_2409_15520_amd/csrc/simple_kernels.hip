@@ -210,12 +210,15 @@ __global__ void __launch_bounds__(256) rope_convert_kernel(const typename Traits
   AT v = stg[idx];
   if (head < n_rot_heads) {
     int p = (int)(row % S);
+    // binary32 staging (bf16 models): one rounded product and one fma, exactly as the GEMM's fused rotary epilogue
     if (i < half) {
       AT c = (AT)cos_tab[p * half + i], s = (AT)sin_tab[p * half + i];
-      v = v * c - stg[idx + half] * s;
+      if constexpr (sizeof(AT) == 4) v = fmaf(v, c, -__fmul_rn(stg[idx + half], s));
+      else v = v * c - stg[idx + half] * s;
     } else {
       AT c = (AT)cos_tab[p * half + i - half], s = (AT)sin_tab[p * half + i - half];
-      v = v * c + stg[idx - half] * s;
+      if constexpr (sizeof(AT) == 4) v = fmaf(v, c, __fmul_rn(stg[idx - half], s));
+      else v = v * c + stg[idx - half] * s;
     }
   }
   Tr::store(out, idx, v);
