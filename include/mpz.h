@@ -266,6 +266,12 @@ mpz_status mpz_debug_gemm_int8(int32_t M, int32_t N, int32_t K, const void* x, c
  * Invalidates the perturbed copies: call mpz_regen_noise again. */
 mpz_status mpz_debug_set_kernel_path(mpz_model* m, int32_t simple_only);
 
+/* Test hook: allow (default) or forbid the two-halves schedule of mpz_forward_perturbed: for small models (every
+ * GEMM on the 128-wide tiles, label-subset loss) the pass is issued as two halves of q copies each on the caller's
+ * stream and on an internal second stream of the same priority, forked from and joined to the caller's stream by
+ * events, so that the halves' kernels overlap.  Losses are bit-identical either way. */
+mpz_status mpz_debug_set_two_halves(mpz_model* m, int32_t enable);
+
 /* Test hook: force one block-tile configuration (1..11; 0 = chosen by shape) for every MFMA GEMM of the model's
  * passes, so that small test shapes can exercise the configurations large workloads select.  Errors: NULL, CONFIG. */
 mpz_status mpz_debug_set_tile_config(mpz_model* m, int32_t tile_cfg);

@@ -259,6 +259,13 @@ def mpz_debug_noise_alu_probe(n_groups: int, q: int, sink_ptr: int, stream_ptr: 
     _check(lib.mpz_debug_noise_alu_probe(n_groups, q, sink_ptr, stream_ptr))
 
 
+def mpz_debug_set_two_halves(handle, enable: bool):
+    lib = load_library()
+    lib.mpz_debug_set_two_halves.restype = C.c_int
+    lib.mpz_debug_set_two_halves.argtypes = [C.c_void_p, C.c_int32]
+    _check(lib.mpz_debug_set_two_halves(handle, int(enable)), handle)
+
+
 def mpz_debug_set_tile_config(handle, tile_cfg: int):
     _check(load_library().mpz_debug_set_tile_config(handle, tile_cfg), handle)
 

@@ -47,3 +47,32 @@ def test_copy_range_errors():
             m.forward_copies(tok, lab, cb, nc)
         assert e.value.status == 3
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name", ["c2_2layers", "c2_int8"])
+def test_two_halves_schedule_changes_no_bit(name):
+    """Small models run the pass as two halves of q copies on two streams; with the hook off it is one pass on the
+    caller's stream.  Losses of three consecutive steps (update in between) are bit-identical, also when the caller's
+    stream is not the default one."""
+    import torch
+    import paper_2409_15520_amd as M
+    w = CASES[name]
+    b = make_bundle(w, b_std=0.01)
+    side = torch.cuda.Stream()
+    runs = []
+    for enable, stream in ((True, None), (False, None), (True, side)):
+        ctx = torch.cuda.stream(stream) if stream is not None else torch.cuda.stream(torch.cuda.current_stream())
+        with ctx:
+            m = gpu_model(b)
+            M.mpz_debug_set_two_halves(m.handle, enable)
+            tok = torch.from_numpy(b["tokens"]).cuda()
+            lab = torch.from_numpy(b["labels"]).cuda()
+            out = []
+            for step in range(3):
+                m.regen_noise(3456, step)
+                out.append(m.forward_perturbed(tok, lab).clone())
+                m.zo_update()
+            torch.cuda.current_stream().synchronize()
+            runs.append(torch.stack(out).cpu().numpy())
+    assert np.array_equal(runs[0].view(np.uint32), runs[1].view(np.uint32))
+    assert np.array_equal(runs[0].view(np.uint32), runs[2].view(np.uint32))
