@@ -133,7 +133,7 @@ struct MfmaGemmArgs {
   int act;                      // -1 none, MPZ_ACT_RELU, MPZ_ACT_GELU_ERF (ignored when dual: SiLU(gate) * up)
   const float* residual;        // [M, ldo] fp32 or null
   int out_f32; void* out; int ldo;
-  int tile_cfg;                 // 0 = choose by shape; 1..11 force a tile configuration (measurement)
+  int tile_cfg;                 // 0 = choose by shape; 1..12 force a tile configuration (measurement)
   // fused rotary embedding (bf16 output only): columns [0, rope_cols) are heads of width rope_dh rotated by the
   // position m % S with tables [max_seq, rope_dh / 2]
   const float* rope_cos; const float* rope_sin; int rope_cols, rope_dh, S;

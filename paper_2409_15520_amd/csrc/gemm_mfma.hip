@@ -754,8 +754,8 @@ bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
 }
 
 int choose_cfg(const MfmaGemmArgs& a) {
-  const bool forced_ok = a.w_scale == nullptr || a.tile_cfg == 1 || a.tile_cfg == 6 || a.tile_cfg == 11;   // int8: fewer instances
-  if (forced_ok && a.tile_cfg >= 1 && a.tile_cfg <= 11 && a.tile_cfg != 4 && a.tile_cfg != 10 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
+  const bool forced_ok = a.w_scale == nullptr || a.tile_cfg == 1 || a.tile_cfg == 6 || a.tile_cfg == 11 || a.tile_cfg == 12;   // int8: fewer instances
+  if (forced_ok && a.tile_cfg >= 1 && a.tile_cfg <= 12 && a.tile_cfg != 4 && a.tile_cfg != 10 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
   // enough 256 x 256 tiles to keep 256 CUs busy for several rounds -> biggest tile; else the largest tile that
   // still gives at least ~2 blocks per CU
   // The L2 -> CU path feeds about 64 B/clk per CU, which a 128 x 128 tile needs in full at MFMA peak; 256 x 256
@@ -766,6 +766,9 @@ int choose_cfg(const MfmaGemmArgs& a) {
   // other half; 192 x 128 tiles, one per CU, balance it (N = 768 projections of the 125M-class models)
   const long t1 = (long)((a.N + 127) / 128) * ((a.M + 127) / 128), t11 = (long)((a.N + 191) / 192) * ((a.M + 127) / 128);
   if (t1 > 256 && t1 < 512 && t11 <= 256 && a.N % 192 == 0 && a.K >= 1536 && a.rope_cos == nullptr && cfg_ok(a, 11)) return 11;
+  // short K: a block lives for a dozen K-tiles, and what hides its first loads and last stores is other waves:
+  // the same 128 x 128 tile with 8 waves of 64 x 32 (16 waves per CU) instead of 4 of 64 x 64
+  if (a.K <= 1536) return 12;
   return 1;
 }
 
@@ -824,7 +827,7 @@ bool mfma_gemm_supported(const MfmaGemmArgs& a) {
     // the rotated column range must end on a block-tile boundary, and a wave tile must hold whole heads
     const int cfg = choose_cfg(a), bn = tile_bn(cfg), tn = (cfg == 5 || cfg == 6) ? 128 : 64;
     if (a.dual || a.out_f32 || a.act >= 0 || a.residual != nullptr || !a.rope_sin || a.S < 1) return false;
-    if ((cfg != 5 && cfg != 6 && cfg != 1) || (a.rope_dh != 64 && a.rope_dh != 128) || a.rope_dh > tn) return false;
+    if ((cfg != 5 && cfg != 6 && cfg != 1 && cfg != 12) || (a.rope_dh != 64 && a.rope_dh != 128) || a.rope_dh > tn) return false;
     if (a.rope_cols % bn || a.rope_cols > a.N || a.N % a.rope_dh) return false;
   }
   return true;
@@ -848,6 +851,8 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     if (cfg == 5 || cfg == 6) {
       if (a.rope_dh == 64) { if (q8) launch_cfg<256, 256, 64, 2, 4, false, 1, true>(st, a); else launch_cfg<256, 256, 64, 2, 4, false, 1>(st, a); }
       else { if (q8) launch_cfg<256, 256, 64, 2, 4, false, 2, true>(st, a); else launch_cfg<256, 256, 64, 2, 4, false, 2>(st, a); }
+    } else if (cfg == 12) {
+      if (q8) launch_cfg<128, 128, 64, 2, 4, false, 1, true>(st, a); else launch_cfg<128, 128, 64, 2, 4, false, 1>(st, a);
     } else {
       if (q8) launch_cfg<128, 128, 64, 2, 2, false, 1, true>(st, a); else launch_cfg<128, 128, 64, 2, 2, false, 1>(st, a);
     }
@@ -857,6 +862,7 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     switch (choose_cfg(a)) {
       case 6: launch_cfg<256, 256, 64, 2, 4, false, 0, true>(st, a); break;
       case 11: launch_cfg<192, 128, 64, 2, 2, false, 0, true>(st, a); break;
+      case 12: launch_cfg<128, 128, 64, 2, 4, false, 0, true>(st, a); break;
       default: launch_cfg<128, 128, 64, 2, 2, false, 0, true>(st, a); break;
     }
     return;
@@ -870,6 +876,7 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     case 8: launch_cfg<256, 128, 32, 4, 2, false>(st, a); break;     // 8 waves of 64 x 64, 61 KB LDS
     case 9: launch_cfg<128, 64, 64, 2, 2, false>(st, a); break;      // 4 waves of 64 x 32: more, smaller blocks
     case 11: launch_cfg<192, 128, 64, 2, 2, false>(st, a); break;    // 4 waves of 96 x 64, 92 KB LDS: 1 block per CU
+    case 12: launch_cfg<128, 128, 64, 2, 4, false>(st, a); break;    // 8 waves of 64 x 32: 16 waves per CU
     default: launch_cfg<128, 128, 64, 2, 2, false>(st, a); break;
   }
 }
