@@ -741,7 +741,7 @@ void launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
   gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP, WQ><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
 }
 
-int tile_bn(int cfg) { return cfg == 11 ? 192 : (cfg == 2 || (cfg >= 5 && cfg <= 8)) ? 256 : 128; }   // 7, 8: 256 x 128 (4 is unused)
+int tile_bn(int cfg) { return (cfg == 11 || cfg == 13) ? 192 : (cfg == 2 || (cfg >= 5 && cfg <= 8)) ? 256 : 128; }   // 7, 8: 256 x 128 (4 is unused)
 int tile_bm(int cfg) { return cfg == 9 ? 64 : (cfg == 3 || cfg == 5 || cfg == 6) ? 256 : 128; }
 
 bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
@@ -755,7 +755,7 @@ bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
 
 int choose_cfg(const MfmaGemmArgs& a) {
   const bool forced_ok = a.w_scale == nullptr || a.tile_cfg == 1 || a.tile_cfg == 6 || a.tile_cfg == 11 || a.tile_cfg == 12;   // int8: fewer instances
-  if (forced_ok && a.tile_cfg >= 1 && a.tile_cfg <= 12 && a.tile_cfg != 4 && a.tile_cfg != 10 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
+  if (forced_ok && a.tile_cfg >= 1 && a.tile_cfg <= 13 && a.tile_cfg != 4 && a.tile_cfg != 10 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
   // enough 256 x 256 tiles to keep 256 CUs busy for several rounds -> biggest tile; else the largest tile that
   // still gives at least ~2 blocks per CU
   // The L2 -> CU path feeds about 64 B/clk per CU, which a 128 x 128 tile needs in full at MFMA peak; 256 x 256
@@ -766,13 +766,13 @@ int choose_cfg(const MfmaGemmArgs& a) {
   // other half; 192 x 128 tiles, one per CU, balance it (N = 768 projections of the 125M-class models)
   const long t1 = (long)((a.N + 127) / 128) * ((a.M + 127) / 128), t11 = (long)((a.N + 191) / 192) * ((a.M + 127) / 128);
   if (t1 > 256 && t1 < 512 && t11 <= 256 && a.N % 192 == 0 && a.K >= 1536 && a.rope_cos == nullptr && cfg_ok(a, 11)) return 11;
-  // short K: a block lives for a dozen K-tiles, and what hides its first loads and last stores is other waves:
-  // the same 128 x 128 tile with 8 waves of 64 x 32 (16 waves per CU) instead of 4 of 64 x 64
-  if (a.K <= 1536) return 12;
-  return 1;
+  // otherwise the 128 x 128 tile with 8 waves of 64 x 32 (16 waves per CU): a block of a short-K problem lives for
+  // a dozen K-tiles, and what hides its first loads and last stores is other waves (10 % over 4 waves of 64 x 64
+  // at K = 768, equal at long K)
+  return 12;
 }
 
-int wave_cols(int cfg) { return cfg == 11 ? 96 : (cfg == 2 || cfg == 5 || cfg == 6) ? 128 : 64; }   // BN / WGN of launch_gemm_mfma's table
+int wave_cols(int cfg) { return (cfg == 11 || cfg == 13) ? 96 : (cfg == 2 || cfg == 5 || cfg == 6) ? 128 : 64; }   // BN / WGN of launch_gemm_mfma's table
 
 // 64 token rows per block, the slots dealt to 4 waves: logsumexp over the per-wave-tile partials (online
 // maximum / rescaled sum per thread, merged through LDS), minus the target's logit
@@ -877,6 +877,7 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     case 9: launch_cfg<128, 64, 64, 2, 2, false>(st, a); break;      // 4 waves of 64 x 32: more, smaller blocks
     case 11: launch_cfg<192, 128, 64, 2, 2, false>(st, a); break;    // 4 waves of 96 x 64, 92 KB LDS: 1 block per CU
     case 12: launch_cfg<128, 128, 64, 2, 4, false>(st, a); break;    // 8 waves of 64 x 32: 16 waves per CU
+    case 13: launch_cfg<192, 128, 64, 2, 4, false>(st, a); break;    // 8 waves of 96 x 32
     default: launch_cfg<128, 128, 64, 2, 2, false>(st, a); break;
   }
 }
