@@ -20,7 +20,7 @@ PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
 PEAK_FP64_VECTOR_TFLOPS = 78.6  # fp32-storage models accumulate in fp64 on the vector ALUs
 PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E
 # HBM bytes per GEMM launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
-GEMM_TRAFFIC = {"c2_opt125m": 107.3e6}   # bytes per launch, profiles/hbm_traffic_gemm_c2_opt125m.md
+GEMM_TRAFFIC = {"c2_opt125m": 105.4e6}   # bytes per launch, profiles/hbm_traffic_gemm_c2_opt125m.md
 
 
 def gemm_flops_per_step(w):
@@ -82,6 +82,9 @@ def main():
                          "the loss runs over real tokens only (mpz_forward_perturbed_varlen)")
     ap.add_argument("--weight-quant", default=None, choices=["none", "int8"],
                     help="weight-only quantisation of the block linears (int8 codes + per-channel scales)")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="issue the whole pass on one stream also for small models (per-kernel counters and traces then "
+                         "see the full-batch kernels only)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device-to-device copies first (a kernel of known traffic, to "
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -116,6 +119,8 @@ def main():
     masters = W.make_lora_masters(w, seeds["lora"])
     tokens, labels = W.make_tokens(w, seeds["tokens"]), W.make_labels(w, seeds["tokens"])
     m = M.ZoModel(w, frozen, masters, device="cuda:0")
+    if args.one_stream:
+        M.mpz_debug_set_two_halves(m.handle, False)
     tok = torch.from_numpy(tokens).cuda()
     lab = torch.from_numpy(labels).cuda()
     lengths = None
@@ -212,6 +217,7 @@ def main():
         "config": {"workload": w.name, "mode": args.mode, "q": w.q, "copies": 2 * w.q, "E": w.E, "S": w.S,
                    "stacked_tokens": tokens_per_step, "layers": w.n_layers, "d_model": w.d_model,
                    "lora_rank": w.lora_rank, "eps": w.eps, "seeds": seeds, "weight_quant": w.weight_quant,
+                   "schedule": "one stream" if args.one_stream else "two halves on two streams where the model is small",
                    "real_tokens_per_copy": int(lengths_host.sum()) if lengths is not None else w.E * w.S},
         "roofline": {"bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": GEMM_TRAFFIC.get(w.name),
