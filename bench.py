@@ -91,7 +91,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (copies would shard across GPUs with one all-gather "
-                 "of q floats, see DESIGN.md); run with --gpus 1")
+                 "of q floats and every GPU replaying the same noise streams); run with --gpus 1")
 
     import numpy as np
     import torch

@@ -507,7 +507,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
 template <int JT>   // number of 32-row MFMA tiles covering n_targets * r bottleneck columns
 __global__ void __launch_bounds__(256, 2) lora_down_mfma_kernel(MfmaLoraDownArgs a) {
   constexpr int KCH = 256, XS = KCH + 8;
-  __shared__ __align__(16) uint16_t sx[2][32 * XS];
+  __shared__ __align__(16) uint16_t sx[3][32 * XS];
   __shared__ float part[3][JT][16][64];          // partial sums of waves 1..3
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lrow = lane & 31, lhalf = lane >> 5;
   const int m0 = blockIdx.x * 32;
@@ -539,29 +539,48 @@ __global__ void __launch_bounds__(256, 2) lora_down_mfma_kernel(MfmaLoraDownArgs
   int grow[4], gcol[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) { int p = tid + 256 * i; grow[i] = p >> 5; gcol[i] = (p & 31) * 8; }
-  u32x4 st[4];
+  // three chunks of x in flight (registers), three LDS buffers: a K = 768 row is fetched in one go
+  constexpr int PD = 3;
+  u32x4 st[PD][4];
   const int nch = a.K / KCH;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) st[i] = *(const u32x4*)(X + (size_t)grow[i] * a.K + gcol[i]);
-  for (int ch = 0; ch < nch; ++ch) {
-    uint16_t* buf = sx[ch & 1];
+  for (int p = 0; p < PD; ++p)
+    if (p < nch) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *(u32x4*)(buf + grow[i] * XS + gcol[i]) = st[i];
-    if (ch + 1 < nch) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) st[i] = *(const u32x4*)(X + (size_t)grow[i] * a.K + (ch + 1) * KCH + gcol[i]);
+      for (int i = 0; i < 4; ++i) st[p][i] = *(const u32x4*)(X + (size_t)grow[i] * a.K + p * KCH + gcol[i]);
     }
-    __syncthreads();                             // chunk ch visible; buffer (ch+1)&1 was last read two chunks ago
-    const int kg = ch * KCH;
+  for (int ch0 = 0; ch0 < nch; ch0 += PD) {
 #pragma unroll
-    for (int kk = 0; kk < 64; kk += 16) {
-      bf16x8 fx = as_frag(*(const u32x4*)(buf + lrow * XS + wave * 64 + kk + lhalf * 8));
+    for (int p = 0; p < PD; ++p) {
+      const int ch = ch0 + p;
+      if (ch >= nch) break;                        // block-uniform
+      uint16_t* buf = sx[p];
+      const int kg = ch * KCH;
+      // this chunk's factor fragments (L2-resident) are fetched first, so that they travel while the x chunk is
+      // stored and the block meets at the barrier
+      u32x4 fh[4][JT], fl[4][JT];
 #pragma unroll
-      for (int t = 0; t < JT; ++t) {
-        u32x4 h = valid[t] ? *(const u32x4*)(Ah[t] + kg + kk) : zero;
-        u32x4 l = valid[t] ? *(const u32x4*)(Al[t] + kg + kk) : zero;
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(h), fx, acc[t], 0, 0, 0);
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(l), fx, acc[t], 0, 0, 0);
+      for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+        for (int t = 0; t < JT; ++t) {
+          fh[s4][t] = valid[t] ? *(const u32x4*)(Ah[t] + kg + s4 * 16) : zero;
+          fl[s4][t] = valid[t] ? *(const u32x4*)(Al[t] + kg + s4 * 16) : zero;
+        }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) *(u32x4*)(buf + grow[i] * XS + gcol[i]) = st[p][i];
+      if (ch + PD < nch) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) st[p][i] = *(const u32x4*)(X + (size_t)grow[i] * a.K + (ch + PD) * KCH + gcol[i]);
+      }
+      __syncthreads();                             // chunk ch visible; its buffer was last read three chunks ago
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4) {
+        bf16x8 fx = as_frag(*(const u32x4*)(buf + lrow * XS + wave * 64 + s4 * 16 + lhalf * 8));
+#pragma unroll
+        for (int t = 0; t < JT; ++t) {
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fh[s4][t]), fx, acc[t], 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(fl[s4][t]), fx, acc[t], 0, 0, 0);
+        }
       }
     }
   }
