@@ -973,7 +973,7 @@ mpz_status mpz_debug_set_two_halves(mpz_model* m, int32_t enable) {
 
 mpz_status mpz_debug_set_tile_config(mpz_model* m, int32_t tile_cfg) {
   if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_set_tile_config: NULL model");
-  if (tile_cfg < 0 || tile_cfg > 13) return fail(m, MPZ_ERR_CONFIG, "tile configuration outside [0, 13]");
+  if (tile_cfg < 0 || tile_cfg > 14) return fail(m, MPZ_ERR_CONFIG, "tile configuration outside [0, 14]");
   m->force_tile_cfg = tile_cfg;
   return MPZ_OK;
 }
