@@ -80,7 +80,7 @@ def main():
     ap.add_argument("--pad-fraction", type=float, default=None,
                     help="right-padded batch of unequal lengths (seeded; about this fraction of the E*S slots is padding): "
                          "the loss runs over real tokens only (mpz_forward_perturbed_varlen)")
-    ap.add_argument("--weight-quant", default=None, choices=["none", "int8"],
+    ap.add_argument("--weight-quant", default=None, choices=["none", "int8", "nf4"],
                     help="weight-only quantisation of the block linears (int8 codes + per-channel scales)")
     ap.add_argument("--one-stream", action="store_true",
                     help="issue the whole pass on one stream also for small models (per-kernel counters and traces then "

@@ -52,7 +52,7 @@ enum { MPZ_ACT_RELU = 0, MPZ_ACT_GELU_ERF = 1, MPZ_ACT_SWIGLU = 2 };
 enum { MPZ_NORM_LAYERNORM = 0, MPZ_NORM_RMSNORM = 1 };
 enum { MPZ_POS_LEARNED = 0, MPZ_POS_ROPE = 1 };
 enum { MPZ_DTYPE_F32 = 0, MPZ_DTYPE_BF16 = 1 };
-enum { MPZ_WEIGHT_QUANT_NONE = 0, MPZ_WEIGHT_QUANT_INT8 = 1 };
+enum { MPZ_WEIGHT_QUANT_NONE = 0, MPZ_WEIGHT_QUANT_INT8 = 1, MPZ_WEIGHT_QUANT_NF4 = 2 };
 enum { MPZ_TARGET_Q = 1, MPZ_TARGET_K = 2, MPZ_TARGET_V = 4, MPZ_TARGET_O = 8 };
 enum {
   MPZ_LOSS_LAST_POS_LABEL_SUBSET = 0, /* 2-way CE over two label-token logits at the last position */
@@ -83,7 +83,13 @@ typedef struct {
                              (Appendix D, "MobiZO with weight-only quantization").  INT8: w_* hold int8 codes and
                              s_* one fp32 scale per output channel, W = code * scale exactly; needs dtype BF16,
                              d_model and d_ffn multiples of 64 and E*S a multiple of 32 (MFMA path only).  The codes
-                             are widened once per step for all 2q copies, inside the GEMM's operand load. */
+                             are widened once per step for all 2q copies, inside the GEMM's operand load.
+                             NF4: w_* hold 4-bit normal-float codes (the sixteen-level type of Q-LoRA, which the
+                             appendix builds on), two per byte, rows of k_in / 2 bytes with element 2j in the low
+                             nibble of byte j; s_* one fp32 absolute maximum per block of 64 consecutive input
+                             channels, [k_out, k_in / 64]; W = bf16(level[code] * max).  Needs dtype BF16 and d_model,
+                             d_ffn multiples of 64.  Each linear is dequantised into a workspace buffer right before
+                             its GEMM: once per pass for all the copies of that pass. */
 } mpz_config;
 
 /* Frozen parameters theta_f of one decoder block (Algorithm 1, input line).  All [dev], borrowed. */
@@ -100,12 +106,13 @@ typedef struct {
   const float* b_up;  /* [d_ffn] (SwiGLU: [2*d_ffn]) or NULL */
   const void* w_down; /* [d, d_ffn] */
   const float* b_down;/* [d] or NULL */
-  /* weight_quant = INT8 only (else ignored): per-output-channel scales, 16-byte aligned; the w_* above are then int8
-   * with the same [k_out, k_in] shapes */
-  const float* s_qkv; /* [d + 2*d_kv] */
-  const float* s_o;   /* [d] */
-  const float* s_up;  /* [d_ffn] (SwiGLU: [2*d_ffn]) */
-  const float* s_down;/* [d] */
+  /* weight_quant = INT8: per-output-channel scales, 16-byte aligned; the w_* above are then int8 with the same
+   * [k_out, k_in] shapes.  NF4: block maxima [k_out, k_in / 64]; the w_* are packed codes [k_out, k_in / 2] bytes,
+   * 4-byte aligned.  NONE: ignored. */
+  const float* s_qkv; /* [d + 2*d_kv] (NF4: [d + 2*d_kv, d / 64]) */
+  const float* s_o;   /* [d] (NF4: [d, d / 64]) */
+  const float* s_up;  /* [d_ffn] (SwiGLU: [2*d_ffn]) (NF4: [rows, d / 64]) */
+  const float* s_down;/* [d] (NF4: [d, d_ffn / 64]) */
 } mpz_layer_weights;
 
 typedef struct {
@@ -260,6 +267,11 @@ mpz_status mpz_debug_gemm_bf16(int32_t M, int32_t N, int32_t K, const void* x, c
 mpz_status mpz_debug_gemm_int8(int32_t M, int32_t N, int32_t K, const void* x, const void* w_codes, const float* w_scale,
                                const float* bias, int32_t act, void* out, int32_t out_f32, int32_t tile_cfg,
                                void* hip_stream);
+
+/* Test hook: the dequantisation of weight_quant = NF4 on its own: codes [dev] n_elems / 2 bytes (two codes per byte,
+ * low nibble first), absmax [dev] [n_elems / 64] fp32, out [dev] [n_elems] bf16 = bf16(level[code] * max).
+ * Errors: NULL, SHAPE (n_elems < 64 or not a multiple of 64). */
+mpz_status mpz_debug_dequant_nf4(const void* codes, const float* absmax, void* out, int64_t n_elems, void* hip_stream);
 
 /* Test hook: simple_only != 0 routes every stage through the shape-agnostic kernels (the only path of
  * fp32 models); 0 restores the default (bf16 models use the MFMA kernels wherever a shape allows).

@@ -59,15 +59,42 @@ def _lora_delta(x, lora, layer: int, target: str, scale: float, prec: Precision)
     return t @ prec.lora_factor(B)
 
 
-def _weight(lw, name: str) -> np.ndarray:
-    """Frozen weight [k_in, k_out] of a block in binary64.  With weight-only 8-bit quantisation (Appendix D,
-    "MobiZO with weight-only quantization": weights are stored in a low-bit format and dequantised for the forward
-    pass) the stored form is an int8 code per element and a scale per output channel; the weight is their exact
-    product (reading: no rounding to the 16-bit operand type on the way)."""
+# The sixteen levels of the 4-bit normal-float type of Q-LoRA (Dettmers et al. 2023, appendix "NormalFloat 4-bit
+# data type"), which Appendix D builds on: quantiles of N(0, 1) scaled to [-1, 1] with an exact zero - seven negative
+# levels, zero, eight positive ones - as binary32 values.
+NF4_LEVELS = np.array([
+    -1.0, -0.6961928009986877, -0.5250730514526367, -0.39491748809814453, -0.28444138169288635,
+    -0.18477343022823334, -0.09105003625154495, 0.0, 0.07958029955625534, 0.16093020141124725,
+    0.24611230194568634, 0.33791524171829224, 0.44070982933044434, 0.5626170039176941, 0.7229568362236023, 1.0],
+    dtype=np.float32)
+NF4_BLOCK = 64
+
+
+def nf4_dequant(codes: np.ndarray, absmax: np.ndarray) -> np.ndarray:
+    """Weight [k_in, k_out] in binary32 from 4-bit codes [k_in, k_out] (0..15) and one absolute maximum per block of
+    64 consecutive input channels of an output channel, [k_in / 64, k_out]: level[code] x absmax, one binary32
+    multiplication per element (reading: blocks run along the input dimension, no second quantisation of the
+    maxima)."""
+    codes = np.asarray(codes)
+    assert codes.dtype == np.uint8 and codes.max(initial=0) < 16 and codes.shape[0] % NF4_BLOCK == 0
+    a = np.repeat(np.asarray(absmax, dtype=np.float32), NF4_BLOCK, axis=0)
+    assert a.shape == codes.shape
+    return NF4_LEVELS[codes] * a
+
+
+def _weight(lw, name: str, prec: Precision) -> np.ndarray:
+    """Frozen weight [k_in, k_out] of a block in binary64.  With weight-only quantisation (Appendix D, "MobiZO with
+    weight-only quantization": weights are stored in a low-bit format and dequantised for the forward pass) the
+    stored form is either an int8 code per element and a scale per output channel - the weight is their exact
+    product (reading: no rounding to the 16-bit operand type on the way) - or a 4-bit normal-float code per element
+    and a maximum per block of 64, dequantised to the operand type as the appendix describes (binary32 product,
+    then the operand rounding)."""
     W = np.asarray(lw["w_" + name])
     s = lw.get("s_" + name)
     if s is None:
         return W.astype(np.float64)
+    if W.dtype == np.uint8:
+        return np.asarray(prec.operand(nf4_dequant(W, s)), dtype=np.float64)
     return W.astype(np.float64) * np.asarray(s, dtype=np.float64)[None, :]
 
 
@@ -119,7 +146,7 @@ def decoder_layer(w, lw, li: int, h, lora, prec: Precision):
     norm_eps = float(np.float32(w.norm_eps))            # hyper-parameters are binary32 numbers
     scale = float(np.float32(w.lora_scale))
     x = prec.operand(_norm(h, lw["ln1_g"], lw["ln1_b"], w.norm, norm_eps))
-    Wqkv, bqkv = _weight(lw, "qkv"), lw["b_qkv"]
+    Wqkv, bqkv = _weight(lw, "qkv", prec), lw["b_qkv"]
     cols = {"q": (0, d), "k": (d, d + w.d_kv), "v": (d + w.d_kv, d + 2 * w.d_kv)}
     proj = {}
     for name, (c0, c1) in cols.items():
@@ -133,10 +160,10 @@ def decoder_layer(w, lw, li: int, h, lora, prec: Precision):
         qh, kh = _rope(qh, cos, sin), _rope(kh, cos, sin)
     qh, kh, vh = prec.operand(qh), prec.operand(kh), prec.operand(vh)
     attn = prec.operand(_attention(qh, kh, vh, H, Hkv, prec))
-    h = prec.stream(h + _linear(attn, _weight(lw, "o"), lw["b_o"], _lora_delta(attn, lora, li, "o", scale, prec)))
+    h = prec.stream(h + _linear(attn, _weight(lw, "o", prec), lw["b_o"], _lora_delta(attn, lora, li, "o", scale, prec)))
 
     x = prec.operand(_norm(h, lw["ln2_g"], lw["ln2_b"], w.norm, norm_eps))
-    up = _linear(x, _weight(lw, "up"), lw["b_up"])
+    up = _linear(x, _weight(lw, "up", prec), lw["b_up"])
     if w.act == "relu":
         u = np.maximum(up, 0.0)
     elif w.act == "gelu":
@@ -145,7 +172,7 @@ def decoder_layer(w, lw, li: int, h, lora, prec: Precision):
         gate, lin = up[..., :w.d_ffn], up[..., w.d_ffn:]
         u = gate / (1.0 + np.exp(-gate)) * lin
     u = prec.operand(u)
-    return prec.stream(h + _linear(u, _weight(lw, "down"), lw["b_down"]))
+    return prec.stream(h + _linear(u, _weight(lw, "down", prec), lw["b_down"]))
 
 
 def head_loss(w, frozen, h, tokens: np.ndarray, labels, prec: Precision, lengths=None) -> float:

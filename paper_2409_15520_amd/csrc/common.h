@@ -118,6 +118,9 @@ void launch_gather_last_rows(hipStream_t st, const float* h, const int32_t* leng
 void launch_copy_mean(hipStream_t st, const float* ce, int rows_per_copy, int count_per_copy, const int32_t* lengths, int E,
                       int S, float* losses, int n_copies);
 void launch_fill_f32(hipStream_t st, float* p, float v, int64_t n);
+// 4-bit normal-float codes (two per byte, low nibble first) + block maxima [n_elems / 64] -> bf16 [n_elems];
+// n_elems % 64 == 0, rows of a multiple of 64 elements stored back to back
+void launch_nf4_dequant(hipStream_t st, const void* codes, const float* absmax, void* out, int64_t n_elems);
 
 // ---- gemm_mfma.hip: bf16 MFMA kernels (gfx950) ------------------------------------------------
 struct MfmaGemmArgs {

@@ -44,6 +44,7 @@ struct Buffers {
   int chunk_rows = 0;
   void* packed = nullptr;     // [2 q_max][packed_per_copy] bf16 hi/lo operand layouts of the perturbed factors
   void* tp[3] = {nullptr, nullptr, nullptr};  // per target [T, rp] duplicated bottleneck activations
+  void* wq = nullptr;         // 4-bit weights: the largest block linear, dequantised to bf16
 };
 
 size_t elem_size(int dtype) { return dtype == MPZ_DTYPE_F32 ? 4 : 2; }
@@ -66,7 +67,9 @@ const char* validate_config(const mpz_config* c) {
   if (c->d_model % 4) return "d_model must be a multiple of 4";
   if (!(c->norm_eps > 0.f) || !std::isfinite(c->lora_scale)) return "norm_eps must be positive and lora_scale finite";
   if (c->loss_mode < 0 || c->loss_mode > 2) return "unknown loss_mode";
-  if (c->weight_quant != MPZ_WEIGHT_QUANT_NONE && c->weight_quant != MPZ_WEIGHT_QUANT_INT8) return "unknown weight_quant";
+  if (c->weight_quant < MPZ_WEIGHT_QUANT_NONE || c->weight_quant > MPZ_WEIGHT_QUANT_NF4) return "unknown weight_quant";
+  if (c->weight_quant == MPZ_WEIGHT_QUANT_NF4 && (c->dtype != MPZ_DTYPE_BF16 || c->d_model % 64 || c->d_ffn % 64))
+    return "4-bit weights need dtype BF16 and d_model, d_ffn multiples of 64";
   if (c->weight_quant == MPZ_WEIGHT_QUANT_INT8 && (c->dtype != MPZ_DTYPE_BF16 || c->d_model % 64 || c->d_ffn % 64 ||
                                                    (c->n_kv_heads * (c->d_model / c->n_heads)) % 2))
     return "int8 weights need dtype BF16 and d_model, d_ffn multiples of 64";
@@ -143,6 +146,13 @@ size_t carve(const mpz_config* c, int q_max, int E_max, int S_max, void* base, B
       per_layer += (tab.local_id[i] & 1) ? (int64_t)tab.cols[i] * rp : (int64_t)2 * tab.rows[i] * tab.cols[i];
     bb.packed = cv.take<uint16_t>((size_t)(n * per_layer * c->n_layers));
     for (int i = 0; i < 3; ++i) bb.tp[i] = cv.take<uint16_t>((size_t)T * rp);
+  }
+  if (c->weight_quant == MPZ_WEIGHT_QUANT_NF4) {
+    const size_t n_qkv = (size_t)(d + 2 * dkv), n_up = (size_t)(c->act == MPZ_ACT_SWIGLU ? 2 * f : f);
+    size_t big = n_qkv * d;
+    if (n_up * d > big) big = n_up * d;
+    if ((size_t)d * f > big) big = (size_t)d * f;
+    bb.wq = cv.take<uint16_t>(big);
   }
   if (b) *b = bb;
   return (cv.off + 255) & ~(size_t)255;
@@ -261,6 +271,17 @@ Buffers view(const mpz_model* m, int E, int S) {
   if (b.stage) b.stage = (char*)b.stage + row0 * m->stage_row_bytes;
   if (c.loss_mode == MPZ_LOSS_LAST_POS_LABEL_SUBSET) b.logits += loss0 * 2;   // [n E, 2]: a range owns its rows
   return b;
+}
+
+// The frozen weight of one block linear as the GEMM reads it.  4-bit weights are dequantised to bf16 here, into the
+// one workspace buffer every linear shares (stream order keeps a GEMM ahead of the next dequantisation): once per
+// pass, whatever the number of copies in it (Appendix D: the inner loop dequantises once per step).
+struct WeightRef { const void* w; const float* scale; };
+WeightRef weight_operand(mpz_model* m, const void* w, const float* s, int N, int K) {
+  if (m->cfg.weight_quant != MPZ_WEIGHT_QUANT_NF4) return {w, s};
+  ProfScope ps(m, MPZ_PROF_PACK, 0.0, (double)N * K * (0.5 + 4.0 / 64.0 + 2.0));
+  launch_nf4_dequant(m->stream, w, s, m->buf.wq, (int64_t)N * K);
+  return {m->buf.wq, nullptr};
 }
 
 // Every base-weight GEMM of the pass goes through here (kernel selection and optional timing).  Returns false
@@ -396,6 +417,8 @@ void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, bool rope, int
       ProfScope ps(m, MPZ_PROF_LORA_DOWN, 2.0 * T * (double)d * nt * r, esz(m) * T * ((double)d + (double)nt * r));
       launch_lora_down_simple(st, da);
     }
+    const WeightRef wq = weight_operand(m, lw.w_qkv, lw.s_qkv, nqkv, d);
+    qa.w = wq.w; qa.w_scale = wq.scale;
     if (rope) {
       qa.out_kind = 0; qa.out = b.qkv;
       qa.rope_cos = b.rope_cos; qa.rope_sin = b.rope_sin; qa.rope_cols = d + dkv; qa.rope_dh = dh; qa.S = S;
@@ -475,6 +498,8 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
       oa.seg[0].col_begin = 0; oa.seg[0].col_end = d; oa.seg[0].t = b.t; oa.seg[0].t_stride = r; oa.seg[0].t_off = 0;
       oa.seg[0].Bc = b.pert + find_tensor(m, l, 3, 1)->offset; oa.seg[0].copy_stride = m->P;
     }
+    const WeightRef wo = weight_operand(m, lw.w_o, lw.s_o, d, d);
+    oa.w = wo.w; oa.w_scale = wo.scale;
     gemm(m, oa);
 
     // feed-forward block
@@ -483,6 +508,8 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     ua.dtype = c.dtype; ua.M = T; ua.N = swiglu ? 2 * f : f; ua.K = d; ua.x = b.x; ua.w = lw.w_up; ua.w_scale = lw.s_up; ua.bias = lw.b_up;
     ua.rank = r; ua.rows_per_copy = rpc; ua.act = swiglu ? -1 : c.act;
     ua.out_kind = swiglu ? 2 : 0; ua.out = swiglu ? b.stage : b.u;
+    const WeightRef wu = weight_operand(m, lw.w_up, lw.s_up, swiglu ? 2 * f : f, d);
+    ua.w = wu.w; ua.w_scale = wu.scale;
     if (!(swiglu && gemm_swiglu_mfma(m, ua, f, b.u))) {
       gemm(m, ua);
       if (swiglu) {
@@ -493,6 +520,8 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     LinearArgs wa{};
     wa.dtype = c.dtype; wa.M = T; wa.N = d; wa.K = f; wa.x = b.u; wa.w = lw.w_down; wa.w_scale = lw.s_down; wa.bias = lw.b_down;
     wa.rank = r; wa.rows_per_copy = rpc; wa.act = -1; wa.residual = b.h; wa.out_kind = 1; wa.out = b.h;
+    const WeightRef wd = weight_operand(m, lw.w_down, lw.s_down, d, f);
+    wa.w = wd.w; wa.w_scale = wd.scale;
     gemm(m, wa);
   }
 }
@@ -640,6 +669,12 @@ mpz_status mpz_init_model(const mpz_config* cfg, const mpz_weights* frozen, floa
       if ((((uintptr_t)lw.s_qkv | (uintptr_t)lw.s_o | (uintptr_t)lw.s_up | (uintptr_t)lw.s_down) & 15u) != 0)
         return fail(nullptr, MPZ_ERR_CONFIG, "int8 weight scales must be 16-byte aligned");
     }
+    if (cfg->weight_quant == MPZ_WEIGHT_QUANT_NF4) {
+      if (!lw.s_qkv || !lw.s_o || !lw.s_up || !lw.s_down) return fail(nullptr, MPZ_ERR_NULL, "4-bit weights need their block maxima");
+      if ((((uintptr_t)lw.s_qkv | (uintptr_t)lw.s_o | (uintptr_t)lw.s_up | (uintptr_t)lw.s_down | (uintptr_t)lw.w_qkv |
+            (uintptr_t)lw.w_o | (uintptr_t)lw.w_up | (uintptr_t)lw.w_down) & 3u) != 0)
+        return fail(nullptr, MPZ_ERR_CONFIG, "4-bit codes and block maxima must be 4-byte aligned");
+    }
   }
   if (((uintptr_t)workspace & 255u) != 0) return fail(nullptr, MPZ_ERR_WORKSPACE, "workspace is not 256-byte aligned");
   size_t need = carve(cfg, q_max, E_max, S_max, nullptr, nullptr);
@@ -656,7 +691,7 @@ mpz_status mpz_init_model(const mpz_config* cfg, const mpz_weights* frozen, floa
     for (auto& lw : m->layers) lw.b_qkv = lw.b_o = lw.b_up = lw.b_down = nullptr;
   if (cfg->norm == MPZ_NORM_RMSNORM)
     for (auto& lw : m->layers) lw.ln1_b = lw.ln2_b = nullptr;
-  if (cfg->weight_quant != MPZ_WEIGHT_QUANT_INT8)
+  if (cfg->weight_quant == MPZ_WEIGHT_QUANT_NONE)
     for (auto& lw : m->layers) lw.s_qkv = lw.s_o = lw.s_up = lw.s_down = nullptr;
   m->w = *frozen;
   m->w.layers = m->layers.data();
@@ -733,6 +768,7 @@ bool use_two_halves(mpz_model* m, int E, int S) {
   const int n = 2 * m->q;
   if (!m->two_halves || m->prof_on || !m->use_mfma || n < 4 || n % 2 || m->lengths != nullptr) return false;
   if (c.loss_mode != MPZ_LOSS_LAST_POS_LABEL_SUBSET) return false;           // the whole-vocabulary scratch is shared
+  if (c.weight_quant == MPZ_WEIGHT_QUANT_NF4) return false;                  // so is the dequantised-weight buffer
   if (((n / 2) * E * S) % 32) return false;
   const long T = (long)n * E * S;
   const int nqkv = c.d_model + 2 * c.n_kv_heads * (c.d_model / c.n_heads);
@@ -969,6 +1005,15 @@ mpz_status mpz_debug_set_two_halves(mpz_model* m, int32_t enable) {
   if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_set_two_halves: NULL model");
   m->two_halves = enable != 0;
   return MPZ_OK;
+}
+
+mpz_status mpz_debug_dequant_nf4(const void* codes, const float* absmax, void* out, int64_t n_elems, void* hip_stream) {
+  if (!codes || !absmax || !out) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_dequant_nf4: NULL argument");
+  if (n_elems < 64 || n_elems % 64) return fail(nullptr, MPZ_ERR_SHAPE, "mpz_debug_dequant_nf4: n_elems must be a positive multiple of 64");
+  if ((((uintptr_t)codes | (uintptr_t)absmax) & 3u) || ((uintptr_t)out & 15u))
+    return fail(nullptr, MPZ_ERR_CONFIG, "mpz_debug_dequant_nf4: codes / absmax 4-byte, out 16-byte aligned");
+  launch_nf4_dequant((hipStream_t)hip_stream, codes, absmax, out, n_elems);
+  return hipGetLastError() == hipSuccess ? MPZ_OK : fail(nullptr, MPZ_ERR_DEVICE, "mpz_debug_dequant_nf4: launch failed");
 }
 
 mpz_status mpz_debug_set_tile_config(mpz_model* m, int32_t tile_cfg) {

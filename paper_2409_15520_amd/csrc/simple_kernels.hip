@@ -371,6 +371,39 @@ __global__ void __launch_bounds__(256) copy_mean_kernel(const float* __restrict_
   }
 }
 
+// 4-bit normal-float weights -> bf16 (Appendix D builds on Q-LoRA's data type: sixteen levels, the quantiles of
+// N(0, 1) scaled to [-1, 1] with an exact zero; one binary32 maximum per block of 64 consecutive input channels).
+// Layout: output-major rows of K / 2 bytes, element 2j of a row in the low nibble of byte j, element 2j + 1 in the
+// high nibble; absmax [rows, K / 64].  A thread turns one 32-bit word (8 codes) into 16 bytes of bf16:
+// level[code] * absmax in binary32, rounded to nearest even.  Rows are contiguous and K % 64 == 0, so word i
+// belongs to block i / 8 whatever the row.
+__global__ void __launch_bounds__(256) nf4_dequant_kernel(const uint32_t* __restrict__ codes,
+                                                          const float* __restrict__ absmax, uint4* __restrict__ out,
+                                                          int64_t words) {
+  __shared__ float level[16];
+  if (threadIdx.x < 16) {
+    constexpr float kLevel[16] = {-1.0f, -0.6961928009986877f, -0.5250730514526367f, -0.39491748809814453f,
+                                  -0.28444138169288635f, -0.18477343022823334f, -0.09105003625154495f, 0.0f,
+                                  0.07958029955625534f, 0.16093020141124725f, 0.24611230194568634f,
+                                  0.33791524171829224f, 0.44070982933044434f, 0.5626170039176941f,
+                                  0.7229568362236023f, 1.0f};
+    level[threadIdx.x] = kLevel[threadIdx.x];
+  }
+  __syncthreads();
+  const int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int64_t i = base + it * 256;
+    if (i >= words) break;
+    const uint32_t c = codes[i];
+    const float a = absmax[i >> 3];
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = __fmul_rn(level[(c >> (4 * e)) & 15u], a);
+    out[i] = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+  }
+}
+
 __global__ void fill_kernel(float* p, float v, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -435,6 +468,11 @@ void launch_ce_rows(hipStream_t st, int dtype, const float* logits, int64_t row_
 void launch_last_pos_subset_logits(hipStream_t st, int dtype, const void* xf, const void* head, int d, int rows, int tok0,
                                    int tok1, float* logits2) {
   MPZ_DISPATCH(dtype, (subset_logits_kernel<ST><<<rows, 64, 0, st>>>((const ST*)xf, (const ST*)head, d, tok0, tok1, logits2)));
+}
+
+void launch_nf4_dequant(hipStream_t st, const void* codes, const float* absmax, void* out, int64_t n_elems) {
+  const int64_t words = n_elems / 8;
+  nf4_dequant_kernel<<<nblk((words + 3) / 4, 256), 256, 0, st>>>((const uint32_t*)codes, absmax, (uint4*)out, words);
 }
 
 void launch_make_targets(hipStream_t st, int mode, const int32_t* tokens, const int32_t* labels, const int32_t* lengths,

@@ -252,6 +252,19 @@ def mpz_debug_gemm_int8(M: int, N: int, K: int, x_ptr: int, w_ptr: int, scale_pt
                                    stream_ptr))
 
 
+def mpz_debug_dequant_nf4(codes_ptr: int, absmax_ptr: int, out_ptr: int, n_elems: int, stream_ptr: int):
+    lib = load_library()
+    lib.mpz_debug_dequant_nf4.restype = C.c_int
+    lib.mpz_debug_dequant_nf4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+    _check(lib.mpz_debug_dequant_nf4(codes_ptr, absmax_ptr, out_ptr, n_elems, stream_ptr))
+
+
+def pack_nf4_codes(codes):
+    """Codes 0..15, one per byte, [rows, k_in] (a torch or numpy uint8 array) -> two per byte [rows, k_in / 2]: element
+    2j of a row in the low nibble of byte j, element 2j + 1 in the high nibble (the library's layout)."""
+    return codes[..., 0::2] | (codes[..., 1::2] << 4)
+
+
 def mpz_debug_noise_alu_probe(n_groups: int, q: int, sink_ptr: int, stream_ptr: int):
     lib = load_library()
     lib.mpz_debug_noise_alu_probe.restype = C.c_int
@@ -302,7 +315,7 @@ def config_from_workload(w) -> MpzConfig:
     cfg.lora_targets = sum(TARGET_BIT[t] for t in w.lora_targets)
     cfg.lora_scale, cfg.perturb_A, cfg.loss_mode = w.lora_scale, int(w.perturb_A), LOSS[w.loss_mode]
     cfg.label_token[0], cfg.label_token[1] = w.label_tokens
-    cfg.weight_quant = {"none": 0, "int8": 1}[getattr(w, "weight_quant", "none")]
+    cfg.weight_quant = {"none": 0, "int8": 1, "nf4": 2}[getattr(w, "weight_quant", "none")]
     return cfg
 
 
@@ -324,9 +337,15 @@ def device_random_weights(w, seed: int, device: str = "cuda:0"):
     zeros = lambda n: torch.zeros(n, device=device, dtype=torch.float32)
     ln = w.norm == "layernorm"
     q8 = getattr(w, "weight_quant", "none") == "int8"
+    q4 = getattr(w, "weight_quant", "none") == "nf4"
 
     def lin(n_out, n_in):
-        """A block linear [k_out, k_in]: model dtype, or (int8 codes, per-output-channel scales)."""
+        """A block linear [k_out, k_in]: model dtype, (int8 codes, per-output-channel scales), or (4-bit codes packed
+        two per byte, block maxima [k_out, k_in / 64])."""
+        if q4:
+            codes = torch.randint(0, 16, (n_out, n_in), generator=g, device=device, dtype=torch.uint8)
+            absmax = 0.048 * (0.75 + 0.5 * torch.rand(n_out, n_in // 64, generator=g, device=device, dtype=torch.float32))
+            return pack_nf4_codes(codes).contiguous(), absmax
         if not q8:
             return rnd(n_out, n_in), None
         codes = (torch.randn(n_out, n_in, generator=g, device=device, dtype=torch.float32) * 32.0).round_().clamp_(-127, 127)
@@ -382,11 +401,17 @@ class ZoModel:
         for i, lw in enumerate(frozen["layers"]):
             for name in ("ln1_g", "ln1_b", "b_qkv", "b_o", "ln2_g", "ln2_b", "b_up", "b_down"):
                 setattr(layers[i], name, dev(lw[name], torch.float32))
-            q8 = getattr(w, "weight_quant", "none") == "int8"
+            quant = getattr(w, "weight_quant", "none")
             for name in ("w_qkv", "w_o", "w_up", "w_down"):          # [k_in, k_out] -> output-major
-                setattr(layers[i], name, dev(lw[name], torch.int8 if q8 else st, transpose=True))
-            for name in ("s_qkv", "s_o", "s_up", "s_down"):
-                setattr(layers[i], name, dev(lw.get(name), torch.float32) if q8 else None)
+                if quant == "nf4" and not on_device:                 # one code per byte -> two per byte along k_in
+                    packed = pack_nf4_codes(np.ascontiguousarray(np.asarray(lw[name]).T))
+                    setattr(layers[i], name, dev(packed, torch.uint8))
+                else:
+                    wt_dtype = {"none": st, "int8": torch.int8, "nf4": torch.uint8}[quant]
+                    setattr(layers[i], name, dev(lw[name], wt_dtype, transpose=True))
+            for name in ("s_qkv", "s_o", "s_up", "s_down"):          # nf4: [k_in / 64, k_out] -> [k_out, k_in / 64]
+                setattr(layers[i], name, dev(lw.get(name), torch.float32, transpose=quant == "nf4")
+                        if quant != "none" else None)
         self._layers = layers
         wt = MpzWeights()
         wt.emb = dev(frozen["emb"], st)

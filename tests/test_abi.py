@@ -69,6 +69,23 @@ def test_invalid_configs_are_rejected_on_the_host(field, value):
     assert M.mpz_workspace_bytes(cfg, 2, 2, 32) == 0
 
 
+def test_four_bit_weights_need_bf16_and_add_the_dequantisation_buffer():
+    w = W.get_workload("c2_opt125m")
+    cfg = M.config_from_workload(w)
+    plain = M.mpz_workspace_bytes(cfg, 4, 8, 128)
+    cfg4 = M.config_from_workload(w.with_(weight_quant="nf4"))
+    assert cfg4.weight_quant == 2
+    # one bf16 copy of the largest block linear (768 x 3072), rounded up to the 256-byte carving
+    assert M.mpz_workspace_bytes(cfg4, 4, 8, 128) - plain == 768 * 3072 * 2
+    cfg4.dtype = 0
+    assert M.mpz_workspace_bytes(cfg4, 4, 8, 128) == 0
+    cfg4.dtype, cfg4.weight_quant = 1, 3
+    assert M.mpz_workspace_bytes(cfg4, 4, 8, 128) == 0
+    with pytest.raises(M.MpzError):
+        M.mpz_debug_dequant_nf4(None, None, None, 64, None)
+    assert np.array_equal(M.pack_nf4_codes(np.array([[1, 2, 15, 0]], dtype=np.uint8)), np.array([[0x21, 0x0F]], dtype=np.uint8))
+
+
 def test_label_tokens_must_be_distinct_and_in_vocab():
     cfg = M.config_from_workload(W.get_workload("c1_tiny_fp32"))
     cfg.label_token[1] = 512

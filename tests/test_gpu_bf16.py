@@ -32,6 +32,11 @@ CASES = {
 # weight-only int8 block linears (codes widened in the GEMM's operand load, scale on the accumulator)
 CASES["c2_int8"] = CASES["c2_2layers"].with_(weight_quant="int8")
 CASES["llama_mfma_int8"] = CASES["llama_mfma"].with_(weight_quant="int8")
+# weight-only 4-bit normal-float block linears (dequantised to bf16 once per pass, right before each GEMM); the
+# miniature runs them through the shape-agnostic kernels
+CASES["c2_nf4"] = CASES["c2_2layers"].with_(weight_quant="nf4")
+CASES["llama_mfma_nf4"] = CASES["llama_mfma"].with_(weight_quant="nf4")
+CASES["mini_llama_nf4"] = MINI_LLAMA.with_(dtype="bf16", d_ffn=128, weight_quant="nf4")
 
 
 @pytest.mark.parametrize("name,eps,b_std", [("mini_llama", 1e-3, 0.01), ("mini_opt", 1e-3, 0.01),
@@ -39,7 +44,10 @@ CASES["llama_mfma_int8"] = CASES["llama_mfma"].with_(weight_quant="int8")
                                             ("llama_mfma", 1e-3, 0.01), ("llama_mfma", 5e-2, 0.05),
                                             ("c2_ragged_copies", 5e-2, 0.05),
                                             ("c2_int8", 1e-3, 0.01), ("c2_int8", 5e-2, 0.05),
-                                            ("llama_mfma_int8", 1e-3, 0.01), ("llama_mfma_int8", 5e-2, 0.05)])
+                                            ("llama_mfma_int8", 1e-3, 0.01), ("llama_mfma_int8", 5e-2, 0.05),
+                                            ("c2_nf4", 1e-3, 0.01), ("c2_nf4", 5e-2, 0.05),
+                                            ("llama_mfma_nf4", 1e-3, 0.01), ("llama_mfma_nf4", 5e-2, 0.05),
+                                            ("mini_llama_nf4", 1e-3, 0.01)])
 def test_each_stage_on_oracle_inputs(name, eps, b_std):
     """Second c2 case: perturbation and B large enough that the low-rank term moves the projections by
     O(10%), so a wrong or missing per-copy term cannot hide under the rounding tolerance."""

@@ -204,3 +204,25 @@ def test_swiglu_dual_gemm_int8_weights(cfg):
     gate, up = x @ wd[:F].T, x @ wd[F:].T
     want = gate / (1.0 + np.exp(-gate)) * up
     assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("rows,K_", [(1, 64), (3, 192), (257, 4096), (1000, 768)])
+def test_nf4_dequantisation_is_bit_exact(rows, K_):
+    """level[code] * block maximum in binary32, rounded to bf16: the same bits as the oracle's dequantisation (sizes
+    from one block to several thread blocks with a ragged tail; every code occurs)."""
+    import torch
+    import paper_2409_15520_amd as M
+    from oracle.model import nf4_dequant
+    rng = np.random.default_rng(rows * 7 + K_)
+    codes = rng.integers(0, 16, size=(K_, rows), dtype=np.uint8)                   # oracle layout [k_in, k_out]
+    codes[:16, 0] = np.arange(16)
+    absmax = (0.048 * (0.5 + rng.random((K_ // 64, rows)))).astype(np.float32)
+    want = BF.operand(nf4_dequant(codes, absmax)).T                                # [k_out, k_in]
+    packed = M.pack_nf4_codes(np.ascontiguousarray(codes.T))
+    assert packed.shape == (rows, K_ // 2) and packed.dtype == np.uint8
+    cd = torch.from_numpy(np.ascontiguousarray(packed)).cuda()
+    ad = torch.from_numpy(np.ascontiguousarray(absmax.T)).cuda()
+    out = torch.full((rows, K_), float("nan"), dtype=torch.bfloat16, device="cuda")
+    M.mpz_debug_dequant_nf4(cd.data_ptr(), ad.data_ptr(), out.data_ptr(), rows * K_, torch.cuda.current_stream().cuda_stream)
+    got = out.float().cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, want)

@@ -42,7 +42,7 @@ class Workload:
     norm_eps: float = 1e-5
     rope_theta: float = 10000.0
     label_tokens: Tuple[int, int] = (0, 1)
-    weight_quant: str = "none"   # "none" | "int8": weight-only quantisation of the block linears (Appendix D)
+    weight_quant: str = "none"   # "none" | "int8" | "nf4": weight-only quantisation of the block linears (Appendix D)
 
     @property
     def d_head(self) -> int:

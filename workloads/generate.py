@@ -39,6 +39,18 @@ def _int8_weight(rng: np.random.Generator, shape):
     return q, s.astype(np.float32)
 
 
+def _nf4_weight(rng: np.random.Generator, shape):
+    """Synthetic weight-only 4-bit linear [k_in, k_out]: one code in 0..15 per element (uniform: the 4-bit normal-float
+    levels are equal-probability bins of a normal weight) and one float32 absolute maximum per block of 64
+    consecutive input channels of one output channel, [k_in / 64, k_out], 0.048 times a factor in [0.75, 1.25]
+    (0.048 = 0.02 times the expected largest of 64 standard normals, about 2.4)."""
+    if shape[0] % 64:
+        raise ValueError("4-bit blocks hold 64 input channels: k_in must be a multiple of 64")
+    codes = rng.integers(0, 16, size=shape, dtype=np.uint8)
+    absmax = np.float32(0.048) * (np.float32(0.75) + np.float32(0.5) * rng.random((shape[0] // 64, shape[1]), dtype=np.float32))
+    return codes, absmax.astype(np.float32)
+
+
 def make_frozen_weights(w: Workload, seed: int, n_layers: Optional[int] = None) -> Dict[str, object]:
     """Frozen parameters as float32 arrays (bf16-representable when w.dtype == 'bf16').
 
@@ -46,7 +58,8 @@ def make_frozen_weights(w: Workload, seed: int, n_layers: Optional[int] = None) 
     concatenation [W_q | W_k | W_v]; for SwiGLU `w_up` is [W_gate | W_up].  `emb` is
     [vocab, d]; `lm_head` is [vocab, d] (the same array as `emb` when embeddings are tied).
     Norm gains/biases are float32.  With w.weight_quant == "int8" the four linears of a block are int8 codes
-    `w_*` [k_in, k_out] with float32 scales `s_*` [k_out] (embeddings and the head stay in the model dtype).
+    `w_*` [k_in, k_out] with float32 scales `s_*` [k_out] (embeddings and the head stay in the model dtype); with
+    "nf4" they are uint8 codes 0..15 `w_*` [k_in, k_out] with float32 block maxima `s_*` [k_in / 64, k_out].
     """
     L = w.n_layers if n_layers is None else n_layers
     bf = w.dtype == "bf16"
@@ -76,6 +89,9 @@ def make_frozen_weights(w: Workload, seed: int, n_layers: Optional[int] = None) 
         if w.weight_quant == "int8":
             for name in ("qkv", "o", "up", "down"):
                 lw["w_" + name], lw["s_" + name] = _int8_weight(rng, lw["w_" + name].shape)
+        elif w.weight_quant == "nf4":
+            for name in ("qkv", "o", "up", "down"):
+                lw["w_" + name], lw["s_" + name] = _nf4_weight(rng, lw["w_" + name].shape)
         elif w.weight_quant != "none":
             raise ValueError(f"unknown weight_quant {w.weight_quant!r}")
         layers.append(lw)
