@@ -852,8 +852,8 @@ void launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
   gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP, WQ, PP><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
 }
 
-int tile_bn(int cfg) { return (cfg == 11 || cfg == 13) ? 192 : (cfg == 2 || (cfg >= 5 && cfg <= 8) || cfg == 14) ? 256 : 128; }   // 7, 8: 256 x 128 (4 is unused)
-int tile_bm(int cfg) { return cfg == 9 ? 64 : (cfg == 3 || cfg == 5 || cfg == 6 || cfg == 14) ? 256 : 128; }
+int tile_bn(int cfg) { return (cfg == 11 || cfg == 13) ? 192 : (cfg == 2 || (cfg >= 5 && cfg <= 8) || cfg == 14 || cfg == 15) ? 256 : 128; }   // 7, 8: 256 x 128 (4 is unused)
+int tile_bm(int cfg) { return cfg == 9 ? 64 : (cfg == 3 || cfg == 5 || cfg == 6 || cfg == 14 || cfg == 15) ? 256 : 128; }
 
 bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
   const int bn = tile_bn(cfg), bm = tile_bm(cfg);
@@ -866,7 +866,7 @@ bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
 
 int choose_cfg(const MfmaGemmArgs& a) {
   const bool forced_ok = a.w_scale == nullptr || a.tile_cfg == 1 || a.tile_cfg == 6 || a.tile_cfg == 11 || a.tile_cfg == 12;   // int8: fewer instances
-  if (forced_ok && a.tile_cfg >= 1 && a.tile_cfg <= 14 && a.tile_cfg != 4 && a.tile_cfg != 10 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
+  if (forced_ok && a.tile_cfg >= 1 && a.tile_cfg <= 15 && a.tile_cfg != 4 && a.tile_cfg != 10 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
   // enough 256 x 256 tiles to keep 256 CUs busy for several rounds -> biggest tile; else the largest tile that
   // still gives at least ~2 blocks per CU
   // The L2 -> CU path feeds about 64 B/clk per CU, which a 128 x 128 tile needs in full at MFMA peak; 256 x 256
@@ -883,7 +883,7 @@ int choose_cfg(const MfmaGemmArgs& a) {
   return 12;
 }
 
-int wave_cols(int cfg) { return (cfg == 11 || cfg == 13) ? 96 : (cfg == 2 || cfg == 5 || cfg == 6 || cfg == 14) ? 128 : 64; }   // BN / WGN of launch_gemm_mfma's table
+int wave_cols(int cfg) { return (cfg == 11 || cfg == 13) ? 96 : (cfg == 2 || cfg == 5 || cfg == 6 || cfg == 14 || cfg == 15) ? 128 : 64; }   // BN / WGN of launch_gemm_mfma's table
 
 // 64 token rows per block, the slots dealt to 4 waves: logsumexp over the per-wave-tile partials (online
 // maximum / rescaled sum per thread, merged through LDS), minus the target's logit
@@ -990,6 +990,7 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     case 12: launch_cfg<128, 128, 64, 2, 4, false>(st, a); break;    // 8 waves of 64 x 32: 16 waves per CU
     case 13: launch_cfg<192, 128, 64, 2, 4, false>(st, a); break;    // 8 waves of 96 x 32
     case 14: launch_cfg<256, 256, 32, 2, 4, false, 0, false, true>(st, a); break;   // 8 waves of 128 x 64, ping-pong schedule
+    case 15: launch_cfg<256, 256, 64, 2, 2, false>(st, a); break;    // 4 waves of 128 x 128: accumulators in AGPRs
     default: launch_cfg<128, 128, 64, 2, 2, false>(st, a); break;
   }
 }

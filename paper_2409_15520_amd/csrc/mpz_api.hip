@@ -1018,7 +1018,7 @@ mpz_status mpz_debug_dequant_nf4(const void* codes, const float* absmax, void* o
 
 mpz_status mpz_debug_set_tile_config(mpz_model* m, int32_t tile_cfg) {
   if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_set_tile_config: NULL model");
-  if (tile_cfg < 0 || tile_cfg > 14) return fail(m, MPZ_ERR_CONFIG, "tile configuration outside [0, 14]");
+  if (tile_cfg < 0 || tile_cfg > 15) return fail(m, MPZ_ERR_CONFIG, "tile configuration outside [0, 15]");
   m->force_tile_cfg = tile_cfg;
   return MPZ_OK;
 }
