@@ -19,12 +19,16 @@ def _bf16_tensor(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(torch.bfloat16).contiguous()
 
 
+# 32768 stacked tokens: the bottleneck kernel switches to its 64-token blocks (one and two 32-column MFMA tiles)
+BIG_T = {"c2_big_T": CASES["c2_2layers"].with_(q=4, E=32), "llama_mfma_big_T": CASES["llama_mfma"].with_(q=4, E=64)}
+
+
 @pytest.mark.parametrize("name,simple", [("c2_2layers", False), ("llama_mfma", False), ("c2_2layers", True),
-                                         ("c2_ragged_copies", False)])
+                                         ("c2_ragged_copies", False), ("c2_big_T", False), ("llama_mfma_big_T", False)])
 def test_qkv_projection_matches_the_mp_lora_layer_equation(name, simple):
     import torch
     import paper_2409_15520_amd as M
-    w = CASES[name].with_(eps=5e-2, n_layers=1)
+    w = (BIG_T[name] if name in BIG_T else CASES[name]).with_(eps=5e-2, n_layers=1)
     b = make_bundle(w, b_std=0.05)
     m = gpu_model(b)
     M.mpz_debug_set_kernel_path(m.handle, simple)
