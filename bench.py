@@ -225,6 +225,10 @@ def main():
                      "launches_per_step": gemm["launches"] / args.steps, "gemm_ms_per_step": gemm["ms"] / args.steps,
                      "algorithmic_flops_per_step": alg},
         "mfma_util_pct": 100.0 * achieved / peak if bf16 else None,
+        # device memory of the step: frozen parameters (shared by all copies), fp32 LoRA masters, and the one
+        # workspace (perturbed factors of all copies, activations of the stacked batch, staging)
+        "memory": {"frozen_bytes": m.frozen_bytes, "lora_master_bytes": int(m.masters.numel()) * 4,
+                   "workspace_bytes": m.workspace_bytes},
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:

@@ -427,6 +427,8 @@ class ZoModel:
         ws_bytes = mpz_workspace_bytes(self.cfg, self.q_max, self.E_max, self.S_max)
         if ws_bytes == 0:
             raise MpzError(2, "invalid configuration for mpz_workspace_bytes")
+        self.workspace_bytes = ws_bytes
+        self.frozen_bytes = sum(t.numel() * t.element_size() for t in self._keep)
         self.workspace = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=self.device)
         ws_ptr = (self.workspace.data_ptr() + 255) & ~255
         self.stream = torch.cuda.current_stream(self.device)

@@ -12,6 +12,9 @@ import pytest
 
 import workloads as W
 from gpu_helpers import make_bundle, gpu_model, oracle_steps
+from oracle import zo
+from oracle.model import decoder_layer
+from oracle.precision import Precision
 
 pytestmark = pytest.mark.gpu
 
@@ -63,4 +66,43 @@ def test_full_size_properties(name):
     assert np.all(same.view(np.uint32) == same.view(np.uint32)[0])
     m.close()
     del m, frozen
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name", ["c3_opt1p3b", "c4_llama1p1b", "c5_llama7b"])
+def test_full_width_block_on_sampled_sequences(name):
+    """One block of the workload at its full d, FFN, heads, q, E and S (host-drawn weights of one layer): the stacked
+    batch of all 2q copies goes through the GPU block; the oracle evaluates two (copy, sequence) pairs of it, each
+    with that copy's perturbed factors, on the same input rows.  Tolerances as in the small-shape stage tests."""
+    import torch
+    w = W.get_workload(name).with_(n_layers=1, eps=5e-2)
+    b = make_bundle(w, b_std=0.05)
+    m = gpu_model(b)
+    m.regen_noise(3456, 0)
+    n, rpc, d = 2 * w.q, w.E * w.S, w.d_model
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    h = torch.randn(n * rpc, d, generator=g, device="cuda", dtype=torch.float32)
+    h_in = h.clone()
+    m.run_layers(h, 0, 1, w.E, w.S)
+    prec = Precision("bf16")
+    lw = b["frozen"]["layers"][0]
+    for c, e in ((1, 0), (n - 2, w.E - 1)):
+        k, sign = c // 2, (+1 if c % 2 == 0 else -1)
+        z = zo.draw_z(b["layout"], 3456, 0, k, b["masters"].size, w.perturb_A)
+        lora = zo.split_factors(b["layout"], zo.perturb(b["masters"], z, sign, w.eps, prec))
+        r0 = c * rpc + e * w.S
+        x = h_in[r0:r0 + w.S].cpu().numpy().astype(np.float64)[None]
+        want = decoder_layer(w, lw, 0, x, lora, prec)[0]
+        got = h[r0:r0 + w.S].cpu().numpy().astype(np.float64)
+        rms = np.sqrt(np.mean(want ** 2))
+        diff = np.abs(got - want)
+        moved = np.sqrt(np.mean((want - x[0]) ** 2)) / rms
+        print(f"\n{name} copy {c} sequence {e}: rms {rms:.3e}, block moved the stream by {moved:.3f} rms, "
+              f"max|d|/rms {diff.max() / rms:.3e}, rms|d|/rms {np.sqrt(np.mean(diff ** 2)) / rms:.3e}", flush=True)
+        assert moved > 0.01                                   # the block does something at this scale
+        assert np.sqrt(np.mean(diff ** 2)) <= 3e-3 * rms
+        assert diff.max() <= 5e-2 * rms
+    m.close()
+    del m, h, h_in
     torch.cuda.empty_cache()
