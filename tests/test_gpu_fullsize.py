@@ -13,7 +13,7 @@ import pytest
 import workloads as W
 from gpu_helpers import make_bundle, gpu_model, oracle_steps
 from oracle import zo
-from oracle.model import decoder_layer
+from oracle.model import decoder_layer, head_loss
 from oracle.precision import Precision
 
 pytestmark = pytest.mark.gpu
@@ -103,6 +103,16 @@ def test_full_width_block_on_sampled_sequences(name):
         assert moved > 0.01                                   # the block does something at this scale
         assert np.sqrt(np.mean(diff ** 2)) <= 3e-3 * rms
         assert diff.max() <= 5e-2 * rms
+    # final norm, head and loss at the full batch (whole-vocabulary cross-entropy fused into the head GEMM for
+    # workloads 3 and 4): two copies against the oracle on the same residual rows
+    tok = torch.from_numpy(b["tokens"]).cuda()
+    lab = torch.from_numpy(b["labels"]).cuda()
+    got = m.head_loss(h, tok, lab).cpu().numpy().astype(np.float64)
+    for c in (1, n - 2):
+        hc = h[c * rpc:(c + 1) * rpc].cpu().numpy().astype(np.float64).reshape(w.E, w.S, d)
+        want = head_loss(w, b["frozen"], hc, b["tokens"], b["labels"], prec)
+        print(f"{name} head + loss copy {c}: {got[c]:.6f} vs {want:.6f}", flush=True)
+        assert abs(got[c] - want) <= 1e-4 * abs(want)
     m.close()
     del m, h, h_in
     torch.cuda.empty_cache()
