@@ -11,7 +11,7 @@ import pytest
 
 import workloads as W
 from gpu_helpers import make_bundle, gpu_model, gpu_steps, oracle_steps, rel_err
-from small_workloads import MINI_LLAMA, MINI_OPT
+from small_workloads import MICRO, MINI_LLAMA, MINI_OPT
 
 pytestmark = pytest.mark.gpu
 
@@ -43,6 +43,27 @@ def test_c1_ten_steps_updated_factors():
                          ids=["llama", "opt_fullvocab", "opt_nexttoken_gelu_scale2", "llama_lastpos_lorafa"])
 def test_small_fp32_models_all_architectures(wl):
     _check(wl, make_bundle(wl, b_std=0.02), 3, g_tol=1e-4, loss_tol=1e-6, theta_tol=1e-3)
+
+
+EDGE = {
+    # the smallest legal batch: one query, one sequence of two tokens (a single next-token position)
+    "q1_E1_S2": MICRO.with_(lora_rank=4, q=1, E=1, S=2, loss_mode="next_token_all_pos"),
+    # odd sizes everywhere: 5 queries, 3 sequences of 7 tokens, sequence length below max_seq
+    "q5_E3_S7": MINI_LLAMA.with_(q=5, E=3, S=7),
+    # the largest rank on the output projection alone; the smallest on the key projection alone
+    "rank64_o_only": MINI_LLAMA.with_(lora_rank=64, lora_targets=("o",)),
+    "rank4_k_only": MINI_OPT.with_(lora_rank=4, lora_targets=("k",)),
+    # untied head on the OPT-style model, sequences as long as the position table
+    "opt_untied_full_positions": MINI_OPT.with_(tie_embeddings=False, S=10, max_seq=10),
+    # many queries on a tiny batch (the q = 64 limit of the noise kernels' query loop is exercised by test_gpu_noise)
+    "q16_E1": MICRO.with_(lora_rank=4, q=16, E=1),
+}
+
+
+@pytest.mark.parametrize("name", list(EDGE))
+def test_edge_shapes_fp32(name):
+    wl = EDGE[name]
+    _check(wl, make_bundle(wl, b_std=0.02), 2, g_tol=1e-4, loss_tol=1e-6, theta_tol=1e-3)
 
 
 def test_eps_zero_gives_bit_identical_losses_equal_to_the_unperturbed_oracle():
