@@ -23,9 +23,10 @@ PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E
 GEMM_TRAFFIC = {"c2_opt125m": 105.4e6}   # bytes per launch, profiles/hbm_traffic_gemm_c2_opt125m.md
 
 
-def gemm_flops_per_step(w):
-    """Algorithmic FLOPs of the base-weight GEMMs (+ LM head where the loss needs the whole vocabulary)."""
-    T = 2 * w.q * w.E * w.S
+def gemm_flops_per_step(w, rows_per_copy=None):
+    """Algorithmic FLOPs of the base-weight GEMMs (+ LM head where the loss needs the whole vocabulary).
+    rows_per_copy: rows a copy occupies in the stacked pass (E*S unless the batch is packed)."""
+    T = 2 * w.q * (w.E * w.S if rows_per_copy is None else rows_per_copy)
     d, f = w.d_model, w.d_ffn
     per_tok = d * (d + 2 * w.d_kv) + d * d + d * f * (2 if w.act == "swiglu" else 1) + f * d
     fl = 2.0 * T * w.n_layers * per_tok
@@ -80,6 +81,9 @@ def main():
     ap.add_argument("--pad-fraction", type=float, default=None,
                     help="right-padded batch of unequal lengths (seeded; about this fraction of the E*S slots is padding): "
                          "the loss runs over real tokens only (mpz_forward_perturbed_varlen)")
+    ap.add_argument("--packed", action="store_true",
+                    help="with --pad-fraction: run the same batch without its padding (mpz_forward_perturbed_packed: the "
+                         "sequences back to back, every kernel over real tokens only)")
     ap.add_argument("--weight-quant", default=None, choices=["none", "int8", "nf4"],
                     help="weight-only quantisation of the block linears (int8 codes + per-channel scales)")
     ap.add_argument("--one-stream", action="store_true",
@@ -129,6 +133,15 @@ def main():
             sys.exit("bench.py: --pad-fraction needs --mode batched or stateful")
         lengths_host = W.make_lengths(w, seeds["tokens"], pad_fraction=args.pad_fraction)
         lengths = torch.from_numpy(lengths_host).cuda()
+    if args.packed and lengths is None:
+        sys.exit("bench.py: --packed needs --pad-fraction")
+    packed_batch = m.pack_batch(tok, lengths) if args.packed else None      # packed once, outside the timed steps
+
+    def forward():
+        if packed_batch is not None:
+            m.forward_packed(packed_batch, lab)
+        else:
+            m.forward_perturbed(tok, lab, lengths)
 
     group = {"batched": 2 * w.q, "inner": 2, "sequential": 1, "stateful": 2 * w.q}[args.mode]
     if args.mode == "stateful":
@@ -136,12 +149,12 @@ def main():
 
     def zo_step(step):
         if args.mode == "stateful":
-            m.forward_perturbed(tok, lab, lengths)
+            forward()
             m.zo_update_regen(step + 1)
             return
         m.regen_noise(seeds["noise"], step)
         if args.mode == "batched":
-            m.forward_perturbed(tok, lab, lengths)
+            forward()
         else:
             m.forward_sequential(tok, lab, group=group)
         m.zo_update()
@@ -171,7 +184,7 @@ def main():
     assert np.all(np.isfinite(losses)), losses
     gemm = prof["gemm"]
     achieved = gemm["flops"] / (gemm["ms"] * 1e-3) / 1e12 if gemm["ms"] > 0 else 0.0
-    alg = gemm_flops_per_step(w)
+    alg = gemm_flops_per_step(w, packed_batch[0].numel() if packed_batch is not None else None)
     assert abs(gemm["flops"] / args.steps - alg) <= 1e-6 * alg, (gemm["flops"] / args.steps, alg)
     bf16 = w.dtype == "bf16"
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP64_VECTOR_TFLOPS
@@ -218,7 +231,8 @@ def main():
                    "stacked_tokens": tokens_per_step, "layers": w.n_layers, "d_model": w.d_model,
                    "lora_rank": w.lora_rank, "eps": w.eps, "seeds": seeds, "weight_quant": w.weight_quant,
                    "schedule": "one stream" if args.one_stream else "two halves on two streams where the model is small",
-                   "real_tokens_per_copy": int(lengths_host.sum()) if lengths is not None else w.E * w.S},
+                   "real_tokens_per_copy": int(lengths_host.sum()) if lengths is not None else w.E * w.S,
+                   "batch_layout": "packed" if args.packed else ("right-padded" if lengths is not None else "full length")},
         "roofline": {"bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": GEMM_TRAFFIC.get(w.name),
                      "kernel": "base-weight GEMMs (all launches of a step)",

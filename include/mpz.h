@@ -200,6 +200,23 @@ mpz_status mpz_forward_copies(mpz_model* m, const int32_t* tokens, const int32_t
 mpz_status mpz_forward_perturbed_varlen(mpz_model* m, const int32_t* tokens, const int32_t* labels, const int32_t* lengths,
                                         int32_t E, int32_t S, float* losses_out);
 
+/* The same batch without the padding: the E sequences of unequal length lie back to back ("packed"), and every
+ * copy of the stacked pass holds rows = total_tokens rounded up to a multiple of 32 (filler rows after the last
+ * sequence; they belong to no sequence, see no attention and carry no loss).  Every row-wise kernel and every GEMM
+ * then runs over real tokens only; attention runs per sequence on its own rows; positions (learned or rotary) count
+ * from each sequence's first token.  The losses equal those of mpz_forward_perturbed_varlen on the padded form of
+ * the same batch (bit for bit with the fp32 kernels).
+ *   tokens       [dev] int32[rows]: the sequences' tokens back to back, then filler ids inside the vocabulary
+ *   labels       [dev] int32[E] class ids (last-position modes) or NULL (next-token mode)
+ *   cu_seqlens   [dev] int32[E + 1]: cu[0] = 0, sequence e holds rows cu[e] .. cu[e+1] - 1, cu[E] = total_tokens;
+ *                every sequence holds at least one token and at most max_len (not checked on the device)
+ *   max_len      the longest sequence, 2 <= max_len <= S_max (sizes the attention launch)
+ * Errors: NULL; STATE (before mpz_regen_noise); SHAPE (E < 1, max_len or total_tokens out of range, rows >
+ * E_max * S_max, in the last-position modes 2q E > 2 q_max E_max); DEVICE. */
+mpz_status mpz_forward_perturbed_packed(mpz_model* m, const int32_t* tokens, const int32_t* labels,
+                                        const int32_t* cu_seqlens, int32_t E, int32_t total_tokens, int32_t max_len,
+                                        float* losses_out);
+
 /* Algorithm 1, projected gradient and update: g_k = (l_{2k} - l_{2k+1}) / (2 eps) in fp64 from the fp32 losses, then
  * theta_l <- theta_l - lr (1/q) sum_k g_k z_k on the fp32 masters, z_k replayed from the (seed,
  * step, q, eps) of the last mpz_regen_noise.

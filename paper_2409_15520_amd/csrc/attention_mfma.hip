@@ -31,8 +31,9 @@ constexpr int QB = 128;   // queries per block
 // passes run from LDS; otherwise each pass streams the chunks.
 template <int DH, int KC>
 __global__ void __launch_bounds__(256, 2) attention_mfma_kernel(const uint16_t* __restrict__ qkv, int qkv_stride,
-                                                             uint16_t* __restrict__ out, int S, int H, int Hkv,
-                                                             float scale) {
+                                                             uint16_t* __restrict__ out, int S_grid, int H, int Hkv,
+                                                             float scale, const int32_t* __restrict__ cu, int E,
+                                                             int rows_per_copy) {
   constexpr int KS = DH + 8;        // K chunk row stride (elements)
   constexpr int VS = KC + 8;        // V^T chunk row stride
   constexpr int NJ = DH / 16;       // MFMA K-steps over the head dimension
@@ -40,10 +41,21 @@ __global__ void __launch_bounds__(256, 2) attention_mfma_kernel(const uint16_t* 
   __shared__ __align__(16) uint16_t sK[KC * KS];
   __shared__ __align__(16) uint16_t sVt[DH * VS];
 
-  const int qblocks = (S + QB - 1) / QB;
+  const int qblocks = (S_grid + QB - 1) / QB;
   const int qb = blockIdx.x % qblocks;
   const int head = (blockIdx.x / qblocks) % H;
   const int seq = blockIdx.x / (qblocks * H);
+  // padded batch: every sequence holds S_grid rows.  Packed batch: S_grid is the longest sequence; this one starts at
+  // its copy's row cu[e] and may be shorter (query blocks past its end leave at once: block-uniform, before any barrier)
+  int S = S_grid;
+  size_t row0 = (size_t)seq * S_grid;
+  if (cu != nullptr) {
+    const int e = seq % E;
+    const int start = cu[e];
+    S = cu[e + 1] - start;
+    row0 = (size_t)(seq / E) * rows_per_copy + start;
+    if (qb * QB >= S) return;
+  }
   const int kvh = head / (H / Hkv);
   const int d = H * DH, dkv = Hkv * DH;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -52,7 +64,6 @@ __global__ void __launch_bounds__(256, 2) attention_mfma_kernel(const uint16_t* 
   const int q0 = qb * QB + wave * 32;             // first query of this wave
   const int qi = q0 + lrow;                       // this lane's query
   const int qi_c = qi < S ? qi : S - 1;
-  const size_t row0 = (size_t)seq * S;
   const uint16_t* kbase = qkv + row0 * qkv_stride + d + kvh * DH;
   const uint16_t* vbase = qkv + row0 * qkv_stride + d + dkv + kvh * DH;
 
@@ -226,14 +237,14 @@ bool attention_mfma_supported(int dh, int qkv_stride, int d) {
 }
 
 void launch_attention_mfma(hipStream_t st, const void* qkv, int qkv_stride, void* out, int n_seq, int S, int H, int Hkv,
-                           int dh) {
+                           int dh, const int32_t* cu, int E, int rows_per_copy) {
   const int qblocks = (S + QB - 1) / QB;
   const unsigned blocks = (unsigned)((size_t)n_seq * H * qblocks);
   const float scale = (float)(1.0 / sqrt((double)dh));
   if (dh == 64)
-    attention_mfma_kernel<64, 128><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale);
+    attention_mfma_kernel<64, 128><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale, cu, E, rows_per_copy);
   else
-    attention_mfma_kernel<128, 64><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale);
+    attention_mfma_kernel<128, 64><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale, cu, E, rows_per_copy);
 }
 
 }  // namespace mpz

@@ -84,11 +84,13 @@ struct LinearArgs {
   void* out;                  // [M, N]
   // optional fused rotary embedding (MFMA path, model-dtype output): see MfmaGemmArgs
   const float* rope_cos; const float* rope_sin; int rope_cols, rope_dh, S;
+  const int32_t* rope_pos;    // packed batches: position of row m % S inside its sequence (null: m % S itself)
 };
 void launch_linear_simple(hipStream_t st, const LinearArgs& a);
 
+// row_pos (packed batches, else null): position of a copy's row inside its own sequence, [E * S]
 void launch_embed(hipStream_t st, int dtype, const int32_t* tokens, const void* emb, const void* pos_emb,
-                  float* h, int n_copies, int E, int S, int d);
+                  const int32_t* row_pos, float* h, int n_copies, int E, int S, int d);
 void launch_norm(hipStream_t st, int dtype, int kind, float eps, const float* h, int64_t h_row_stride,
                  const float* g, const float* b, void* out, int rows, int d);
 // t[T, r_tot] = OP(scale * x A_c) for up to 4 targets sharing the input x
@@ -101,10 +103,13 @@ struct LoraDownArgs {
 };
 void launch_lora_down_simple(hipStream_t st, const LoraDownArgs& a);
 // q/k: rotate (optionally) and convert staging -> model dtype; v: convert. staging is [T, n_cols] accumulate type
+// row_pos (packed batches, else null): position of row % S inside its own sequence
 void launch_rope_convert(hipStream_t st, int dtype, const void* staging, void* out, int T, int S, int n_cols,
-                         int d_head, int n_rot_heads, const float* cos_tab, const float* sin_tab);
+                         int d_head, int n_rot_heads, const float* cos_tab, const float* sin_tab, const int32_t* row_pos);
+// cu == null: n_seq sequences of S rows back to back.  Packed batches: S is the longest sequence, sequence s of the
+// n_seq = copies * E starts at row (s / E) * rows_per_copy + cu[s % E] and holds cu[s % E + 1] - cu[s % E] rows.
 void launch_attention_simple(hipStream_t st, int dtype, const void* qkv, int qkv_stride, void* out, int n_seq, int S,
-                             int H, int Hkv, int dh);
+                             int H, int Hkv, int dh, const int32_t* cu, int E, int rows_per_copy);
 void launch_swiglu(hipStream_t st, int dtype, const void* staging, void* out, int T, int f);
 // per-row CE from fp32 logits; target[r] < 0 => row skipped (ce = 0)
 void launch_ce_rows(hipStream_t st, int dtype, const float* logits, int64_t row_stride, int n_cols, const int32_t* target,
@@ -112,7 +117,11 @@ void launch_ce_rows(hipStream_t st, int dtype, const float* logits, int64_t row_
 void launch_last_pos_subset_logits(hipStream_t st, int dtype, const void* xf, const void* head, int d, int rows,
                                    int tok0, int tok1, float* logits2);
 void launch_make_targets(hipStream_t st, int mode, const int32_t* tokens, const int32_t* labels, const int32_t* lengths,
-                         int tok0, int tok1, int32_t* target, int n_copies, int E, int S);
+                         const int32_t* row_end, int tok0, int tok1, int32_t* target, int n_copies, int E, int S);
+// packed batch: per row of a copy, its position in its sequence and the row after the sequence's last (-1: filler)
+void launch_packed_index(hipStream_t st, const int32_t* cu, int E, int rows, int32_t* row_pos, int32_t* row_end);
+void launch_gather_last_rows_packed(hipStream_t st, const float* h, const int32_t* cu, int n_copies, int E,
+                                    int rows_per_copy, int d, float* out);
 void launch_gather_last_rows(hipStream_t st, const float* h, const int32_t* lengths, int n_copies, int E, int S, int d,
                              float* out);
 void launch_copy_mean(hipStream_t st, const float* ce, int rows_per_copy, int count_per_copy, const int32_t* lengths, int E,
@@ -138,8 +147,9 @@ struct MfmaGemmArgs {
   int out_f32; void* out; int ldo;
   int tile_cfg;                 // 0 = choose by shape; 1..12 force a tile configuration (measurement)
   // fused rotary embedding (bf16 output only): columns [0, rope_cols) are heads of width rope_dh rotated by the
-  // position m % S with tables [max_seq, rope_dh / 2]
+  // position m % S with tables [max_seq, rope_dh / 2]; packed batches: position rope_pos[m % S] (S = rows per copy)
   const float* rope_cos; const float* rope_sin; int rope_cols, rope_dh, S;
+  const int32_t* rope_pos;
   // fused cross-entropy (LM head): when ce_max is set nothing is stored to `out`; every wave tile writes, per token
   // row, the maximum and the sum of exp(logit - maximum) over its columns to slot [tile_n * waves_n + wave_n][M] of
   // ce_max / ce_sum, and the wave holding column ce_target[m] writes that logit to ce_tlogit[m]
@@ -167,8 +177,9 @@ void launch_pack_factors(hipStream_t st, const float* pert, int64_t P, int n_cop
 
 // ---- attention_mfma.hip ---------------------------------------------------------------------------
 bool attention_mfma_supported(int dh, int qkv_stride, int d);
+// cu / E / rows_per_copy: as for launch_attention_simple
 void launch_attention_mfma(hipStream_t st, const void* qkv, int qkv_stride, void* out, int n_seq, int S, int H, int Hkv,
-                           int dh);
+                           int dh, const int32_t* cu, int E, int rows_per_copy);
 
 
 // ---- rowwise.hip ----------------------------------------------------------------------------------

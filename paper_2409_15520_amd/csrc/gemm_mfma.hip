@@ -485,7 +485,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
       for (int j = 0; j < NJ; ++j) {
         int m = m0 + wm + j * 32 + lrow;
         m = m < a.M ? m : a.M - 1;
-        const int pos = m % a.S;
+        const int pos = a.rope_pos != nullptr ? a.rope_pos[m % a.S] : m % a.S;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
           if ((i / HP) % 2 != 0) continue;                  // upper halves are rotated together with their lower half

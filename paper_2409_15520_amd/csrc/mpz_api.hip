@@ -45,6 +45,8 @@ struct Buffers {
   void* packed = nullptr;     // [2 q_max][packed_per_copy] bf16 hi/lo operand layouts of the perturbed factors
   void* tp[3] = {nullptr, nullptr, nullptr};  // per target [T, rp] duplicated bottleneck activations
   void* wq = nullptr;         // 4-bit weights: the largest block linear, dequantised to bf16
+  int32_t* row_pos = nullptr; // packed batches: per row of a copy, its position inside its sequence
+  int32_t* row_end = nullptr; //   and the row after its sequence's last one (-1: filler row)
 };
 
 size_t elem_size(int dtype) { return dtype == MPZ_DTYPE_F32 ? 4 : 2; }
@@ -110,7 +112,10 @@ size_t carve(const mpz_config* c, int q_max, int E_max, int S_max, void* base, B
   std::vector<mpz_lora_tensor> lay; LoraLayerTable tab;
   build_layout(c, lay, tab);
   int64_t P = (int64_t)tab.per_layer * c->n_layers;
-  int64_t n = 2 * (int64_t)q_max, T = n * E_max * S_max;
+  // rows per copy rounded up to whole 32-row tiles: a packed batch (mpz_forward_perturbed_packed) of anything that
+  // fits as a padded batch then fits as well
+  const int64_t rpc_max = ((int64_t)E_max * S_max + 31) / 32 * 32;
+  int64_t n = 2 * (int64_t)q_max, T = n * rpc_max;
   int d = c->d_model, dh = d / c->n_heads, dkv = c->n_kv_heads * dh, f = c->d_ffn;
   size_t es = elem_size(c->dtype), as = acc_size(c->dtype);
   Buffers bb;
@@ -147,6 +152,8 @@ size_t carve(const mpz_config* c, int q_max, int E_max, int S_max, void* base, B
     bb.packed = cv.take<uint16_t>((size_t)(n * per_layer * c->n_layers));
     for (int i = 0; i < 3; ++i) bb.tp[i] = cv.take<uint16_t>((size_t)T * rp);
   }
+  bb.row_pos = cv.take<int32_t>((size_t)rpc_max);
+  bb.row_end = cv.take<int32_t>((size_t)rpc_max);
   if (c->weight_quant == MPZ_WEIGHT_QUANT_NF4) {
     const size_t n_qkv = (size_t)(d + 2 * dkv), n_up = (size_t)(c->act == MPZ_ACT_SWIGLU ? 2 * f : f);
     size_t big = n_qkv * d;
@@ -176,6 +183,9 @@ struct mpz_model {
   int cb = 0, nc = 0;                           // copies [cb, cb + nc) processed by the current pass
   int force_tile_cfg = 0;                       // test hook: GEMM block-tile configuration (0 = by shape)
   const int32_t* lengths = nullptr;             // [dev] per-sequence lengths of the pass in flight (right-padded batch), or null
+  // packed (padding-free) batch of the pass in flight: cu [dev, E + 1] sequence starts inside a copy, `total` real
+  // rows per copy, the longest sequence.  The pass then runs with one "sequence" of rows-per-copy rows per copy.
+  struct Packed { const int32_t* cu = nullptr; int E = 0, total = 0, max_len = 0; } pk;
   const char* deferred = nullptr;               // set by a launch helper that had to refuse; reported by check_device
   // second stream for the two-halves schedule of small models (see forward_two_halves); default priority
   hipStream_t stream2 = nullptr;
@@ -294,6 +304,7 @@ bool gemm(mpz_model* m, const LinearArgs& a) {
     g.n_seg = a.n_seg; g.rows_per_copy = a.rows_per_copy; g.act = -1; g.out_f32 = 0; g.out = a.out; g.ldo = a.N;
     for (int i = 0; i < a.n_seg; ++i) g.seg[i] = a.mseg[i];
     g.rope_cos = a.rope_cos; g.rope_sin = a.rope_sin; g.rope_cols = a.rope_cols; g.rope_dh = a.rope_dh; g.S = a.S;
+    g.rope_pos = a.rope_pos;
     g.tile_cfg = m->force_tile_cfg;
     if (!mfma_gemm_supported(g)) return false;
     ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)a.N * a.K, 2.0 * ((double)a.M * a.K + (double)a.N * a.K + (double)a.M * a.N));
@@ -354,8 +365,8 @@ void norm(mpz_model* m, const float* h, int64_t h_row_stride, const float* g, co
 void run_embed(mpz_model* m, const int32_t* tokens, int E, int S, float* h) {
   const mpz_config& c = m->cfg;
   ProfScope ps(m, MPZ_PROF_EMBED, 0.0, (double)m->nc * E * S * (double)c.d_model * (4.0 + esz(m)));
-  launch_embed(m->stream, c.dtype, tokens, m->w.emb, c.pos == MPZ_POS_ROPE ? nullptr : m->w.pos_emb, h, m->nc, E, S,
-               c.d_model);
+  launch_embed(m->stream, c.dtype, tokens, m->w.emb, c.pos == MPZ_POS_ROPE ? nullptr : m->w.pos_emb,
+               m->pk.cu ? m->buf.row_pos : nullptr, h, m->nc, E, S, c.d_model);
 }
 
 // q/k/v projections of the MP-LoRA layer for all stacked copies: x = b.x [T, d] -> out [T, d + 2 d_kv]
@@ -422,12 +433,14 @@ void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, bool rope, int
     if (rope) {
       qa.out_kind = 0; qa.out = b.qkv;
       qa.rope_cos = b.rope_cos; qa.rope_sin = b.rope_sin; qa.rope_cols = d + dkv; qa.rope_dh = dh; qa.S = S;
+      qa.rope_pos = m->pk.cu ? b.row_pos : nullptr;
       if (gemm(m, qa)) return;
       qa.rope_cos = qa.rope_sin = nullptr;
       qa.out_kind = 2; qa.out = b.stage;
       gemm(m, qa);
       ProfScope ps(m, MPZ_PROF_ROPE, 0.0, (double)T * nqkv * (acc_size(c.dtype) + esz(m)));
-      launch_rope_convert(st, c.dtype, b.stage, b.qkv, T, S, nqkv, dh, c.n_heads + c.n_kv_heads, b.rope_cos, b.rope_sin);
+      launch_rope_convert(st, c.dtype, b.stage, b.qkv, T, S, nqkv, dh, c.n_heads + c.n_kv_heads, b.rope_cos, b.rope_sin,
+                          m->pk.cu ? b.row_pos : nullptr);
       return;
     }
     qa.out_kind = out_kind; qa.out = out;
@@ -455,11 +468,13 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
 
     {
       // causal-useful work: Q K^T and P V over the S (S + 1) / 2 visible (query, key) pairs of every head
-      ProfScope ps(m, MPZ_PROF_ATTENTION, 2.0 * n * E * c.n_heads * (double)S * (S + 1) * dh, esz(m) * T * ((double)nqkv + d));
+      // (packed batches: booked as if every sequence had the longest one's length - an upper bound)
+      const int aE = m->pk.cu ? m->pk.E : E, aS = m->pk.cu ? m->pk.max_len : S;
+      ProfScope ps(m, MPZ_PROF_ATTENTION, 2.0 * n * aE * c.n_heads * (double)aS * (aS + 1) * dh, esz(m) * T * ((double)nqkv + d));
       if (m->use_mfma && attention_mfma_supported(dh, nqkv, d))
-        launch_attention_mfma(st, b.qkv, nqkv, b.attn, n * E, S, c.n_heads, c.n_kv_heads, dh);
+        launch_attention_mfma(st, b.qkv, nqkv, b.attn, n * aE, aS, c.n_heads, c.n_kv_heads, dh, m->pk.cu, aE, rpc);
       else
-        launch_attention_simple(st, c.dtype, b.qkv, nqkv, b.attn, n * E, S, c.n_heads, c.n_kv_heads, dh);
+        launch_attention_simple(st, c.dtype, b.qkv, nqkv, b.attn, n * aE, aS, c.n_heads, c.n_kv_heads, dh, m->pk.cu, aE, rpc);
     }
 
     // output projection (+ adapter) added to the residual stream
@@ -559,13 +574,21 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
   b.h = const_cast<float*>(h);
   const int n = m->nc, rpc = E * S, T = n * rpc;
   const int d = c.d_model;
+  const bool packed = m->pk.cu != nullptr;        // then E = 1 and S = rows per copy; the sequences are m->pk's
+  const int Es = packed ? m->pk.E : E;            // sequences per copy
+  const int nt_count = packed ? m->pk.total - m->pk.E : E * (S - 1);   // next-token positions per copy (full lengths)
   { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 0.0);
-    launch_make_targets(st, c.loss_mode, tokens, labels, m->lengths, c.label_token[0], c.label_token[1], b.target, n, E, S); }
+    if (c.loss_mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS)
+      launch_make_targets(st, c.loss_mode, tokens, labels, m->lengths, packed ? b.row_end : nullptr, c.label_token[0],
+                          c.label_token[1], b.target, n, E, S);
+    else
+      launch_make_targets(st, c.loss_mode, tokens, labels, nullptr, nullptr, c.label_token[0], c.label_token[1], b.target,
+                          n, Es, S); }
   if (c.loss_mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS) {
     norm(m, b.h, d, m->w.lnf_g, m->w.lnf_b, b.x, T);
     if (head_ce_fused(m, b, b.x, T, c.vocab, d, rpc, b.target, b.ce)) {
       ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 4.0 * T);
-      launch_copy_mean(st, b.ce, rpc, E * (S - 1), m->lengths, E, S, losses_out, n);
+      launch_copy_mean(st, b.ce, rpc, nt_count, m->lengths, E, S, losses_out, n);
       return;
     }
     for (int r0 = 0; r0 < T; r0 += b.chunk_rows) {
@@ -579,13 +602,14 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
         launch_ce_rows(st, c.dtype, b.logits, c.vocab, c.vocab, b.target + r0, b.ce + r0, rows); }
     }
     { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 4.0 * T);
-      launch_copy_mean(st, b.ce, rpc, E * (S - 1), m->lengths, E, S, losses_out, n); }
+      launch_copy_mean(st, b.ce, rpc, nt_count, m->lengths, E, S, losses_out, n); }
   } else {
-    const int rows_all = n * E;
-    if (m->lengths != nullptr) {                 // last real token of every sequence, gathered into the (idle) FFN buffer
+    const int rows_all = n * Es;
+    if (m->lengths != nullptr || packed) {       // last real token of every sequence, gathered into the (idle) FFN buffer
       float* last = (float*)b.u;
       { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 8.0 * rows_all * d);
-        launch_gather_last_rows(st, b.h, m->lengths, n, E, S, d, last); }
+        if (packed) launch_gather_last_rows_packed(st, b.h, m->pk.cu, n, Es, rpc, d, last);
+        else launch_gather_last_rows(st, b.h, m->lengths, n, E, S, d, last); }
       norm(m, last, d, m->w.lnf_g, m->w.lnf_b, b.x, rows_all);
     } else {
       norm(m, b.h + (size_t)(S - 1) * d, (int64_t)S * d, m->w.lnf_g, m->w.lnf_b, b.x, rows_all);
@@ -608,7 +632,7 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
       }
     }
     { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 4.0 * rows_all);
-      launch_copy_mean(st, b.ce, E, E, nullptr, E, S, losses_out, n); }
+      launch_copy_mean(st, b.ce, Es, Es, nullptr, Es, S, losses_out, n); }
   }
 }
 
@@ -766,7 +790,7 @@ namespace {
 bool use_two_halves(mpz_model* m, int E, int S) {
   const mpz_config& c = m->cfg;
   const int n = 2 * m->q;
-  if (!m->two_halves || m->prof_on || !m->use_mfma || n < 4 || n % 2 || m->lengths != nullptr) return false;
+  if (!m->two_halves || m->prof_on || !m->use_mfma || n < 4 || n % 2 || m->lengths != nullptr || m->pk.cu != nullptr) return false;
   if (c.loss_mode != MPZ_LOSS_LAST_POS_LABEL_SUBSET) return false;           // the whole-vocabulary scratch is shared
   if (c.weight_quant == MPZ_WEIGHT_QUANT_NF4) return false;                  // so is the dequantised-weight buffer
   if (((n / 2) * E * S) % 32) return false;
@@ -836,6 +860,34 @@ mpz_status mpz_forward_perturbed_varlen(mpz_model* m, const int32_t* tokens, con
   const mpz_status st = mpz_forward_perturbed(m, tokens, labels, E, S, losses_out);
   m->lengths = nullptr;
   return st;
+}
+
+mpz_status mpz_forward_perturbed_packed(mpz_model* m, const int32_t* tokens, const int32_t* labels,
+                                        const int32_t* cu_seqlens, int32_t E, int32_t total_tokens, int32_t max_len,
+                                        float* losses_out) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_forward_perturbed_packed: NULL model");
+  if (!tokens || !cu_seqlens || !losses_out) return fail(m, MPZ_ERR_NULL, "mpz_forward_perturbed_packed: NULL tokens, cu_seqlens or losses_out");
+  if (m->cfg.loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS && !labels) return fail(m, MPZ_ERR_NULL, "this loss mode needs labels");
+  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_forward_perturbed_packed before mpz_regen_noise");
+  const int64_t rows = ((int64_t)total_tokens + 31) / 32 * 32;      // rows per copy: the MFMA kernels want whole 32-row tiles per copy
+  if (E < 1 || max_len < 2 || max_len > m->S_max || total_tokens < (int64_t)2 * E || total_tokens > (int64_t)E * max_len)
+    return fail(m, MPZ_ERR_SHAPE, "mpz_forward_perturbed_packed: need E >= 1, 2 <= max_len <= S_max, 2 E <= total_tokens <= E max_len");
+  if (rows > ((int64_t)m->E_max * m->S_max + 31) / 32 * 32)
+    return fail(m, MPZ_ERR_SHAPE, "mpz_forward_perturbed_packed: more rows per copy than E_max * S_max (rounded up to 32)");
+  if ((size_t)2 * m->cfg.d_ffn * elem_size(m->cfg.dtype) < (size_t)4 * m->cfg.d_model && m->cfg.loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS)
+    return fail(m, MPZ_ERR_SHAPE, "mpz_forward_perturbed_packed: d_ffn too small to stage the last-token rows");
+  if ((int64_t)2 * m->q * E > (int64_t)2 * m->q_max * m->E_max && m->cfg.loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS)
+    return fail(m, MPZ_ERR_SHAPE, "mpz_forward_perturbed_packed: more sequences than E_max");
+  if (m->cfg.weight_quant == MPZ_WEIGHT_QUANT_INT8 && !m->use_mfma)
+    return fail(m, MPZ_ERR_SHAPE, "int8 weights: MFMA kernels only");
+  m->pk.cu = cu_seqlens; m->pk.E = E; m->pk.total = total_tokens; m->pk.max_len = max_len;
+  launch_packed_index(m->stream, cu_seqlens, E, (int)rows, m->buf.row_pos, m->buf.row_end);
+  m->cb = 0; m->nc = 2 * m->q;
+  run_embed(m, tokens, 1, (int)rows, m->buf.h);
+  run_layers(m, m->buf.h, 0, m->cfg.n_layers, 1, (int)rows);
+  run_head(m, m->buf.h, tokens, labels, 1, (int)rows, losses_out);
+  m->pk = mpz_model::Packed();
+  return check_device(m, "mpz_forward_perturbed_packed");
 }
 
 mpz_status mpz_forward_copies(mpz_model* m, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
@@ -970,9 +1022,9 @@ mpz_status mpz_debug_attention(mpz_model* m, const void* qkv, int32_t n_seq, int
   const mpz_config& c = m->cfg;
   const int d = c.d_model, dh = d / c.n_heads, nqkv = d + 2 * c.n_kv_heads * dh;
   if (m->use_mfma && attention_mfma_supported(dh, nqkv, d))
-    launch_attention_mfma(m->stream, qkv, nqkv, out, n_seq, S, c.n_heads, c.n_kv_heads, dh);
+    launch_attention_mfma(m->stream, qkv, nqkv, out, n_seq, S, c.n_heads, c.n_kv_heads, dh, nullptr, 1, S);
   else
-    launch_attention_simple(m->stream, c.dtype, qkv, nqkv, out, n_seq, S, c.n_heads, c.n_kv_heads, dh);
+    launch_attention_simple(m->stream, c.dtype, qkv, nqkv, out, n_seq, S, c.n_heads, c.n_kv_heads, dh, nullptr, 1, S);
   return check_device(m, "mpz_debug_attention");
 }
 

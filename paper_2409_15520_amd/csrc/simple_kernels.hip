@@ -72,12 +72,12 @@ template <typename T> __device__ __forceinline__ T block_max(T v, T* red) {
 // ---- embedding --------------------------------------------------------------------------------
 template <typename ST>
 __global__ void embed_kernel(const int32_t* __restrict__ tokens, const ST* __restrict__ emb, const ST* __restrict__ pos,
-                             float* __restrict__ h, int n_copies, int E, int S, int d) {
+                             const int32_t* __restrict__ row_pos, float* __restrict__ h, int n_copies, int E, int S, int d) {
   using Tr = Traits<ST>;
   int64_t row = blockIdx.x;                       // (c*E + e)*S + p
-  int p = (int)(row % S);
-  int e = (int)((row / S) % E);
-  int tok = tokens[e * S + p];
+  int rc = (int)(row % ((int64_t)E * S));         // row inside the copy = index into the token batch
+  int p = row_pos != nullptr ? row_pos[rc] : rc % S;   // packed batch: position inside the row's own sequence
+  int tok = tokens[rc];
   for (int i = threadIdx.x; i < d; i += blockDim.x) {
     typename Tr::AT v = Tr::load(emb, (int64_t)tok * d + i);
     if (pos != nullptr) v += Tr::load(pos, (int64_t)p * d + i);
@@ -199,7 +199,8 @@ __global__ void __launch_bounds__(256) linear_kernel(LinearArgs a) {
 template <typename ST>
 __global__ void __launch_bounds__(256) rope_convert_kernel(const typename Traits<ST>::AT* __restrict__ stg, ST* __restrict__ out,
                                                            int64_t total, int S, int n_cols, int d_head, int n_rot_heads,
-                                                           const float* __restrict__ cos_tab, const float* __restrict__ sin_tab) {
+                                                           const float* __restrict__ cos_tab, const float* __restrict__ sin_tab,
+                                                           const int32_t* __restrict__ row_pos) {
   using Tr = Traits<ST>;
   using AT = typename Tr::AT;
   int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -210,6 +211,7 @@ __global__ void __launch_bounds__(256) rope_convert_kernel(const typename Traits
   AT v = stg[idx];
   if (head < n_rot_heads) {
     int p = (int)(row % S);
+    if (row_pos != nullptr) p = row_pos[p];       // packed batch (S = rows per copy): position inside the sequence
     // binary32 staging (bf16 models): one rounded product and one fma, exactly as the GEMM's fused rotary epilogue
     if (i < half) {
       AT c = (AT)cos_tab[p * half + i], s = (AT)sin_tab[p * half + i];
@@ -227,7 +229,8 @@ __global__ void __launch_bounds__(256) rope_convert_kernel(const typename Traits
 // ---- causal attention, one wave per (sequence, head, query position) --------------------------------
 template <typename ST>
 __global__ void __launch_bounds__(64) attention_kernel(const ST* __restrict__ qkv, int qkv_stride, ST* __restrict__ out,
-                                                       int S, int H, int Hkv, int dh, float scale) {
+                                                       int S, int H, int Hkv, int dh, float scale,
+                                                       const int32_t* __restrict__ cu, int E, int rows_per_copy) {
   using Tr = Traits<ST>;
   using AT = typename Tr::AT;
   extern __shared__ unsigned char smem_raw[];
@@ -238,13 +241,19 @@ __global__ void __launch_bounds__(64) attention_kernel(const ST* __restrict__ qk
   int64_t seq = blockIdx.x / ((int64_t)S * H);
   int kvh = head / (H / Hkv);
   int d = H * dh, dkv = Hkv * dh;
-  int64_t row_i = seq * S + i;
+  int64_t row0 = seq * S;
+  if (cu != nullptr) {                    // packed batch: S is the longest sequence, this one may be shorter
+    const int e = (int)(seq % E);
+    row0 = (seq / E) * rows_per_copy + cu[e];
+    if (i >= cu[e + 1] - cu[e]) return;   // block-uniform
+  }
+  int64_t row_i = row0 + i;
   const ST* qp = qkv + row_i * qkv_stride + head * dh;
   for (int c = threadIdx.x; c < dh; c += 64) qv[c] = Tr::load(qp, c);
   __syncthreads();
   AT mx = -1e30;
   for (int j = threadIdx.x; j <= i; j += 64) {
-    const ST* kp = qkv + (seq * S + j) * qkv_stride + d + kvh * dh;
+    const ST* kp = qkv + (row0 + j) * qkv_stride + d + kvh * dh;
     AT dot = 0;
     for (int c = 0; c < dh; ++c) dot += qv[c] * Tr::load(kp, c);
     AT s = (AT)(float)dot * (AT)scale;
@@ -262,7 +271,7 @@ __global__ void __launch_bounds__(64) attention_kernel(const ST* __restrict__ qk
   __syncthreads();
   for (int c = threadIdx.x; c < dh; c += 64) {
     AT acc = 0;
-    for (int j = 0; j <= i; ++j) acc += sc[j] * Tr::load(qkv, (seq * S + j) * qkv_stride + d + dkv + kvh * dh + c);
+    for (int j = 0; j <= i; ++j) acc += sc[j] * Tr::load(qkv, (row0 + j) * qkv_stride + d + dkv + kvh * dh + c);
     Tr::store(out, row_i * d + head * dh + c, acc / sum);
   }
 }
@@ -328,11 +337,16 @@ __device__ __forceinline__ int seq_len(const int32_t* lengths, int e, int S) {
 }
 
 __global__ void make_targets_kernel(int mode, const int32_t* __restrict__ tokens, const int32_t* __restrict__ labels,
-                                    const int32_t* __restrict__ lengths, int tok0, int tok1,
-                                    int32_t* __restrict__ target, int n_copies, int E, int S) {
+                                    const int32_t* __restrict__ lengths, const int32_t* __restrict__ row_end, int tok0,
+                                    int tok1, int32_t* __restrict__ target, int n_copies, int E, int S) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS) {
     if (idx >= (int64_t)n_copies * E * S) return;
+    if (row_end != nullptr) {                     // packed batch (E = 1, S = rows per copy): the next row of the same sequence
+      int rc = (int)(idx % S);
+      target[idx] = (rc + 1 < row_end[rc]) ? tokens[rc + 1] : -1;
+      return;
+    }
     int p = (int)(idx % S), e = (int)((idx / S) % E);
     target[idx] = (p < seq_len(lengths, e, S) - 1) ? tokens[e * S + p + 1] : -1;
   } else {
@@ -349,6 +363,34 @@ __global__ void __launch_bounds__(256) gather_last_rows_kernel(const float* __re
                                                                float* __restrict__ out) {
   const int r = blockIdx.x, e = r % E;
   const float* src = h + ((int64_t)r * S + seq_len(lengths, e, S) - 1) * d;
+  for (int i = threadIdx.x; i < d; i += 256) out[(int64_t)r * d + i] = src[i];
+}
+
+// Packed batch: the E sequences of a copy lie back to back, sequence e in rows cu[e] .. cu[e+1] - 1 (cu[0] = 0); rows
+// from cu[E] up to the copy's padded row count are filler.  For every row of a copy: its position inside its
+// sequence, and the row after its sequence's last one (-1 for filler rows).
+__global__ void __launch_bounds__(256) packed_index_kernel(const int32_t* __restrict__ cu, int E, int rows,
+                                                           int32_t* __restrict__ row_pos, int32_t* __restrict__ row_end) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= rows) return;
+  if (r >= cu[E]) { row_pos[r] = 0; row_end[r] = -1; return; }
+  int lo = 0, hi = E;                             // the last e with cu[e] <= r (empty sequences are stepped over)
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cu[mid] <= r) lo = mid; else hi = mid;
+  }
+  row_pos[r] = r - cu[lo];
+  row_end[r] = cu[lo + 1];
+}
+
+// last row of every sequence of a packed batch, gathered into a dense [n_copies * E, d] block
+__global__ void __launch_bounds__(256) gather_last_rows_packed_kernel(const float* __restrict__ h,
+                                                                      const int32_t* __restrict__ cu, int E,
+                                                                      int rows_per_copy, int d, float* __restrict__ out) {
+  const int r = blockIdx.x, e = r % E, c = r / E;
+  int last = cu[e + 1] - 1;
+  last = last < 0 ? 0 : last;
+  const float* src = h + ((int64_t)c * rows_per_copy + last) * d;
   for (int i = threadIdx.x; i < d; i += 256) out[(int64_t)r * d + i] = src[i];
 }
 
@@ -419,10 +461,11 @@ inline unsigned nblk(int64_t n, int per) { return (unsigned)((n + per - 1) / per
     else { using ST = bf16_t; __VA_ARGS__; }                      \
   } while (0)
 
-void launch_embed(hipStream_t st, int dtype, const int32_t* tokens, const void* emb, const void* pos_emb, float* h,
+void launch_embed(hipStream_t st, int dtype, const int32_t* tokens, const void* emb, const void* pos_emb,
+                  const int32_t* row_pos, float* h,
                   int n_copies, int E, int S, int d) {
   unsigned rows = (unsigned)((int64_t)n_copies * E * S);
-  MPZ_DISPATCH(dtype, (embed_kernel<ST><<<rows, 128, 0, st>>>(tokens, (const ST*)emb, (const ST*)pos_emb, h, n_copies, E, S, d)));
+  MPZ_DISPATCH(dtype, (embed_kernel<ST><<<rows, 128, 0, st>>>(tokens, (const ST*)emb, (const ST*)pos_emb, row_pos, h, n_copies, E, S, d)));
 }
 
 void launch_norm(hipStream_t st, int dtype, int kind, float eps, const float* h, int64_t h_row_stride, const float* g,
@@ -441,17 +484,18 @@ void launch_linear_simple(hipStream_t st, const LinearArgs& a) {
 }
 
 void launch_rope_convert(hipStream_t st, int dtype, const void* staging, void* out, int T, int S, int n_cols, int d_head,
-                         int n_rot_heads, const float* cos_tab, const float* sin_tab) {
+                         int n_rot_heads, const float* cos_tab, const float* sin_tab, const int32_t* row_pos) {
   int64_t total = (int64_t)T * n_cols;
   MPZ_DISPATCH(dtype, (rope_convert_kernel<ST><<<nblk(total, 256), 256, 0, st>>>(
-                          (const typename Traits<ST>::AT*)staging, (ST*)out, total, S, n_cols, d_head, n_rot_heads, cos_tab, sin_tab)));
+                          (const typename Traits<ST>::AT*)staging, (ST*)out, total, S, n_cols, d_head, n_rot_heads, cos_tab, sin_tab, row_pos)));
 }
 
 void launch_attention_simple(hipStream_t st, int dtype, const void* qkv, int qkv_stride, void* out, int n_seq, int S, int H,
-                             int Hkv, int dh) {
+                             int Hkv, int dh, const int32_t* cu, int E, int rows_per_copy) {
   unsigned blocks = (unsigned)((int64_t)n_seq * H * S);
   MPZ_DISPATCH(dtype, (attention_kernel<ST><<<blocks, 64, (size_t)(S + dh) * sizeof(typename Traits<ST>::AT), st>>>(
-                          (const ST*)qkv, qkv_stride, (ST*)out, S, H, Hkv, dh, (float)(1.0 / sqrt((double)dh)))));
+                          (const ST*)qkv, qkv_stride, (ST*)out, S, H, Hkv, dh, (float)(1.0 / sqrt((double)dh)), cu, E,
+                          rows_per_copy)));
 }
 
 void launch_swiglu(hipStream_t st, int dtype, const void* staging, void* out, int T, int f) {
@@ -476,9 +520,18 @@ void launch_nf4_dequant(hipStream_t st, const void* codes, const float* absmax, 
 }
 
 void launch_make_targets(hipStream_t st, int mode, const int32_t* tokens, const int32_t* labels, const int32_t* lengths,
-                         int tok0, int tok1, int32_t* target, int n_copies, int E, int S) {
+                         const int32_t* row_end, int tok0, int tok1, int32_t* target, int n_copies, int E, int S) {
   int64_t n = (mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS) ? (int64_t)n_copies * E * S : (int64_t)n_copies * E;
-  make_targets_kernel<<<nblk(n, 256), 256, 0, st>>>(mode, tokens, labels, lengths, tok0, tok1, target, n_copies, E, S);
+  make_targets_kernel<<<nblk(n, 256), 256, 0, st>>>(mode, tokens, labels, lengths, row_end, tok0, tok1, target, n_copies, E, S);
+}
+
+void launch_packed_index(hipStream_t st, const int32_t* cu, int E, int rows, int32_t* row_pos, int32_t* row_end) {
+  packed_index_kernel<<<nblk(rows, 256), 256, 0, st>>>(cu, E, rows, row_pos, row_end);
+}
+
+void launch_gather_last_rows_packed(hipStream_t st, const float* h, const int32_t* cu, int n_copies, int E,
+                                    int rows_per_copy, int d, float* out) {
+  gather_last_rows_packed_kernel<<<n_copies * E, 256, 0, st>>>(h, cu, E, rows_per_copy, d, out);
 }
 
 void launch_gather_last_rows(hipStream_t st, const float* h, const int32_t* lengths, int n_copies, int E, int S, int d,

@@ -189,6 +189,16 @@ def mpz_forward_perturbed_varlen(handle, tokens_ptr: int, labels_ptr: Optional[i
            handle)
 
 
+def mpz_forward_perturbed_packed(handle, tokens_ptr: int, labels_ptr: Optional[int], cu_ptr: int, E: int,
+                                 total_tokens: int, max_len: int, losses_ptr: int):
+    lib = load_library()
+    lib.mpz_forward_perturbed_packed.restype = C.c_int
+    lib.mpz_forward_perturbed_packed.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                                 C.c_int32, C.c_void_p]
+    _check(lib.mpz_forward_perturbed_packed(handle, tokens_ptr, labels_ptr, cu_ptr, E, total_tokens, max_len, losses_ptr),
+           handle)
+
+
 def mpz_forward_copies(handle, tokens_ptr: int, labels_ptr: Optional[int], E: int, S: int, copy_begin: int,
                        n_copies: int, losses_ptr: int):
     _check(load_library().mpz_forward_copies(handle, tokens_ptr, labels_ptr, E, S, copy_begin, n_copies, losses_ptr),
@@ -453,6 +463,34 @@ class ZoModel:
         mpz_forward_perturbed(self.handle, tokens.data_ptr(), None if labels is None else labels.data_ptr(), E, S,
                               self.losses.data_ptr())
         return self.losses[:2 * self.q]
+
+    def pack_batch(self, tokens, lengths):
+        """The right-padded batch tokens [E, S] with lengths [E] (int32 device tensors) without its padding: the real
+        tokens back to back, filler up to a multiple of 32 rows, and the sequence starts.  One host read of the lengths
+        (the launches are sized by the total and the longest length).  Returns a tuple for forward_packed."""
+        torch = self.torch
+        E, S = tokens.shape
+        len_host = lengths.cpu()
+        total, max_len = int(len_host.sum()), int(len_host.max())
+        rows = (total + 31) // 32 * 32
+        cu = torch.zeros(E + 1, dtype=torch.int32, device=tokens.device)
+        cu[1:] = torch.cumsum(lengths, 0)
+        keep = torch.arange(S, device=tokens.device)[None, :] < lengths[:, None]
+        packed = torch.zeros(rows, dtype=torch.int32, device=tokens.device)
+        packed[:total] = tokens[keep]
+        return packed, cu, E, total, max_len
+
+    def forward_packed(self, batch, labels=None):
+        """batch: what pack_batch returned (kept alive by the caller until the stream has consumed it)."""
+        packed, cu, E, total, max_len = batch
+        mpz_forward_perturbed_packed(self.handle, packed.data_ptr(), None if labels is None else labels.data_ptr(),
+                                     cu.data_ptr(), E, total, max_len, self.losses.data_ptr())
+        return self.losses[:2 * self.q]
+
+    def forward_perturbed_packed(self, tokens, labels, lengths):
+        """pack_batch + forward_packed.  Returns losses[2q] (device)."""
+        self._packed_keep = self.pack_batch(tokens, lengths)
+        return self.forward_packed(self._packed_keep, labels)
 
     def forward_copies(self, tokens, labels, copy_begin: int, n_copies: int):
         E, S = tokens.shape
