@@ -169,6 +169,9 @@ struct MfmaLoraDownArgs {
   int64_t copy_stride;
   void* tp[3];                  // per target [T, rp] bf16
 };
+// measurement: `blocks` x 8 waves x iters x 8 MFMAs (32x32x16 bf16), fragments from operands [>= 12288 bf16], optionally
+// re-read from LDS every step; out [blocks * 512] fp32
+void launch_mfma_probe(hipStream_t st, const void* operands, int blocks, int iters, int with_lds, float* out);
 bool mfma_lora_down_supported(const MfmaLoraDownArgs& a);
 void launch_lora_down_mfma(hipStream_t st, const MfmaLoraDownArgs& a);
 void launch_pack_factors(hipStream_t st, const float* pert, int64_t P, int n_copies, const LoraLayerTable& tab,

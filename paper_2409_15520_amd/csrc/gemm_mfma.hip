@@ -590,6 +590,55 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   }
 }
 
+// ---- measurement: the matrix cores alone, and with the main loop's fragment reads ---------------------------
+// 8 waves per block (two per SIMD, the large tile's occupancy); a wave holds the 128 x 64 wave tile's 8 accumulator
+// tiles and issues 8 MFMAs per step.  Operand fragments come from `operands` (the caller chooses the bit patterns:
+// the rate the chip sustains depends on how many operand bits toggle).  with_lds = 0: fragments stay in registers;
+// 1: the 4 + 2 fragments of every step are read from LDS again, as in gemm_bf16_kernel's main loop.
+__global__ void __launch_bounds__(512, 1) mfma_probe_kernel(const uint16_t* __restrict__ operands, int iters, int with_lds,
+                                                            float* __restrict__ out) {
+  __shared__ __align__(16) uint16_t lds[(256 + 256) * 72];         // a 256 x 64 W tile and a 256 x 64 x tile, rows of 64 (+8)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lrow = lane & 31, lhalf = lane >> 5;
+  for (int i = tid; i < (256 + 256) * 72 / 8; i += 512)
+    *(u32x4*)(lds + i * 8) = *(const u32x4*)(operands + (size_t)(i % 1536) * 8);
+  __syncthreads();
+  const uint16_t* mw = lds + (wave / 4) * 128 * 72;                // this wave's 128 W rows and 64 x rows
+  const uint16_t* mx = lds + (256 + (wave % 4) * 64) * 72;
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  bf16x8 fw[4], fx[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) fw[i] = as_frag(*(const u32x4*)(mw + (i * 32 + lrow) * 72 + lhalf * 8));
+#pragma unroll
+  for (int j = 0; j < 2; ++j) fx[j] = as_frag(*(const u32x4*)(mx + (j * 32 + lrow) * 72 + lhalf * 8));
+  for (int it = 0; it < iters; ++it) {
+    if (with_lds) {
+      const int kk = (it & 3) * 16;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fw[i] = as_frag(*(const u32x4*)(mw + (i * 32 + lrow) * 72 + kk + lhalf * 8));
+#pragma unroll
+      for (int j = 0; j < 2; ++j) fx[j] = as_frag(*(const u32x4*)(mx + (j * 32 + lrow) * 72 + kk + lhalf * 8));
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fx[j], acc[i][j], 0, 0, 0);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sum += acc[i][j][e];
+  out[(size_t)blockIdx.x * 512 + tid] = sum;
+}
+
 // ---- LoRA bottleneck: tp[m] = [t | t | 0], t = bf16(scale * x (A_hi + A_lo)) for the block's copy ----------
 // HBM-bound (it reads x once).  One block = 32 tokens.  x streams through LDS in chunks of 256 K-elements with
 // fully coalesced 16-byte loads (a wave reads two whole 512-byte row pieces per instruction; reading MFMA
@@ -993,6 +1042,10 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     case 15: launch_cfg<256, 256, 64, 2, 2, false>(st, a); break;    // 4 waves of 128 x 128: accumulators in AGPRs
     default: launch_cfg<128, 128, 64, 2, 2, false>(st, a); break;
   }
+}
+
+void launch_mfma_probe(hipStream_t st, const void* operands, int blocks, int iters, int with_lds, float* out) {
+  mfma_probe_kernel<<<blocks, 512, 0, st>>>((const uint16_t*)operands, iters, with_lds, out);
 }
 
 bool mfma_lora_down_supported(const MfmaLoraDownArgs& a) {

@@ -1059,6 +1059,15 @@ mpz_status mpz_debug_set_two_halves(mpz_model* m, int32_t enable) {
   return MPZ_OK;
 }
 
+mpz_status mpz_debug_mfma_probe(const void* operands, int32_t blocks, int32_t iters, int32_t with_lds, float* out,
+                                void* hip_stream) {
+  if (!operands || !out) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_mfma_probe: NULL argument");
+  if (blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 24)) return fail(nullptr, MPZ_ERR_SHAPE, "mpz_debug_mfma_probe: blocks or iters out of range");
+  if (((uintptr_t)operands & 15u) != 0) return fail(nullptr, MPZ_ERR_CONFIG, "mpz_debug_mfma_probe: operands must be 16-byte aligned");
+  launch_mfma_probe((hipStream_t)hip_stream, operands, blocks, iters, with_lds != 0, out);
+  return hipGetLastError() == hipSuccess ? MPZ_OK : fail(nullptr, MPZ_ERR_DEVICE, "mpz_debug_mfma_probe: launch failed");
+}
+
 mpz_status mpz_debug_dequant_nf4(const void* codes, const float* absmax, void* out, int64_t n_elems, void* hip_stream) {
   if (!codes || !absmax || !out) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_dequant_nf4: NULL argument");
   if (n_elems < 64 || n_elems % 64) return fail(nullptr, MPZ_ERR_SHAPE, "mpz_debug_dequant_nf4: n_elems must be a positive multiple of 64");
