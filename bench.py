@@ -70,9 +70,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2_opt125m")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--mode", default="batched", choices=["batched", "inner", "sequential", "stateful"],
+    ap.add_argument("--mode", default="batched", choices=["batched", "inner", "outer", "sequential", "stateful"],
                     help="batched: all 2q copies in one pass (inner + outer loop parallel); inner: one query per pass, "
-                         "both signs together (inner-loop parallelisation only); sequential: one pass per copy "
+                         "both signs together (inner-loop parallelisation only); outer: all q queries per pass, the + "
+                         "and the - copies in two passes (outer-loop parallelisation only); sequential: one pass per copy "
                          "(MeZO-style); stateful: batched pass, then update + re-perturbation in one kernel from the "
                          "stored pairs (Algorithm 2) instead of regenerate + replay")
     ap.add_argument("--q", type=int, default=None, help="override the workload's number of queries")
@@ -145,7 +146,7 @@ def main():
         else:
             m.forward_perturbed(tok, lab, lengths)
 
-    group = {"batched": 2 * w.q, "inner": 2, "sequential": 1, "stateful": 2 * w.q}[args.mode]
+    group = {"batched": 2 * w.q, "inner": 2, "outer": w.q, "sequential": 1, "stateful": 2 * w.q}[args.mode]
     if args.mode == "stateful":
         m.regen_noise(seeds["noise"], 0)          # the only stand-alone noise pass of the run
 
@@ -157,6 +158,8 @@ def main():
         m.regen_noise(seeds["noise"], step)
         if args.mode == "batched":
             forward()
+        elif args.mode == "outer":
+            m.forward_outer_only(tok, lab)
         else:
             m.forward_sequential(tok, lab, group=group)
         m.zo_update()

@@ -188,6 +188,13 @@ mpz_status mpz_forward_perturbed(mpz_model* m, const int32_t* tokens, const int3
 mpz_status mpz_forward_copies(mpz_model* m, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
                               int32_t copy_begin, int32_t n_copies, float* losses_out);
 
+/* As mpz_forward_copies, for every copy_step-th copy: the pass evaluates copies copy_begin + copy_step * i, i <
+ * n_copies, and writes losses_out[copy_begin + copy_step * i].  With copy_step = 2, copy_begin = 0 / 1 and n_copies = q
+ * this is the outer loop alone (Section 3): all q queries in one pass, the + and the - perturbation in two passes.
+ * Same losses, bit for bit, as the batched pass.  Errors as mpz_forward_copies (SHAPE also for copy_step < 1). */
+mpz_status mpz_forward_copies_strided(mpz_model* m, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
+                                      int32_t copy_begin, int32_t n_copies, int32_t copy_step, float* losses_out);
+
 /* mpz_forward_perturbed on a right-padded batch of sequences of unequal length (Section 3 argues that spending the
  * batch on q queries of E = B / q sequences shortens the padding that batching brings): sequence e has lengths[e] real
  * tokens, 2 <= lengths[e] <= S (values outside are clamped), followed by padding whose token ids are arbitrary but

@@ -124,8 +124,9 @@ void launch_gather_last_rows_packed(hipStream_t st, const float* h, const int32_
                                     int rows_per_copy, int d, float* out);
 void launch_gather_last_rows(hipStream_t st, const float* h, const int32_t* lengths, int n_copies, int E, int S, int d,
                              float* out);
+// losses[i * loss_stride] = mean of copy i's per-row losses
 void launch_copy_mean(hipStream_t st, const float* ce, int rows_per_copy, int count_per_copy, const int32_t* lengths, int E,
-                      int S, float* losses, int n_copies);
+                      int S, float* losses, int n_copies, int loss_stride);
 void launch_fill_f32(hipStream_t st, float* p, float v, int64_t n);
 // 4-bit normal-float codes (two per byte, low nibble first) + block maxima [n_elems / 64] -> bf16 [n_elems];
 // n_elems % 64 == 0, rows of a multiple of 64 elements stored back to back

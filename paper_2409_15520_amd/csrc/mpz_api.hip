@@ -180,7 +180,8 @@ struct mpz_model {
   int64_t P = 0;
   bool have_noise = false;
   uint64_t seed = 0; uint32_t step = 0; int q = 0; float eps = 0.f;
-  int cb = 0, nc = 0;                           // copies [cb, cb + nc) processed by the current pass
+  int cb = 0, nc = 0;                           // copies cb + cstep i, i < nc, are processed by the current pass
+  int cstep = 1;                                //   (their activations occupy rows [cb, cb + nc) * E * S of the workspace)
   int force_tile_cfg = 0;                       // test hook: GEMM block-tile configuration (0 = by shape)
   const int32_t* lengths = nullptr;             // [dev] per-sequence lengths of the pass in flight (right-padded batch), or null
   // packed (padding-free) batch of the pass in flight: cu [dev, E + 1] sequence starts inside a copy, `total` real
@@ -383,7 +384,7 @@ void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, bool rope, int
     // q/k/v projections of the MP-LoRA layer: shared W, per-copy (A_c, B_c)
     LoraDownArgs da{};
     da.dtype = c.dtype; da.T = T; da.K = d; da.rank = r; da.rows_per_copy = rpc; da.x = b.x; da.scale = c.lora_scale;
-    da.copy_stride = m->P; da.t = b.t;
+    da.copy_stride = m->P * m->cstep; da.t = b.t;
     LinearArgs qa{};
     qa.dtype = c.dtype; qa.M = T; qa.N = nqkv; qa.K = d; qa.x = b.x; qa.w = lw.w_qkv; qa.w_scale = lw.s_qkv; qa.bias = lw.b_qkv;
     qa.rank = r; qa.rows_per_copy = rpc; qa.act = -1; qa.residual = nullptr;
@@ -394,7 +395,7 @@ void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, bool rope, int
       da.Ac[nt] = b.pert + find_tensor(m, l, t, 0)->offset;
       LoraSeg& sg = qa.seg[nt];
       sg.col_begin = col0[t]; sg.col_end = col1[t]; sg.t = b.t; sg.t_off = nt * r;
-      sg.Bc = b.pert + find_tensor(m, l, t, 1)->offset; sg.copy_stride = m->P;
+      sg.Bc = b.pert + find_tensor(m, l, t, 1)->offset; sg.copy_stride = m->P * m->cstep;
       ++nt;
     }
     for (int i = 0; i < nt; ++i) qa.seg[i].t_stride = nt * r;
@@ -404,7 +405,7 @@ void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, bool rope, int
     if (nt && m->use_mfma) {
       MfmaLoraDownArgs md{};
       md.T = T; md.K = d; md.rank = r; md.n_targets = nt; md.rows_per_copy = rpc; md.rp = m->rp; md.x = b.x;
-      md.scale = c.lora_scale; md.copy_stride = m->packed_per_copy;
+      md.scale = c.lora_scale; md.copy_stride = m->packed_per_copy * m->cstep;
       int i = 0;
       for (int t = 0; t < 3; ++t) {
         if (!(c.lora_targets & (1u << t))) continue;
@@ -412,7 +413,7 @@ void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, bool rope, int
         md.ap[i] = packed_l + m->packed_off[ia] * 2; md.tp[i] = b.tp[i];
         MfmaLoraSeg& ms = qa.mseg[i];
         ms.col_begin = col0[t]; ms.col_end = col1[t]; ms.tp = b.tp[i]; ms.bp = packed_l + m->packed_off[ib] * 2;
-        ms.rp = m->rp; ms.copy_stride = m->packed_per_copy;
+        ms.rp = m->rp; ms.copy_stride = m->packed_per_copy * m->cstep;
         ++i;
       }
       MfmaGemmArgs probe{};
@@ -481,7 +482,7 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     const char* packed_l = (const char*)b.packed + (size_t)l * m->packed_per_layer * 2;
     LoraDownArgs da{};
     da.dtype = c.dtype; da.T = T; da.K = d; da.rank = r; da.rows_per_copy = rpc; da.scale = c.lora_scale;
-    da.copy_stride = m->P; da.t = b.t;
+    da.copy_stride = m->P * m->cstep; da.t = b.t;
     LinearArgs oa{};
     oa.dtype = c.dtype; oa.M = T; oa.N = d; oa.K = d; oa.x = b.attn; oa.w = lw.w_o; oa.w_scale = lw.s_o; oa.bias = lw.b_o;
     oa.rank = r; oa.rows_per_copy = rpc; oa.act = -1; oa.residual = b.h; oa.out_kind = 1; oa.out = b.h;
@@ -492,11 +493,11 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
       if (m->use_mfma) {
         MfmaLoraDownArgs md{};
         md.T = T; md.K = d; md.rank = r; md.n_targets = 1; md.rows_per_copy = rpc; md.rp = m->rp; md.x = b.attn;
-        md.scale = c.lora_scale; md.copy_stride = m->packed_per_copy;
+        md.scale = c.lora_scale; md.copy_stride = m->packed_per_copy * m->cstep;
         md.ap[0] = packed_l + m->packed_off[tensor_slot(m, 3, 0)] * 2; md.tp[0] = b.tp[0];
         MfmaLoraSeg& ms = oa.mseg[0];
         ms.col_begin = 0; ms.col_end = d; ms.tp = b.tp[0]; ms.bp = packed_l + m->packed_off[tensor_slot(m, 3, 1)] * 2;
-        ms.rp = m->rp; ms.copy_stride = m->packed_per_copy;
+        ms.rp = m->rp; ms.copy_stride = m->packed_per_copy * m->cstep;
         MfmaGemmArgs probe{};
         probe.M = T; probe.N = d; probe.K = d; probe.n_seg = 1; probe.rows_per_copy = rpc; probe.seg[0] = ms;
         if (mfma_lora_down_supported(md) && mfma_gemm_supported(probe)) {
@@ -511,7 +512,7 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
       }
       oa.n_seg = 1;
       oa.seg[0].col_begin = 0; oa.seg[0].col_end = d; oa.seg[0].t = b.t; oa.seg[0].t_stride = r; oa.seg[0].t_off = 0;
-      oa.seg[0].Bc = b.pert + find_tensor(m, l, 3, 1)->offset; oa.seg[0].copy_stride = m->P;
+      oa.seg[0].Bc = b.pert + find_tensor(m, l, 3, 1)->offset; oa.seg[0].copy_stride = m->P * m->cstep;
     }
     const WeightRef wo = weight_operand(m, lw.w_o, lw.s_o, d, d);
     oa.w = wo.w; oa.w_scale = wo.scale;
@@ -588,7 +589,7 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
     norm(m, b.h, d, m->w.lnf_g, m->w.lnf_b, b.x, T);
     if (head_ce_fused(m, b, b.x, T, c.vocab, d, rpc, b.target, b.ce)) {
       ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 4.0 * T);
-      launch_copy_mean(st, b.ce, rpc, nt_count, m->lengths, E, S, losses_out, n);
+      launch_copy_mean(st, b.ce, rpc, nt_count, m->lengths, E, S, losses_out, n, m->cstep);
       return;
     }
     for (int r0 = 0; r0 < T; r0 += b.chunk_rows) {
@@ -602,7 +603,7 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
         launch_ce_rows(st, c.dtype, b.logits, c.vocab, c.vocab, b.target + r0, b.ce + r0, rows); }
     }
     { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 4.0 * T);
-      launch_copy_mean(st, b.ce, rpc, nt_count, m->lengths, E, S, losses_out, n); }
+      launch_copy_mean(st, b.ce, rpc, nt_count, m->lengths, E, S, losses_out, n, m->cstep); }
   } else {
     const int rows_all = n * Es;
     if (m->lengths != nullptr || packed) {       // last real token of every sequence, gathered into the (idle) FFN buffer
@@ -632,7 +633,7 @@ void run_head(mpz_model* m, const float* h, const int32_t* tokens, const int32_t
       }
     }
     { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 4.0 * rows_all);
-      launch_copy_mean(st, b.ce, Es, Es, nullptr, Es, S, losses_out, n); }
+      launch_copy_mean(st, b.ce, Es, Es, nullptr, Es, S, losses_out, n, m->cstep); }
   }
 }
 
@@ -905,6 +906,27 @@ mpz_status mpz_forward_copies(mpz_model* m, const int32_t* tokens, const int32_t
   run_head(m, h, tokens, labels, E, S, losses_out + copy_begin);
   m->cb = 0; m->nc = 2 * m->q;
   return check_device(m, "mpz_forward_copies");
+}
+
+mpz_status mpz_forward_copies_strided(mpz_model* m, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
+                                      int32_t copy_begin, int32_t n_copies, int32_t copy_step, float* losses_out) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_forward_copies_strided: NULL model");
+  if (!tokens || !losses_out) return fail(m, MPZ_ERR_NULL, "mpz_forward_copies_strided: NULL tokens or losses_out");
+  if (m->cfg.loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS && !labels) return fail(m, MPZ_ERR_NULL, "this loss mode needs labels");
+  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_forward_copies_strided before mpz_regen_noise");
+  if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
+  if (copy_begin < 0 || n_copies < 1 || copy_step < 1 || copy_begin + (int64_t)(n_copies - 1) * copy_step >= 2 * m->q ||
+      copy_begin + n_copies > 2 * m->q_max)
+    return fail(m, MPZ_ERR_SHAPE, "copies outside [0, 2q)");
+  if (m->cfg.weight_quant == MPZ_WEIGHT_QUANT_INT8 && ((E * S) % 32 || !m->use_mfma))
+    return fail(m, MPZ_ERR_SHAPE, "int8 weights: E*S must be a multiple of 32 (MFMA kernels only)");
+  m->cb = copy_begin; m->nc = n_copies; m->cstep = copy_step;
+  float* h = m->buf.h + (size_t)copy_begin * E * S * m->cfg.d_model;
+  run_embed(m, tokens, E, S, h);
+  run_layers(m, h, 0, m->cfg.n_layers, E, S);
+  run_head(m, h, tokens, labels, E, S, losses_out + copy_begin);
+  m->cb = 0; m->nc = 2 * m->q; m->cstep = 1;
+  return check_device(m, "mpz_forward_copies_strided");
 }
 
 mpz_status mpz_debug_embed(mpz_model* m, const int32_t* tokens, int32_t E, int32_t S, float* h_out) {

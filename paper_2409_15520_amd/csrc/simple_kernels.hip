@@ -398,7 +398,7 @@ __global__ void __launch_bounds__(256) gather_last_rows_packed_kernel(const floa
 // next-token positions of the padded batch, sum_e (length_e - 1).
 __global__ void __launch_bounds__(256) copy_mean_kernel(const float* __restrict__ ce, int rows_per_copy, int count,
                                                         const int32_t* __restrict__ lengths, int E, int S,
-                                                        float* __restrict__ losses) {
+                                                        float* __restrict__ losses, int loss_stride) {
   __shared__ double red[4];
   const float* p = ce + (int64_t)blockIdx.x * rows_per_copy;
   double s = 0;
@@ -409,7 +409,7 @@ __global__ void __launch_bounds__(256) copy_mean_kernel(const float* __restrict_
       count = 0;
       for (int e = 0; e < E; ++e) count += seq_len(lengths, e, S) - 1;
     }
-    losses[blockIdx.x] = (float)(s / (double)count);
+    losses[(int64_t)blockIdx.x * loss_stride] = (float)(s / (double)count);
   }
 }
 
@@ -540,8 +540,8 @@ void launch_gather_last_rows(hipStream_t st, const float* h, const int32_t* leng
 }
 
 void launch_copy_mean(hipStream_t st, const float* ce, int rows_per_copy, int count_per_copy, const int32_t* lengths, int E,
-                      int S, float* losses, int n_copies) {
-  copy_mean_kernel<<<n_copies, 256, 0, st>>>(ce, rows_per_copy, count_per_copy, lengths, E, S, losses);
+                      int S, float* losses, int n_copies, int loss_stride) {
+  copy_mean_kernel<<<n_copies, 256, 0, st>>>(ce, rows_per_copy, count_per_copy, lengths, E, S, losses, loss_stride);
 }
 
 void launch_fill_f32(hipStream_t st, float* p, float v, int64_t n) {

@@ -189,6 +189,16 @@ def mpz_forward_perturbed_varlen(handle, tokens_ptr: int, labels_ptr: Optional[i
            handle)
 
 
+def mpz_forward_copies_strided(handle, tokens_ptr: int, labels_ptr: Optional[int], E: int, S: int, copy_begin: int,
+                               n_copies: int, copy_step: int, losses_ptr: int):
+    lib = load_library()
+    lib.mpz_forward_copies_strided.restype = C.c_int
+    lib.mpz_forward_copies_strided.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                               C.c_int32, C.c_int32, C.c_void_p]
+    _check(lib.mpz_forward_copies_strided(handle, tokens_ptr, labels_ptr, E, S, copy_begin, n_copies, copy_step, losses_ptr),
+           handle)
+
+
 def mpz_forward_perturbed_packed(handle, tokens_ptr: int, labels_ptr: Optional[int], cu_ptr: int, E: int,
                                  total_tokens: int, max_len: int, losses_ptr: int):
     lib = load_library()
@@ -498,6 +508,15 @@ class ZoModel:
         """pack_batch + forward_packed.  Returns losses[2q] (device)."""
         self._packed_keep = self.pack_batch(tokens, lengths)
         return self.forward_packed(self._packed_keep, labels)
+
+    def forward_outer_only(self, tokens, labels=None):
+        """The outer loop alone: all q queries in one pass, first the + copies, then the - copies (two passes of q
+        copies).  Returns losses[2q] (device), the same numbers as forward_perturbed."""
+        E, S = tokens.shape
+        lab = None if labels is None else labels.data_ptr()
+        for sign in (0, 1):
+            mpz_forward_copies_strided(self.handle, tokens.data_ptr(), lab, E, S, sign, self.q, 2, self.losses.data_ptr())
+        return self.losses[:2 * self.q]
 
     def forward_copies(self, tokens, labels, copy_begin: int, n_copies: int):
         E, S = tokens.shape

@@ -28,6 +28,17 @@ def test_sequential_and_grouped_passes_are_bit_identical_to_the_batched_pass(w):
     assert np.array_equal(batched.view(np.uint32), seq.view(np.uint32))
     assert np.array_equal(batched.view(np.uint32), outer.view(np.uint32))
     assert len(set(batched.tolist())) == 2 * w.q              # copies really differ
+    # the outer loop alone: all + copies in one pass, all - copies in another (every second copy each)
+    m.losses.zero_()
+    signs = m.forward_outer_only(tok, lab).cpu().numpy().copy()
+    assert np.array_equal(batched.view(np.uint32), signs.view(np.uint32))
+    # and a strided pass touches nothing but its own copies' losses
+    if w.q >= 2:
+        import paper_2409_15520_amd as M
+        m.losses.fill_(-1.0)
+        M.mpz_forward_copies_strided(m.handle, tok.data_ptr(), lab.data_ptr(), w.E, w.S, 1, w.q, 2, m.losses.data_ptr())
+        part = m.losses[:2 * w.q].cpu().numpy()
+        assert np.array_equal(part[1::2].view(np.uint32), batched[1::2].view(np.uint32)) and np.all(part[0::2] == -1.0)
 
 
 def test_copy_range_errors():
@@ -45,6 +56,10 @@ def test_copy_range_errors():
     for cb, nc in ((-1, 1), (0, 0), (3, 2), (4, 1)):
         with pytest.raises(M.MpzError) as e:
             m.forward_copies(tok, lab, cb, nc)
+        assert e.value.status == 3
+    for cb, nc, step in ((0, 2, 0), (0, 3, 2), (1, 2, 3), (2, 2, 2)):          # 2q = 4 copies
+        with pytest.raises(M.MpzError) as e:
+            M.mpz_forward_copies_strided(m.handle, tok.data_ptr(), lab.data_ptr(), w.E, w.S, cb, nc, step, m.losses.data_ptr())
         assert e.value.status == 3
     torch.cuda.synchronize()
 
