@@ -118,6 +118,35 @@ def test_gemm_every_tile_configuration_and_ragged_edges(cfg, M_, N_, K_):
     assert np.abs(got - want).max() <= 2e-6 * np.sqrt(K_) * np.abs(want).max()
 
 
+# shapes whose tile configuration is chosen by the library (0): the 8-wave 128 x 128 tile, the 192 x 128 tile (N = 768
+# with a long K), the 256 x 256 tile (512 or more of them), each with ragged edges, plus one row / one tile extremes
+@pytest.mark.parametrize("M_,N_,K_,act,bf16_out", [
+    (1, 4, 64, -1, False), (33, 68, 128, 1, True), (1000, 772, 320, 0, False), (8192, 768, 1536, -1, True),
+    (8190, 764, 1600, 0, False), (8192, 4096, 128, 0, True), (8100, 4100, 192, 1, False), (4096, 8200, 64, -1, True)])
+def test_gemm_with_the_tile_chosen_by_shape(M_, N_, K_, act, bf16_out):
+    import torch
+    import paper_2409_15520_amd as M
+    from scipy.special import erf
+    rng = np.random.default_rng(M_ * 7 + N_)
+    x = BF.operand(rng.standard_normal((M_, K_)))
+    w = BF.operand(0.05 * rng.standard_normal((N_, K_)))
+    bias = rng.standard_normal(N_).astype(np.float32)
+    xd, wd = _bf16_tensor(x), _bf16_tensor(w)
+    bd = torch.from_numpy(bias).cuda()
+    out = torch.full((M_, N_), float("nan"), dtype=torch.bfloat16 if bf16_out else torch.float32, device="cuda")
+    M.mpz_debug_gemm_bf16(M_, N_, K_, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), act, out.data_ptr(), not bf16_out,
+                          torch.cuda.current_stream().cuda_stream, 0)
+    got = out.float().cpu().numpy().astype(np.float64)
+    y = x @ w.T + bias
+    want = y if act < 0 else (np.maximum(y, 0.0) if act == 0 else 0.5 * y * (1.0 + erf(y / np.sqrt(2.0))))
+    assert np.isfinite(got).all()
+    tol = 2e-6 * np.sqrt(K_) * np.abs(want).max()
+    if bf16_out:
+        assert np.abs(got - want).max() <= tol + 2.0 ** -8 * np.abs(want).max()      # one bf16 rounding of the result
+    else:
+        assert np.abs(got - want).max() <= tol
+
+
 @pytest.mark.parametrize("cfg", [1, 5, 6])
 def test_swiglu_dual_gemm(cfg):
     import torch
