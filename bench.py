@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--pad-fraction", type=float, default=None,
                     help="right-padded batch of unequal lengths (seeded; about this fraction of the E*S slots is padding): "
                          "the loss runs over real tokens only (mpz_forward_perturbed_varlen)")
+    ap.add_argument("--tile-config", type=int, default=0,
+                    help="measurement: force one GEMM block-tile configuration (mpz_debug_set_tile_config) instead of the "
+                         "choice by shape")
     ap.add_argument("--packed", action="store_true",
                     help="with --pad-fraction: run the same batch without its padding (mpz_forward_perturbed_packed: the "
                          "sequences back to back, every kernel over real tokens only)")
@@ -128,6 +131,8 @@ def main():
     m = M.ZoModel(w, frozen, masters, device="cuda:0")
     if args.one_stream:
         M.mpz_debug_set_two_halves(m.handle, False)
+    if args.tile_config:
+        M.mpz_debug_set_tile_config(m.handle, args.tile_config)
     tok = torch.from_numpy(tokens).cuda()
     lab = torch.from_numpy(labels).cuda()
     lengths = None
@@ -234,7 +239,7 @@ def main():
         "dtype": "bf16" if bf16 else "f64", "data": "synthetic",
         "config": {"workload": w.name, "mode": args.mode, "q": w.q, "copies": 2 * w.q, "E": w.E, "S": w.S,
                    "stacked_tokens": tokens_per_step, "layers": w.n_layers, "d_model": w.d_model,
-                   "lora_rank": w.lora_rank, "eps": w.eps, "seeds": seeds, "weight_quant": w.weight_quant,
+                   "lora_rank": w.lora_rank, "eps": w.eps, "seeds": seeds, "weight_quant": w.weight_quant, "tile_config": args.tile_config,
                    "schedule": "one stream" if args.one_stream else "two halves on two streams where the model is small",
                    "real_tokens_per_copy": int(lengths_host.sum()) if lengths is not None else w.E * w.S,
                    "batch_layout": "packed" if args.packed else ("right-padded" if lengths is not None else "full length")},
