@@ -572,19 +572,41 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
         const f32x4 v = {acc[0][i][j][g * 4], acc[0][i][j][g * 4 + 1], acc[0][i][j][g * 4 + 2], acc[0][i][j][g * 4 + 3]};
         *(f32x4*)(ep + lrow * EPS + i * 32 + g * 8 + lhalf * 4) = v;
       }
+    // RB pieces at a time: all their residual loads are issued before the first is used (a piece past M or N reads
+    // a clamped, in-bounds address and is not stored), and the kind of output is decided outside the loops
+    constexpr int R = 32 * LPR / 64, RB = R % 8 == 0 ? 8 : 4;
+    static_assert(R % RB == 0, "pieces must deal out evenly to the batches");
 #pragma unroll
-    for (int r = 0; r < 32 * LPR / 64; ++r) {
-      const int idx = r * 64 + lane, row = idx / LPR, c4 = idx % LPR;
-      const int m = m0 + wm + j * 32 + row, n = n0 + wn + c4 * 4;
-      f32x4 v = *(const f32x4*)(ep + row * EPS + c4 * 4);
-      if (m >= a.M || n >= a.N) continue;
-      const size_t o = (size_t)m * a.ldo + n;
-      if (a.residual != nullptr) v += *(const f32x4*)(a.residual + o);
+    for (int r0 = 0; r0 < R; r0 += RB) {
+      f32x4 v[RB];
+      size_t o[RB];
+      bool ok[RB];
+#pragma unroll
+      for (int r = 0; r < RB; ++r) {
+        const int idx = (r0 + r) * 64 + lane, row = idx / LPR, c4 = idx % LPR;
+        const int m = m0 + wm + j * 32 + row, n = n0 + wn + c4 * 4;
+        ok[r] = m < a.M && n < a.N;
+        o[r] = (size_t)(m < a.M ? m : a.M - 1) * a.ldo + (n < a.N ? n : 0);
+        v[r] = *(const f32x4*)(ep + row * EPS + c4 * 4);
+      }
+      if (a.residual != nullptr) {
+        f32x4 rs[RB];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) rs[r] = *(const f32x4*)(a.residual + o[r]);
+#pragma unroll
+        for (int r = 0; r < RB; ++r) v[r] += rs[r];
+      }
       if (a.out_f32) {
-        *(f32x4*)((float*)a.out + o) = v;
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+          if (ok[r]) *(f32x4*)((float*)a.out + o[r]) = v[r];
       } else {
-        u32x2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-        *(u32x2*)((uint16_t*)a.out + o) = pk;
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+          if (ok[r]) {
+            u32x2 pk = {pack_bf16x2(v[r][0], v[r][1]), pack_bf16x2(v[r][2], v[r][3])};
+            *(u32x2*)((uint16_t*)a.out + o[r]) = pk;
+          }
       }
     }
   }
