@@ -22,6 +22,9 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 __device__ __forceinline__ bf16x8 as_frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f)); }
+// the same arithmetic as a real call: where all of a block's accumulators are live around it, inlining erff 128 times
+// would cost registers that the common path (no GELU) never needs
+__device__ __noinline__ float gelu_erf_call(float v) { return gelu_erf(v); }
 
 // Instruction interleave of one main-loop phase.  Issued as a burst, the tile's global loads occupy the address
 // path for ~16 cycles each and its LDS stores for ~8, during which the issuing wave cannot feed the matrix core:
@@ -449,6 +452,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   // Epilogue, part 1 (accumulator layout: a lane holds, for token m = lrow, features nb + g*8 + lhalf*4 + (0..3),
   // g = 0..3, of every MFMA tile): bias, activation or gating, rotary embedding -- everything that needs no
   // other token's data -- written back into acc[0].
+  const bool relu = !DUAL && a.act == MPZ_ACT_RELU;
 #pragma unroll
   for (int i = 0; i < NI; ++i)
 #pragma unroll
@@ -468,14 +472,20 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
           if (DUAL) {
             const float u = acc[NW - 1][i][j][g * 4 + e] + bu[e];
             v = v / (1.0f + expf(-v)) * u;                 // SiLU(gate) * up
-          } else if (a.act == MPZ_ACT_RELU) {
-            v = v > 0.f ? v : 0.f;
-          } else if (a.act == MPZ_ACT_GELU_ERF) {
-            v = gelu_erf(v);
+          } else {
+            v = (relu && !(v > 0.f)) ? 0.f : v;            // a select, not a branch per element
           }
           acc[0][i][j][g * 4 + e] = v;
         }
     }
+  if (!DUAL && a.act == MPZ_ACT_GELU_ERF) {                // rare (no workload of the paper uses it): one cold loop
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[0][i][j][e] = gelu_erf_call(acc[0][i][j][e]);
+  }
   if constexpr (HP > 0) {
     static_assert(!DUAL && NI >= 2 * HP && NI % (2 * HP) == 0, "a wave tile must hold whole heads");
     if (n0 < a.rope_cols) {
