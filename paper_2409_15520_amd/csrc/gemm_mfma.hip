@@ -771,20 +771,20 @@ __global__ void __launch_bounds__(256, 2) lora_down_mfma_kernel(MfmaLoraDownArgs
     for (int e = 0; e < 16; ++e) acc[t][e] = ((acc[t][e] + part[0][t][e][lane]) + part[1][t][e][lane]) + part[2][t][e][lane];
   // lane holds token m0 + lrow, bottleneck columns j = t*32 + g*8 + lhalf*4 + e
   const int m = m0 + lrow;
+  // (ranks are multiples of 4: the 4 consecutive columns of a lane belong to one target and go out as one 8-byte store)
 #pragma unroll
   for (int t = 0; t < JT; ++t)
 #pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        int j = t * 32 + g * 8 + lhalf * 4 + e;
-        if (j >= R) continue;
-        int tgt = j / a.rank, jr = j % a.rank;
-        uint16_t v = f32_to_bf16(acc[t][g * 4 + e] * a.scale).bits;
-        uint16_t* row = (uint16_t*)a.tp[tgt] + (size_t)m * a.rp;
-        row[jr] = v;
-        row[a.rank + jr] = v;
-      }
+    for (int g = 0; g < 4; ++g) {
+      const int j = t * 32 + g * 8 + lhalf * 4;
+      if (j >= R) continue;
+      const int tgt = j / a.rank, jr = j % a.rank;
+      const u32x2 pk = {pack_bf16x2(acc[t][g * 4] * a.scale, acc[t][g * 4 + 1] * a.scale),
+                        pack_bf16x2(acc[t][g * 4 + 2] * a.scale, acc[t][g * 4 + 3] * a.scale)};
+      uint16_t* row = (uint16_t*)a.tp[tgt] + (size_t)m * a.rp;
+      *(u32x2*)(row + jr) = pk;
+      *(u32x2*)(row + a.rank + jr) = pk;
+    }
   // zero padding up to rp (done by lhalf 0 lanes; rp - 2 rank is 0 or 8)
   if (lhalf == 0)
     for (int tgt = 0; tgt < a.n_targets; ++tgt)
@@ -1082,7 +1082,7 @@ void launch_mfma_probe(hipStream_t st, const void* operands, int blocks, int ite
 
 bool mfma_lora_down_supported(const MfmaLoraDownArgs& a) {
   int R = a.n_targets * a.rank;
-  return a.K % 256 == 0 && a.T % 32 == 0 && a.rows_per_copy % 32 == 0 && R <= 64 && a.rp % 8 == 0;
+  return a.K % 256 == 0 && a.T % 32 == 0 && a.rows_per_copy % 32 == 0 && R <= 64 && a.rp % 8 == 0 && a.rank % 4 == 0;
 }
 
 void launch_lora_down_mfma(hipStream_t st, const MfmaLoraDownArgs& a) {
