@@ -21,7 +21,7 @@ PEAK_FP64_VECTOR_TFLOPS = 78.6  # fp32-storage models accumulate in fp64 on the 
 PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E
 # HBM bytes per GEMM launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
 # (the counters see what the XCD-private L2s fetch from the fabric: Infinity Cache or HBM)
-GEMM_TRAFFIC = {"c2_opt125m": 105.4e6, "c3_opt1p3b": 1861.7e6, "c4_llama1p1b": 3150.5e6,
+GEMM_TRAFFIC = {"c2_opt125m": 102.5e6, "c3_opt1p3b": 1861.7e6, "c4_llama1p1b": 3150.5e6,
                 "c5_llama7b": 1483.0e6}   # bytes per launch, profiles/hbm_traffic_gemm_<workload>.md
 
 
