@@ -431,20 +431,27 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
       if (n0 < sg.col_begin || n0 >= sg.col_end) continue;
       const uint16_t* tp = (const uint16_t*)sg.tp;
       for (int ks = 0; ks < sg.rp; ks += 16) {
+        // all fragments of the step first, then its MFMAs: the block waits for L2 once per step, not once per tile
+        bf16x8 lx[NJ], lw[NJ][NI];
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
           int mt = m0 + wm + j * 32;                       // first row of this MFMA tile
           mt = mt < a.M ? mt : a.M - 32;                   // tiles past the end compute discarded values in bounds
           const int copy = mt / a.rows_per_copy;
           const uint16_t* bp = (const uint16_t*)sg.bp + (size_t)copy * sg.copy_stride;
-          const bf16x8 fx = as_frag(*(const u32x4*)(tp + (size_t)(mt + lrow) * sg.rp + ks + lhalf * 8));
+          lx[j] = as_frag(*(const u32x4*)(tp + (size_t)(mt + lrow) * sg.rp + ks + lhalf * 8));
 #pragma unroll
           for (int i = 0; i < NI; ++i) {
             const int n = n0 + wn + i * 32 + lrow - sg.col_begin;
-            const bf16x8 fw = as_frag(*(const u32x4*)(bp + (size_t)n * sg.rp + ks + lhalf * 8));
-            acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fx, acc[0][i][j], 0, 0, 0);
+            lw[j][i] = as_frag(*(const u32x4*)(bp + (size_t)n * sg.rp + ks + lhalf * 8));
           }
         }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+          for (int i = 0; i < NI; ++i)
+            acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lw[j][i], lx[j], acc[0][i][j], 0, 0, 0);
       }
     }
   }
