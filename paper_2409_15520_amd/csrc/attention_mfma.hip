@@ -58,7 +58,8 @@ __global__ void __launch_bounds__(256, 2) attention_mfma_kernel(const uint16_t* 
   }
   const int kvh = head / (H / Hkv);
   const int d = H * DH, dkv = Hkv * DH;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // a scalar: the tile-visibility tests below are wave-uniform
   const int lrow = lane & 31, lhalf = lane >> 5;
 
   const int q0 = qb * QB + wave * 32;             // first query of this wave
