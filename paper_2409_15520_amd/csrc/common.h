@@ -27,6 +27,14 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
+// SiLU(g) * u in binary32 for the bf16 models: g * u / (1 + 2^(-g log2 e)) with the hardware exp2 and reciprocal
+// (1 ulp each; the result is rounded to bf16 right after).  One definition for the fused SwiGLU epilogue and the
+// stand-alone kernel, so that both give the same bits.
+__device__ __forceinline__ float silu_mul_f32(float g, float u) {
+  const float e = __builtin_amdgcn_exp2f(g * -1.4426950408889634f);
+  return g * __builtin_amdgcn_rcpf(1.0f + e) * u;
+}
+
 // Position of the LoRA factors inside one layer's slice of the flat master vector.
 struct LoraLayerTable {
   int32_t n_tensors;          // 2 per adapted target

@@ -478,7 +478,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
           float v = acc[0][i][j][g * 4 + e] + bg[e];
           if (DUAL) {
             const float u = acc[NW - 1][i][j][g * 4 + e] + bu[e];
-            v = v / (1.0f + expf(-v)) * u;                 // SiLU(gate) * up
+            v = silu_mul_f32(v, u);                        // SiLU(gate) * up
           } else {
             v = (relu && !(v > 0.f)) ? 0.f : v;            // a select, not a branch per element
           }

@@ -286,7 +286,8 @@ __global__ void __launch_bounds__(256) swiglu_kernel(const typename Traits<ST>::
   int64_t row = idx / f;
   int c = (int)(idx % f);
   AT g = stg[row * 2 * f + c], u = stg[row * 2 * f + f + c];
-  Tr::store(out, idx, g / ((AT)1 + Tr::exp_(-g)) * u);
+  if constexpr (sizeof(AT) == 4) Tr::store(out, idx, silu_mul_f32(g, u));      // bf16 models: as the fused epilogue
+  else Tr::store(out, idx, g / ((AT)1 + Tr::exp_(-g)) * u);
 }
 
 // ---- loss ----------------------------------------------------------------------------------------
