@@ -316,6 +316,11 @@ mpz_status mpz_debug_set_kernel_path(mpz_model* m, int32_t simple_only);
  * events, so that the halves' kernels overlap.  Losses are bit-identical either way. */
 mpz_status mpz_debug_set_two_halves(mpz_model* m, int32_t enable);
 
+/* Test hook: allow (default) or forbid the kernel that does a block's first pre-norm and the LoRA bottleneck of the
+ * q/k/v projections in one pass over the residual rows (bf16 models with d_model 768, 1024 or 2048); without it the
+ * two run as separate kernels.  Same bits either way. */
+mpz_status mpz_debug_set_fused_norm_lora(mpz_model* m, int32_t enable);
+
 /* Test hook: force one block-tile configuration (1..15; 0 = chosen by shape) for every MFMA GEMM of the model's
  * passes, so that small test shapes can exercise the configurations large workloads select.  Errors: NULL, CONFIG. */
 mpz_status mpz_debug_set_tile_config(mpz_model* m, int32_t tile_cfg);

@@ -195,6 +195,10 @@ void launch_attention_mfma(hipStream_t st, const void* qkv, int qkv_stride, void
 
 
 // ---- rowwise.hip ----------------------------------------------------------------------------------
+// norm_rows + lora_down_mfma in one kernel (h dense [T, d] fp32 -> out [T, d] bf16 and a.tp); a.x is ignored
+bool norm_lora_supported(int d, const MfmaLoraDownArgs& a);
+void launch_norm_lora(hipStream_t st, int kind, float eps, const float* h, const float* g, const float* b, void* out,
+                      const MfmaLoraDownArgs& a);
 bool norm_rows_supported(int d, int64_t h_row_stride);
 void launch_norm_rows(hipStream_t st, int kind, float eps, const float* h, int64_t h_row_stride, const float* g,
                       const float* b, void* out, int rows, int d);

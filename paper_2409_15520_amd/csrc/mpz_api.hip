@@ -182,6 +182,7 @@ struct mpz_model {
   uint64_t seed = 0; uint32_t step = 0; int q = 0; float eps = 0.f;
   int cb = 0, nc = 0;                           // copies cb + cstep i, i < nc, are processed by the current pass
   int cstep = 1;                                //   (their activations occupy rows [cb, cb + nc) * E * S of the workspace)
+  bool fuse_norm_lora = true;                   // test hook: pre-norm and LoRA bottleneck in one kernel where shapes allow
   int force_tile_cfg = 0;                       // test hook: GEMM block-tile configuration (0 = by shape)
   const int32_t* lengths = nullptr;             // [dev] per-sequence lengths of the pass in flight (right-padded batch), or null
   // packed (padding-free) batch of the pass in flight: cu [dev, E + 1] sequence starts inside a copy, `total` real
@@ -373,7 +374,10 @@ void run_embed(mpz_model* m, const int32_t* tokens, int E, int S, float* h) {
 // q/k/v projections of the MP-LoRA layer for all stacked copies: x = b.x [T, d] -> out [T, d + 2 d_kv]
 // rope: apply the rotary embedding to q and k and write the operand type to b.qkv (fused into the GEMM epilogue
 // where the shape allows, else through the accumulate-type staging buffer); otherwise write `out` as `out_kind` says.
-void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, bool rope, int out_kind, void* out) {
+// norm_h != null: b.x has not been computed yet; it is the pre-norm of the residual rows norm_h [T, d], done here -
+// in one kernel with the LoRA bottleneck where the shapes allow, else as the plain norm ahead of everything else.
+void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, bool rope, int out_kind, void* out,
+             const float* norm_h = nullptr) {
   const mpz_config& c = m->cfg;
   hipStream_t st = m->stream;
   const mpz_layer_weights& lw = m->layers[l];
@@ -420,11 +424,20 @@ void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, bool rope, int
       probe.M = T; probe.N = nqkv; probe.K = d; probe.n_seg = nt; probe.rows_per_copy = rpc;
       for (int k = 0; k < nt; ++k) probe.seg[k] = qa.mseg[k];
       if (mfma_lora_down_supported(md) && mfma_gemm_supported(probe)) {
-        { ProfScope ps(m, MPZ_PROF_LORA_DOWN, 4.0 * T * (double)d * nt * r, 2.0 * T * ((double)d + (double)nt * m->rp));
-          launch_lora_down_mfma(st, md); }
+        if (norm_h != nullptr && m->fuse_norm_lora && norm_lora_supported(d, md)) {
+          // booked under the norm: one read of the fp32 rows, one write of the operand rows and of t
+          ProfScope ps(m, MPZ_PROF_NORM, 4.0 * T * (double)d * nt * r, (double)T * d * (4.0 + esz(m)) + 2.0 * T * (double)nt * m->rp);
+          launch_norm_lora(st, c.norm, c.norm_eps, norm_h, lw.ln1_g, lw.ln1_b, b.x, md);
+          norm_h = nullptr;
+        } else {
+          if (norm_h != nullptr) { norm(m, norm_h, d, lw.ln1_g, lw.ln1_b, b.x, T); norm_h = nullptr; }
+          ProfScope ps(m, MPZ_PROF_LORA_DOWN, 4.0 * T * (double)d * nt * r, 2.0 * T * ((double)d + (double)nt * m->rp));
+          launch_lora_down_mfma(st, md);
+        }
         qa.mfma_lora = 1; lora_done = true;
       }
     }
+    if (norm_h != nullptr) { norm(m, norm_h, d, lw.ln1_g, lw.ln1_b, b.x, T); norm_h = nullptr; }
     if (nt && !lora_done) {
       ProfScope ps(m, MPZ_PROF_LORA_DOWN, 2.0 * T * (double)d * nt * r, esz(m) * T * ((double)d + (double)nt * r));
       launch_lora_down_simple(st, da);
@@ -463,9 +476,7 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
 
   for (int l = l0; l < l1; ++l) {
     const mpz_layer_weights& lw = m->layers[l];
-    norm(m, b.h, d, lw.ln1_g, lw.ln1_b, b.x, T);
-
-    run_qkv(m, b, l, E, S, rope, 0, b.qkv);
+    run_qkv(m, b, l, E, S, rope, 0, b.qkv, b.h);      // pre-norm, LoRA bottleneck, projection
 
     {
       // causal-useful work: Q K^T and P V over the S (S + 1) / 2 visible (query, key) pairs of every head
@@ -1097,6 +1108,12 @@ mpz_status mpz_debug_dequant_nf4(const void* codes, const float* absmax, void* o
     return fail(nullptr, MPZ_ERR_CONFIG, "mpz_debug_dequant_nf4: codes / absmax 4-byte, out 16-byte aligned");
   launch_nf4_dequant((hipStream_t)hip_stream, codes, absmax, out, n_elems);
   return hipGetLastError() == hipSuccess ? MPZ_OK : fail(nullptr, MPZ_ERR_DEVICE, "mpz_debug_dequant_nf4: launch failed");
+}
+
+mpz_status mpz_debug_set_fused_norm_lora(mpz_model* m, int32_t enable) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_set_fused_norm_lora: NULL model");
+  m->fuse_norm_lora = enable != 0;
+  return MPZ_OK;
 }
 
 mpz_status mpz_debug_set_tile_config(mpz_model* m, int32_t tile_cfg) {

@@ -299,6 +299,13 @@ def mpz_debug_noise_alu_probe(n_groups: int, q: int, sink_ptr: int, stream_ptr: 
     _check(lib.mpz_debug_noise_alu_probe(n_groups, q, sink_ptr, stream_ptr))
 
 
+def mpz_debug_set_fused_norm_lora(handle, enable: bool):
+    lib = load_library()
+    lib.mpz_debug_set_fused_norm_lora.restype = C.c_int
+    lib.mpz_debug_set_fused_norm_lora.argtypes = [C.c_void_p, C.c_int32]
+    _check(lib.mpz_debug_set_fused_norm_lora(handle, int(enable)), handle)
+
+
 def mpz_debug_set_two_halves(handle, enable: bool):
     lib = load_library()
     lib.mpz_debug_set_two_halves.restype = C.c_int

@@ -91,3 +91,22 @@ def test_two_halves_schedule_changes_no_bit(name):
             runs.append(torch.stack(out).cpu().numpy())
     assert np.array_equal(runs[0].view(np.uint32), runs[1].view(np.uint32))
     assert np.array_equal(runs[0].view(np.uint32), runs[2].view(np.uint32))
+
+
+@pytest.mark.parametrize("name", ["c2_2layers", "llama_mfma", "c2_ragged_copies"])
+def test_fused_norm_and_bottleneck_kernel_changes_no_bit(name):
+    """The first pre-norm of a block and the LoRA bottleneck of its q/k/v projections run as one kernel where the
+    shapes allow; with the hook off they are two kernels.  Same arithmetic, same order: identical losses."""
+    import torch
+    import paper_2409_15520_amd as M
+    w = CASES[name]
+    b = make_bundle(w, b_std=0.05)
+    m = gpu_model(b)
+    tok = torch.from_numpy(b["tokens"]).cuda()
+    lab = torch.from_numpy(b["labels"]).cuda()
+    out = []
+    for enable in (True, False):
+        M.mpz_debug_set_fused_norm_lora(m.handle, enable)
+        m.regen_noise(3456, 0)
+        out.append(m.forward_perturbed(tok, lab).cpu().numpy().copy())
+    assert np.array_equal(out[0].view(np.uint32), out[1].view(np.uint32)), out
