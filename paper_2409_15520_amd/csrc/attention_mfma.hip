@@ -29,8 +29,11 @@ constexpr int QB = 128;   // queries per block
 
 // KC = keys per LDS chunk.  When every key the block can see fits one chunk, K and V are loaded once and both
 // passes run from LDS; otherwise each pass streams the chunks.
-template <int DH, int KC>
-__global__ void __launch_bounds__(256, 2) attention_mfma_kernel(const uint16_t* __restrict__ qkv, int qkv_stride,
+// MINB = blocks per CU the register allocation is held to: 2 leaves 134 registers (3 waves per SIMD), 4 squeezes the
+// same code into 128 (4 waves per SIMD, no spills), which pays once a block streams several key chunks (S = 512:
+// 11.9 -> 11.1 ms per step on the 1.1B-shaped workload) and costs 3 % at S = 256, where a block lives for two.
+template <int DH, int KC, int MINB>
+__global__ void __launch_bounds__(256, MINB) attention_mfma_kernel(const uint16_t* __restrict__ qkv, int qkv_stride,
                                                              uint16_t* __restrict__ out, int S_grid, int H, int Hkv,
                                                              float scale, const int32_t* __restrict__ cu, int E,
                                                              int rows_per_copy) {
@@ -242,10 +245,12 @@ void launch_attention_mfma(hipStream_t st, const void* qkv, int qkv_stride, void
   const int qblocks = (S + QB - 1) / QB;
   const unsigned blocks = (unsigned)((size_t)n_seq * H * qblocks);
   const float scale = (float)(1.0 / sqrt((double)dh));
-  if (dh == 64)
-    attention_mfma_kernel<64, 128><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale, cu, E, rows_per_copy);
+  if (dh == 64 && S > 256)
+    attention_mfma_kernel<64, 128, 4><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale, cu, E, rows_per_copy);
+  else if (dh == 64)
+    attention_mfma_kernel<64, 128, 2><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale, cu, E, rows_per_copy);
   else
-    attention_mfma_kernel<128, 64><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale, cu, E, rows_per_copy);
+    attention_mfma_kernel<128, 64, 2><<<blocks, 256, 0, st>>>((const uint16_t*)qkv, qkv_stride, (uint16_t*)out, S, H, Hkv, scale, cu, E, rows_per_copy);
 }
 
 }  // namespace mpz
