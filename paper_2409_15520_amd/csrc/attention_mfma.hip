@@ -103,7 +103,9 @@ __global__ void __launch_bounds__(256, MINB) attention_mfma_kernel(const uint16_
   }
   // V^T into LDS: a thread takes two consecutive keys and 8 head-dim elements and writes 8 words
   // {V[key][dv], V[key+1][dv]}; consecutive lanes hold consecutive key pairs, so the 32-bit writes of a wave fall
-  // into consecutive banks (a per-element 16-bit scatter would serialise on a handful of banks).
+  // into consecutive banks (a per-element 16-bit scatter would serialise on a handful of banks).  Inside every
+  // group of 16 keys the pairs are stored in the order 0 1 4 5 2 3 6 7: the 8 keys of one MFMA K-step that a lane
+  // half needs (k + 4 lhalf + (0..3) and k + 8 + 4 lhalf + (0..3)) are then 16 contiguous bytes.
 #define MPZ_FETCH_V(c)                                                             \
   _Pragma("unroll") for (int it = 0; it < VL; ++it) {                              \
     const int i = tid + 256 * it, kp = i % (KC / 2), ch = i / (KC / 2);            \
@@ -115,7 +117,8 @@ __global__ void __launch_bounds__(256, MINB) attention_mfma_kernel(const uint16_
 #define MPZ_PUT_V()                                                                \
   _Pragma("unroll") for (int it = 0; it < VL; ++it) {                              \
     const int i = tid + 256 * it, kp = i % (KC / 2), ch = i / (KC / 2);            \
-    uint32_t* dst = (uint32_t*)sVt + kp;                                           \
+    const int pp = kp & 7;                                                         \
+    uint32_t* dst = (uint32_t*)sVt + (kp & ~7) + ((pp & 1) | ((pp & 2) << 1) | ((pp & 4) >> 1)); \
     _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                \
       dst[(ch * 8 + 2 * e) * (VS / 2)] = (rv0[it][e] & 0xFFFFu) | (rv1[it][e] << 16);        \
       dst[(ch * 8 + 2 * e + 1) * (VS / 2)] = (rv0[it][e] >> 16) | (rv1[it][e] & 0xFFFF0000u); \
@@ -201,12 +204,10 @@ __global__ void __launch_bounds__(256, MINB) attention_mfma_kernel(const uint16_
       for (int hstep = 0; hstep < 2; ++hstep) {
         u32x4 pfrag = {pw[hstep * 4], pw[hstep * 4 + 1], pw[hstep * 4 + 2], pw[hstep * 4 + 3]};
         bf16x8 fp = __builtin_bit_cast(bf16x8, pfrag);
-        const int kl = t * 32 + hstep * 16 + lhalf * 4;   // key offset inside the chunk
+        const int kl = t * 32 + hstep * 16 + lhalf * 8;   // this half's 8 keys of the step, as stored
 #pragma unroll
         for (int vt = 0; vt < NT; ++vt) {
-          const uint16_t* vp = sVt + (vt * 32 + lrow) * VS + kl;
-          u32x2 a = *(const u32x2*)vp, b = *(const u32x2*)(vp + 8);
-          u32x4 vfrag = {a[0], a[1], b[0], b[1]};
+          const u32x4 vfrag = *(const u32x4*)(sVt + (vt * 32 + lrow) * VS + kl);
           oacc[vt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vfrag), fp, oacc[vt], 0, 0, 0);
         }
       }
