@@ -44,10 +44,21 @@ __global__ void __launch_bounds__(256, MINB) attention_mfma_kernel(const uint16_
   __shared__ __align__(16) uint16_t sK[KC * KS];
   __shared__ __align__(16) uint16_t sVt[DH * VS];
 
+  // Hardware deals consecutive workgroups round-robin to the 8 XCDs; give each XCD a contiguous range of the
+  // (sequence, head, query block) order instead, so that the blocks that read one sequence's K and V (all query
+  // blocks, and under grouped-query attention all heads of the group) share an L2.
+  // (1.3B-shaped workload, S = 256: 5.4 -> 4.5 ms per step; with a single query block per head and no key sharing
+  // there is nothing to share and the plain order is kept)
+  int pid = blockIdx.x;
   const int qblocks = (S_grid + QB - 1) / QB;
-  const int qb = blockIdx.x % qblocks;
-  const int head = (blockIdx.x / qblocks) % H;
-  const int seq = blockIdx.x / (qblocks * H);
+  if (qblocks * (H / Hkv) > 1) {
+    const int nblk = gridDim.x, per = nblk / 8, rem = nblk % 8;
+    const int xcd = pid % 8, idx = pid / 8;
+    pid = xcd * per + (xcd < rem ? xcd : rem) + idx;
+  }
+  const int qb = pid % qblocks;
+  const int head = (pid / qblocks) % H;
+  const int seq = pid / (qblocks * H);
   // padded batch: every sequence holds S_grid rows.  Packed batch: S_grid is the longest sequence; this one starts at
   // its copy's row cu[e] and may be shorter (query blocks past its end leave at once: block-uniform, before any barrier)
   int S = S_grid;
