@@ -174,7 +174,7 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a);
 struct MfmaLoraDownArgs {
   int T, K, rank, n_targets, rows_per_copy, rp;
   const void* x; float scale;
-  const void* ap[3];            // packed A copies per target: copy c at ap[i] + c*copy_stride, [2][r][K] bf16 (hi rows, lo rows)
+  const void* ap[3];            // packed A copies per target: copy c at ap[i] + c*copy_stride, [2][K / 8][r][8] bf16 (hi part, lo part; element (j, k) of a part at ((k / 8) r + j) 8 + k % 8)
   int64_t copy_stride;
   void* tp[3];                  // per target [T, rp] bf16
 };

@@ -694,7 +694,8 @@ __global__ void __launch_bounds__(256, 2) lora_down_mfma_kernel(MfmaLoraDownArgs
   const int copy = m0 / a.rows_per_copy;
   const int R = a.n_targets * a.rank;
   const uint16_t* X = (const uint16_t*)a.x + (size_t)m0 * a.K;
-  // packed A: per copy [n_targets][2][rank][K]  (hi rows then lo rows), K contiguous
+  // packed A: per copy and target [2][K / 8][rank][8] (hi part then lo part): the 16-byte pieces that the lanes of
+  // a wave fetch for one MFMA operand (rank rows x 2 neighbouring chunks of 8 k) are contiguous
   const uint16_t* Ah[JT];
   const uint16_t* Al[JT];
   bool valid[JT];
@@ -705,8 +706,8 @@ __global__ void __launch_bounds__(256, 2) lora_down_mfma_kernel(MfmaLoraDownArgs
     int jj = valid[t] ? j : 0;
     int tgt = jj / a.rank, jr = jj % a.rank;
     const uint16_t* base = (const uint16_t*)a.ap[tgt] + (size_t)copy * a.copy_stride;
-    Ah[t] = base + (size_t)jr * a.K + wave * 64 + lhalf * 8;
-    Al[t] = base + (size_t)(a.rank + jr) * a.K + wave * 64 + lhalf * 8;
+    Ah[t] = base + ((size_t)(wave * 8 + lhalf) * a.rank + jr) * 8;
+    Al[t] = Ah[t] + (size_t)a.K * a.rank;
   }
   f32x16 acc[JT];
 #pragma unroll
@@ -743,8 +744,8 @@ __global__ void __launch_bounds__(256, 2) lora_down_mfma_kernel(MfmaLoraDownArgs
       for (int s4 = 0; s4 < 4; ++s4)
 #pragma unroll
         for (int t = 0; t < JT; ++t) {
-          fh[s4][t] = valid[t] ? *(const u32x4*)(Ah[t] + kg + s4 * 16) : zero;
-          fl[s4][t] = valid[t] ? *(const u32x4*)(Al[t] + kg + s4 * 16) : zero;
+          fh[s4][t] = valid[t] ? *(const u32x4*)(Ah[t] + (size_t)(kg + s4 * 16) * a.rank) : zero;
+          fl[s4][t] = valid[t] ? *(const u32x4*)(Al[t] + (size_t)(kg + s4 * 16) * a.rank) : zero;
         }
 #pragma unroll
       for (int i = 0; i < 4; ++i) *(u32x4*)(buf + grow[i] * XS + gcol[i]) = st[p][i];
@@ -799,7 +800,7 @@ __global__ void __launch_bounds__(256, 2) lora_down_mfma_kernel(MfmaLoraDownArgs
 }
 
 // ---- pack the perturbed fp32 factors into the bf16 hi/lo operand layouts ---------------------------------
-// A [K, r] (master layout) -> ap [2][r][K];  B [r, k_out] -> bp [k_out][rp] = [hi(r) | lo(r) | 0]
+// A [K, r] (master layout) -> ap [2][K / 8][r][8] (hi part, lo part);  B [r, k_out] -> bp [k_out][rp] = [hi(r) | lo(r) | 0]
 __global__ void __launch_bounds__(256) pack_factors_kernel(const float* __restrict__ pert, int64_t P, int n_copies,
                                                            LoraLayerTable tab, int n_layers, int rank, int rp,
                                                            uint16_t* __restrict__ packed, int64_t packed_per_copy) {
@@ -824,11 +825,12 @@ __global__ void __launch_bounds__(256) pack_factors_kernel(const float* __restri
   for (int t = i; t < tab.n_tensors; ++t)
     per_layer_packed += (tab.local_id[t] & 1) ? (int64_t)tab.cols[t] * rp : (int64_t)2 * tab.rows[t] * tab.cols[t];
   uint16_t* dst = packed + (int64_t)copy * packed_per_copy + (int64_t)layer * per_layer_packed + poff;
-  if ((tab.local_id[i] & 1) == 0) {              // A [K, r]: element (k, j) -> hi at [j][k], lo at [r + j][k]
+  if ((tab.local_id[i] & 1) == 0) {              // A [K, r]: element (k, j) -> [k / 8][j][k % 8] of the hi and of the lo part
     int K = tab.rows[i];
     int k = local / rank, j = local % rank;
-    dst[(int64_t)j * K + k] = hi;
-    dst[(int64_t)(rank + j) * K + k] = lo;
+    const int64_t o = ((int64_t)(k / 8) * rank + j) * 8 + k % 8;
+    dst[o] = hi;
+    dst[(int64_t)K * rank + o] = lo;
   } else {                                        // B [r, k_out]: element (j, n) -> [n][j] hi, [n][r + j] lo
     int kout = tab.cols[i];
     int j = local / kout, n = local % kout;
@@ -841,8 +843,8 @@ __global__ void __launch_bounds__(256) pack_factors_kernel(const float* __restri
 
 
 // The same packing with 16-byte accesses on the side that matters.  Work items per (copy, layer): for an A factor
-// one thread per 8 consecutive k (reads 8 whole rows of A, contiguous; writes one 16-byte chunk of each of the 2r
-// K-contiguous output rows, contiguous across lanes); for a B factor one thread per output feature n (reads
+// one thread per 8 consecutive k (reads 8 whole rows of A, contiguous; writes the r 16-byte pieces of that chunk in
+// the hi part and in the lo part, each run contiguous); for a B factor one thread per output feature n (reads
 // column n of B, contiguous across lanes; writes its whole packed row [hi | lo | 0]).
 template <int RANK>
 __global__ void __launch_bounds__(256) pack_factors_vec_kernel(const float* __restrict__ pert, int64_t P, int n_copies,
@@ -870,7 +872,7 @@ __global__ void __launch_bounds__(256) pack_factors_vec_kernel(const float* __re
     per_layer_packed += (tab.local_id[t] & 1) ? (int64_t)tab.cols[t] * rp : (int64_t)2 * tab.rows[t] * tab.cols[t];
   const float* src = pert + (int64_t)copy * P + (int64_t)layer * tab.per_layer + tab.off[i];
   uint16_t* dst = packed + (int64_t)copy * packed_per_copy + (int64_t)layer * per_layer_packed + poff;
-  if ((tab.local_id[i] & 1) == 0) {                // A [K, r]: rows k0..k0+7 -> chunk k0 of rows j (hi) and r + j (lo)
+  if ((tab.local_id[i] & 1) == 0) {                // A [K, r]: rows k0..k0+7 -> pieces [k0 / 8][j] of the hi and of the lo part
     const int K = tab.rows[i], k0 = item * 8;
     float v[8][RANK];
 #pragma unroll
@@ -891,8 +893,8 @@ __global__ void __launch_bounds__(256) pack_factors_vec_kernel(const float* __re
         lo[e / 2] = (uint32_t)l0.bits | ((uint32_t)l1.bits << 16);
       }
       const u32x4 hv = {hi[0], hi[1], hi[2], hi[3]}, lv = {lo[0], lo[1], lo[2], lo[3]};
-      *(u32x4*)(dst + (int64_t)j * K + k0) = hv;
-      *(u32x4*)(dst + (int64_t)(RANK + j) * K + k0) = lv;
+      *(u32x4*)(dst + ((int64_t)item * RANK + j) * 8) = hv;
+      *(u32x4*)(dst + (int64_t)K * RANK + ((int64_t)item * RANK + j) * 8) = lv;
     }
   } else {                                         // B [r, k_out]: column n -> packed row n = [hi(r) | lo(r) | 0]
     const int kout = tab.cols[i], n = item;

@@ -139,8 +139,8 @@ __global__ void __launch_bounds__(256, NV <= 4 ? 2 : 1) norm_lora_kernel(int kin
     int jj = valid[t] ? j : 0;
     int tgt = jj / a.rank, jr = jj % a.rank;
     const uint16_t* base = (const uint16_t*)a.ap[tgt] + (size_t)copy * a.copy_stride;
-    Ah[t] = base + (size_t)jr * D + wave * 64 + lhalf * 8;
-    Al[t] = base + (size_t)(a.rank + jr) * D + wave * 64 + lhalf * 8;
+    Ah[t] = base + ((size_t)(wave * 8 + lhalf) * a.rank + jr) * 8;      // [2][K / 8][rank][8], as in lora_down_mfma_kernel
+    Al[t] = Ah[t] + (size_t)D * a.rank;
   }
   f32x16 acc[JT];
 #pragma unroll
@@ -153,8 +153,8 @@ __global__ void __launch_bounds__(256, NV <= 4 ? 2 : 1) norm_lora_kernel(int kin
   for (int s4 = 0; s4 < 4; ++s4)
 #pragma unroll
     for (int t = 0; t < JT; ++t) {
-      fh[s4][t] = valid[t] ? *(const u32x4*)(Ah[t] + s4 * 16) : zero;
-      fl[s4][t] = valid[t] ? *(const u32x4*)(Al[t] + s4 * 16) : zero;
+      fh[s4][t] = valid[t] ? *(const u32x4*)(Ah[t] + (size_t)(s4 * 16) * a.rank) : zero;
+      fl[s4][t] = valid[t] ? *(const u32x4*)(Al[t] + (size_t)(s4 * 16) * a.rank) : zero;
     }
 #pragma unroll
   for (int ch = 0; ch < NV; ++ch) {
@@ -168,8 +168,8 @@ __global__ void __launch_bounds__(256, NV <= 4 ? 2 : 1) norm_lora_kernel(int kin
       for (int s4 = 0; s4 < 4; ++s4)
 #pragma unroll
         for (int t = 0; t < JT; ++t) {
-          fh[s4][t] = valid[t] ? *(const u32x4*)(Ah[t] + (ch + 1) * 256 + s4 * 16) : zero;
-          fl[s4][t] = valid[t] ? *(const u32x4*)(Al[t] + (ch + 1) * 256 + s4 * 16) : zero;
+          fh[s4][t] = valid[t] ? *(const u32x4*)(Ah[t] + (size_t)((ch + 1) * 256 + s4 * 16) * a.rank) : zero;
+          fl[s4][t] = valid[t] ? *(const u32x4*)(Al[t] + (size_t)((ch + 1) * 256 + s4 * 16) * a.rank) : zero;
         }
     }
 #pragma unroll
