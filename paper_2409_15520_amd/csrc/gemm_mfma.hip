@@ -843,8 +843,8 @@ __global__ void __launch_bounds__(256) pack_factors_kernel(const float* __restri
 
 
 // The same packing with 16-byte accesses on the side that matters.  Work items per (copy, layer): for an A factor
-// one thread per 8 consecutive k (reads 8 whole rows of A, contiguous; writes the r 16-byte pieces of that chunk in
-// the hi part and in the lo part, each run contiguous); for a B factor one thread per output feature n (reads
+// one thread per (chunk of 8 consecutive k, column j): consecutive lanes read consecutive floats of a row of A and
+// write consecutive 16-byte pieces of the hi part and of the lo part; for a B factor one thread per output feature n (reads
 // column n of B, contiguous across lanes; writes its whole packed row [hi | lo | 0]).
 template <int RANK>
 __global__ void __launch_bounds__(256) pack_factors_vec_kernel(const float* __restrict__ pert, int64_t P, int n_copies,
@@ -862,7 +862,7 @@ __global__ void __launch_bounds__(256) pack_factors_vec_kernel(const float* __re
   int64_t poff = 0;
   for (;; ++i) {                                   // which factor of the layer, and where its packed form starts
     const bool isB = tab.local_id[i] & 1;
-    const int cnt = isB ? tab.cols[i] : tab.rows[i] / 8;
+    const int cnt = isB ? tab.cols[i] : tab.rows[i] / 8 * RANK;
     if (item < cnt) break;
     item -= cnt;
     poff += isB ? (int64_t)tab.cols[i] * rp : (int64_t)2 * tab.rows[i] * tab.cols[i];
@@ -872,30 +872,22 @@ __global__ void __launch_bounds__(256) pack_factors_vec_kernel(const float* __re
     per_layer_packed += (tab.local_id[t] & 1) ? (int64_t)tab.cols[t] * rp : (int64_t)2 * tab.rows[t] * tab.cols[t];
   const float* src = pert + (int64_t)copy * P + (int64_t)layer * tab.per_layer + tab.off[i];
   uint16_t* dst = packed + (int64_t)copy * packed_per_copy + (int64_t)layer * per_layer_packed + poff;
-  if ((tab.local_id[i] & 1) == 0) {                // A [K, r]: rows k0..k0+7 -> pieces [k0 / 8][j] of the hi and of the lo part
-    const int K = tab.rows[i], k0 = item * 8;
-    float v[8][RANK];
+  if ((tab.local_id[i] & 1) == 0) {                // A [K, r]: rows k0..k0+7 of column j -> piece [k0 / 8][j] of the hi and of the lo part
+    const int K = tab.rows[i], chunk = item / RANK, j = item % RANK, k0 = chunk * 8;
+    float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
+    for (int e = 0; e < 8; ++e) v[e] = src[(int64_t)(k0 + e) * RANK + j];
+    uint32_t hi[4], lo[4];
 #pragma unroll
-      for (int c = 0; c < RANK / 4; ++c) {
-        const f32x4 t = *(const f32x4*)(src + (int64_t)(k0 + e) * RANK + c * 4);
-        v[e][c * 4] = t[0]; v[e][c * 4 + 1] = t[1]; v[e][c * 4 + 2] = t[2]; v[e][c * 4 + 3] = t[3];
-      }
-#pragma unroll
-    for (int j = 0; j < RANK; ++j) {
-      uint32_t hi[4], lo[4];
-#pragma unroll
-      for (int e = 0; e < 8; e += 2) {
-        const bf16_t h0 = f32_to_bf16(v[e][j]), h1 = f32_to_bf16(v[e + 1][j]);
-        const bf16_t l0 = f32_to_bf16(v[e][j] - bf16_to_f32(h0)), l1 = f32_to_bf16(v[e + 1][j] - bf16_to_f32(h1));
-        hi[e / 2] = (uint32_t)h0.bits | ((uint32_t)h1.bits << 16);
-        lo[e / 2] = (uint32_t)l0.bits | ((uint32_t)l1.bits << 16);
-      }
-      const u32x4 hv = {hi[0], hi[1], hi[2], hi[3]}, lv = {lo[0], lo[1], lo[2], lo[3]};
-      *(u32x4*)(dst + ((int64_t)item * RANK + j) * 8) = hv;
-      *(u32x4*)(dst + (int64_t)K * RANK + ((int64_t)item * RANK + j) * 8) = lv;
+    for (int e = 0; e < 8; e += 2) {
+      const bf16_t h0 = f32_to_bf16(v[e]), h1 = f32_to_bf16(v[e + 1]);
+      const bf16_t l0 = f32_to_bf16(v[e] - bf16_to_f32(h0)), l1 = f32_to_bf16(v[e + 1] - bf16_to_f32(h1));
+      hi[e / 2] = (uint32_t)h0.bits | ((uint32_t)h1.bits << 16);
+      lo[e / 2] = (uint32_t)l0.bits | ((uint32_t)l1.bits << 16);
     }
+    const u32x4 hv = {hi[0], hi[1], hi[2], hi[3]}, lv = {lo[0], lo[1], lo[2], lo[3]};
+    *(u32x4*)(dst + (int64_t)item * 8) = hv;
+    *(u32x4*)(dst + (int64_t)K * RANK + (int64_t)item * 8) = lv;
   } else {                                         // B [r, k_out]: column n -> packed row n = [hi(r) | lo(r) | 0]
     const int kout = tab.cols[i], n = item;
     uint16_t* row = dst + (int64_t)n * rp;
@@ -1108,7 +1100,7 @@ void launch_pack_factors(hipStream_t st, const float* pert, int64_t P, int n_cop
   for (int t = 0; t < tab.n_tensors; ++t) {
     const bool isB = tab.local_id[t] & 1;
     if (!isB && tab.rows[t] % 8) vec = false;
-    items += isB ? tab.cols[t] : tab.rows[t] / 8;
+    items += isB ? tab.cols[t] : tab.rows[t] / 8 * rank;
   }
   if (vec) {
     const int64_t total = (int64_t)items * n_layers * n_copies;
