@@ -828,9 +828,14 @@ __global__ void __launch_bounds__(256) pack_factors_kernel(const float* __restri
   if ((tab.local_id[i] & 1) == 0) {              // A [K, r]: element (k, j) -> [k / 8][j][k % 8] of the hi and of the lo part
     int K = tab.rows[i];
     int k = local / rank, j = local % rank;
-    const int64_t o = ((int64_t)(k / 8) * rank + j) * 8 + k % 8;
-    dst[o] = hi;
-    dst[(int64_t)K * rank + o] = lo;
+    if (K % 8 == 0) {
+      const int64_t o = ((int64_t)(k / 8) * rank + j) * 8 + k % 8;
+      dst[o] = hi;
+      dst[(int64_t)K * rank + o] = lo;
+    } else {                                      // no whole chunks: plain rows, which stay inside the factor's 2 r K elements
+      dst[(int64_t)j * K + k] = hi;               // (the bottleneck kernels that read this buffer need K % 256 == 0)
+      dst[(int64_t)(rank + j) * K + k] = lo;
+    }
   } else {                                        // B [r, k_out]: element (j, n) -> [n][j] hi, [n][r + j] lo
     int kout = tab.cols[i];
     int j = local / kout, n = local % kout;
