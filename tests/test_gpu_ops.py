@@ -20,11 +20,14 @@ def _bf16_tensor(a):
 
 
 # 32768 stacked tokens: the bottleneck kernel switches to its 64-token blocks (one and two 32-column MFMA tiles)
-BIG_T = {"c2_big_T": CASES["c2_2layers"].with_(q=4, E=32), "llama_mfma_big_T": CASES["llama_mfma"].with_(q=4, E=64)}
+BIG_T = {"c2_big_T": CASES["c2_2layers"].with_(q=4, E=32), "llama_mfma_big_T": CASES["llama_mfma"].with_(q=4, E=64),
+         # a rank that the vectorised packing kernel does not take: the element-wise one writes the same operand layouts
+         "c2_rank12": CASES["c2_2layers"].with_(lora_rank=12)}
 
 
 @pytest.mark.parametrize("name,simple", [("c2_2layers", False), ("llama_mfma", False), ("c2_2layers", True),
-                                         ("c2_ragged_copies", False), ("c2_big_T", False), ("llama_mfma_big_T", False)])
+                                         ("c2_ragged_copies", False), ("c2_big_T", False), ("llama_mfma_big_T", False),
+                                         ("c2_rank12", False)])
 def test_qkv_projection_matches_the_mp_lora_layer_equation(name, simple):
     import torch
     import paper_2409_15520_amd as M
