@@ -740,13 +740,17 @@ __global__ void __launch_bounds__(256, 2) lora_down_mfma_kernel(MfmaLoraDownArgs
       // this chunk's factor fragments (L2-resident) are fetched first, so that they travel while the x chunk is
       // stored and the block meets at the barrier
       u32x4 fh[4][JT], fl[4][JT];
+      const int r16 = 16 * a.rank;                 // elements between the pieces of consecutive K-steps
 #pragma unroll
-      for (int s4 = 0; s4 < 4; ++s4)
+      for (int t = 0; t < JT; ++t) {
+        const uint16_t* ph = Ah[t] + kg * a.rank;
+        const uint16_t* pl = Al[t] + kg * a.rank;
 #pragma unroll
-        for (int t = 0; t < JT; ++t) {
-          fh[s4][t] = valid[t] ? *(const u32x4*)(Ah[t] + (size_t)(kg + s4 * 16) * a.rank) : zero;
-          fl[s4][t] = valid[t] ? *(const u32x4*)(Al[t] + (size_t)(kg + s4 * 16) * a.rank) : zero;
+        for (int s4 = 0; s4 < 4; ++s4) {
+          fh[s4][t] = valid[t] ? *(const u32x4*)(ph + s4 * r16) : zero;
+          fl[s4][t] = valid[t] ? *(const u32x4*)(pl + s4 * r16) : zero;
         }
+      }
 #pragma unroll
       for (int i = 0; i < 4; ++i) *(u32x4*)(buf + grow[i] * XS + gcol[i]) = st[p][i];
       if (ch + PD < nch) {
