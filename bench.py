@@ -84,6 +84,8 @@ def main():
                          "(MeZO-style); stateful: batched pass, then update + re-perturbation in one kernel from the "
                          "stored pairs (Algorithm 2) instead of regenerate + replay")
     ap.add_argument("--q", type=int, default=None, help="override the workload's number of queries")
+    ap.add_argument("--lora-targets", default=None, help="override the adapted projections, e.g. q,v or o")
+    ap.add_argument("--lora-rank", type=int, default=None, help="override the LoRA rank")
     ap.add_argument("--E", type=int, default=None, help="override the sequences per copy")
     ap.add_argument("--S", type=int, default=None, help="override the sequence length")
     ap.add_argument("--device-init", action="store_true",
@@ -123,7 +125,9 @@ def main():
         torch.cuda.synchronize()
         del a, b
     w = W.get_workload(args.workload)
-    over = {k: v for k, v in (("q", args.q), ("E", args.E), ("S", args.S), ("weight_quant", args.weight_quant))
+    over = {k: v for k, v in (("q", args.q), ("E", args.E), ("S", args.S), ("weight_quant", args.weight_quant),
+                              ("lora_rank", args.lora_rank),
+                              ("lora_targets", tuple(args.lora_targets.split(",")) if args.lora_targets else None))
             if v is not None}
     if over:
         w = w.with_(**over)
