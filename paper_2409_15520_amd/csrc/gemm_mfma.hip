@@ -943,8 +943,8 @@ void launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
   gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP, WQ, PP><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
 }
 
-int tile_bn(int cfg) { return (cfg == 11 || cfg == 13) ? 192 : (cfg == 2 || (cfg >= 5 && cfg <= 8) || cfg == 14 || cfg == 15) ? 256 : 128; }   // 7, 8: 256 x 128 (4 is unused)
-int tile_bm(int cfg) { return cfg == 9 ? 64 : (cfg == 3 || cfg == 5 || cfg == 6 || cfg == 14 || cfg == 15) ? 256 : 128; }
+int tile_bn(int cfg) { return cfg == 10 ? 64 : (cfg == 11 || cfg == 13) ? 192 : (cfg == 2 || (cfg >= 5 && cfg <= 8) || cfg == 14 || cfg == 15) ? 256 : 128; }   // 7, 8: 256 x 128 (4 is unused)
+int tile_bm(int cfg) { return (cfg == 9 || cfg == 10) ? 64 : (cfg == 3 || cfg == 5 || cfg == 6 || cfg == 14 || cfg == 15) ? 256 : 128; }
 
 bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
   const int bn = tile_bn(cfg), bm = tile_bm(cfg);
@@ -957,7 +957,7 @@ bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
 
 int choose_cfg(const MfmaGemmArgs& a) {
   const bool forced_ok = a.w_scale == nullptr || a.tile_cfg == 1 || a.tile_cfg == 6 || a.tile_cfg == 11 || a.tile_cfg == 12;   // int8: fewer instances
-  if (forced_ok && a.tile_cfg >= 1 && a.tile_cfg <= 15 && a.tile_cfg != 4 && a.tile_cfg != 10 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
+  if (forced_ok && a.tile_cfg >= 1 && a.tile_cfg <= 15 && a.tile_cfg != 4 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
   // enough 256 x 256 tiles to keep 256 CUs busy for several rounds -> biggest tile; else the largest tile that
   // still gives at least ~2 blocks per CU
   // The L2 -> CU path feeds about 64 B/clk per CU, which a 128 x 128 tile needs in full at MFMA peak; 256 x 256
@@ -968,16 +968,18 @@ int choose_cfg(const MfmaGemmArgs& a) {
   // other half; 192 x 128 tiles, one per CU, balance it (N = 768 projections of the 125M-class models)
   const long t1 = (long)((a.N + 127) / 128) * ((a.M + 127) / 128), t11 = (long)((a.N + 191) / 192) * ((a.M + 127) / 128);
   if (t1 > 256 && t1 < 512 && t11 <= 256 && a.N % 192 == 0 && a.K >= 1536 && a.rope_cos == nullptr && cfg_ok(a, 11)) return 11;
-  // fewer 128 x 128 tiles than CUs (single-copy and single-query passes): 128 x 64 tiles, twice the blocks
-  // (one pass per copy on the 125M-shaped workload: 8.2 -> 7.9 ms per step, one pass per query: 4.8 -> 4.7)
-  if (t1 < 256 && a.rope_cos == nullptr && a.w_scale == nullptr && a.ce_max == nullptr && cfg_ok(a, 9)) return 9;
+  // fewer 128 x 128 tiles than CUs (single-copy and single-query passes): 128 x 64 tiles, twice the blocks, and
+  // 64 x 64 tiles if that is still less than one block per CU (one pass per copy on the 125M-shaped workload:
+  // 8.2 -> 7.4 ms per step; 2 x 64 tokens through the 7B-shaped model: 75 -> 67 ms)
+  if (t1 < 256 && a.rope_cos == nullptr && a.w_scale == nullptr && a.ce_max == nullptr && cfg_ok(a, 9))
+    return (2 * t1 < 256 && cfg_ok(a, 10)) ? 10 : 9;
   // otherwise the 128 x 128 tile with 8 waves of 64 x 32 (16 waves per CU): a block of a short-K problem lives for
   // a dozen K-tiles, and what hides its first loads and last stores is other waves (10 % over 4 waves of 64 x 64
   // at K = 768, equal at long K)
   return 12;
 }
 
-int wave_cols(int cfg) { return (cfg == 11 || cfg == 13) ? 96 : (cfg == 2 || cfg == 5 || cfg == 6 || cfg == 14 || cfg == 15) ? 128 : 64; }   // BN / WGN of launch_gemm_mfma's table
+int wave_cols(int cfg) { return cfg == 10 ? 32 : (cfg == 11 || cfg == 13) ? 96 : (cfg == 2 || cfg == 5 || cfg == 6 || cfg == 14 || cfg == 15) ? 128 : 64; }   // BN / WGN of launch_gemm_mfma's table
 
 // 64 token rows per block, the slots dealt to 4 waves: logsumexp over the per-wave-tile partials (online
 // maximum / rescaled sum per thread, merged through LDS), minus the target's logit
@@ -1009,7 +1011,9 @@ __global__ void __launch_bounds__(256) ce_combine_kernel(int slots, int M, const
 
 }  // namespace
 
-int mfma_gemm_ce_slots(const MfmaGemmArgs& a) {
+int mfma_gemm_ce_slots(const MfmaGemmArgs& a0) {
+  MfmaGemmArgs a = a0;
+  if (a.ce_max == nullptr) a.ce_max = (float*)a.out;     // the caller asks before it has carved the buffers: the tile is chosen as for the launch
   const int cfg = choose_cfg(a);
   return ((a.N + tile_bn(cfg) - 1) / tile_bn(cfg)) * (tile_bn(cfg) / wave_cols(cfg));
 }
@@ -1080,6 +1084,7 @@ void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     case 7: launch_cfg<256, 128, 64, 4, 2, false>(st, a); break;     // 8 waves of 64 x 64, 110 KB LDS
     case 8: launch_cfg<256, 128, 32, 4, 2, false>(st, a); break;     // 8 waves of 64 x 64, 61 KB LDS
     case 9: launch_cfg<128, 64, 64, 2, 2, false>(st, a); break;      // 4 waves of 64 x 32: more, smaller blocks
+    case 10: launch_cfg<64, 64, 64, 2, 2, false>(st, a); break;      // 4 waves of 32 x 32: the smallest blocks
     case 11: launch_cfg<192, 128, 64, 2, 2, false>(st, a); break;    // 4 waves of 96 x 64, 92 KB LDS: 1 block per CU
     case 12: launch_cfg<128, 128, 64, 2, 4, false>(st, a); break;    // 8 waves of 64 x 32: 16 waves per CU
     case 13: launch_cfg<192, 128, 64, 2, 4, false>(st, a); break;    // 8 waves of 96 x 32
