@@ -922,12 +922,10 @@ __global__ void __launch_bounds__(256) pack_factors_vec_kernel(const float* __re
 }
 
 // ---- tile configurations ----------------------------------------------------------------------------
-//  id  BN  BM  BK sets   LDS      use
-//   1 128 128  64  2    73.7 KB   small N (more blocks)
-//   2 256 128  32  2    61.4 KB   general
-//   3 128 256  32  2    61.4 KB   general, tall
-//   4 256 256  32  1    81.9 KB   large problems (lowest LDS traffic per MFMA)
-//  dual (SwiGLU): 2 x 128 x 128 x 32, 2 sets, 61.4 KB
+// The numbered configurations (BN x BM x BK, waves) are listed where they are instantiated, in launch_gemm_mfma;
+// choose_cfg picks among 6 (256 x 256 x 64, 8 waves: large problems), 12 and 1 (128 x 128 x 64 with 8 or 4 waves),
+// 11 (192 x 128 x 64), 9 and 10 (128 x 64 and 64 x 64: problems with fewer tiles than CUs); the others are kept for
+// measurement.  LDS = stages x (BN + BM) x (BK + 8) x 2 bytes, or the epilogue strips if those are larger.
 template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP = 0, bool WQ = false, bool PP = false>
 void launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
   constexpr size_t lds_stages = (size_t)(PP ? 3 : 2) * ((DUAL ? 2 : 1) * BN + BM) * (BK + 8) * 2;
