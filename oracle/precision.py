@@ -66,3 +66,18 @@ class Precision:
         hi = _bf16_rne(x32)
         lo = _bf16_rne(x32 - hi)                  # x32 - hi is exact in binary32
         return hi.astype(np.float64) + lo.astype(np.float64)
+
+
+class JitterPrecision(Precision):
+    """Diagnostic, not part of the method: the bf16 contract with every operand nudged by a relative error of
+    fp32-accumulation size before it is rounded - a stand-in for 'the same arithmetic with another summation
+    order'.  The distance between a run with this class and a run with Precision("bf16") measures how far two
+    correct implementations of a bf16 workload can drift apart (the floor the parity tests quote)."""
+
+    def __init__(self, rel: float = 1e-6, seed: int = 0):
+        super().__init__("bf16")
+        self.rel, self.rng = rel, np.random.default_rng(seed)
+
+    def operand(self, x):
+        x = np.asarray(x, dtype=np.float64)
+        return super().operand(x * (1.0 + self.rel * self.rng.standard_normal(x.shape)))

@@ -3,7 +3,7 @@ import numpy as np
 
 import workloads as W
 from oracle import zo
-from oracle.precision import Precision
+from oracle.precision import Precision, JitterPrecision  # noqa: F401  (re-exported for the tests)
 
 
 def make_bundle(w, b_std=0.0, wseed=1234, lseed=99, tseed=2345):
@@ -67,17 +67,3 @@ def oracle_traces(b, seed=3456, step=0, mode=None):
     L = len(traces[0])
     H = [np.concatenate([t[i].reshape(-1, w.d_model) for t in traces], axis=0).astype(np.float32) for i in range(L)]
     return H, np.array(losses)
-
-
-class JitterPrecision(Precision):
-    """bf16 contract with every operand nudged by a relative error of fp32-accumulation size before it
-    is rounded: a stand-in for 'the same arithmetic with another summation order', used to measure how far
-    two correct implementations of the bf16 workloads can drift apart."""
-
-    def __init__(self, rel=1e-6, seed=0):
-        super().__init__("bf16")
-        self.rel, self.rng = rel, np.random.default_rng(seed)
-
-    def operand(self, x):
-        x = np.asarray(x, dtype=np.float64)
-        return super().operand(x * (1.0 + self.rel * self.rng.standard_normal(x.shape)))
