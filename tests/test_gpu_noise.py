@@ -36,10 +36,14 @@ def test_normal_transform_bit_exact_over_all_uniform_inputs():
     assert np.array_equal(_bits(got), _bits(want))
 
 
-@pytest.mark.parametrize("name", ["c1_tiny_fp32", "c2_opt125m"])
+@pytest.mark.parametrize("name", ["c1_tiny_fp32", "c2_opt125m", "c4_llama1p1b", "c5_llama7b"])
 def test_noise_tensors_perturbed_copies_and_update_bit_exact(name):
+    """Two blocks of each layout: ranks 4 / 8 on q, v (workloads 1, 2), rank 16 on q, k, v, o with the narrow k / v of
+    grouped-query attention (workload 4, its 16 queries), rank 16 at d = 4096 (workload 5)."""
     import torch
     w = W.get_workload(name).with_(n_layers=2)
+    if name in ("c4_llama1p1b", "c5_llama7b"):               # the frozen weights play no part here: a small vocabulary
+        w = w.with_(vocab=512, E=1, S=64, max_seq=64, label_tokens=(3, 400))
     b = make_bundle(w, b_std=0.01)
     mdl = gpu_model(b)
     lay = b["layout"]

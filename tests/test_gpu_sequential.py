@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import workloads as W
-from gpu_helpers import make_bundle, gpu_model
+from gpu_helpers import make_bundle, gpu_model, oracle_steps
 from small_workloads import MINI_LLAMA
 from test_gpu_bf16 import CASES
 
@@ -32,6 +32,14 @@ def test_sequential_and_grouped_passes_are_bit_identical_to_the_batched_pass(w):
     m.losses.zero_()
     signs = m.forward_outer_only(tok, lab).cpu().numpy().copy()
     assert np.array_equal(batched.view(np.uint32), signs.view(np.uint32))
+    # and against the oracle, which evaluates the 2q copies one by one (Algorithm 1 as printed): the sequential and the
+    # outer-loop-only passes give its losses - to fp32 rounding on the fp32 path, to the bf16 bar on the MFMA path
+    want = oracle_steps(b, 1)[0][0]
+    tol = 1e-6 if w.dtype == "f32" else 2e-2
+    for nm, got in (("sequential", seq), ("pairs", outer), ("outer loop only", signs)):
+        err = np.abs(got.astype(np.float64) - want).max() / np.abs(want).max()
+        print(f"\n{w.name} {nm} pass vs oracle: max rel loss error {err:.2e}")
+        assert err <= tol, (nm, got, want)
     # and a strided pass touches nothing but its own copies' losses
     if w.q >= 2:
         import paper_2409_15520_amd as M
@@ -110,3 +118,41 @@ def test_fused_norm_and_bottleneck_kernel_changes_no_bit(name):
         m.regen_noise(3456, 0)
         out.append(m.forward_perturbed(tok, lab).cpu().numpy().copy())
     assert np.array_equal(out[0].view(np.uint32), out[1].view(np.uint32)), out
+
+
+RANK4_MFMA = W.Workload(
+    name="rank4_mfma", n_layers=2, d_model=256, n_heads=4, n_kv_heads=4, d_ffn=512, vocab=512, max_seq=64,
+    act="relu", norm="layernorm", pos="learned", has_bias=True, tie_embeddings=True, dtype="bf16",
+    lora_rank=4, lora_targets=("q", "o"), loss_mode="last_pos_full_vocab", q=3, E=2, S=64, steps=1, label_tokens=(5, 300))
+
+
+@pytest.mark.parametrize("w,perturb_A", [(CASES["c2_2layers"], True), (CASES["llama_mfma"], True), (CASES["llama_mfma"], False),
+                                         (RANK4_MFMA, True), (CASES["mini_llama"], True)],
+                         ids=["c2_2layers_r8_qv", "llama_mfma_r16_qkvo", "llama_mfma_lora_fa", "rank4_qo", "mini_llama_fallback"])
+def test_noise_written_straight_into_the_operand_layouts_changes_no_bit(w, perturb_A):
+    """bf16 models: mpz_regen_noise writes the perturbed factors directly as bf16 hi / lo MFMA operands (one kernel, no
+    fp32 copies); with the hook off it writes fp32 copies and packs them.  Same factors, so the same losses, and the
+    fp32 copies - made on demand for the test hook, for the stateful update and for shapes the MFMA kernels refuse
+    (the miniature model) - are the same bits too."""
+    import torch
+    import paper_2409_15520_amd as M
+    w = w.with_(perturb_A=perturb_A)
+    b = make_bundle(w, b_std=0.05)
+    m = gpu_model(b)
+    tok = torch.from_numpy(b["tokens"]).cuda()
+    lab = torch.from_numpy(b["labels"]).cuda()
+    losses, copies, after = [], [], []
+    for fused in (True, False):
+        M.mpz_debug_set_fused_perturb_pack(m.handle, fused)
+        m.masters.copy_(torch.from_numpy(b["masters"]).cuda())
+        m.regen_noise(3456, 5, eps=5e-2)
+        losses.append(m.forward_perturbed(tok, lab).cpu().numpy().copy())
+        copies.append(m.perturbed_copy(2 * w.q - 1).cpu().numpy().copy())
+        m.zo_update_regen(6)                       # the stateful update reads the stored fp32 pairs
+        losses.append(m.forward_perturbed(tok, lab).cpu().numpy().copy())
+        after.append(m.masters.cpu().numpy().copy())
+    assert len(set(losses[0].tolist())) == 2 * w.q
+    assert np.array_equal(losses[0].view(np.uint32), losses[2].view(np.uint32)), (losses[0], losses[2])
+    assert np.array_equal(losses[1].view(np.uint32), losses[3].view(np.uint32)), (losses[1], losses[3])
+    assert np.array_equal(copies[0].view(np.uint32), copies[1].view(np.uint32))
+    assert np.array_equal(after[0].view(np.uint32), after[1].view(np.uint32))
