@@ -282,7 +282,7 @@ mpz_status mpz_debug_attention(mpz_model* m, const void* qkv, int32_t n_seq, int
 
 /* Test / measurement hook: the bf16 MFMA GEMM alone, out[M, N] = act(x[M, K] w[N, K]^T + bias), all [dev], x and w bf16,
  * out bf16 or fp32 (out_f32), act = -1 (none), MPZ_ACT_RELU, MPZ_ACT_GELU_ERF, or MPZ_ACT_SWIGLU (then w has 2N rows,
- * gate then up, bias 2N, out = SiLU(gate) * up); tile_cfg 0 = chosen by shape, 1..15 = a fixed block-tile configuration (unsupported numbers fall back to the choice by shape).  Errors: NULL, SHAPE (K % 64, N % 4). */
+ * gate then up, bias 2N, out = SiLU(gate) * up); tile_cfg 0 = chosen by shape; 1, 6, 9, 10, 11, 12 = that block-tile configuration (other numbers fall back to the choice by shape).  Errors: NULL, SHAPE (K % 64, N % 4). */
 mpz_status mpz_debug_gemm_bf16(int32_t M, int32_t N, int32_t K, const void* x, const void* w, const float* bias,
                                int32_t act, void* out, int32_t out_f32, int32_t tile_cfg, void* hip_stream);
 /* The same with weight-only int8 weights: w_codes [dev] int8 [N, K] (SwiGLU: [2N, K]), w_scale [dev] fp32 [N] ([2N]),
@@ -315,13 +315,21 @@ mpz_status mpz_debug_set_kernel_path(mpz_model* m, int32_t simple_only);
  * stream and on an internal second stream of the same priority, forked from and joined to the caller's stream by
  * events, so that the halves' kernels overlap.  Losses are bit-identical either way. */
 mpz_status mpz_debug_set_two_halves(mpz_model* m, int32_t enable);
+/* Number of streams the last mpz_forward_perturbed was issued on: 2 with the two-halves schedule, 1 without, 0
+ * before the first pass (or for a NULL handle). */
+int32_t mpz_debug_last_pass_streams(const mpz_model* m);
 
 /* Test hook: allow (default) or forbid the kernel that does a block's first pre-norm and the LoRA bottleneck of the
  * q/k/v projections in one pass over the residual rows (bf16 models with d_model 768, 1024 or 2048); without it the
  * two run as separate kernels.  Same bits either way. */
 mpz_status mpz_debug_set_fused_norm_lora(mpz_model* m, int32_t enable);
 
-/* Test hook: force one block-tile configuration (1..15; 0 = chosen by shape) for every MFMA GEMM of the model's
+/* Test hook: allow (default) or forbid the kernel that writes the perturbed factors of a bf16 model straight into the
+ * bf16 hi / lo MFMA operand layouts; without it mpz_regen_noise writes fp32 copies first and packs them in a second
+ * kernel.  Same bits either way.  Invalidates the perturbed copies: call mpz_regen_noise again. */
+mpz_status mpz_debug_set_fused_perturb_pack(mpz_model* m, int32_t enable);
+
+/* Test hook: force one block-tile configuration (1, 6, 9, 10, 11 or 12; 0 = chosen by shape) for every MFMA GEMM of the model's
  * passes, so that small test shapes can exercise the configurations large workloads select.  Errors: NULL, CONFIG. */
 mpz_status mpz_debug_set_tile_config(mpz_model* m, int32_t tile_cfg);
 

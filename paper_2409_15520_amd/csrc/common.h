@@ -47,6 +47,12 @@ struct LoraLayerTable {
 // ---- noise.hip -------------------------------------------------------------------------
 void launch_perturb(hipStream_t st, const float* masters, float* pert /*[2q][P]*/, int64_t P,
                     const LoraLayerTable& tab, uint64_t seed, uint32_t step, int q, float eps, int perturb_A);
+// the same perturbation written straight into the bf16 hi / lo MFMA operand layouts of all 2q copies (see
+// launch_pack_factors for the layouts); supported for ranks 4 / 8 / 16 with K % 8 == 0 and k_out % 4 == 0
+bool perturb_pack_supported(const LoraLayerTable& tab, int rank, int rp);
+void launch_perturb_pack(hipStream_t st, const float* masters, void* packed, int64_t packed_per_copy,
+                         const LoraLayerTable& tab, int n_layers, int rank, int rp, uint64_t seed, uint32_t step, int q,
+                         float eps, int perturb_A);
 void launch_update(hipStream_t st, float* masters, int64_t P, const LoraLayerTable& tab, uint64_t seed,
                    uint32_t step, int q, float eps, float lr, int perturb_A, const float* losses,
                    float* proj_grads_out);
@@ -154,7 +160,7 @@ struct MfmaGemmArgs {
   int act;                      // -1 none, MPZ_ACT_RELU, MPZ_ACT_GELU_ERF (ignored when dual: SiLU(gate) * up)
   const float* residual;        // [M, ldo] fp32 or null
   int out_f32; void* out; int ldo;
-  int tile_cfg;                 // 0 = choose by shape; 1..12 force a tile configuration (measurement)
+  int tile_cfg;                 // 0 = choose by shape; 1, 6, 9, 10, 11, 12 force that tile configuration (tests)
   // fused rotary embedding (bf16 output only): columns [0, rope_cols) are heads of width rope_dh rotated by the
   // position m % S with tables [max_seq, rope_dh / 2]; packed batches: position rope_pos[m % S] (S = rows per copy)
   const float* rope_cos; const float* rope_sin; int rope_cols, rope_dh, S;
@@ -169,7 +175,8 @@ int mfma_gemm_ce_slots(const MfmaGemmArgs& a);      // partial slots per row the
 // ce[m] = logsumexp over the slots - target logit (0 where ce_target[m] < 0)
 void launch_ce_combine(hipStream_t st, int slots, int M, const float* ce_max, const float* ce_sum, const float* ce_tlogit,
                        const int32_t* ce_target, float* ce);
-void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a);
+// hipSuccess, or the error of raising the kernel instance's dynamic LDS limit (then nothing was launched)
+hipError_t launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a);
 
 struct MfmaLoraDownArgs {
   int T, K, rank, n_targets, rows_per_copy, rp;

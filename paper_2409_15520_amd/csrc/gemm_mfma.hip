@@ -7,6 +7,8 @@
 // Orientation: the MFMA "A" operand is a W tile (rows = output features n), the "B" operand an X tile
 // (rows = tokens m), so every lane ends up with 4 consecutive n of one token: bias / residual / stores
 // are 8- or 16-byte accesses along the contiguous output dimension.
+#include <mutex>
+
 #include "common.h"
 #include "../../include/mpz.h"
 
@@ -94,7 +96,7 @@ __device__ __forceinline__ void i8x16_to_bf16(u32x4 in, u32x4& lo8, u32x4& hi8) 
 // conflict-free for BK = 32 and BK = 64.
 // HP > 0: rotary embedding fused into the epilogue for head width 64 * HP (the partner column d_head/2 away sits in
 // the same lane, HP MFMA tiles further), for output columns below rope_cols; the result is stored as bf16.
-template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP, bool WQ, bool PP>
+template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP, bool WQ>
 __global__ void __launch_bounds__(64 * WGN * WGM, (BN * BM * (DUAL ? 2 : 1) <= 256 * 128 && WGN * WGM == 4 && !(BN == 192 && BK == 64)) ? 2 : 1)
 gemm_bf16_kernel(MfmaGemmArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -108,7 +110,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   constexpr int LW = BN * WCH / NT, LX = BM * CPR / NT;                  // chunks per thread and tile
   static_assert(BN * WCH % NT == 0 && BM * CPR % NT == 0, "tile rows must deal out evenly to the threads");
   uint16_t* sW = (uint16_t*)smem;                        // [2 stages][NW][BN][LDS_STRIDE]
-  constexpr int NSTG = PP ? 3 : 2;                       // LDS stages (and register sets) of operand tiles
+  constexpr int NSTG = 2;                                // LDS stages (and register sets) of operand tiles
   uint16_t* sX = sW + NSTG * NW * TILE_W;                // [stages][BM][LDS_STRIDE]
 
   // XCD-aware tile order: hardware deals consecutive workgroups round-robin to the 8 XCDs; give each XCD
@@ -286,96 +288,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   // Tile kt+1 sits in one register set (in flight or landed) while tile kt+2 is fetched into the other: a load
   // has two MFMA phases to arrive before its LDS store needs it.  Loads past the last tile fall outside the
   // buffers (zeros); what they put into the idle LDS stage is never read.
-  if constexpr (PP) {
-    // Ping-pong schedule.  The two waves that share a SIMD (wave w and w + 4 of the block) take turns: while one
-    // issues the 16 MFMAs of a K-tile back to back from fragments it already holds, the other does its memory work
-    // (LDS store of a landed tile, global fetch of a later one, fragment reads for its next MFMA turn); a block
-    // barrier ends every turn.  The matrix core then sees one uninterrupted MFMA stream per SIMD instead of two waves
-    // that want it, and leave it, at the same moments.  Tile j sits in LDS stage j % 3 and came through register
-    // set j % 3: it is stored during iteration j - 2 (fetched three iterations before that) and read in the memory
-    // turn of iteration j - 1.
-    // The loop runs in threes; for tiles past the last one the token-side fragments are zeroed.
-    static_assert(BK == 32 && WGN * WGM == 8 && !WQ, "ping-pong schedule: BK = 32, 8 waves, bf16 weights");
-    const bool first = __builtin_amdgcn_readfirstlane(wave) < 4;     // wave-uniform: a scalar branch
-    bf16x8 fw[2][NW][NI], fx[2][NJ];
-#define MPZ_PP_READ(stage)                                                         \
-  {                                                                                \
-    const uint16_t* cw = sW + (stage) * NW * TILE_W;                               \
-    const uint16_t* cx = sX + (stage) * TILE_X;                                    \
-    MPZ_READ_FRAGS(0, cw, cx, 0)                                                   \
-    MPZ_READ_FRAGS(1, cw, cx, 16)                                                  \
-    __builtin_amdgcn_sched_barrier(0);                                             \
-  }
-#define MPZ_PP_MFMA()                                                              \
-  {                                                                                \
-    MPZ_MFMAS(0)                                                                   \
-    MPZ_MFMAS(1)                                                                   \
-    _Pragma("unroll") for (int g_ = 0; g_ < NW * LW + LX; ++g_) {                  \
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                           \
-      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                           \
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                           \
-      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                           \
-    }                                                                              \
-    __builtin_amdgcn_sched_barrier(0);                                             \
-    __builtin_amdgcn_s_setprio(0);                                                 \
-  }
-#define MPZ_PP_STORE_FETCH(set, kt)                                                \
-  {                                                                                \
-    const int soff = (kt) * BK * 2;                                                \
-    _Pragma("unroll") for (int d = 0; d < NW; ++d)                                 \
-      _Pragma("unroll") for (int i = 0; i < LW; ++i) {                             \
-        *(u32x4*)(sW + ((set) * NW + d) * TILE_W + ldsW[i]) = rw[set][d][i];       \
-        rw[set][d][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, voffW[d][i], soff, 0); \
-      }                                                                            \
-    _Pragma("unroll") for (int i = 0; i < LX; ++i) {                               \
-      *(u32x4*)(sX + (set) * TILE_X + ldsX[i]) = rx[set][i];                       \
-      rx[set][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcX, voffX[i], soff, 0); \
-    }                                                                              \
-  }
-#define MPZ_PP_ZERO_X()                                                            \
-  {                                                                                \
-    _Pragma("unroll") for (int s_ = 0; s_ < 2; ++s_)                               \
-      _Pragma("unroll") for (int j_ = 0; j_ < NJ; ++j_) fx[s_][j_] = as_frag(u32x4{0u, 0u, 0u, 0u}); \
-    __builtin_amdgcn_sched_barrier(0);                                             \
-  }
-#define MPZ_PP_TURN_BARRIER() { __builtin_amdgcn_sched_barrier(0); __syncthreads(); __builtin_amdgcn_sched_barrier(0); }
-// one iteration = tile j = j0 + u: stages / sets u, (u + 1) % 3, (u + 2) % 3 hold tiles j, j + 1, j + 2.  Both groups
-// run the same two turns; the second group is one turn behind (it waits at one extra barrier before the loop, the
-// first group at one after it), so one group's MFMA turn is the other's memory turn.
-#define MPZ_PP_ITER(u, j)                                                          \
-  {                                                                                \
-    /* MFMA turn: the stores and fetches ride along (they issue between MFMAs, which the matrix core paces) */ \
-    __builtin_amdgcn_s_setprio(1);                                                 \
-    MPZ_PP_STORE_FETCH(((u) + 2) % 3, (j) + 5)                                     \
-    MPZ_PP_MFMA()                                                                  \
-    MPZ_PP_TURN_BARRIER()                                                          \
-    MPZ_PP_READ(((u) + 1) % 3)                   /* memory turn: fragments for the next MFMA turn */ \
-    if ((j) + 1 >= nk) MPZ_PP_ZERO_X()           /* the loop runs in threes: tiles past the last one add nothing */ \
-    MPZ_PP_TURN_BARRIER()                                                          \
-  }
-    MPZ_LOAD_GLOBAL(0, 0)
-    MPZ_LOAD_GLOBAL(1, 1)
-    MPZ_LOAD_GLOBAL(2, 2)
-    MPZ_STORE_LDS(0, 0)
-    MPZ_STORE_LDS(1, 1)
-    MPZ_LOAD_GLOBAL(0, 3)
-    MPZ_LOAD_GLOBAL(1, 4)
-    __syncthreads();
-    MPZ_PP_READ(0)
-    if (!first) MPZ_PP_TURN_BARRIER()
-    for (int j0 = 0; j0 < nk; j0 += 3) {
-      MPZ_PP_ITER(0, j0)
-      MPZ_PP_ITER(1, j0 + 1)
-      MPZ_PP_ITER(2, j0 + 2)
-    }
-    if (first) MPZ_PP_TURN_BARRIER()
-#undef MPZ_PP_READ
-#undef MPZ_PP_MFMA
-#undef MPZ_PP_TURN_BARRIER
-#undef MPZ_PP_STORE_FETCH
-#undef MPZ_PP_ZERO_X
-#undef MPZ_PP_ITER
-  } else {
+  {
   MPZ_LOAD_GLOBAL(0, 0)
   MPZ_LOAD_GLOBAL(1, 1)                  // both in flight before the first wait
   MPZ_STORE_LDS(0, 0)
@@ -924,25 +837,30 @@ __global__ void __launch_bounds__(256) pack_factors_vec_kernel(const float* __re
 // ---- tile configurations ----------------------------------------------------------------------------
 // The numbered configurations (BN x BM x BK, waves) are listed where they are instantiated, in launch_gemm_mfma;
 // choose_cfg picks among 6 (256 x 256 x 64, 8 waves: large problems), 12 and 1 (128 x 128 x 64 with 8 or 4 waves),
-// 11 (192 x 128 x 64), 9 and 10 (128 x 64 and 64 x 64: problems with fewer tiles than CUs); the others are kept for
-// measurement.  LDS = stages x (BN + BM) x (BK + 8) x 2 bytes, or the epilogue strips if those are larger.
-template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP = 0, bool WQ = false, bool PP = false>
-void launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
-  constexpr size_t lds_stages = (size_t)(PP ? 3 : 2) * ((DUAL ? 2 : 1) * BN + BM) * (BK + 8) * 2;
+// 11 (192 x 128 x 64), 9 and 10 (128 x 64 and 64 x 64: problems with fewer tiles than CUs).  LDS = stages x (BN + BM) x (BK + 8) x 2 bytes, or the epilogue strips if those are larger.
+template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP = 0, bool WQ = false>
+hipError_t launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
+  constexpr size_t lds_stages = (size_t)2 * ((DUAL ? 2 : 1) * BN + BM) * (BK + 8) * 2;
   constexpr size_t lds_strips = (size_t)WGN * WGM * 32 * (BN / WGN + 4) * 4;          // epilogue: one strip per wave
   constexpr size_t lds = lds_stages > lds_strips ? lds_stages : lds_strips;
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP, WQ, PP>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attr_set = true;
-  }
+  // the kernel's dynamic LDS limit is raised once per instance (two host threads may arrive here together); a
+  // refusal is remembered and makes every launch of this instance fail with that error instead of an opaque one
+  static std::once_flag once;
+  static hipError_t attr_status = hipSuccess;
+  std::call_once(once, [] {
+    attr_status = hipFuncSetAttribute((const void*)gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP, WQ>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  });
+  if (attr_status != hipSuccess) return attr_status;
   const int tiles = ((a.N + BN - 1) / BN) * ((a.M + BM - 1) / BM);
-  gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP, WQ, PP><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
+  gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP, WQ><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
+  return hipSuccess;
 }
 
-int tile_bn(int cfg) { return cfg == 10 ? 64 : (cfg == 11 || cfg == 13) ? 192 : (cfg == 2 || (cfg >= 5 && cfg <= 8) || cfg == 14 || cfg == 15) ? 256 : 128; }   // 7, 8: 256 x 128 (4 is unused)
-int tile_bm(int cfg) { return (cfg == 9 || cfg == 10) ? 64 : (cfg == 3 || cfg == 5 || cfg == 6 || cfg == 14 || cfg == 15) ? 256 : 128; }
+// block tile of configuration cfg (1, 6, 9, 10, 11, 12; see launch_gemm_mfma)
+int tile_bn(int cfg) { return cfg == 10 ? 64 : cfg == 11 ? 192 : cfg == 6 ? 256 : 128; }
+int tile_bm(int cfg) { return (cfg == 9 || cfg == 10) ? 64 : cfg == 6 ? 256 : 128; }
+bool known_cfg(int cfg) { return cfg == 1 || cfg == 6 || (cfg >= 9 && cfg <= 12); }
 
 bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
   const int bn = tile_bn(cfg), bm = tile_bm(cfg);
@@ -955,7 +873,7 @@ bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
 
 int choose_cfg(const MfmaGemmArgs& a) {
   const bool forced_ok = a.w_scale == nullptr || a.tile_cfg == 1 || a.tile_cfg == 6 || a.tile_cfg == 11 || a.tile_cfg == 12;   // int8: fewer instances
-  if (forced_ok && a.tile_cfg >= 1 && a.tile_cfg <= 15 && a.tile_cfg != 4 && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
+  if (forced_ok && known_cfg(a.tile_cfg) && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
   // enough 256 x 256 tiles to keep 256 CUs busy for several rounds -> biggest tile; else the largest tile that
   // still gives at least ~2 blocks per CU
   // The L2 -> CU path feeds about 64 B/clk per CU, which a 128 x 128 tile needs in full at MFMA peak; 256 x 256
@@ -977,7 +895,7 @@ int choose_cfg(const MfmaGemmArgs& a) {
   return 12;
 }
 
-int wave_cols(int cfg) { return cfg == 10 ? 32 : (cfg == 11 || cfg == 13) ? 96 : (cfg == 2 || cfg == 5 || cfg == 6 || cfg == 14 || cfg == 15) ? 128 : 64; }   // BN / WGN of launch_gemm_mfma's table
+int wave_cols(int cfg) { return cfg == 10 ? 32 : cfg == 11 ? 96 : cfg == 6 ? 128 : 64; }   // BN / WGN of launch_gemm_mfma's table
 
 // 64 token rows per block, the slots dealt to 4 waves: logsumexp over the per-wave-tile partials (online
 // maximum / rescaled sum per thread, merged through LDS), minus the target's logit
@@ -1034,61 +952,44 @@ bool mfma_gemm_supported(const MfmaGemmArgs& a) {
     // the rotated column range must end on a block-tile boundary, and a wave tile must hold whole heads
     const int cfg = choose_cfg(a), bn = tile_bn(cfg), tn = wave_cols(cfg);
     if (a.dual || a.out_f32 || a.act >= 0 || a.residual != nullptr || !a.rope_sin || a.S < 1) return false;
-    if ((cfg != 5 && cfg != 6 && cfg != 1 && cfg != 12) || (a.rope_dh != 64 && a.rope_dh != 128) || a.rope_dh > tn) return false;
+    if ((cfg != 6 && cfg != 1 && cfg != 12) || (a.rope_dh != 64 && a.rope_dh != 128) || a.rope_dh > tn) return false;
     if (a.rope_cols % bn || a.rope_cols > a.N || a.N % a.rope_dh) return false;
   }
   return true;
 }
 
-void launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
+hipError_t launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
   const bool q8 = a.w_scale != nullptr;      // int8 weights: the configurations the model path uses
   if (a.dual) {
     const long tb = (long)((a.N + 127) / 128) * ((a.M + 255) / 256);
-    if ((a.tile_cfg == 0 && tb >= 512) || a.tile_cfg == 6) {               // 2 x 128 x 256, 8 waves
-      if (q8) launch_cfg<128, 256, 64, 2, 4, true, 0, true>(st, a); else launch_cfg<128, 256, 64, 2, 4, true>(st, a);
-    } else if (a.tile_cfg == 5 && !q8) {
-      launch_cfg<128, 256, 32, 2, 4, true>(st, a);
-    } else {
-      if (q8) launch_cfg<128, 128, 32, 2, 2, true, 0, true>(st, a); else launch_cfg<128, 128, 32, 2, 2, true>(st, a);
-    }
-    return;
+    if ((a.tile_cfg == 0 && tb >= 512) || a.tile_cfg == 6)                 // 2 x 128 x 256, 8 waves
+      return q8 ? launch_cfg<128, 256, 64, 2, 4, true, 0, true>(st, a) : launch_cfg<128, 256, 64, 2, 4, true>(st, a);
+    return q8 ? launch_cfg<128, 128, 32, 2, 2, true, 0, true>(st, a) : launch_cfg<128, 128, 32, 2, 2, true>(st, a);
   }
-  if (a.rope_cos != nullptr) {             // fused rotary epilogue: only the two configurations the model path uses
+  if (a.rope_cos != nullptr) {             // fused rotary epilogue: only the configurations the model path uses
     const int cfg = choose_cfg(a);
-    if (cfg == 5 || cfg == 6) {
-      if (a.rope_dh == 64) { if (q8) launch_cfg<256, 256, 64, 2, 4, false, 1, true>(st, a); else launch_cfg<256, 256, 64, 2, 4, false, 1>(st, a); }
-      else { if (q8) launch_cfg<256, 256, 64, 2, 4, false, 2, true>(st, a); else launch_cfg<256, 256, 64, 2, 4, false, 2>(st, a); }
-    } else if (cfg == 12) {
-      if (q8) launch_cfg<128, 128, 64, 2, 4, false, 1, true>(st, a); else launch_cfg<128, 128, 64, 2, 4, false, 1>(st, a);
-    } else {
-      if (q8) launch_cfg<128, 128, 64, 2, 2, false, 1, true>(st, a); else launch_cfg<128, 128, 64, 2, 2, false, 1>(st, a);
+    if (cfg == 6) {
+      if (a.rope_dh == 64) return q8 ? launch_cfg<256, 256, 64, 2, 4, false, 1, true>(st, a) : launch_cfg<256, 256, 64, 2, 4, false, 1>(st, a);
+      return q8 ? launch_cfg<256, 256, 64, 2, 4, false, 2, true>(st, a) : launch_cfg<256, 256, 64, 2, 4, false, 2>(st, a);
     }
-    return;
+    if (cfg == 12) return q8 ? launch_cfg<128, 128, 64, 2, 4, false, 1, true>(st, a) : launch_cfg<128, 128, 64, 2, 4, false, 1>(st, a);
+    return q8 ? launch_cfg<128, 128, 64, 2, 2, false, 1, true>(st, a) : launch_cfg<128, 128, 64, 2, 2, false, 1>(st, a);
   }
   if (q8) {
     switch (choose_cfg(a)) {
-      case 6: launch_cfg<256, 256, 64, 2, 4, false, 0, true>(st, a); break;
-      case 11: launch_cfg<192, 128, 64, 2, 2, false, 0, true>(st, a); break;
-      case 12: launch_cfg<128, 128, 64, 2, 4, false, 0, true>(st, a); break;
-      default: launch_cfg<128, 128, 64, 2, 2, false, 0, true>(st, a); break;
+      case 6: return launch_cfg<256, 256, 64, 2, 4, false, 0, true>(st, a);
+      case 11: return launch_cfg<192, 128, 64, 2, 2, false, 0, true>(st, a);
+      case 12: return launch_cfg<128, 128, 64, 2, 4, false, 0, true>(st, a);
+      default: return launch_cfg<128, 128, 64, 2, 2, false, 0, true>(st, a);
     }
-    return;
   }
   switch (choose_cfg(a)) {
-    case 2: launch_cfg<256, 128, 32, 2, 2, false>(st, a); break;
-    case 3: launch_cfg<128, 256, 32, 2, 2, false>(st, a); break;
-    case 5: launch_cfg<256, 256, 32, 2, 4, false>(st, a); break;     // 8 waves of 128 x 64
-    case 6: launch_cfg<256, 256, 64, 2, 4, false>(st, a); break;     // 8 waves, BK 64 (147 KB LDS), 128 KB in flight
-    case 7: launch_cfg<256, 128, 64, 4, 2, false>(st, a); break;     // 8 waves of 64 x 64, 110 KB LDS
-    case 8: launch_cfg<256, 128, 32, 4, 2, false>(st, a); break;     // 8 waves of 64 x 64, 61 KB LDS
-    case 9: launch_cfg<128, 64, 64, 2, 2, false>(st, a); break;      // 4 waves of 64 x 32: more, smaller blocks
-    case 10: launch_cfg<64, 64, 64, 2, 2, false>(st, a); break;      // 4 waves of 32 x 32: the smallest blocks
-    case 11: launch_cfg<192, 128, 64, 2, 2, false>(st, a); break;    // 4 waves of 96 x 64, 92 KB LDS: 1 block per CU
-    case 12: launch_cfg<128, 128, 64, 2, 4, false>(st, a); break;    // 8 waves of 64 x 32: 16 waves per CU
-    case 13: launch_cfg<192, 128, 64, 2, 4, false>(st, a); break;    // 8 waves of 96 x 32
-    case 14: launch_cfg<256, 256, 32, 2, 4, false, 0, false, true>(st, a); break;   // 8 waves of 128 x 64, ping-pong schedule
-    case 15: launch_cfg<256, 256, 64, 2, 2, false>(st, a); break;    // 4 waves of 128 x 128: accumulators in AGPRs
-    default: launch_cfg<128, 128, 64, 2, 2, false>(st, a); break;
+    case 6: return launch_cfg<256, 256, 64, 2, 4, false>(st, a);     // 8 waves of 128 x 64, BK 64 (147 KB LDS), 128 KB in flight
+    case 9: return launch_cfg<128, 64, 64, 2, 2, false>(st, a);      // 4 waves of 64 x 32: more, smaller blocks
+    case 10: return launch_cfg<64, 64, 64, 2, 2, false>(st, a);      // 4 waves of 32 x 32: the smallest blocks
+    case 11: return launch_cfg<192, 128, 64, 2, 2, false>(st, a);    // 4 waves of 96 x 64, 92 KB LDS: 1 block per CU
+    case 12: return launch_cfg<128, 128, 64, 2, 4, false>(st, a);    // 8 waves of 64 x 32: 16 waves per CU
+    default: return launch_cfg<128, 128, 64, 2, 2, false>(st, a);    // 1: 4 waves of 64 x 64
   }
 }
 

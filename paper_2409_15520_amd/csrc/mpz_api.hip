@@ -107,50 +107,25 @@ void build_layout(const mpz_config* c, std::vector<mpz_lora_tensor>& out, LoraLa
   }
 }
 
-size_t carve(const mpz_config* c, int q_max, int E_max, int S_max, void* base, Buffers* b) {
-  Carver cv(base);
+// What lives as long as the model handle: rotary tables, the perturbed factor copies that mpz_regen_noise leaves for
+// the passes (master layout and MFMA operand layouts), the row tables of packed batches, the dequantisation buffer.
+void carve_persistent(const mpz_config* c, int q_max, int E_max, int S_max, Carver& cv, Buffers& bb) {
   std::vector<mpz_lora_tensor> lay; LoraLayerTable tab;
   build_layout(c, lay, tab);
-  int64_t P = (int64_t)tab.per_layer * c->n_layers;
-  // rows per copy rounded up to whole 32-row tiles: a packed batch (mpz_forward_perturbed_packed) of anything that
-  // fits as a padded batch then fits as well
+  const int64_t P = (int64_t)tab.per_layer * c->n_layers, n = 2 * (int64_t)q_max;
   const int64_t rpc_max = ((int64_t)E_max * S_max + 31) / 32 * 32;
-  int64_t n = 2 * (int64_t)q_max, T = n * rpc_max;
-  int d = c->d_model, dh = d / c->n_heads, dkv = c->n_kv_heads * dh, f = c->d_ffn;
-  size_t es = elem_size(c->dtype), as = acc_size(c->dtype);
-  Buffers bb;
+  const int d = c->d_model, dh = d / c->n_heads, dkv = c->n_kv_heads * dh, f = c->d_ffn;
   if (c->pos == MPZ_POS_ROPE) {
     bb.rope_cos = cv.take<float>((size_t)c->max_seq * (dh / 2));
     bb.rope_sin = cv.take<float>((size_t)c->max_seq * (dh / 2));
   }
   bb.pert = cv.take<float>((size_t)(n * P));
-  bb.h = cv.take<float>((size_t)T * d);
-  bb.x = cv.take<unsigned char>((size_t)T * d * es);
-  bb.qkv = cv.take<unsigned char>((size_t)T * (d + 2 * dkv) * es);
-  bb.attn = cv.take<unsigned char>((size_t)T * d * es);
-  bb.t = cv.take<unsigned char>((size_t)T * 4 * c->lora_rank * es);
-  bb.u = cv.take<unsigned char>((size_t)T * f * es);
-  size_t stage_elems = 0;
-  if (c->pos == MPZ_POS_ROPE) stage_elems = (size_t)T * (d + 2 * dkv);
-  if (c->act == MPZ_ACT_SWIGLU && (size_t)T * 2 * f > stage_elems) stage_elems = (size_t)T * 2 * f;
-  if (stage_elems) bb.stage = cv.take<unsigned char>(stage_elems * as);
-  int64_t loss_rows = c->loss_mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS ? T : n * E_max;
-  if (c->loss_mode == MPZ_LOSS_LAST_POS_LABEL_SUBSET) {
-    bb.chunk_rows = (int)loss_rows;
-    bb.logits = cv.take<float>((size_t)loss_rows * 2);
-  } else {
-    bb.chunk_rows = (int)(loss_rows < 4096 ? loss_rows : 4096);
-    bb.logits = cv.take<float>((size_t)bb.chunk_rows * c->vocab);
-  }
-  bb.ce = cv.take<float>((size_t)loss_rows);
-  bb.target = cv.take<int32_t>((size_t)loss_rows);
   if (c->dtype == MPZ_DTYPE_BF16) {
-    int rp = (2 * c->lora_rank + 15) / 16 * 16;
+    const int rp = (2 * c->lora_rank + 15) / 16 * 16;
     int64_t per_layer = 0;
     for (int i = 0; i < tab.n_tensors; ++i)
       per_layer += (tab.local_id[i] & 1) ? (int64_t)tab.cols[i] * rp : (int64_t)2 * tab.rows[i] * tab.cols[i];
     bb.packed = cv.take<uint16_t>((size_t)(n * per_layer * c->n_layers));
-    for (int i = 0; i < 3; ++i) bb.tp[i] = cv.take<uint16_t>((size_t)T * rp);
   }
   bb.row_pos = cv.take<int32_t>((size_t)rpc_max);
   bb.row_end = cv.take<int32_t>((size_t)rpc_max);
@@ -161,6 +136,48 @@ size_t carve(const mpz_config* c, int q_max, int E_max, int S_max, void* base, B
     if ((size_t)d * f > big) big = (size_t)d * f;
     bb.wq = cv.take<uint16_t>(big);
   }
+}
+
+// What one pass needs and nothing outlives: the activations of ONE block for n stacked copies of rpc rows each
+// (E sequences per copy), staging, and the loss scratch.  Every buffer is written by the pass before it is read.
+void carve_activations(const mpz_config* c, int64_t n, int64_t rpc, int64_t E, Carver& cv, Buffers& bb) {
+  const int64_t T = n * rpc;
+  const int d = c->d_model, dh = d / c->n_heads, dkv = c->n_kv_heads * dh, f = c->d_ffn;
+  const size_t es = elem_size(c->dtype), as = acc_size(c->dtype);
+  bb.h = cv.take<float>((size_t)T * d);
+  bb.x = cv.take<unsigned char>((size_t)T * d * es);
+  bb.qkv = cv.take<unsigned char>((size_t)T * (d + 2 * dkv) * es);
+  bb.attn = cv.take<unsigned char>((size_t)T * d * es);
+  bb.t = cv.take<unsigned char>((size_t)T * 4 * c->lora_rank * es);
+  bb.u = cv.take<unsigned char>((size_t)T * f * es);
+  size_t stage_elems = 0;
+  if (c->pos == MPZ_POS_ROPE) stage_elems = (size_t)T * (d + 2 * dkv);
+  if (c->act == MPZ_ACT_SWIGLU && (size_t)T * 2 * f > stage_elems) stage_elems = (size_t)T * 2 * f;
+  bb.stage = stage_elems ? cv.take<unsigned char>(stage_elems * as) : nullptr;
+  const int64_t loss_rows = c->loss_mode == MPZ_LOSS_NEXT_TOKEN_ALL_POS ? T : n * E;
+  if (c->loss_mode == MPZ_LOSS_LAST_POS_LABEL_SUBSET) {
+    bb.chunk_rows = (int)loss_rows;
+    bb.logits = cv.take<float>((size_t)loss_rows * 2);
+  } else {
+    bb.chunk_rows = (int)(loss_rows < 4096 ? loss_rows : 4096);
+    bb.logits = cv.take<float>((size_t)bb.chunk_rows * c->vocab);
+  }
+  bb.ce = cv.take<float>((size_t)loss_rows);
+  bb.target = cv.take<int32_t>((size_t)loss_rows);
+  for (int i = 0; i < 3; ++i) bb.tp[i] = nullptr;
+  if (c->dtype == MPZ_DTYPE_BF16) {
+    const int rp = (2 * c->lora_rank + 15) / 16 * 16;
+    for (int i = 0; i < 3; ++i) bb.tp[i] = cv.take<uint16_t>((size_t)T * rp);
+  }
+}
+
+size_t carve(const mpz_config* c, int q_max, int E_max, int S_max, void* base, Buffers* b) {
+  Carver cv(base);
+  Buffers bb;
+  carve_persistent(c, q_max, E_max, S_max, cv, bb);
+  // rows per copy rounded up to whole 32-row tiles: a packed batch (mpz_forward_perturbed_packed) of anything that
+  // fits as a padded batch then fits as well
+  carve_activations(c, 2 * (int64_t)q_max, ((int64_t)E_max * S_max + 31) / 32 * 32, E_max, cv, bb);
   if (b) *b = bb;
   return (cv.off + 255) & ~(size_t)255;
 }
@@ -183,16 +200,21 @@ struct mpz_model {
   int cb = 0, nc = 0;                           // copies cb + cstep i, i < nc, are processed by the current pass
   int cstep = 1;                                //   (their activations occupy rows [cb, cb + nc) * E * S of the workspace)
   bool fuse_norm_lora = true;                   // test hook: pre-norm and LoRA bottleneck in one kernel where shapes allow
+  bool fuse_perturb_pack = true;                // test hook: noise -> bf16 operand layouts in one kernel (no fp32 copies)
+  bool pert_valid = false;                      // buf.pert holds the fp32 copies of the last mpz_regen_noise (else only
+                                                //   the bf16 operand layouts exist; ensure_pert regenerates them)
   int force_tile_cfg = 0;                       // test hook: GEMM block-tile configuration (0 = by shape)
   const int32_t* lengths = nullptr;             // [dev] per-sequence lengths of the pass in flight (right-padded batch), or null
   // packed (padding-free) batch of the pass in flight: cu [dev, E + 1] sequence starts inside a copy, `total` real
   // rows per copy, the longest sequence.  The pass then runs with one "sequence" of rows-per-copy rows per copy.
   struct Packed { const int32_t* cu = nullptr; int E = 0, total = 0, max_len = 0; } pk;
   const char* deferred = nullptr;               // set by a launch helper that had to refuse; reported by check_device
+  hipError_t deferred_device = hipSuccess;      // a HIP error met while setting up a launch; reported by check_device
   // second stream for the two-halves schedule of small models (see forward_two_halves); default priority
   hipStream_t stream2 = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   bool two_halves = true;                       // test hook: allow that schedule
+  int last_pass_streams = 0;                    // streams the last batched pass was issued on (0: none yet)
   size_t stage_row_bytes = 0;                   // staging bytes per stacked token (a copy range owns its rows of the buffer)
   std::string err;
   // optional per-launch timing by kernel category (mpz_profile_begin / _end)
@@ -229,6 +251,7 @@ mpz_status check_device(mpz_model* m, const char* where) {
     return fail(m, MPZ_ERR_SHAPE, std::string(where) + ": " + msg);
   }
   hipError_t e = hipGetLastError();
+  if (m && m->deferred_device != hipSuccess) { e = m->deferred_device; m->deferred_device = hipSuccess; }
   if (e != hipSuccess) return fail(m, MPZ_ERR_DEVICE, std::string(where) + ": " + hipGetErrorString(e));
   return MPZ_OK;
 }
@@ -296,6 +319,12 @@ WeightRef weight_operand(mpz_model* m, const void* w, const float* s, int N, int
   return {m->buf.wq, nullptr};
 }
 
+// A GEMM launch whose set-up error (the kernel's LDS limit could not be raised) is kept for check_device
+void launch_checked(mpz_model* m, const MfmaGemmArgs& g) {
+  const hipError_t e = launch_gemm_mfma(m->stream, g);
+  if (e != hipSuccess && m->deferred_device == hipSuccess) m->deferred_device = e;
+}
+
 // Every base-weight GEMM of the pass goes through here (kernel selection and optional timing).  Returns false
 // (nothing launched) only when a fused rotary epilogue was requested and the shape does not allow it.
 bool gemm(mpz_model* m, const LinearArgs& a) {
@@ -310,7 +339,7 @@ bool gemm(mpz_model* m, const LinearArgs& a) {
     g.tile_cfg = m->force_tile_cfg;
     if (!mfma_gemm_supported(g)) return false;
     ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)a.N * a.K, 2.0 * ((double)a.M * a.K + (double)a.N * a.K + (double)a.M * a.N));
-    launch_gemm_mfma(m->stream, g);
+    launch_checked(m, g);
     return true;
   }
   ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)a.N * a.K,
@@ -323,7 +352,7 @@ bool gemm(mpz_model* m, const LinearArgs& a) {
     g.out_f32 = a.out_kind != 0; g.out = a.out; g.ldo = a.N;   // bf16 models stage in fp32
     g.tile_cfg = m->force_tile_cfg;
     for (int i = 0; i < a.n_seg; ++i) g.seg[i] = a.mseg[i];
-    if (mfma_gemm_supported(g)) { launch_gemm_mfma(m->stream, g); return true; }
+    if (mfma_gemm_supported(g)) { launch_checked(m, g); return true; }
   }
   if (a.w_scale != nullptr) {                  // no shape-agnostic kernel reads int8 weights: refuse, loudly
     m->deferred = "int8 weights: a GEMM of this pass has a shape the MFMA kernel does not take";
@@ -343,7 +372,7 @@ bool gemm_swiglu_mfma(mpz_model* m, const LinearArgs& a, int f, void* u_out) {
   if (!mfma_gemm_supported(g)) return false;
   ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)(2 * f) * a.K,
                2.0 * ((double)a.M * a.K + 2.0 * f * a.K + (double)a.M * f));
-  launch_gemm_mfma(m->stream, g);
+  launch_checked(m, g);
   return true;
 }
 
@@ -352,6 +381,52 @@ int tensor_slot(const mpz_model* m, int target, int factor) {
   for (int i = 0; i < m->tab.n_tensors; ++i)
     if (m->tab.local_id[i] == target * 2 + factor) return i;
   return 0;
+}
+
+// The fp32 perturbed copies (master layout) of the last mpz_regen_noise.  bf16 models whose pass runs on the MFMA
+// kernels read only the bf16 operand layouts, so mpz_regen_noise writes those alone; whoever needs the fp32 form
+// (a shape the MFMA kernels refuse, the stateful update, the test hook) regenerates it here from the same seed -
+// the masters have not changed since, so these are the same factors.  Enqueued on the model's stream.
+void ensure_pert(mpz_model* m) {
+  if (m->pert_valid) return;
+  ProfScope ps(m, MPZ_PROF_NOISE, 0.0, 4.0 * m->P * (1.0 + 2.0 * m->q));
+  launch_perturb(m->stream, m->masters, m->buf.pert, m->P, m->tab, m->seed, m->step, m->q, m->eps, m->cfg.perturb_A);
+  m->pert_valid = true;
+}
+
+// Will every adapted projection of a pass over copies of E x S rows take the MFMA low-rank path (the same checks as
+// run_qkv / run_layers make when they choose)?  If not, the pass reads the fp32 copies.
+bool lora_path_is_mfma(const mpz_model* m, int E, int S) {
+  if (!m->use_mfma) return false;
+  const mpz_config& c = m->cfg;
+  // (judged for the largest pass, all 2q copies: what it allows, every smaller range of copies allows too)
+  const int rpc = E * S, T = 2 * m->q * rpc, d = c.d_model, dkv = c.n_kv_heads * (d / c.n_heads), nqkv = d + 2 * dkv;
+  const int col0[3] = {0, d, d + dkv}, col1[3] = {d, d + dkv, nqkv};
+  MfmaLoraDownArgs md{};
+  md.T = T; md.K = d; md.rank = c.lora_rank; md.rows_per_copy = rpc; md.rp = m->rp;
+  MfmaGemmArgs probe{};
+  probe.M = T; probe.N = nqkv; probe.K = d; probe.rows_per_copy = rpc;
+  int nt = 0;
+  for (int t = 0; t < 3; ++t)
+    if (c.lora_targets & (1u << t)) {
+      probe.seg[nt].col_begin = col0[t]; probe.seg[nt].col_end = col1[t]; probe.seg[nt].rp = m->rp;
+      ++nt;
+    }
+  md.n_targets = nt; probe.n_seg = nt;
+  if (nt && !(mfma_lora_down_supported(md) && mfma_gemm_supported(probe))) return false;
+  if (c.lora_targets & MPZ_TARGET_O) {
+    md.n_targets = 1;
+    MfmaGemmArgs po{};
+    po.M = T; po.N = d; po.K = d; po.rows_per_copy = rpc; po.n_seg = 1;
+    po.seg[0].col_begin = 0; po.seg[0].col_end = d; po.seg[0].rp = m->rp;
+    if (!(mfma_lora_down_supported(md) && mfma_gemm_supported(po))) return false;
+  }
+  return true;
+}
+
+// Called by every pass before its first launch, on the caller's stream: make the fp32 copies if this pass reads them.
+void prepare_factors(mpz_model* m, int E, int S) {
+  if (!m->pert_valid && !lora_path_is_mfma(m, E, S)) ensure_pert(m);
 }
 
 // fp32 residual rows -> operand type
@@ -439,6 +514,7 @@ void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, bool rope, int
     }
     if (norm_h != nullptr) { norm(m, norm_h, d, lw.ln1_g, lw.ln1_b, b.x, T); norm_h = nullptr; }
     if (nt && !lora_done) {
+      if (!m->pert_valid) m->deferred = "internal: a pass needs the fp32 factor copies and they were not prepared";
       ProfScope ps(m, MPZ_PROF_LORA_DOWN, 2.0 * T * (double)d * nt * r, esz(m) * T * ((double)d + (double)nt * r));
       launch_lora_down_simple(st, da);
     }
@@ -518,6 +594,7 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
         }
       }
       if (!o_done) {
+        if (!m->pert_valid) m->deferred = "internal: a pass needs the fp32 factor copies and they were not prepared";
         ProfScope ps(m, MPZ_PROF_LORA_DOWN, 2.0 * T * (double)d * r, esz(m) * T * ((double)d + (double)r));
         launch_lora_down_simple(st, oda);
       }
@@ -573,7 +650,7 @@ bool head_ce_fused(mpz_model* m, const Buffers& b, const void* x, int rows, int 
   if (!mfma_gemm_supported(g)) return false;
   { ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * rows * (double)vocab * d,
                  2.0 * ((double)rows * d + (double)vocab * d) + 8.0 * slots * (double)rows);
-    launch_gemm_mfma(m->stream, g); }
+    launch_checked(m, g); }
   { ProfScope ps(m, MPZ_PROF_LOSS, 0.0, 8.0 * slots * (double)rows);
     launch_ce_combine(m->stream, slots, rows, g.ce_max, g.ce_sum, g.ce_tlogit, target, ce); }
   return true;
@@ -778,14 +855,23 @@ mpz_status mpz_regen_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t q
   if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_regen_noise: NULL model");
   if (q < 1 || q > m->q_max) return fail(m, MPZ_ERR_SHAPE, "q outside [1, q_max]");
   if (!std::isfinite(eps) || eps < 0.f) return fail(m, MPZ_ERR_CONFIG, "eps must be finite and non-negative");
-  {
-    ProfScope ps(m, MPZ_PROF_NOISE, 0.0, 4.0 * m->P * (1.0 + 2.0 * q));
-    launch_perturb(m->stream, m->masters, m->buf.pert, m->P, m->tab, seed, step, q, eps, m->cfg.perturb_A);
+  if (m->use_mfma && m->fuse_perturb_pack && perturb_pack_supported(m->tab, m->cfg.lora_rank, m->rp)) {
+    // bf16 models: the noise goes straight into the bf16 hi / lo operand layouts; no fp32 copy is written
+    ProfScope ps(m, MPZ_PROF_NOISE, 0.0, 4.0 * m->P + 2.0 * q * 2.0 * m->packed_per_copy);
+    launch_perturb_pack(m->stream, m->masters, m->buf.packed, m->packed_per_copy, m->tab, m->cfg.n_layers, m->cfg.lora_rank,
+                        m->rp, seed, step, q, eps, m->cfg.perturb_A);
+    m->pert_valid = false;
+  } else {
+    {
+      ProfScope ps(m, MPZ_PROF_NOISE, 0.0, 4.0 * m->P * (1.0 + 2.0 * q));
+      launch_perturb(m->stream, m->masters, m->buf.pert, m->P, m->tab, seed, step, q, eps, m->cfg.perturb_A);
+    }
+    m->pert_valid = true;
+    ProfScope ps_pack(m, MPZ_PROF_PACK, 0.0, m->use_mfma ? 2.0 * q * (4.0 * m->P + 2.0 * m->packed_per_copy) : 0.0);
+    if (m->use_mfma)
+      launch_pack_factors(m->stream, m->buf.pert, m->P, 2 * q, m->tab, m->cfg.n_layers, m->cfg.lora_rank, m->rp, m->buf.packed,
+                          m->packed_per_copy);
   }
-  ProfScope ps_pack(m, MPZ_PROF_PACK, 0.0, m->use_mfma ? 2.0 * q * (4.0 * m->P + 2.0 * m->packed_per_copy) : 0.0);
-  if (m->use_mfma)
-    launch_pack_factors(m->stream, m->buf.pert, m->P, 2 * q, m->tab, m->cfg.n_layers, m->cfg.lora_rank, m->rp, m->buf.packed,
-                        m->packed_per_copy);
   m->have_noise = true; m->seed = seed; m->step = step; m->q = q; m->eps = eps;
   m->cb = 0; m->nc = 2 * q;
   return check_device(m, "mpz_regen_noise");
@@ -848,20 +934,32 @@ void forward_two_halves(mpz_model* m, const int32_t* tokens, const int32_t* labe
 
 }  // namespace
 
+namespace {
+// Argument checks shared by every pass over E x S token batches: nothing is enqueued on a refused call.
+mpz_status validate_pass(mpz_model* m, const char* who, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
+                         const float* losses_out) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, std::string(who) + ": NULL model");
+  if (!tokens || !losses_out) return fail(m, MPZ_ERR_NULL, std::string(who) + ": NULL tokens or losses_out");
+  if (m->cfg.loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS && !labels) return fail(m, MPZ_ERR_NULL, std::string(who) + ": this loss mode needs labels");
+  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, std::string(who) + " before mpz_regen_noise");
+  if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, std::string(who) + ": E or S outside what the model was initialised for");
+  if (m->cfg.weight_quant == MPZ_WEIGHT_QUANT_INT8 && ((E * S) % 32 || !m->use_mfma))
+    return fail(m, MPZ_ERR_SHAPE, std::string(who) + ": int8 weights: E*S must be a multiple of 32 (MFMA kernels only)");
+  return MPZ_OK;
+}
+}  // namespace
+
 mpz_status mpz_forward_perturbed(mpz_model* m, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
                                  float* losses_out) {
-  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_forward_perturbed: NULL model");
-  if (!tokens || !losses_out) return fail(m, MPZ_ERR_NULL, "mpz_forward_perturbed: NULL tokens or losses_out");
-  if (m->cfg.loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS && !labels) return fail(m, MPZ_ERR_NULL, "this loss mode needs labels");
-  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_forward_perturbed before mpz_regen_noise");
-  if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
-  if (m->cfg.weight_quant == MPZ_WEIGHT_QUANT_INT8 && ((E * S) % 32 || !m->use_mfma))
-    return fail(m, MPZ_ERR_SHAPE, "int8 weights: E*S must be a multiple of 32 (MFMA kernels only)");
+  if (const mpz_status st = validate_pass(m, "mpz_forward_perturbed", tokens, labels, E, S, losses_out)) return st;
   m->cb = 0; m->nc = 2 * m->q;
+  prepare_factors(m, E, S);
   if (use_two_halves(m, E, S)) {
+    m->last_pass_streams = 2;
     forward_two_halves(m, tokens, labels, E, S, losses_out);
     return check_device(m, "mpz_forward_perturbed");
   }
+  m->last_pass_streams = 1;
   run_embed(m, tokens, E, S, m->buf.h);
   run_layers(m, m->buf.h, 0, m->cfg.n_layers, E, S);
   run_head(m, m->buf.h, tokens, labels, E, S, losses_out);
@@ -900,6 +998,7 @@ mpz_status mpz_forward_perturbed_packed(mpz_model* m, const int32_t* tokens, con
     return fail(m, MPZ_ERR_SHAPE, "int8 weights: MFMA kernels only");
   m->pk.cu = cu_seqlens; m->pk.E = E; m->pk.total = total_tokens; m->pk.max_len = max_len;
   launch_packed_index(m->stream, cu_seqlens, E, (int)rows, m->buf.row_pos, m->buf.row_end);
+  prepare_factors(m, 1, (int)rows);
   m->cb = 0; m->nc = 2 * m->q;
   run_embed(m, tokens, 1, (int)rows, m->buf.h);
   run_layers(m, m->buf.h, 0, m->cfg.n_layers, 1, (int)rows);
@@ -910,12 +1009,9 @@ mpz_status mpz_forward_perturbed_packed(mpz_model* m, const int32_t* tokens, con
 
 mpz_status mpz_forward_copies(mpz_model* m, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
                               int32_t copy_begin, int32_t n_copies, float* losses_out) {
-  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_forward_copies: NULL model");
-  if (!tokens || !losses_out) return fail(m, MPZ_ERR_NULL, "mpz_forward_copies: NULL tokens or losses_out");
-  if (m->cfg.loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS && !labels) return fail(m, MPZ_ERR_NULL, "this loss mode needs labels");
-  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_forward_copies before mpz_regen_noise");
-  if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
+  if (const mpz_status st = validate_pass(m, "mpz_forward_copies", tokens, labels, E, S, losses_out)) return st;
   if (copy_begin < 0 || n_copies < 1 || copy_begin + n_copies > 2 * m->q) return fail(m, MPZ_ERR_SHAPE, "copy range outside [0, 2q)");
+  prepare_factors(m, E, S);
   m->cb = copy_begin; m->nc = n_copies;
   float* h = m->buf.h + (size_t)copy_begin * E * S * m->cfg.d_model;
   run_embed(m, tokens, E, S, h);
@@ -927,16 +1023,11 @@ mpz_status mpz_forward_copies(mpz_model* m, const int32_t* tokens, const int32_t
 
 mpz_status mpz_forward_copies_strided(mpz_model* m, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
                                       int32_t copy_begin, int32_t n_copies, int32_t copy_step, float* losses_out) {
-  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_forward_copies_strided: NULL model");
-  if (!tokens || !losses_out) return fail(m, MPZ_ERR_NULL, "mpz_forward_copies_strided: NULL tokens or losses_out");
-  if (m->cfg.loss_mode != MPZ_LOSS_NEXT_TOKEN_ALL_POS && !labels) return fail(m, MPZ_ERR_NULL, "this loss mode needs labels");
-  if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_forward_copies_strided before mpz_regen_noise");
-  if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
+  if (const mpz_status st = validate_pass(m, "mpz_forward_copies_strided", tokens, labels, E, S, losses_out)) return st;
   if (copy_begin < 0 || n_copies < 1 || copy_step < 1 || copy_begin + (int64_t)(n_copies - 1) * copy_step >= 2 * m->q ||
       copy_begin + n_copies > 2 * m->q_max)
     return fail(m, MPZ_ERR_SHAPE, "copies outside [0, 2q)");
-  if (m->cfg.weight_quant == MPZ_WEIGHT_QUANT_INT8 && ((E * S) % 32 || !m->use_mfma))
-    return fail(m, MPZ_ERR_SHAPE, "int8 weights: E*S must be a multiple of 32 (MFMA kernels only)");
+  prepare_factors(m, E, S);
   m->cb = copy_begin; m->nc = n_copies; m->cstep = copy_step;
   float* h = m->buf.h + (size_t)copy_begin * E * S * m->cfg.d_model;
   run_embed(m, tokens, E, S, h);
@@ -959,6 +1050,7 @@ mpz_status mpz_debug_run_layers(mpz_model* m, float* h, int32_t layer_begin, int
   if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_debug_run_layers before mpz_regen_noise");
   if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
   if (layer_begin < 0 || layer_end > m->cfg.n_layers || layer_begin > layer_end) return fail(m, MPZ_ERR_SHAPE, "layer range outside the model");
+  prepare_factors(m, E, S);
   run_layers(m, h, layer_begin, layer_end, E, S);
   return check_device(m, "mpz_debug_run_layers");
 }
@@ -994,6 +1086,7 @@ mpz_status mpz_zo_update_regen(mpz_model* m, const float* losses, float lr, uint
   if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "mpz_zo_update_regen before mpz_regen_noise");
   if (!(m->eps > 0.f)) return fail(m, MPZ_ERR_CONFIG, "the stored pairs were made with eps = 0: the two-point quotient is undefined");
   if (!std::isfinite(lr)) return fail(m, MPZ_ERR_CONFIG, "lr must be finite");
+  ensure_pert(m);                               // the stored pairs in fp32 (a stateful run keeps them from here on)
   {
     ProfScope ps(m, MPZ_PROF_UPDATE, 0.0, 8.0 * m->P * (1.0 + 2.0 * m->q));
     launch_update_regen(m->stream, m->masters, m->buf.pert, m->P, m->tab, m->seed, next_step, m->q, m->eps, lr,
@@ -1038,6 +1131,7 @@ mpz_status mpz_debug_perturbed_copy(mpz_model* m, int32_t c, float* out) {
   if (!m || !out) return fail(m, MPZ_ERR_NULL, "mpz_debug_perturbed_copy: NULL argument");
   if (!m->have_noise) return fail(m, MPZ_ERR_STATE, "no perturbed copies: call mpz_regen_noise first");
   if (c < 0 || c >= 2 * m->q) return fail(m, MPZ_ERR_SHAPE, "copy index outside [0, 2q)");
+  ensure_pert(m);
   hipError_t e = hipMemcpyAsync(out, m->buf.pert + (int64_t)c * m->P, (size_t)m->P * 4, hipMemcpyDeviceToDevice, m->stream);
   if (e != hipSuccess) return fail(m, MPZ_ERR_DEVICE, hipGetErrorString(e));
   return MPZ_OK;
@@ -1049,6 +1143,7 @@ mpz_status mpz_debug_qkv_projection(mpz_model* m, const void* x, int32_t layer, 
   if (E < 1 || E > m->E_max || S < 2 || S > m->S_max) return fail(m, MPZ_ERR_SHAPE, "E or S outside what the model was initialised for");
   if (layer < 0 || layer >= m->cfg.n_layers) return fail(m, MPZ_ERR_SHAPE, "layer outside the model");
   if (m->cfg.dtype != MPZ_DTYPE_BF16) return fail(m, MPZ_ERR_CONFIG, "mpz_debug_qkv_projection is for bf16 models");
+  prepare_factors(m, E, S);
   Buffers b = m->buf;
   b.x = const_cast<void*>(x);
   run_qkv(m, b, layer, E, S, false, 1, out);
@@ -1075,7 +1170,8 @@ mpz_status mpz_debug_gemm_bf16(int32_t M, int32_t N, int32_t K, const void* x, c
   g.out_f32 = out_f32; g.out = out; g.ldo = N; g.tile_cfg = tile_cfg;
   if (act == MPZ_ACT_SWIGLU) { g.dual = 1; g.dual_offset = N; g.w_rows = 2 * N; g.act = -1; }
   if (!mfma_gemm_supported(g)) return fail(nullptr, MPZ_ERR_SHAPE, "shape not supported by the MFMA GEMM (K % 64, N % 4)");
-  launch_gemm_mfma((hipStream_t)hip_stream, g);
+  const hipError_t le = launch_gemm_mfma((hipStream_t)hip_stream, g);
+  if (le != hipSuccess) return fail(nullptr, MPZ_ERR_DEVICE, std::string("mpz_debug_gemm_bf16: ") + hipGetErrorString(le));
   return check_device(nullptr, "mpz_debug_gemm_bf16");
 }
 
@@ -1088,7 +1184,8 @@ mpz_status mpz_debug_gemm_int8(int32_t M, int32_t N, int32_t K, const void* x, c
   g.act = act; g.out_f32 = out_f32; g.out = out; g.ldo = N; g.tile_cfg = tile_cfg;
   if (act == MPZ_ACT_SWIGLU) { g.dual = 1; g.dual_offset = N; g.w_rows = 2 * N; g.act = -1; }
   if (!mfma_gemm_supported(g)) return fail(nullptr, MPZ_ERR_SHAPE, "shape not supported by the MFMA GEMM (K % 64, N % 4, scale alignment)");
-  launch_gemm_mfma((hipStream_t)hip_stream, g);
+  const hipError_t le = launch_gemm_mfma((hipStream_t)hip_stream, g);
+  if (le != hipSuccess) return fail(nullptr, MPZ_ERR_DEVICE, std::string("mpz_debug_gemm_int8: ") + hipGetErrorString(le));
   return check_device(nullptr, "mpz_debug_gemm_int8");
 }
 
@@ -1097,6 +1194,8 @@ mpz_status mpz_debug_set_two_halves(mpz_model* m, int32_t enable) {
   m->two_halves = enable != 0;
   return MPZ_OK;
 }
+
+int32_t mpz_debug_last_pass_streams(const mpz_model* m) { return m ? m->last_pass_streams : 0; }
 
 mpz_status mpz_debug_mfma_probe(const void* operands, int32_t blocks, int32_t iters, int32_t with_lds, float* out,
                                 void* hip_stream) {
@@ -1122,9 +1221,17 @@ mpz_status mpz_debug_set_fused_norm_lora(mpz_model* m, int32_t enable) {
   return MPZ_OK;
 }
 
+mpz_status mpz_debug_set_fused_perturb_pack(mpz_model* m, int32_t enable) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_set_fused_perturb_pack: NULL model");
+  m->fuse_perturb_pack = enable != 0;
+  m->have_noise = false;
+  return MPZ_OK;
+}
+
 mpz_status mpz_debug_set_tile_config(mpz_model* m, int32_t tile_cfg) {
   if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_set_tile_config: NULL model");
-  if (tile_cfg < 0 || tile_cfg > 15) return fail(m, MPZ_ERR_CONFIG, "tile configuration outside [0, 15]");
+  if (!(tile_cfg == 0 || tile_cfg == 1 || tile_cfg == 6 || (tile_cfg >= 9 && tile_cfg <= 12)))
+    return fail(m, MPZ_ERR_CONFIG, "tile configuration must be 0 (by shape), 1, 6, 9, 10, 11 or 12");
   m->force_tile_cfg = tile_cfg;
   return MPZ_OK;
 }

@@ -132,6 +132,122 @@ __global__ void __launch_bounds__(256) perturb_kernel(const float4* __restrict__
   }
 }
 
+// Perturbation written straight into the bf16 MFMA operand layouts (the stacked pass of a bf16 model reads nothing
+// else): value = master (+/-) eps z as in perturb_kernel, then hi = bf16(value), lo = bf16(value - hi).
+//   A [K, r] of copy c  ->  [2][K / 8][r][8]: element (k, j) of the hi part at ((k / 8) r + j) 8 + k % 8, lo part K r further
+//   B [r, k_out]        ->  [k_out][rp] = [hi(r) | lo(r) | 0]
+// One thread = one query k (both signs) x one work item of a layer: for an A factor 8 consecutive rows k x 4 columns j
+// (8 generator calls -> four 16-byte pieces of each part), for a B factor 4 rows j x 4 output features (4 calls ->
+// an 8-byte piece of the hi and of the lo half of four packed rows).  Same generator coordinates as perturb_kernel:
+// the two paths give the same factors.
+// two values -> {hi pair, lo pair} (low half = first value); round-to-nearest-even conversions in hardware
+__device__ __forceinline__ void split_bf16x2(float a, float b, uint32_t& hi, uint32_t& lo) {
+  hi = pack_bf16x2(a, b);
+  lo = pack_bf16x2(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xFFFF0000u));
+}
+
+template <int RANK>
+__global__ void __launch_bounds__(256) perturb_pack_kernel(const float* __restrict__ masters, uint16_t* __restrict__ packed,
+                                                           int64_t packed_per_copy, LoraLayerTable tab, int n_layers, int rp,
+                                                           int items_per_layer, uint32_t k0, uint32_t k1, uint32_t step,
+                                                           float eps, int perturb_A) {
+  typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+  typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)items_per_layer * n_layers) return;
+  const uint32_t kq = blockIdx.y;                       // query
+  const int layer = (int)(idx / items_per_layer);
+  int item = (int)(idx % items_per_layer);
+  int i = 0;
+  int64_t poff = 0;
+  for (;; ++i) {                                        // which factor of the layer, and where its packed form starts
+    const bool isB = tab.local_id[i] & 1;
+    const int cnt = isB ? tab.cols[i] / 4 * (RANK / 4) : tab.rows[i] / 8 * (RANK / 4);
+    if (item < cnt) break;
+    item -= cnt;
+    poff += isB ? (int64_t)tab.cols[i] * rp : (int64_t)2 * tab.rows[i] * tab.cols[i];
+  }
+  int64_t per_layer_packed = 0;
+  for (int t = 0; t < tab.n_tensors; ++t)
+    per_layer_packed += (tab.local_id[t] & 1) ? (int64_t)tab.cols[t] * rp : (int64_t)2 * tab.rows[t] * tab.cols[t];
+  const uint32_t tensor_id = (uint32_t)(layer * 8 + tab.local_id[i]);
+  const float* src = masters + (int64_t)layer * tab.per_layer + tab.off[i];
+  uint16_t* dst_p = packed + (int64_t)(2 * kq) * packed_per_copy + (int64_t)layer * per_layer_packed + poff;
+  uint16_t* dst_m = dst_p + packed_per_copy;
+  if ((tab.local_id[i] & 1) == 0) {                     // A [K, r]
+    const int K = tab.rows[i], chunk = item / (RANK / 4), j0 = (item % (RANK / 4)) * 4, kb = chunk * 8;
+    const bool frozen = !perturb_A;
+    uint32_t hp[4][4], lp[4][4], hm[4][4], lm[4][4];    // [column][pair of rows]
+#pragma unroll
+    for (int k2 = 0; k2 < 4; ++k2) {
+      float vp[2][4], vm[2][4];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int64_t e = (int64_t)(kb + 2 * k2 + h) * RANK + j0;   // flat element index of (k, j0): a multiple of 4
+        const float4 m = *(const float4*)(src + e);
+        const float mv[4] = {m.x, m.y, m.z, m.w};
+        float z[4] = {0.f, 0.f, 0.f, 0.f};
+        if (!frozen) normals4(philox4x32_10((uint32_t)(e >> 2), tensor_id, step, kq, k0, k1), z);
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const float p = eps * z[jj];
+          vp[h][jj] = frozen ? mv[jj] : mv[jj] + p;
+          vm[h][jj] = frozen ? mv[jj] : mv[jj] - p;
+        }
+      }
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        split_bf16x2(vp[0][jj], vp[1][jj], hp[jj][k2], lp[jj][k2]);
+        split_bf16x2(vm[0][jj], vm[1][jj], hm[jj][k2], lm[jj][k2]);
+      }
+    }
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const int64_t o = ((int64_t)chunk * RANK + j0 + jj) * 8;
+      *(u32x4*)(dst_p + o) = u32x4{hp[jj][0], hp[jj][1], hp[jj][2], hp[jj][3]};
+      *(u32x4*)(dst_p + (int64_t)K * RANK + o) = u32x4{lp[jj][0], lp[jj][1], lp[jj][2], lp[jj][3]};
+      *(u32x4*)(dst_m + o) = u32x4{hm[jj][0], hm[jj][1], hm[jj][2], hm[jj][3]};
+      *(u32x4*)(dst_m + (int64_t)K * RANK + o) = u32x4{lm[jj][0], lm[jj][1], lm[jj][2], lm[jj][3]};
+    }
+  } else {                                              // B [r, k_out]: rows j0 .. j0+3, features n0 .. n0+3
+    const int kout = tab.cols[i], j0 = (item % (RANK / 4)) * 4, n0 = (item / (RANK / 4)) * 4;
+    float vp[4][4], vm[4][4];                           // [row j][feature]
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int64_t e = (int64_t)(j0 + j) * kout + n0;
+      const float4 m = *(const float4*)(src + e);
+      const float mv[4] = {m.x, m.y, m.z, m.w};
+      float z[4];
+      normals4(philox4x32_10((uint32_t)(e >> 2), tensor_id, step, kq, k0, k1), z);
+#pragma unroll
+      for (int nn = 0; nn < 4; ++nn) {
+        const float p = eps * z[nn];
+        vp[j][nn] = mv[nn] + p;
+        vm[j][nn] = mv[nn] - p;
+      }
+    }
+#pragma unroll
+    for (int nn = 0; nn < 4; ++nn) {
+      uint16_t* rowp = dst_p + (int64_t)(n0 + nn) * rp;
+      uint16_t* rowm = dst_m + (int64_t)(n0 + nn) * rp;
+      uint32_t h0, h1, l0, l1;
+      split_bf16x2(vp[0][nn], vp[1][nn], h0, l0);
+      split_bf16x2(vp[2][nn], vp[3][nn], h1, l1);
+      *(u32x2*)(rowp + j0) = u32x2{h0, h1};
+      *(u32x2*)(rowp + RANK + j0) = u32x2{l0, l1};
+      split_bf16x2(vm[0][nn], vm[1][nn], h0, l0);
+      split_bf16x2(vm[2][nn], vm[3][nn], h1, l1);
+      *(u32x2*)(rowm + j0) = u32x2{h0, h1};
+      *(u32x2*)(rowm + RANK + j0) = u32x2{l0, l1};
+      if (j0 == 0)
+        for (int c = 2 * RANK; c < rp; c += 4) {
+          *(u32x2*)(rowp + c) = u32x2{0u, 0u};
+          *(u32x2*)(rowm + c) = u32x2{0u, 0u};
+        }
+    }
+  }
+}
+
 constexpr int MAX_Q = 64;
 
 __global__ void __launch_bounds__(256) update_kernel(float4* __restrict__ masters, int64_t n_groups, LoraLayerTable tab,
@@ -249,6 +365,31 @@ void launch_perturb(hipStream_t st, const float* masters, float* pert, int64_t P
   int64_t ng = P / 4;
   perturb_kernel<<<blocks_for(ng, 256), 256, 0, st>>>((const float4*)masters, (float4*)pert, ng, tab,
                                                       (uint32_t)seed, (uint32_t)(seed >> 32), step, q, eps, perturb_A);
+}
+
+bool perturb_pack_supported(const LoraLayerTable& tab, int rank, int rp) {
+  if (!(rank == 4 || rank == 8 || rank == 16) || rp % 4) return false;
+  for (int t = 0; t < tab.n_tensors; ++t) {
+    const bool isB = tab.local_id[t] & 1;
+    if (!isB && tab.rows[t] % 8) return false;
+    if (isB && tab.cols[t] % 4) return false;
+    if (tab.off[t] % 4) return false;
+  }
+  return tab.per_layer % 4 == 0;
+}
+
+void launch_perturb_pack(hipStream_t st, const float* masters, void* packed, int64_t packed_per_copy,
+                         const LoraLayerTable& tab, int n_layers, int rank, int rp, uint64_t seed, uint32_t step, int q,
+                         float eps, int perturb_A) {
+  int items = 0;
+  for (int t = 0; t < tab.n_tensors; ++t)
+    items += (tab.local_id[t] & 1) ? tab.cols[t] / 4 * (rank / 4) : tab.rows[t] / 8 * (rank / 4);
+  const dim3 grid(blocks_for((int64_t)items * n_layers, 256), (unsigned)q);
+  const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+  uint16_t* pk = (uint16_t*)packed;
+  if (rank == 4) perturb_pack_kernel<4><<<grid, 256, 0, st>>>(masters, pk, packed_per_copy, tab, n_layers, rp, items, k0, k1, step, eps, perturb_A);
+  else if (rank == 8) perturb_pack_kernel<8><<<grid, 256, 0, st>>>(masters, pk, packed_per_copy, tab, n_layers, rp, items, k0, k1, step, eps, perturb_A);
+  else perturb_pack_kernel<16><<<grid, 256, 0, st>>>(masters, pk, packed_per_copy, tab, n_layers, rp, items, k0, k1, step, eps, perturb_A);
 }
 
 void launch_update(hipStream_t st, float* masters, int64_t P, const LoraLayerTable& tab, uint64_t seed, uint32_t step,

@@ -306,11 +306,25 @@ def mpz_debug_set_fused_norm_lora(handle, enable: bool):
     _check(lib.mpz_debug_set_fused_norm_lora(handle, int(enable)), handle)
 
 
+def mpz_debug_set_fused_perturb_pack(handle, enable: bool):
+    lib = load_library()
+    lib.mpz_debug_set_fused_perturb_pack.restype = C.c_int
+    lib.mpz_debug_set_fused_perturb_pack.argtypes = [C.c_void_p, C.c_int32]
+    _check(lib.mpz_debug_set_fused_perturb_pack(handle, int(enable)), handle)
+
+
 def mpz_debug_set_two_halves(handle, enable: bool):
     lib = load_library()
     lib.mpz_debug_set_two_halves.restype = C.c_int
     lib.mpz_debug_set_two_halves.argtypes = [C.c_void_p, C.c_int32]
     _check(lib.mpz_debug_set_two_halves(handle, int(enable)), handle)
+
+
+def mpz_debug_last_pass_streams(handle) -> int:
+    lib = load_library()
+    lib.mpz_debug_last_pass_streams.restype = C.c_int32
+    lib.mpz_debug_last_pass_streams.argtypes = [C.c_void_p]
+    return int(lib.mpz_debug_last_pass_streams(handle))
 
 
 def mpz_debug_set_tile_config(handle, tile_cfg: int):

@@ -102,7 +102,7 @@ def test_attention_matches_oracle_on_the_same_operands(name, S, simple):
     assert (np.abs(got - want) <= 1.01 * ulp + 2.0 ** -8 * np.abs(v).max()).all()
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 3, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15])
+@pytest.mark.parametrize("cfg", [1, 6, 9, 10, 11, 12])
 @pytest.mark.parametrize("M_,N_,K_", [(512, 512, 256), (300, 260, 192), (1024, 768, 64)])
 def test_gemm_every_tile_configuration_and_ragged_edges(cfg, M_, N_, K_):
     """x W^T + bias with ReLU, fp32 output, against the fp64 product of the same bf16 operands."""
@@ -152,7 +152,7 @@ def test_gemm_with_the_tile_chosen_by_shape(M_, N_, K_, act, bf16_out):
         assert np.abs(got - want).max() <= tol
 
 
-@pytest.mark.parametrize("cfg", [1, 5, 6])
+@pytest.mark.parametrize("cfg", [1, 6])
 def test_swiglu_dual_gemm(cfg):
     import torch
     import paper_2409_15520_amd as M
@@ -171,7 +171,7 @@ def test_swiglu_dual_gemm(cfg):
     assert np.mean(got != want) < 2e-3 and (np.abs(got - want) <= 1.01 * ulp + 1e-7).all()
 
 
-@pytest.mark.parametrize("tile_cfg", [0, 1, 2, 6, 11, 12])
+@pytest.mark.parametrize("tile_cfg", [0, 1, 6, 9, 11, 12])
 @pytest.mark.parametrize("loss_mode", ["next_token_all_pos", "last_pos_full_vocab"])
 def test_fused_head_cross_entropy(tile_cfg, loss_mode):
     """LM head with the cross-entropy folded into the GEMM (logits stay in the accumulators, per-tile maximum /

@@ -29,9 +29,9 @@ def _oracle(name):
 
 
 @pytest.mark.parametrize("name,tile_cfg", [("c3_width", 0), ("c4_width", 0), ("c5_width", 0),
-                                           ("c3_width", 5), ("c4_width", 5), ("c5_width", 5), ("c4_width", 1)])
+                                           ("c3_width", 6), ("c4_width", 6), ("c5_width", 6), ("c4_width", 1)])
 def test_full_width_stages_and_losses(name, tile_cfg):
-    """tile_cfg 5 forces the 256 x 256 eight-wave tiles (with the fused rotary epilogue for both head widths and the
+    """tile_cfg 6 forces the 256 x 256 eight-wave tiles (with the fused rotary epilogue for both head widths and the
     eight-wave SwiGLU kernel) that the full-size workloads select."""
     import torch
     import paper_2409_15520_amd as M
