@@ -179,6 +179,22 @@ mpz_status mpz_regen_noise(mpz_model* m, uint64_t seed, uint32_t step, int32_t q
 mpz_status mpz_forward_perturbed(mpz_model* m, const int32_t* tokens, const int32_t* labels,
                                  int32_t E, int32_t S, float* losses_out);
 
+/* For callers that cannot allocate or size a workspace when they call (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): mpz_forward_perturbed with the per-pass activations (residual stream,
+ * operand rows, bottleneck activations, loss scratch) in a file-scope device array of the library instead of the
+ * caller's workspace.  Same arguments, same kernels, same losses bit for bit (the pass is issued on the model's stream
+ * alone).  Calls no hipMalloc / hipFree and creates no stream or event.  The array holds
+ * mpz_noalloc_scratch_bytes() = 16 MiB per GPU for the life of the process; a pass whose activations for
+ * (2q, E, S) need more is refused with MPZ_ERR_WORKSPACE (the message states both sizes) and nothing is launched.
+ * Inputs, outputs, the perturbed factor copies of mpz_regen_noise and the tables made by mpz_init_model stay where
+ * they are (caller memory).  Every call on one GPU shares that GPU's array and nothing in it needs clearing (each
+ * buffer is written before it is read), but calls that overlap in time on one GPU - two models, two streams - race:
+ * serialise them.  Other errors as mpz_forward_perturbed, plus STATE while mpz_profile_begin is in effect or when the
+ * current device is not the model's, and DEVICE when the array's address cannot be obtained. */
+mpz_status mpz_forward_perturbed_noalloc(mpz_model* m, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
+                                         float* losses_out);
+size_t mpz_noalloc_scratch_bytes(void);
+
 /* The same pass restricted to the copies [copy_begin, copy_begin + n_copies) of the last mpz_regen_noise; writes
  * losses_out[copy_begin .. copy_begin + n_copies) and leaves the other entries untouched.  n_copies = 1 in a loop
  * over all 2q copies is the sequential evaluation that Section 3 starts from (one forward pass per perturbed

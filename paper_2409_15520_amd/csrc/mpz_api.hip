@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -13,7 +14,34 @@
 
 using namespace mpz;
 
+// Scratch of mpz_forward_perturbed_noalloc: the activations of one pass, for callers that cannot hand over (or
+// allocate) a workspace large enough at call time.  One copy per GPU, held until the process ends; its device address
+// is looked up once per device (scratch_address) and only that pointer is ever given to kernels.
+#define MPZ_NOALLOC_SCRATCH_BYTES ((size_t)16 << 20)
+static __device__ __align__(256) unsigned char scratch[MPZ_NOALLOC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up on first use per device), or null with *err set.
+void* scratch_address(int* device_out, hipError_t* err) {
+  int dev = -1;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (device_out) *device_out = dev;
+  if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    *err = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess || ptr == nullptr) { if (*err == hipSuccess) *err = hipErrorInvalidSymbol; return nullptr; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
 
 thread_local std::string g_last_error;
 
@@ -215,6 +243,7 @@ struct mpz_model {
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   bool two_halves = true;                       // test hook: allow that schedule
   int last_pass_streams = 0;                    // streams the last batched pass was issued on (0: none yet)
+  int device = -1;                              // HIP device that was current at mpz_init_model
   size_t stage_row_bytes = 0;                   // staging bytes per stacked token (a copy range owns its rows of the buffer)
   std::string err;
   // optional per-launch timing by kernel category (mpz_profile_begin / _end)
@@ -811,6 +840,11 @@ mpz_status mpz_init_model(const mpz_config* cfg, const mpz_weights* frozen, floa
   if (cfg->norm == MPZ_NORM_RMSNORM) m->w.lnf_b = nullptr;
   m->masters = lora_masters;
   m->stream = (hipStream_t)hip_stream;
+  {
+    hipError_t e = hipSuccess;                   // set-up of the allocation-free entry point: this device's scratch
+    (void)scratch_address(&m->device, &e);       // address; a failure is reported by that entry point, not here
+    (void)hipGetLastError();
+  }
   m->q_max = q_max; m->E_max = E_max; m->S_max = S_max;
   build_layout(cfg, m->tensors, m->tab);
   m->P = (int64_t)m->tab.per_layer * cfg->n_layers;
@@ -965,6 +999,44 @@ mpz_status mpz_forward_perturbed(mpz_model* m, const int32_t* tokens, const int3
   run_head(m, m->buf.h, tokens, labels, E, S, losses_out);
   return check_device(m, "mpz_forward_perturbed");
 }
+
+mpz_status mpz_forward_perturbed_noalloc(mpz_model* m, const int32_t* tokens, const int32_t* labels, int32_t E, int32_t S,
+                                         float* losses_out) {
+  if (const mpz_status st = validate_pass(m, "mpz_forward_perturbed_noalloc", tokens, labels, E, S, losses_out)) return st;
+  if (m->prof_on) return fail(m, MPZ_ERR_STATE, "mpz_forward_perturbed_noalloc: not while per-launch timing is on (it creates events)");
+  const int64_t n = 2 * (int64_t)m->q, rpc = ((int64_t)E * S + 31) / 32 * 32;
+  size_t need;
+  {
+    Carver sizing(nullptr);
+    Buffers none;
+    carve_activations(&m->cfg, n, rpc, E, sizing, none);
+    need = sizing.off;
+  }
+  if (need > MPZ_NOALLOC_SCRATCH_BYTES) {
+    char msg[192];
+    snprintf(msg, sizeof msg, "mpz_forward_perturbed_noalloc: this pass needs %zu bytes of activations, the static scratch "
+             "holds %zu: use mpz_forward_perturbed with a workspace", need, (size_t)MPZ_NOALLOC_SCRATCH_BYTES);
+    return fail(m, MPZ_ERR_WORKSPACE, msg);
+  }
+  int dev = -1;
+  hipError_t e = hipSuccess;
+  void* ptr = scratch_address(&dev, &e);
+  if (ptr == nullptr) return fail(m, MPZ_ERR_DEVICE, std::string("mpz_forward_perturbed_noalloc: hipGetSymbolAddress: ") + hipGetErrorString(e));
+  if (dev != m->device) return fail(m, MPZ_ERR_STATE, "mpz_forward_perturbed_noalloc: the current device is not the one the model was initialised on");
+  const Buffers saved = m->buf;
+  Carver cv(ptr);
+  carve_activations(&m->cfg, n, rpc, E, cv, m->buf);       // the persistent pointers (factor copies, tables) stay
+  prepare_factors(m, E, S);
+  m->cb = 0; m->nc = 2 * m->q;
+  m->last_pass_streams = 1;                                // one stream: the second stream of small models is created on demand
+  run_embed(m, tokens, E, S, m->buf.h);
+  run_layers(m, m->buf.h, 0, m->cfg.n_layers, E, S);
+  run_head(m, m->buf.h, tokens, labels, E, S, losses_out);
+  m->buf = saved;
+  return check_device(m, "mpz_forward_perturbed_noalloc");
+}
+
+size_t mpz_noalloc_scratch_bytes(void) { return MPZ_NOALLOC_SCRATCH_BYTES; }
 
 mpz_status mpz_forward_perturbed_varlen(mpz_model* m, const int32_t* tokens, const int32_t* labels, const int32_t* lengths,
                                         int32_t E, int32_t S, float* losses_out) {

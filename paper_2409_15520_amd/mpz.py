@@ -183,6 +183,20 @@ def mpz_forward_perturbed(handle, tokens_ptr: int, labels_ptr: Optional[int], E:
     _check(load_library().mpz_forward_perturbed(handle, tokens_ptr, labels_ptr, E, S, losses_ptr), handle)
 
 
+def mpz_forward_perturbed_noalloc(handle, tokens_ptr: int, labels_ptr: Optional[int], E: int, S: int, losses_ptr: int):
+    lib = load_library()
+    lib.mpz_forward_perturbed_noalloc.restype = C.c_int
+    lib.mpz_forward_perturbed_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    _check(lib.mpz_forward_perturbed_noalloc(handle, tokens_ptr, labels_ptr, E, S, losses_ptr), handle)
+
+
+def mpz_noalloc_scratch_bytes() -> int:
+    lib = load_library()
+    lib.mpz_noalloc_scratch_bytes.restype = C.c_size_t
+    lib.mpz_noalloc_scratch_bytes.argtypes = []
+    return int(lib.mpz_noalloc_scratch_bytes())
+
+
 def mpz_forward_perturbed_varlen(handle, tokens_ptr: int, labels_ptr: Optional[int], lengths_ptr: int, E: int, S: int,
                                  losses_ptr: int):
     _check(load_library().mpz_forward_perturbed_varlen(handle, tokens_ptr, labels_ptr, lengths_ptr, E, S, losses_ptr),
