@@ -48,5 +48,46 @@ def build_library(verbose: bool = True) -> str:
     return LIB
 
 
+def build_host_sanitized(verbose: bool = True) -> str:
+    """The same sources with AddressSanitizer and UndefinedBehaviorSanitizer on the HOST code only (argument
+    validation, workspace carving, launch arithmetic); device code is compiled as usual.  Returns the path of
+    _build/san/libmpz_san.so; load it with MPZ_LIBRARY=<path> and the ASan runtime preloaded (sanitizer_runtime())."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out_dir = os.path.join(BUILD_DIR, "san")
+    os.makedirs(out_dir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+    flags = [f if f != "-O3" else "-O1" for f in COMMON] + ["-g"] + san
+
+    def compile_one(src):
+        obj = os.path.join(out_dir, src.replace(".hip", ".o"))
+        r = subprocess.run([hipcc, *flags, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj],
+                           capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc (host-sanitised) failed on {src}:\n{r.stderr}")
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, len(sources()))) as ex:
+        objs = list(ex.map(compile_one, sources()))
+    lib = os.path.join(out_dir, "libmpz_san.so")
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address,undefined", "-fno-gpu-sanitize",
+                        "-shared-libsan", "-o", lib, *objs], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("linking libmpz_san.so failed:\n" + r.stderr)
+    if verbose:
+        print(f"built {lib}")
+    return lib
+
+
+def sanitizer_runtime() -> str:
+    """Path of the shared ASan runtime of the ROCm clang (to LD_PRELOAD ahead of an uninstrumented python)."""
+    clang = os.path.join(os.path.dirname(os.path.realpath(os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"))), "..", "lib", "llvm",
+                         "bin", "clang")
+    r = subprocess.run([clang, "-print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True)
+    return r.stdout.strip()
+
+
 if __name__ == "__main__":
-    build_library()
+    if "--sanitize-host" in sys.argv:
+        print(build_host_sanitized(), sanitizer_runtime())
+    else:
+        build_library()

@@ -13,7 +13,8 @@ from typing import Dict, Optional
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libmpz.so")
+# MPZ_LIBRARY names another build of the same library (e.g. the host-sanitised one of build.py --sanitize-host)
+_LIB_PATH = os.environ.get("MPZ_LIBRARY") or os.path.join(_PKG, "libmpz.so")
 _lib = None
 
 ACT = {"relu": 0, "gelu": 1, "swiglu": 2}
