@@ -301,6 +301,19 @@ mpz_status mpz_debug_attention(mpz_model* m, const void* qkv, int32_t n_seq, int
  * gate then up, bias 2N, out = SiLU(gate) * up); tile_cfg 0 = chosen by shape; 1, 6, 9, 10, 11, 12 = that block-tile configuration (other numbers fall back to the choice by shape).  Errors: NULL, SHAPE (K % 64, N % 4). */
 mpz_status mpz_debug_gemm_bf16(int32_t M, int32_t N, int32_t K, const void* x, const void* w, const float* bias,
                                int32_t act, void* out, int32_t out_f32, int32_t tile_cfg, void* hip_stream);
+/* The same GEMM through the split-K path that passes over at most 256 stacked tokens take (k_splits blocks per output
+ * tile stream disjoint shares of K and leave fp32 partial sums in `partial`; a second kernel adds them in a fixed order
+ * and applies bias, activation, the fp32 residual [M, N] (may be NULL) and the output type).  k_splits = 0: the count
+ * the library would choose for this shape (1 = no split: the one-block kernel runs); >= 2: forced.  partial [dev]
+ * fp32[partial_elems], at least k_splits * M * N (SwiGLU: 2 N) elements.  mpz_debug_gemm_splits returns the chosen
+ * count.  Errors: NULL, SHAPE. */
+mpz_status mpz_debug_gemm_bf16_splitk(int32_t M, int32_t N, int32_t K, const void* x, const void* w, const float* bias,
+                                      int32_t act, const float* residual, void* out, int32_t out_f32, int32_t k_splits,
+                                      float* partial, size_t partial_elems, void* hip_stream);
+int32_t mpz_debug_gemm_splits(int32_t M, int32_t N, int32_t K, int32_t dual, size_t partial_elems);
+/* Test hook: allow (default) or forbid the split-K GEMMs inside a model's passes. */
+mpz_status mpz_debug_set_split_k(mpz_model* m, int32_t enable);
+
 /* The same with weight-only int8 weights: w_codes [dev] int8 [N, K] (SwiGLU: [2N, K]), w_scale [dev] fp32 [N] ([2N]),
  * 16-byte aligned; out = act(x (codes * scale)^T + bias).  Tile configurations 1, 6, 11 and 12 only (others fall back to
  * the choice by shape). */

@@ -169,7 +169,15 @@ struct MfmaGemmArgs {
   // row, the maximum and the sum of exp(logit - maximum) over its columns to slot [tile_n * waves_n + wave_n][M] of
   // ce_max / ce_sum, and the wave holding column ce_target[m] writes that logit to ce_tlogit[m]
   float* ce_max; float* ce_sum; float* ce_tlogit; const int32_t* ce_target;
+  // split K (few stacked tokens: the weight stream is what takes the time, and one block per output tile would
+  // leave most of the chip idle): k_splits > 1 blocks share an output tile, each takes a contiguous share of the
+  // K-tiles and writes its raw fp32 sums to partial[split][M][ldp] (dual: the second weight tile N columns to the
+  // right); bias, activation, rotary embedding, residual and the output type are then the reduction kernel's
+  // (launch_gemm_mfma does both).  0 or 1: off.
+  int k_splits; float* partial; int ldp;
 };
+// k_splits a launch of these arguments would use given room for `partial_capacity` floats (1 = no split)
+int mfma_gemm_splits(const MfmaGemmArgs& a, size_t partial_capacity);
 bool mfma_gemm_supported(const MfmaGemmArgs& a);
 int mfma_gemm_ce_slots(const MfmaGemmArgs& a);      // partial slots per row the launch will write (depends on the tile)
 // ce[m] = logsumexp over the slots - target logit (0 where ce_target[m] < 0)

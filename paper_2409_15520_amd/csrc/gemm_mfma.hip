@@ -173,7 +173,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   }
 #define MPZ_LOAD_GLOBAL(set, kt)                                                   \
   {                                                                                \
-    const int soff = (kt) * BK * 2;                                                \
+    const int soff = ((kt) + kt0) * BK * 2;                                        \
     _Pragma("unroll") for (int d = 0; d < NW; ++d)                                 \
       _Pragma("unroll") for (int i = 0; i < LW; ++i)                               \
         rw[set][d][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, voffW[d][i], WQ ? soff / 2 : soff, 0); \
@@ -224,7 +224,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   {                                                                                \
     const uint16_t* cw = sW + (cur) * NW * TILE_W;                                 \
     const uint16_t* cx = sX + (cur) * TILE_X;                                      \
-    const int soff = (ktl) * BK * 2;                                               \
+    const int soff = ((ktl) + kt0) * BK * 2;                                       \
     bf16x8 fw[2][NW][NI], fx[2][NJ];                                               \
     MPZ_READ_FRAGS(0, cw, cx, 0)                                                   \
     _Pragma("unroll") for (int s = 0; s < KS; ++s) {                               \
@@ -257,6 +257,14 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[d][i][j][e] = 0.f;
 
+  // K-tiles of this block: all of them, or with split K (grid.y = k_splits blocks per output tile, each leaving a raw
+  // fp32 partial sum for the reduction kernel) the split's share.  A split's fetches past its last tile read the
+  // next split's tiles (or zeros past the end): they land in the idle LDS stage and are never used.
+  const int nk_all = a.K / BK;
+  const int split = a.k_splits > 1 ? (int)blockIdx.y : 0;
+  const int kt0 = a.k_splits > 1 ? (int)((long)nk_all * split / a.k_splits) : 0;
+  const int nk = a.k_splits > 1 ? (int)((long)nk_all * (split + 1) / a.k_splits) - kt0 : nk_all;
+  const bool raw = a.k_splits > 1;
   // Short-K GEMMs spend a visible share of a block's life after the main loop waiting for the low-rank operands:
   // small tiles fetch the fragments of a one-step segment (rank <= 8) now, behind the main loop (they are issued
   // first, so they have landed long before any tile load the loop waits for).
@@ -264,7 +272,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   bf16x8 pre_fw[PREF ? NJ : 1][PREF ? NI : 1], pre_fx[PREF ? NJ : 1];
   int pre_seg = -1;
   if constexpr (PREF) {
-    for (int s = 0; s < a.n_seg; ++s)
+    for (int s = 0; s < a.n_seg && split == 0; ++s)          // (with split K the low-rank term goes into split 0's sum)
       if (n0 >= a.seg[s].col_begin && n0 < a.seg[s].col_end && a.seg[s].rp == 16) pre_seg = s;
     if (pre_seg >= 0) {
       const MfmaLoraSeg& sg = a.seg[pre_seg];
@@ -283,7 +291,6 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
     __builtin_amdgcn_sched_barrier(0);
   }
 
-  const int nk = a.K / BK;
   constexpr int NM = NW * NI * NJ, NF = NW * NI + NJ, NV = NW * LW + LX, KS = BK / 16;
   // Tile kt+1 sits in one register set (in flight or landed) while tile kt+2 is fetched into the other: a load
   // has two MFMA phases to arrive before its LDS store needs it.  Loads past the last tile fall outside the
@@ -339,7 +346,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
       for (int i = 0; i < NI; ++i)
         acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pre_fw[j][i], pre_fx[j], acc[0][i][j], 0, 0, 0);
   } else if constexpr (!DUAL) {
-    for (int s = 0; s < a.n_seg; ++s) {
+    for (int s = 0; s < a.n_seg && split == 0; ++s) {
       const MfmaLoraSeg& sg = a.seg[s];
       if (n0 < sg.col_begin || n0 >= sg.col_end) continue;
       const uint16_t* tp = (const uint16_t*)sg.tp;
@@ -373,6 +380,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   // g = 0..3, of every MFMA tile): bias, activation or gating, rotary embedding -- everything that needs no
   // other token's data -- written back into acc[0].
   const bool relu = !DUAL && a.act == MPZ_ACT_RELU;
+  if (!raw) {
 #pragma unroll
   for (int i = 0; i < NI; ++i)
 #pragma unroll
@@ -398,7 +406,8 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
           acc[0][i][j][g * 4 + e] = v;
         }
     }
-  if (!DUAL && a.act == MPZ_ACT_GELU_ERF) {                // rare (no workload of the paper uses it): one cold loop
+  }
+  if (!raw && !DUAL && a.act == MPZ_ACT_GELU_ERF) {                // rare (no workload of the paper uses it): one cold loop
 #pragma unroll
     for (int i = 0; i < NI; ++i)
 #pragma unroll
@@ -408,7 +417,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   }
   if constexpr (HP > 0) {
     static_assert(!DUAL && NI >= 2 * HP && NI % (2 * HP) == 0, "a wave tile must hold whole heads");
-    if (n0 < a.rope_cols) {
+    if (!raw && n0 < a.rope_cols) {
       // q / k columns: y_lo = x_lo cos - x_hi sin, y_hi = x_hi cos + x_lo sin with (lo, hi) = columns (c, c + d_head/2)
       const int half = 32 * HP;
 #pragma unroll
@@ -493,13 +502,21 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   constexpr int LPR = TN / 4;                              // lanes per token row on the way out
   float* ep = (float*)smem + wave * 32 * EPS;
   __syncthreads();                                         // every wave is done with the operand stages
+  // With split K the raw sums of this split go out instead (fp32, no bias / activation / residual; both weight tiles
+  // of a dual launch, the second N columns to the right): partial[split][m][d N + n], row stride ldp.
+  const int nd = raw ? NW : 1;
+  const int ld = raw ? a.ldp : a.ldo;
+  float* const praw = raw ? a.partial + (size_t)split * a.M * a.ldp : nullptr;
+#pragma unroll
+  for (int d = 0; d < NW; ++d) {
+  if (d >= nd) break;
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
 #pragma unroll
     for (int i = 0; i < NI; ++i)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const f32x4 v = {acc[0][i][j][g * 4], acc[0][i][j][g * 4 + 1], acc[0][i][j][g * 4 + 2], acc[0][i][j][g * 4 + 3]};
+        const f32x4 v = {acc[d][i][j][g * 4], acc[d][i][j][g * 4 + 1], acc[d][i][j][g * 4 + 2], acc[d][i][j][g * 4 + 3]};
         *(f32x4*)(ep + lrow * EPS + i * 32 + g * 8 + lhalf * 4) = v;
       }
     // RB pieces at a time: all their residual loads are issued before the first is used (a piece past M or N reads
@@ -516,8 +533,14 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
         const int idx = (r0 + r) * 64 + lane, row = idx / LPR, c4 = idx % LPR;
         const int m = m0 + wm + j * 32 + row, n = n0 + wn + c4 * 4;
         ok[r] = m < a.M && n < a.N;
-        o[r] = (size_t)(m < a.M ? m : a.M - 1) * a.ldo + (n < a.N ? n : 0);
+        o[r] = (size_t)(m < a.M ? m : a.M - 1) * ld + (n < a.N ? n : 0) + (raw ? d * a.N : 0);
         v[r] = *(const f32x4*)(ep + row * EPS + c4 * 4);
+      }
+      if (raw) {
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+          if (ok[r]) *(f32x4*)(praw + o[r]) = v[r];
+        continue;
       }
       if (a.residual != nullptr) {
         f32x4 rs[RB];
@@ -539,6 +562,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
           }
       }
     }
+  }
   }
 }
 
@@ -853,14 +877,15 @@ hipError_t launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
   });
   if (attr_status != hipSuccess) return attr_status;
   const int tiles = ((a.N + BN - 1) / BN) * ((a.M + BM - 1) / BM);
-  gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP, WQ><<<tiles, 64 * WGN * WGM, lds, st>>>(a);
+  const dim3 grid((unsigned)tiles, (unsigned)(a.k_splits > 1 ? a.k_splits : 1));
+  gemm_bf16_kernel<BN, BM, BK, WGN, WGM, DUAL, HP, WQ><<<grid, 64 * WGN * WGM, lds, st>>>(a);
   return hipSuccess;
 }
 
-// block tile of configuration cfg (1, 6, 9, 10, 11, 12; see launch_gemm_mfma)
-int tile_bn(int cfg) { return cfg == 10 ? 64 : cfg == 11 ? 192 : cfg == 6 ? 256 : 128; }
+// block tile of configuration cfg (1, 6, 9, 10, 11, 12, 13; see launch_gemm_mfma)
+int tile_bn(int cfg) { return (cfg == 10 || cfg == 13) ? 64 : cfg == 11 ? 192 : cfg == 6 ? 256 : 128; }
 int tile_bm(int cfg) { return (cfg == 9 || cfg == 10) ? 64 : cfg == 6 ? 256 : 128; }
-bool known_cfg(int cfg) { return cfg == 1 || cfg == 6 || (cfg >= 9 && cfg <= 12); }
+bool known_cfg(int cfg) { return cfg == 1 || cfg == 6 || (cfg >= 9 && cfg <= 13); }
 
 bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
   const int bn = tile_bn(cfg), bm = tile_bm(cfg);
@@ -871,7 +896,19 @@ bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
   return true;
 }
 
+// split K: output features per block.  Wide or long-K projections stream through 128-feature tiles, the others through
+// 64-feature tiles (twice the blocks); a dual launch has one tile shape.
+int split_tile_bn(const MfmaGemmArgs& a) { return (a.dual || a.N >= 8192 || a.K >= 8192 || a.w_scale != nullptr) ? 128 : 64; }
+
 int choose_cfg(const MfmaGemmArgs& a) {
+  // split K (at most 256 stacked tokens): a block takes all the tokens it can (the weights are then fetched from HBM
+  // once) and as few output features as the low-rank segments allow, so that there are many blocks to stream them
+  if (a.k_splits > 1) {
+    const int forced = a.tile_cfg % 100;                 // measurement: tile_cfg = 100 k_splits + tile
+    if (a.w_scale == nullptr && (forced == 1 || forced == 9 || forced == 10 || forced == 12 || forced == 13) && cfg_ok(a, forced)) return forced;
+    if (split_tile_bn(a) == 128 || !cfg_ok(a, 13)) return a.M <= 64 ? 9 : 1;     // 128 features x 64 or 128 tokens
+    return a.M <= 64 ? 10 : 13;                                                   // 64 features x 64 or 128 tokens
+  }
   const bool forced_ok = a.w_scale == nullptr || a.tile_cfg == 1 || a.tile_cfg == 6 || a.tile_cfg == 11 || a.tile_cfg == 12;   // int8: fewer instances
   if (forced_ok && known_cfg(a.tile_cfg) && cfg_ok(a, a.tile_cfg)) return a.tile_cfg;
   // enough 256 x 256 tiles to keep 256 CUs busy for several rounds -> biggest tile; else the largest tile that
@@ -895,7 +932,7 @@ int choose_cfg(const MfmaGemmArgs& a) {
   return 12;
 }
 
-int wave_cols(int cfg) { return cfg == 10 ? 32 : cfg == 11 ? 96 : cfg == 6 ? 128 : 64; }   // BN / WGN of launch_gemm_mfma's table
+int wave_cols(int cfg) { return (cfg == 10 || cfg == 13) ? 32 : cfg == 11 ? 96 : cfg == 6 ? 128 : 64; }   // BN / WGN of launch_gemm_mfma's table
 
 // 64 token rows per block, the slots dealt to 4 waves: logsumexp over the per-wave-tile partials (online
 // maximum / rescaled sum per thread, merged through LDS), minus the target's logit
@@ -948,6 +985,12 @@ bool mfma_gemm_supported(const MfmaGemmArgs& a) {
   if (!cfg_ok(a, 1)) return false;
   if (a.dual && a.n_seg) return false;
   if (a.ce_max != nullptr && (a.dual || a.rope_cos != nullptr || !a.ce_sum || !a.ce_tlogit || !a.ce_target)) return false;
+  if (a.k_splits > 1) {
+    if (a.ce_max != nullptr || a.partial == nullptr || a.ldp < (a.dual ? 2 : 1) * a.N || a.ldp % 4 || a.ldo % 4) return false;
+    if (a.rope_cos != nullptr && (a.dual || a.out_f32 || a.act >= 0 || a.residual != nullptr || !a.rope_sin || a.S < 1 ||
+                                  a.rope_dh % 8 || a.rope_cols % a.rope_dh || a.rope_cols > a.N)) return false;
+    return true;                                         // the rotation is the reduction kernel's: no tile constraints
+  }
   if (a.rope_cos != nullptr) {
     // the rotated column range must end on a block-tile boundary, and a wave tile must hold whole heads
     const int cfg = choose_cfg(a), bn = tile_bn(cfg), tn = wave_cols(cfg);
@@ -958,8 +1001,106 @@ bool mfma_gemm_supported(const MfmaGemmArgs& a) {
   return true;
 }
 
+int mfma_gemm_splits(const MfmaGemmArgs& a, size_t partial_capacity) {
+  if (a.tile_cfg >= 100) {                               // test / measurement: tile_cfg = 100 k_splits (+ tile) forces the count
+    const int ks = a.tile_cfg / 100, nk = a.K / 64;
+    return (ks >= 2 && ks <= nk && ks <= 64 && (size_t)ks * a.M * (a.dual ? 2 : 1) * a.N <= partial_capacity) ? ks : 1;
+  }
+  if (a.M > 256 || a.tile_cfg != 0 || a.ce_max != nullptr || partial_capacity == 0) return 1;
+  // about one block per CU (measured on the 7B-shaped projections at 64 and 128 tokens: 2 - 8 splits are within 10 % of
+  // each other, more only adds partial-sum traffic), every split at least 8 K-tiles long, and the partial sums
+  // (written and read once) no more than the weight bytes
+  const int bn = split_tile_bn(a);
+  const long tiles = (long)((a.N + bn - 1) / bn) * (a.M > 128 ? 2 : 1);
+  if (tiles >= 256) return 1;                            // enough blocks without it
+  long ks = (255 + tiles) / tiles;
+  const long by_k = a.K / 512, by_traffic = a.K / (4L * a.M);
+  ks = ks < by_k ? ks : by_k;
+  ks = ks < by_traffic ? ks : by_traffic;
+  ks = ks < 16 ? ks : 16;
+  while (ks > 1 && (size_t)ks * a.M * (a.dual ? 2 : 1) * a.N > partial_capacity) --ks;
+  return ks >= 2 ? (int)ks : 1;
+}
+
+namespace {
+
+// Sum of the k_splits partial sums in a fixed order (split 0 first), then what the one-block kernel does in its
+// epilogue: bias, activation or SiLU(gate) * up, rotary embedding (same two operations per element), residual, output
+// type.  One thread = 4 consecutive output features of one token (for rotated heads: of the lower half, and the 4
+// partner features of the upper half).
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(MfmaGemmArgs a) {
+  const int n4 = a.N / 4;
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)a.M * n4) return;
+  const int m = (int)(idx / n4), n = (int)(idx % n4) * 4;
+  const size_t plane = (size_t)a.M * a.ldp;
+  auto sum4 = [&](int col) {
+    const float* p = a.partial + (size_t)m * a.ldp + col;
+    f32x4 v = *(const f32x4*)p;
+    for (int s = 1; s < a.k_splits; ++s) v += *(const f32x4*)(p + s * plane);
+    return v;
+  };
+  auto store4 = [&](int col, f32x4 v) {
+    const size_t o = (size_t)m * a.ldo + col;
+    if (a.residual != nullptr) v += *(const f32x4*)(a.residual + o);
+    if (a.out_f32) *(f32x4*)((float*)a.out + o) = v;
+    else *(u32x2*)((uint16_t*)a.out + o) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+  };
+  if (a.rope_cos != nullptr && n < a.rope_cols) {
+    const int half = a.rope_dh / 2, c = n % a.rope_dh;
+    if (c >= half) return;                               // done by the thread of the lower half
+    f32x4 lo = sum4(n), hi = sum4(n + half);
+    if (a.bias != nullptr) { lo += *(const f32x4*)(a.bias + n); hi += *(const f32x4*)(a.bias + n + half); }
+    const int pos = a.rope_pos != nullptr ? a.rope_pos[m % a.S] : m % a.S;
+    const f32x4 cs = *(const f32x4*)(a.rope_cos + (size_t)pos * half + c);
+    const f32x4 sn = *(const f32x4*)(a.rope_sin + (size_t)pos * half + c);
+    f32x4 ylo, yhi;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      ylo[e] = fmaf(lo[e], cs[e], -__fmul_rn(hi[e], sn[e]));
+      yhi[e] = fmaf(hi[e], cs[e], __fmul_rn(lo[e], sn[e]));
+    }
+    store4(n, ylo);
+    store4(n + half, yhi);
+    return;
+  }
+  f32x4 v = sum4(n);
+  if (a.bias != nullptr) v += *(const f32x4*)(a.bias + n);
+  if (a.dual) {
+    f32x4 u = sum4(a.N + n);
+    if (a.bias != nullptr) u += *(const f32x4*)(a.bias + a.dual_offset + n);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = silu_mul_f32(v[e], u[e]);
+  } else if (a.act == MPZ_ACT_RELU) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+  } else if (a.act == MPZ_ACT_GELU_ERF) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
+  }
+  store4(n, v);
+}
+
+}  // namespace
+
 hipError_t launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
   const bool q8 = a.w_scale != nullptr;      // int8 weights: the configurations the model path uses
+  if (a.k_splits > 1) {                      // raw partial sums per split, then the reduction with the epilogue
+    hipError_t e;
+    if (a.dual) e = q8 ? launch_cfg<128, 128, 32, 2, 2, true, 0, true>(st, a) : launch_cfg<128, 128, 32, 2, 2, true>(st, a);
+    else
+      switch (choose_cfg(a)) {
+        case 9: e = q8 ? launch_cfg<128, 64, 64, 2, 2, false, 0, true>(st, a) : launch_cfg<128, 64, 64, 2, 2, false>(st, a); break;
+        case 10: e = launch_cfg<64, 64, 64, 2, 2, false>(st, a); break;
+        case 12: e = launch_cfg<128, 128, 64, 2, 4, false>(st, a); break;
+        case 13: e = launch_cfg<64, 128, 64, 2, 2, false>(st, a); break;
+        default: e = q8 ? launch_cfg<128, 128, 64, 2, 2, false, 0, true>(st, a) : launch_cfg<128, 128, 64, 2, 2, false>(st, a); break;
+      }
+    if (e != hipSuccess) return e;
+    const long items = (long)a.M * (a.N / 4);
+    splitk_reduce_kernel<<<(unsigned)((items + 255) / 256), 256, 0, st>>>(a);
+    return hipSuccess;
+  }
   if (a.dual) {
     const long tb = (long)((a.N + 127) / 128) * ((a.M + 255) / 256);
     if ((a.tile_cfg == 0 && tb >= 512) || a.tile_cfg == 6)                 // 2 x 128 x 256, 8 waves
@@ -989,6 +1130,7 @@ hipError_t launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     case 10: return launch_cfg<64, 64, 64, 2, 2, false>(st, a);      // 4 waves of 32 x 32: the smallest blocks
     case 11: return launch_cfg<192, 128, 64, 2, 2, false>(st, a);    // 4 waves of 96 x 64, 92 KB LDS: 1 block per CU
     case 12: return launch_cfg<128, 128, 64, 2, 4, false>(st, a);    // 8 waves of 64 x 32: 16 waves per CU
+    case 13: return launch_cfg<64, 128, 64, 2, 2, false>(st, a);     // 4 waves of 32 x 64: all of <= 128 tokens, few features
     default: return launch_cfg<128, 128, 64, 2, 2, false>(st, a);    // 1: 4 waves of 64 x 64
   }
 }

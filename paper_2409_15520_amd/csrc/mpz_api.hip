@@ -73,6 +73,8 @@ struct Buffers {
   void* packed = nullptr;     // [2 q_max][packed_per_copy] bf16 hi/lo operand layouts of the perturbed factors
   void* tp[3] = {nullptr, nullptr, nullptr};  // per target [T, rp] duplicated bottleneck activations
   void* wq = nullptr;         // 4-bit weights: the largest block linear, dequantised to bf16
+  float* splitk = nullptr;    // partial sums of the split-K GEMMs of a pass over at most 256 stacked tokens
+  size_t splitk_elems = 0;
   int32_t* row_pos = nullptr; // packed batches: per row of a copy, its position inside its sequence
   int32_t* row_end = nullptr; //   and the row after its sequence's last one (-1: filler row)
 };
@@ -166,6 +168,22 @@ void carve_persistent(const mpz_config* c, int q_max, int E_max, int S_max, Carv
   }
 }
 
+// Room for the partial sums of a split-K GEMM (passes over at most 256 stacked tokens: mfma_gemm_splits keeps
+// k_splits * M <= K / 4 and k_splits <= 16, and splits only K >= 1024): the largest of the block's four linears.
+size_t splitk_capacity(const mpz_config* c, int64_t T) {
+  if (c->dtype != MPZ_DTYPE_BF16) return 0;
+  const int64_t Mx = T < 256 ? T : 256;
+  const int d = c->d_model, dkv = c->n_kv_heads * (d / c->n_heads), f = c->d_ffn;
+  const int64_t shapes[4][2] = {{d, d + 2 * dkv}, {d, d}, {d, c->act == MPZ_ACT_SWIGLU ? 2 * f : f}, {f, d}};   // K, columns
+  int64_t cap = 0;
+  for (const auto& s : shapes) {
+    if (s[0] < 1024) continue;
+    const int64_t rows = 16 * Mx < s[0] / 4 ? 16 * Mx : s[0] / 4;
+    if (rows * s[1] > cap) cap = rows * s[1];
+  }
+  return (size_t)cap;
+}
+
 // What one pass needs and nothing outlives: the activations of ONE block for n stacked copies of rpc rows each
 // (E sequences per copy), staging, and the loss scratch.  Every buffer is written by the pass before it is read.
 void carve_activations(const mpz_config* c, int64_t n, int64_t rpc, int64_t E, Carver& cv, Buffers& bb) {
@@ -197,6 +215,8 @@ void carve_activations(const mpz_config* c, int64_t n, int64_t rpc, int64_t E, C
     const int rp = (2 * c->lora_rank + 15) / 16 * 16;
     for (int i = 0; i < 3; ++i) bb.tp[i] = cv.take<uint16_t>((size_t)T * rp);
   }
+  bb.splitk_elems = splitk_capacity(c, T);
+  bb.splitk = bb.splitk_elems ? cv.take<float>(bb.splitk_elems) : nullptr;
 }
 
 size_t carve(const mpz_config* c, int q_max, int E_max, int S_max, void* base, Buffers* b) {
@@ -228,6 +248,7 @@ struct mpz_model {
   int cb = 0, nc = 0;                           // copies cb + cstep i, i < nc, are processed by the current pass
   int cstep = 1;                                //   (their activations occupy rows [cb, cb + nc) * E * S of the workspace)
   bool fuse_norm_lora = true;                   // test hook: pre-norm and LoRA bottleneck in one kernel where shapes allow
+  bool split_k = true;                          // test hook: split-K GEMMs for passes over few stacked tokens
   bool fuse_perturb_pack = true;                // test hook: noise -> bf16 operand layouts in one kernel (no fp32 copies)
   bool pert_valid = false;                      // buf.pert holds the fp32 copies of the last mpz_regen_noise (else only
                                                 //   the bf16 operand layouts exist; ensure_pert regenerates them)
@@ -348,6 +369,15 @@ WeightRef weight_operand(mpz_model* m, const void* w, const float* s, int N, int
   return {m->buf.wq, nullptr};
 }
 
+// Few stacked tokens: let k_splits blocks share an output tile (see MfmaGemmArgs).  Called once the shape and the
+// epilogue of g are filled in, before mfma_gemm_supported.
+void plan_split(const mpz_model* m, MfmaGemmArgs& g) {
+  g.k_splits = 1; g.partial = nullptr; g.ldp = 0;
+  if (m->buf.splitk == nullptr || !m->split_k) return;
+  const int ks = mfma_gemm_splits(g, m->buf.splitk_elems);
+  if (ks > 1) { g.k_splits = ks; g.partial = m->buf.splitk; g.ldp = (g.dual ? 2 : 1) * g.N; }
+}
+
 // A GEMM launch whose set-up error (the kernel's LDS limit could not be raised) is kept for check_device
 void launch_checked(mpz_model* m, const MfmaGemmArgs& g) {
   const hipError_t e = launch_gemm_mfma(m->stream, g);
@@ -366,6 +396,7 @@ bool gemm(mpz_model* m, const LinearArgs& a) {
     g.rope_cos = a.rope_cos; g.rope_sin = a.rope_sin; g.rope_cols = a.rope_cols; g.rope_dh = a.rope_dh; g.S = a.S;
     g.rope_pos = a.rope_pos;
     g.tile_cfg = m->force_tile_cfg;
+    plan_split(m, g);
     if (!mfma_gemm_supported(g)) return false;
     ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)a.N * a.K, 2.0 * ((double)a.M * a.K + (double)a.N * a.K + (double)a.M * a.N));
     launch_checked(m, g);
@@ -381,6 +412,7 @@ bool gemm(mpz_model* m, const LinearArgs& a) {
     g.out_f32 = a.out_kind != 0; g.out = a.out; g.ldo = a.N;   // bf16 models stage in fp32
     g.tile_cfg = m->force_tile_cfg;
     for (int i = 0; i < a.n_seg; ++i) g.seg[i] = a.mseg[i];
+    plan_split(m, g);
     if (mfma_gemm_supported(g)) { launch_checked(m, g); return true; }
   }
   if (a.w_scale != nullptr) {                  // no shape-agnostic kernel reads int8 weights: refuse, loudly
@@ -398,6 +430,7 @@ bool gemm_swiglu_mfma(mpz_model* m, const LinearArgs& a, int f, void* u_out) {
   g.M = a.M; g.N = f; g.K = a.K; g.x = a.x; g.w = a.w; g.w_scale = a.w_scale; g.w_rows = 2 * f; g.bias = a.bias; g.dual = 1; g.dual_offset = f;
   g.rows_per_copy = a.rows_per_copy; g.act = -1; g.out_f32 = 0; g.out = u_out; g.ldo = f;
   g.tile_cfg = m->force_tile_cfg;
+  plan_split(m, g);
   if (!mfma_gemm_supported(g)) return false;
   ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)(2 * f) * a.K,
                2.0 * ((double)a.M * a.K + 2.0 * f * a.K + (double)a.M * f));
@@ -927,6 +960,7 @@ bool use_two_halves(mpz_model* m, int E, int S) {
   if (c.weight_quant == MPZ_WEIGHT_QUANT_NF4) return false;                  // so is the dequantised-weight buffer
   if (((n / 2) * E * S) % 32) return false;
   const long T = (long)n * E * S;
+  if (m->split_k && m->buf.splitk != nullptr && T / 2 <= 256) return false;  // so is the split-K partial-sum buffer
   const int nqkv = c.d_model + 2 * c.n_kv_heads * (c.d_model / c.n_heads);
   if ((long)((nqkv + 255) / 256) * ((T + 255) / 256) >= 512) return false;   // large problems fill the chip alone
   if (!m->stream2) {
@@ -1247,6 +1281,35 @@ mpz_status mpz_debug_gemm_bf16(int32_t M, int32_t N, int32_t K, const void* x, c
   return check_device(nullptr, "mpz_debug_gemm_bf16");
 }
 
+mpz_status mpz_debug_gemm_bf16_splitk(int32_t M, int32_t N, int32_t K, const void* x, const void* w, const float* bias,
+                                      int32_t act, const float* residual, void* out, int32_t out_f32, int32_t k_splits,
+                                      float* partial, size_t partial_elems, void* hip_stream) {
+  if (!x || !w || !out || !partial) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_gemm_bf16_splitk: NULL argument");
+  const int forced_tile = k_splits / 1000;       // measurement: k_splits + 1000 x tile configuration
+  k_splits %= 1000;
+  if (k_splits < 0 || k_splits > 64) return fail(nullptr, MPZ_ERR_SHAPE, "mpz_debug_gemm_bf16_splitk: k_splits outside [0, 64]");
+  MfmaGemmArgs g{};
+  g.M = M; g.N = N; g.K = K; g.x = x; g.w = w; g.w_rows = N; g.bias = bias; g.rows_per_copy = M; g.act = act;
+  g.residual = residual; g.out_f32 = out_f32; g.out = out; g.ldo = N; g.tile_cfg = 100 * k_splits;
+  if (act == MPZ_ACT_SWIGLU) { g.dual = 1; g.dual_offset = N; g.w_rows = 2 * N; g.act = -1; }
+  if (K % 64 || N % 4 || M < 1 || N < 1) return fail(nullptr, MPZ_ERR_SHAPE, "shape not supported by the MFMA GEMM (K % 64, N % 4)");
+  const int ks = mfma_gemm_splits(g, partial_elems);
+  if (k_splits >= 2 && ks != k_splits) return fail(nullptr, MPZ_ERR_SHAPE, "mpz_debug_gemm_bf16_splitk: k_splits does not fit K or the partial buffer");
+  g.tile_cfg = ks > 1 ? 100 * ks + forced_tile : 0;
+  if (ks > 1) { g.k_splits = ks; g.partial = partial; g.ldp = (g.dual ? 2 : 1) * N; }
+  if (!mfma_gemm_supported(g)) return fail(nullptr, MPZ_ERR_SHAPE, "shape not supported by the MFMA GEMM");
+  const hipError_t le = launch_gemm_mfma((hipStream_t)hip_stream, g);
+  if (le != hipSuccess) return fail(nullptr, MPZ_ERR_DEVICE, std::string("mpz_debug_gemm_bf16_splitk: ") + hipGetErrorString(le));
+  if (check_device(nullptr, "mpz_debug_gemm_bf16_splitk") != MPZ_OK) return MPZ_ERR_DEVICE;
+  return MPZ_OK;
+}
+
+int32_t mpz_debug_gemm_splits(int32_t M, int32_t N, int32_t K, int32_t dual, size_t partial_elems) {
+  MfmaGemmArgs g{};
+  g.M = M; g.N = N; g.K = K; g.dual = dual != 0;
+  return mfma_gemm_splits(g, partial_elems);
+}
+
 mpz_status mpz_debug_gemm_int8(int32_t M, int32_t N, int32_t K, const void* x, const void* w_codes, const float* w_scale,
                                const float* bias, int32_t act, void* out, int32_t out_f32, int32_t tile_cfg,
                                void* hip_stream) {
@@ -1290,6 +1353,12 @@ mpz_status mpz_debug_dequant_nf4(const void* codes, const float* absmax, void* o
 mpz_status mpz_debug_set_fused_norm_lora(mpz_model* m, int32_t enable) {
   if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_set_fused_norm_lora: NULL model");
   m->fuse_norm_lora = enable != 0;
+  return MPZ_OK;
+}
+
+mpz_status mpz_debug_set_split_k(mpz_model* m, int32_t enable) {
+  if (!m) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_set_split_k: NULL model");
+  m->split_k = enable != 0;
   return MPZ_OK;
 }
 

@@ -277,6 +277,31 @@ def mpz_debug_gemm_bf16(M: int, N: int, K: int, x_ptr: int, w_ptr: int, bias_ptr
                                               stream_ptr))
 
 
+def mpz_debug_gemm_bf16_splitk(M: int, N: int, K: int, x_ptr: int, w_ptr: int, bias_ptr: Optional[int], act: int,
+                               residual_ptr: Optional[int], out_ptr: int, out_f32: bool, k_splits: int, partial_ptr: int,
+                               partial_elems: int, stream_ptr: int):
+    lib = load_library()
+    lib.mpz_debug_gemm_bf16_splitk.restype = C.c_int
+    lib.mpz_debug_gemm_bf16_splitk.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                               C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+    _check(lib.mpz_debug_gemm_bf16_splitk(M, N, K, x_ptr, w_ptr, bias_ptr, act, residual_ptr, out_ptr, int(out_f32), k_splits,
+                                          partial_ptr, partial_elems, stream_ptr))
+
+
+def mpz_debug_gemm_splits(M: int, N: int, K: int, dual: bool, partial_elems: int) -> int:
+    lib = load_library()
+    lib.mpz_debug_gemm_splits.restype = C.c_int32
+    lib.mpz_debug_gemm_splits.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_size_t]
+    return int(lib.mpz_debug_gemm_splits(M, N, K, int(dual), partial_elems))
+
+
+def mpz_debug_set_split_k(handle, enable: bool):
+    lib = load_library()
+    lib.mpz_debug_set_split_k.restype = C.c_int
+    lib.mpz_debug_set_split_k.argtypes = [C.c_void_p, C.c_int32]
+    _check(lib.mpz_debug_set_split_k(handle, int(enable)), handle)
+
+
 def mpz_debug_gemm_int8(M: int, N: int, K: int, x_ptr: int, w_ptr: int, scale_ptr: int, bias_ptr: Optional[int], act: int,
                         out_ptr: int, out_f32: bool, stream_ptr: int, tile_cfg: int = 0):
     lib = load_library()

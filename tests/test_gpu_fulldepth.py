@@ -37,6 +37,8 @@ def test_full_depth_query0_against_the_oracle(name):
     import torch
     import paper_2409_15520_amd as M
     path = os.path.join(GOLDEN, f"full_depth_query0_{name}.json")
+    if not os.path.exists(path):
+        pytest.skip(f"{path} has not been written yet (tests/golden/make_full_depth_golden.py {name})")
     gold = json.load(open(path))
     w = W.get_workload(name)
     seeds = gold["seeds"]

@@ -264,3 +264,77 @@ def test_nf4_dequantisation_is_bit_exact(rows, K_):
     M.mpz_debug_dequant_nf4(cd.data_ptr(), ad.data_ptr(), out.data_ptr(), rows * K_, torch.cuda.current_stream().cuda_stream)
     got = out.float().cpu().numpy().astype(np.float64)
     assert np.array_equal(got, want)
+
+
+# Split K (passes over at most 256 stacked tokens): k_splits blocks per output tile, fp32 partial sums, reduction kernel
+# with the epilogue.  Shapes: the 7B-shaped projections at 64 / 128 tokens, ragged M and N, every tile the path picks
+# (M <= 64: 128 x 64; M <= 128: 64 x 128; else 128 x 128), forced and chosen split counts.
+@pytest.mark.parametrize("M_,N_,K_,act,resid,bf16_out,ks", [
+    (128, 4096, 4096, -1, True, False, 0), (64, 12288, 4096, -1, False, True, 0), (128, 4096, 11008, -1, True, False, 0),
+    (64, 768, 3072, 0, False, True, 4), (200, 1028, 2048, 1, True, False, 3), (33, 260, 1024, 0, True, True, 2),
+    (256, 2048, 2048, -1, False, False, 0), (100, 516, 1536, -1, False, False, 24)])
+def test_gemm_split_k(M_, N_, K_, act, resid, bf16_out, ks):
+    import torch
+    import paper_2409_15520_amd as M
+    from scipy.special import erf
+    rng = np.random.default_rng(M_ * 7 + N_ + ks)
+    x = BF.operand(rng.standard_normal((M_, K_)))
+    w = BF.operand(0.05 * rng.standard_normal((N_, K_)))
+    bias = rng.standard_normal(N_).astype(np.float32)
+    res = rng.standard_normal((M_, N_)).astype(np.float32) if resid else None
+    xd, wd = _bf16_tensor(x), _bf16_tensor(w)
+    bd = torch.from_numpy(bias).cuda()
+    rd = torch.from_numpy(res).cuda() if resid else None
+    cap = 64 * M_ * N_
+    chosen = M.mpz_debug_gemm_splits(M_, N_, K_, False, cap)
+    if ks == 0:
+        assert chosen >= 2, "these shapes are meant to take the split-K path on their own"
+    part = torch.full((cap,), float("nan"), dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    outs = []
+    for split in (True, False):
+        out = torch.full((M_, N_), float("nan"), dtype=torch.bfloat16 if bf16_out else torch.float32, device="cuda")
+        if split:
+            M.mpz_debug_gemm_bf16_splitk(M_, N_, K_, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), act,
+                                         rd.data_ptr() if resid else None, out.data_ptr(), not bf16_out, ks, part.data_ptr(), cap, st)
+        else:                                      # the one-block kernel (no residual argument on this hook: added below)
+            M.mpz_debug_gemm_bf16(M_, N_, K_, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), act, out.data_ptr(), not bf16_out, st, 0)
+        outs.append(out.float().cpu().numpy().astype(np.float64))
+    y = x @ w.T + bias
+    y = np.maximum(y, 0.0) if act == 0 else (0.5 * y * (1.0 + erf(y / np.sqrt(2.0))) if act == 1 else y)
+    want = y + (res if resid else 0.0)
+    got = outs[0]
+    assert np.isfinite(got).all()
+    tol = 2e-6 * np.sqrt(K_) * np.abs(want).max()
+    if bf16_out:
+        assert np.abs(got - want).max() <= tol + 2.0 ** -8 * np.abs(want).max()
+    else:
+        assert np.abs(got - want).max() <= tol
+        # against the one-block kernel: the same products summed in another order
+        one = outs[1] + (res if resid else 0.0)
+        assert np.abs(got - one).max() <= 4e-6 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("M_,ks", [(128, 0), (64, 4), (256, 2)])
+def test_swiglu_dual_gemm_split_k(M_, ks):
+    import torch
+    import paper_2409_15520_amd as M
+    F_, K_ = 1408, 2048
+    rng = np.random.default_rng(M_ + ks)
+    x = BF.operand(rng.standard_normal((M_, K_)))
+    w = BF.operand(0.03 * rng.standard_normal((2 * F_, K_)))
+    xd, wd = _bf16_tensor(x), _bf16_tensor(w)
+    cap = 16 * M_ * 2 * F_
+    if ks == 0:
+        assert M.mpz_debug_gemm_splits(M_, F_, K_, True, cap) >= 2
+    part = torch.full((cap,), float("nan"), dtype=torch.float32, device="cuda")
+    out = torch.zeros((M_, F_), dtype=torch.bfloat16, device="cuda")
+    M.mpz_debug_gemm_bf16_splitk(M_, F_, K_, xd.data_ptr(), wd.data_ptr(), None, 2, None, out.data_ptr(), False, ks,
+                                 part.data_ptr(), cap, torch.cuda.current_stream().cuda_stream)
+    got = out.float().cpu().numpy().astype(np.float64)
+    g, u = x @ w[:F_].T, x @ w[F_:].T
+    want = BF.operand(g / (1.0 + np.exp(-g)) * u)
+    ulp = np.maximum(np.abs(want), 1e-30) * 2.0 ** -7
+    # one bf16 rounding, plus the fp32 summation error of a K = 2048 gate (about 3e-6 absolute) carried through
+    # SiLU'(g) u where the gate nearly cancels
+    assert np.mean(got != want) < 2e-3 and (np.abs(got - want) <= 1.01 * ulp + 1e-5 * (1.0 + np.abs(u))).all()
