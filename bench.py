@@ -360,11 +360,14 @@ def probe(args):
     ops = {"zeros": torch.zeros(12288, dtype=torch.bfloat16, device="cuda"),
            "random N(0,1)": torch.randn(12288, generator=g, device="cuda").to(torch.bfloat16)}
     iters = 20000
+    modes = {0: "registers only", 1: "6 LDS fragment reads per 8 MFMAs"}
     for name, t in ops.items():
-        for with_lds in (False, True):
-            ms = timed(lambda i: M.mpz_debug_mfma_probe(t.data_ptr(), 256, iters, with_lds, out.data_ptr(), stream), 5)
-            print(f"MFMA loop, operands {name}, {'6 LDS fragment reads per 8 MFMAs' if with_lds else 'registers only'}: "
-                  f"{256 * 8 * iters * 8 * 32768.0 / ms / 1e9:.0f} TFLOP/s", flush=True)
+        for mode, what in modes.items():
+            ms = timed(lambda i: M.mpz_debug_mfma_probe(t.data_ptr(), 256, iters, mode, out.data_ptr(), stream), 5)
+            print(f"MFMA loop, operands {name}, {what}: {256 * 8 * iters * 8 * 32768.0 / ms / 1e9:.0f} TFLOP/s", flush=True)
+    ms = timed(lambda i: M.mpz_debug_mfma_probe(ops["zeros"].data_ptr(), 256, iters, 2, out.data_ptr(), stream), 5)
+    print(f"LDS fragment reads alone (ds_read_b128, 8 waves per CU): {256 * 8 * iters * 6 * 1024.0 / ms / 1e6:.0f} GB/s "
+          f"= {8 * iters * 6 * 1024.0 / (ms * 1e-3) / 2.4e9:.1f} bytes per CU and cycle at 2.4 GHz", flush=True)
     g.manual_seed(2)
     rot = args.probe_rotate
     for shape in args.probe_shapes.split(","):

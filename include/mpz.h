@@ -323,8 +323,8 @@ mpz_status mpz_debug_gemm_int8(int32_t M, int32_t N, int32_t K, const void* x, c
 
 /* Measurement hook: the matrix cores alone.  blocks x 8 waves each issue iters x 8 MFMAs (32x32x16 bf16, 32768 FLOP
  * each) on independent accumulators; the operand fragments are taken from operands [dev] bf16[12288] (16-byte aligned),
- * so the caller chooses the bit patterns; with_lds != 0 re-reads the 4 + 2 fragments of every step from LDS as the GEMM's
- * main loop does.  out [dev] fp32[blocks * 512] receives checksums.  The caller times it (events around the call).
+ * so the caller chooses the bit patterns; with_lds = 1 re-reads the 4 + 2 fragments of every step from LDS before its MFMAs,
+ * 2 does the fragment reads alone (no MFMA: the LDS read rate).  out [dev] fp32[blocks * 512] receives checksums.  The caller times it (events around the call).
  * Errors: NULL, SHAPE, CONFIG. */
 mpz_status mpz_debug_mfma_probe(const void* operands, int32_t blocks, int32_t iters, int32_t with_lds, float* out,
                                 void* hip_stream);

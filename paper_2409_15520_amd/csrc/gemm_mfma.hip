@@ -293,6 +293,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
 
   constexpr int NM = NW * NI * NJ, NF = NW * NI + NJ, NV = NW * LW + LX, KS = BK / 16;
   // Tile kt+1 sits in one register set (in flight or landed) while tile kt+2 is fetched into the other: a load
+  // Tile kt+1 sits in one register set (in flight or landed) while tile kt+2 is fetched into the other: a load
   // has two MFMA phases to arrive before its LDS store needs it.  Loads past the last tile fall outside the
   // buffers (zeros); what they put into the idle LDS stage is never read.
   {
@@ -592,6 +593,28 @@ __global__ void __launch_bounds__(512, 1) mfma_probe_kernel(const uint16_t* __re
   for (int i = 0; i < 4; ++i) fw[i] = as_frag(*(const u32x4*)(mw + (i * 32 + lrow) * 72 + lhalf * 8));
 #pragma unroll
   for (int j = 0; j < 2; ++j) fx[j] = as_frag(*(const u32x4*)(mx + (j * 32 + lrow) * 72 + lhalf * 8));
+  if (with_lds == 2) {
+    // LDS fragment reads alone (no MFMA), 24 in flight per wave (the 6 fragments of four K-steps) before any is
+    // consumed: the rate at which the LDS delivers ds_read_b128 to the 8 waves of a CU
+    u32x4 chk = {0u, 0u, 0u, 0u};
+    for (int it = 0; it < iters; it += 4) {
+      u32x4 r[4][6];
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[s4][i] = *(const u32x4*)(mw + (i * 32 + lrow) * 72 + s4 * 16 + lhalf * 8);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) r[s4][4 + j] = *(const u32x4*)(mx + (j * 32 + lrow) * 72 + s4 * 16 + lhalf * 8);
+      }
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+        for (int i = 0; i < 6; ++i) chk ^= r[s4][i];
+      asm volatile("" ::: "memory");                       // the next round reads LDS again
+    }
+    out[(size_t)blockIdx.x * 512 + tid] = __uint_as_float(chk[0] ^ chk[1] ^ chk[2] ^ chk[3]);
+    return;
+  }
   for (int it = 0; it < iters; ++it) {
     if (with_lds) {
       const int kk = (it & 3) * 16;

@@ -1337,7 +1337,8 @@ mpz_status mpz_debug_mfma_probe(const void* operands, int32_t blocks, int32_t it
   if (!operands || !out) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_mfma_probe: NULL argument");
   if (blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 24)) return fail(nullptr, MPZ_ERR_SHAPE, "mpz_debug_mfma_probe: blocks or iters out of range");
   if (((uintptr_t)operands & 15u) != 0) return fail(nullptr, MPZ_ERR_CONFIG, "mpz_debug_mfma_probe: operands must be 16-byte aligned");
-  launch_mfma_probe((hipStream_t)hip_stream, operands, blocks, iters, with_lds != 0, out);
+  if (with_lds < 0 || with_lds > 2) return fail(nullptr, MPZ_ERR_CONFIG, "mpz_debug_mfma_probe: with_lds outside [0, 2]");
+  launch_mfma_probe((hipStream_t)hip_stream, operands, blocks, iters, with_lds, out);
   return hipGetLastError() == hipSuccess ? MPZ_OK : fail(nullptr, MPZ_ERR_DEVICE, "mpz_debug_mfma_probe: launch failed");
 }
 

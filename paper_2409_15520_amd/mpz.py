@@ -312,7 +312,7 @@ def mpz_debug_gemm_int8(M: int, N: int, K: int, x_ptr: int, w_ptr: int, scale_pt
                                    stream_ptr))
 
 
-def mpz_debug_mfma_probe(operands_ptr: int, blocks: int, iters: int, with_lds: bool, out_ptr: int, stream_ptr: int):
+def mpz_debug_mfma_probe(operands_ptr: int, blocks: int, iters: int, with_lds: int, out_ptr: int, stream_ptr: int):
     lib = load_library()
     lib.mpz_debug_mfma_probe.restype = C.c_int
     lib.mpz_debug_mfma_probe.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
