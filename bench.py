@@ -31,10 +31,10 @@ ALL_WORKLOADS = ("c1_tiny_fp32", "c2_opt125m", "c3_opt1p3b", "c4_llama1p1b", "c5
 # Bytes the XCD-private L2s fetch from / write to the fabric per GEMM launch, measured with rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE on the workload's default configuration (file under profiles/ that holds the run).  Reported only when
 # the run has that configuration; None otherwise.
-GEMM_TRAFFIC = {"c2_opt125m": (102.5e6, "profiles/hbm_traffic_gemm_c2_opt125m.md"),
-                "c3_opt1p3b": (1861.7e6, "profiles/hbm_traffic_gemm_c3_opt1p3b.md"),
-                "c4_llama1p1b": (3150.5e6, "profiles/hbm_traffic_gemm_c4_llama1p1b.md"),
-                "c5_llama7b": (1483.0e6, "profiles/hbm_traffic_gemm_c5_llama7b.md")}
+GEMM_TRAFFIC = {"c2_opt125m": (102.4e6, "profiles/hbm_traffic_gemm_c2_opt125m.md"),
+                "c3_opt1p3b": (1862.3e6, "profiles/hbm_traffic_gemm_c3_opt1p3b.md"),
+                "c4_llama1p1b": (3150.0e6, "profiles/hbm_traffic_gemm_c4_llama1p1b.md"),
+                "c5_llama7b": (1481.7e6, "profiles/hbm_traffic_gemm_c5_llama7b.md")}
 SEEDS = {"weights": 1234, "lora": 99, "tokens": 2345, "noise": 3456}
 
 

@@ -21,6 +21,10 @@ CASES = {
     "c3_fewtok": W.get_workload("c3_opt1p3b").with_(n_layers=2, q=1, E=1, S=128),
     "c4_fewtok": W.get_workload("c4_llama1p1b").with_(n_layers=2, q=2, E=1, S=64),
     "c5_fewtok": W.get_workload("c5_llama7b").with_(n_layers=1, q=1, E=1, S=64),
+    # the same regime with weight-only int8 block linears (codes widened in the operand load, the per-channel scale
+    # applied to every split's partial sum before the low-rank term) and with 4-bit weights (dequantised, then split)
+    "c4_fewtok_int8": W.get_workload("c4_llama1p1b").with_(n_layers=1, q=2, E=1, S=64, weight_quant="int8"),
+    "c5_fewtok_nf4": W.get_workload("c5_llama7b").with_(n_layers=1, q=1, E=1, S=64, weight_quant="nf4"),
 }
 
 
@@ -36,7 +40,8 @@ def _oracle(name):
 
 @pytest.mark.parametrize("name,tile_cfg", [("c3_width", 0), ("c4_width", 0), ("c5_width", 0),
                                            ("c3_width", 6), ("c4_width", 6), ("c5_width", 6), ("c4_width", 1),
-                                           ("c3_fewtok", 0), ("c4_fewtok", 0), ("c5_fewtok", 0)])
+                                           ("c3_fewtok", 0), ("c4_fewtok", 0), ("c5_fewtok", 0),
+                                           ("c4_fewtok_int8", 0), ("c5_fewtok_nf4", 0)])
 def test_full_width_stages_and_losses(name, tile_cfg):
     """tile_cfg 6 forces the 256 x 256 eight-wave tiles (with the fused rotary epilogue for both head widths and the
     eight-wave SwiGLU kernel) that the full-size workloads select."""
@@ -50,7 +55,7 @@ def test_full_width_stages_and_losses(name, tile_cfg):
     tok = torch.from_numpy(b["tokens"]).cuda()
     lab = torch.from_numpy(b["labels"]).cuda()
     assert np.array_equal(m.embed(tok).cpu().numpy(), H[0])
-    fewtok = name.endswith("fewtok")
+    fewtok = "fewtok" in name
     if fewtok:                                     # these cases are here for the split-K path: it must be the one taken
         T = 2 * w.q * w.E * w.S
         assert M.mpz_debug_gemm_splits(T, w.d_model, w.d_model, False, 1 << 40) >= 2
