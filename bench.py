@@ -290,6 +290,14 @@ def run_workload(w, args, steps, warmup, device_init, want_cpu_baseline, overrid
             kernels[name].update({"bound": "hbm", "frac_of_bound": kernels[name]["frac_hbm_peak"]})
     if "gemm" in kernels:
         kernels["gemm"].update({"bound": "mfma" if bf16 else "alu", "frac_of_bound": achieved / peak})
+    # attention: the causal-useful FLOPs of Q K^T and P V against the same contraction peak (its two passes over the
+    # keys and the exponentials are overhead of the kernel, not work of the problem); the loss kernels read their
+    # logits or partial sums once
+    if "attention" in kernels and "tflops" in kernels["attention"]:
+        kernels["attention"].update({"bound": "mfma" if bf16 else "alu",
+                                     "frac_of_bound": kernels["attention"]["tflops"] / peak})
+    if "loss" in kernels and "frac_hbm_peak" in kernels["loss"]:
+        kernels["loss"].update({"bound": "hbm", "frac_of_bound": kernels["loss"]["frac_hbm_peak"]})
     two_halves = timed_streams == 2
     traffic = GEMM_TRAFFIC.get(w.name) if (not overridden and args.mode == "batched" and not args.tile_config) else None
     out = {
