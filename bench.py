@@ -376,6 +376,26 @@ def probe(args):
     ms = timed(lambda i: M.mpz_debug_mfma_probe(ops["zeros"].data_ptr(), 256, iters, 2, out.data_ptr(), stream), 5)
     print(f"LDS fragment reads alone (ds_read_b128, 8 waves per CU): {256 * 8 * iters * 6 * 1024.0 / ms / 1e6:.0f} GB/s "
           f"= {8 * iters * 6 * 1024.0 / (ms * 1e-3) / 2.4e9:.1f} bytes per CU and cycle at 2.4 GHz", flush=True)
+    # what the memory system gives a read-only kernel: the ceiling of the few-token (split-K) GEMMs, which stream every
+    # weight once.  100.7 MB = the Q|K|V weight of the 7B shape, eight buffers in rotation (nothing warm in a cache) and
+    # one buffer (resident in the Infinity Cache)
+    rows, row_bytes = 12288, 8192
+    bufs = [torch.randint(0, 2 ** 31 - 1, (rows * row_bytes // 4,), dtype=torch.int32, device="cuda", generator=g)
+            for _ in range(8)]
+    sums = torch.zeros(1 << 16, dtype=torch.int32, device="cuda")
+    for what, rr, rb, seg, ks, lds, mode in (
+            ("2048 sequential streams of 48 KB", 2048, 1, 16384, 1, 0, 0),
+            ("weight tiles of 128 rows x 128 B (the 128 x 64 bf16 tile), 4 K-splits = 384 blocks", rows, 128, 128, 4, 73728, 0),
+            ("the same with the activation tile fetched beside every weight tile", rows, 128, 128, 4, 73728, 1),
+            ("the same with both tiles staged through LDS behind block barriers", rows, 128, 128, 4, 73728, 3)):
+        rbytes = rows * row_bytes // rr
+        res = []
+        for nrot in (8, 1):
+            ms = timed(lambda i: M.mpz_debug_hbm_read_probe(bufs[i % nrot].data_ptr(), rr, rbytes, rb, seg, ks, lds, mode,
+                                                            sums.data_ptr(), stream), 20)
+            res.append(f"{ms * 1e3:.1f} us = {rows * row_bytes / ms / 1e9:.2f} TB/s")
+        print(f"HBM read of 100.7 MB, {what}: cold {res[0]}; resident in the Infinity Cache {res[1]}", flush=True)
+    del bufs
     g.manual_seed(2)
     rot = args.probe_rotate
     for shape in args.probe_shapes.split(","):

@@ -329,6 +329,19 @@ mpz_status mpz_debug_gemm_int8(int32_t M, int32_t N, int32_t K, const void* x, c
 mpz_status mpz_debug_mfma_probe(const void* operands, int32_t blocks, int32_t iters, int32_t with_lds, float* out,
                                 void* hip_stream);
 
+/* Measurement hook: the read rate of the memory system for the access pattern of a GEMM's weight operand.  buf [dev] is
+ * read as [rows][row_bytes] (16-byte aligned, never written); a block of 256 threads owns rows_per_block consecutive
+ * rows and one of k_splits equal shares of each row, and walks its share in tiles of rows_per_block x seg_bytes, the next
+ * tile in flight while the current one is consumed (rows_per_block = 128, seg_bytes = 128: the 128 x 64 bf16 tile of the
+ * few-token GEMMs; rows_per_block = 1 with a long seg_bytes: one sequential stream per block).  lds_bytes of dynamic
+ * LDS per block limit how many blocks a CU holds.  mode bit 0: every tile is accompanied by the tile of rows
+ * 0 .. rows_per_block - 1 at the same row offset (what the activation operand of a GEMM adds: the same for all blocks);
+ * bit 1: the tiles pass through LDS with two block barriers per tile (needs lds_bytes >= the staged bytes).  out [dev] uint32[rows / rows_per_block * k_splits] receives
+ * checksums.  The caller times it.  Errors: NULL, CONFIG (alignment), SHAPE (rows % rows_per_block, row_bytes %
+ * (seg_bytes * k_splits), rows_per_block * seg_bytes not 4, 8, 16, 32 or 64 KiB, lds_bytes outside [0, 160 KiB] or too small for mode bit 1). */
+mpz_status mpz_debug_hbm_read_probe(const void* buf, int64_t rows, int64_t row_bytes, int32_t rows_per_block, int32_t seg_bytes,
+                                    int32_t k_splits, int32_t lds_bytes, int32_t mode, uint32_t* out, void* hip_stream);
+
 /* Test hook: the dequantisation of weight_quant = NF4 on its own: codes [dev] n_elems / 2 bytes (two codes per byte,
  * low nibble first), absmax [dev] [n_elems / 64] fp32, out [dev] [n_elems] bf16 = bf16(level[code] * max).
  * Errors: NULL, SHAPE (n_elems < 64 or not a multiple of 64). */
@@ -348,9 +361,10 @@ mpz_status mpz_debug_set_two_halves(mpz_model* m, int32_t enable);
  * before the first pass (or for a NULL handle). */
 int32_t mpz_debug_last_pass_streams(const mpz_model* m);
 
-/* Test hook: allow (default) or forbid the kernel that does a block's first pre-norm and the LoRA bottleneck of the
- * q/k/v projections in one pass over the residual rows (bf16 models with d_model 768, 1024 or 2048); without it the
- * two run as separate kernels.  Same bits either way. */
+/* Test hook: allow (default) or forbid the kernels that fuse a pre-norm with its neighbour: a block's first pre-norm with
+ * the LoRA bottleneck of the q/k/v projections in one pass over the residual rows (bf16 models with d_model 768, 1024
+ * or 2048), and, in passes over few tokens, the reduction of a split-K projection into the residual stream with the
+ * pre-norm that follows it.  Without them each runs as two kernels.  Same bits either way. */
 mpz_status mpz_debug_set_fused_norm_lora(mpz_model* m, int32_t enable);
 
 /* Test hook: allow (default) or forbid the kernel that writes the perturbed factors of a bf16 model straight into the

@@ -173,8 +173,9 @@ struct MfmaGemmArgs {
   // leave most of the chip idle): k_splits > 1 blocks share an output tile, each takes a contiguous share of the
   // K-tiles and writes its raw fp32 sums to partial[split][M][ldp] (dual: the second weight tile N columns to the
   // right); bias, activation, rotary embedding, residual and the output type are then the reduction kernel's
-  // (launch_gemm_mfma does both).  0 or 1: off.
-  int k_splits; float* partial; int ldp;
+  // (launch_gemm_mfma does both).  0 or 1: off.  defer_reduce: launch_gemm_mfma leaves the reduction to the caller
+  // (launch_splitk_reduce_norm: the reduction in one kernel with the pre-norm that follows the projection).
+  int k_splits; float* partial; int ldp; int defer_reduce;
 };
 // k_splits a launch of these arguments would use given room for `partial_capacity` floats (1 = no split)
 int mfma_gemm_splits(const MfmaGemmArgs& a, size_t partial_capacity);
@@ -196,6 +197,9 @@ struct MfmaLoraDownArgs {
 // measurement: `blocks` x 8 waves x iters x 8 MFMAs (32x32x16 bf16), fragments from operands [>= 12288 bf16], optionally
 // re-read from LDS every step; out [blocks * 512] fp32
 void launch_mfma_probe(hipStream_t st, const void* operands, int blocks, int iters, int with_lds, float* out);
+// read-only traffic probe: tiles of rb rows x seg_bytes of a [rows][row_bytes] buffer, L = rb * seg_bytes / 4096 in {1,2,4,8,16}
+hipError_t launch_hbm_read_probe(hipStream_t st, const void* buf, long rows, long row_bytes, int rb, int seg_bytes, int k_splits,
+                                 int lds_bytes, int mode, uint32_t* out);
 bool mfma_lora_down_supported(const MfmaLoraDownArgs& a);
 void launch_lora_down_mfma(hipStream_t st, const MfmaLoraDownArgs& a);
 void launch_pack_factors(hipStream_t st, const float* pert, int64_t P, int n_copies, const LoraLayerTable& tab,
@@ -215,6 +219,11 @@ bool norm_lora_supported(int d, const MfmaLoraDownArgs& a);
 void launch_norm_lora(hipStream_t st, int kind, float eps, const float* h, const float* g, const float* b, void* out,
                       const MfmaLoraDownArgs& a);
 bool norm_rows_supported(int d, int64_t h_row_stride);
+// split-K projection into the residual stream + the pre-norm of the same rows in one kernel (same bits as the
+// reduction kernel followed by launch_norm_rows); `a` is the GEMM launched with defer_reduce
+bool splitk_reduce_norm_supported(const MfmaGemmArgs& a);
+void launch_splitk_reduce_norm(hipStream_t st, const MfmaGemmArgs& a, int kind, float eps, const float* g, const float* b,
+                               void* out);
 void launch_norm_rows(hipStream_t st, int kind, float eps, const float* h, int64_t h_row_stride, const float* g,
                       const float* b, void* out, int rows, int d);
 

@@ -567,6 +567,67 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   }
 }
 
+// Measurement: what the memory system delivers to a read-only kernel whose access pattern is that of a GEMM's weight
+// operand.  The buffer is [rows][row_bytes]; a block owns `rb` consecutive rows and a 1/k_splits share of each row and
+// walks it in tiles of rb rows x seg bytes (thread t takes the 16-byte chunks t, t + 256, ... of a tile, chunk c =
+// 16 bytes number c % (seg / 16) of row c / (seg / 16): a wave's load covers 1024 / seg rows); the next tile is
+// fetched before the current one is consumed.  rb = 128, seg = 128 is the 128 x 64 bf16 tile of the few-token GEMMs;
+// rb = 1 and a long seg is a sequential stream per block.  `lds_bytes` of dynamic LDS limit the blocks per CU.  mode
+// bit 0: every tile is accompanied by the tile of rows 0 .. rb - 1 at the same row offset (the activation operand:
+// the same for all blocks, so it comes from L2); bit 1: the tiles go through LDS with two barriers per tile.
+template <int L>
+__global__ void __launch_bounds__(256) hbm_read_probe_kernel(const u32x4* __restrict__ buf, long row_chunks, int rb, int seg_chunks,
+                                                             int tiles_per_split, int mode, uint32_t* __restrict__ out) {
+  extern __shared__ __align__(16) unsigned char probe_smem[];
+  u32x4* lds = (u32x4*)probe_smem;
+  const int tid = threadIdx.x;
+  const long koff = (long)blockIdx.y * tiles_per_split * seg_chunks;
+  const u32x4* base = buf + (long)blockIdx.x * rb * row_chunks + koff;
+  const u32x4* xbase = buf + koff;                       // mode bit 0: the tile of rows 0 .. rb - 1, shared by all blocks
+  const bool with_x = mode & 1, via_lds = mode & 2;
+  long off[L];
+#pragma unroll
+  for (int i = 0; i < L; ++i) {
+    const int c = tid + 256 * i;
+    off[i] = (long)(c / seg_chunks) * row_chunks + c % seg_chunks;
+  }
+  u32x4 cur[L], nxt[L], xcur[L], xnxt[L], acc = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int i = 0; i < L; ++i) {
+    cur[i] = base[off[i]];
+    xcur[i] = with_x ? xbase[off[i]] : acc;
+  }
+  for (int t = 0; t < tiles_per_split; ++t) {
+    const long adv = (long)(t + 1 < tiles_per_split ? t + 1 : t) * seg_chunks;
+#pragma unroll
+    for (int i = 0; i < L; ++i) {
+      nxt[i] = base[adv + off[i]];
+      xnxt[i] = with_x ? xbase[adv + off[i]] : acc;
+    }
+    if (via_lds) {                                       // mode bit 1: both tiles through LDS, two barriers per tile
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < L; ++i) {
+        lds[tid + 256 * i] = cur[i];
+        if (with_x) lds[256 * L + tid + 256 * i] = xcur[i];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < L; ++i) {
+        acc ^= lds[(tid * 7 + 256 * i) % (256 * L)];
+        if (with_x) acc ^= lds[256 * L + (tid * 5 + 256 * i) % (256 * L)];
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < L; ++i) acc ^= cur[i] ^ xcur[i];
+    }
+#pragma unroll
+    for (int i = 0; i < L; ++i) { cur[i] = nxt[i]; xcur[i] = xnxt[i]; }
+  }
+  if (tid == 0) out[blockIdx.y * gridDim.x + blockIdx.x] = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+}
+
+
 // ---- measurement: the matrix cores alone, and with the main loop's fragment reads ---------------------------
 // 8 waves per block (two per SIMD, the large tile's occupancy); a wave holds the 128 x 64 wave tile's 8 accumulator
 // tiles and issues 8 MFMAs per step.  Operand fragments come from `operands` (the caller chooses the bit patterns:
@@ -1034,7 +1095,8 @@ int mfma_gemm_splits(const MfmaGemmArgs& a, size_t partial_capacity) {
   // each other, more only adds partial-sum traffic), every split at least 8 K-tiles long, and the partial sums
   // (written and read once) no more than the weight bytes
   const int bn = split_tile_bn(a);
-  const long tiles = (long)((a.N + bn - 1) / bn) * (a.M > 128 ? 2 : 1);
+  const int n_rows = (a.dual && a.dual_offset == a.N) ? 2 * a.N : a.N;     // stacked gate || up runs as one plain GEMM
+  const long tiles = (long)((n_rows + bn - 1) / bn) * (a.M > 128 ? 2 : 1);
   if (tiles >= 256) return 1;                            // enough blocks without it
   long ks = (255 + tiles) / tiles;
   const long by_k = a.K / 512, by_traffic = a.K / (4L * a.M);
@@ -1110,16 +1172,22 @@ hipError_t launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
   const bool q8 = a.w_scale != nullptr;      // int8 weights: the configurations the model path uses
   if (a.k_splits > 1) {                      // raw partial sums per split, then the reduction with the epilogue
     hipError_t e;
-    if (a.dual) e = q8 ? launch_cfg<128, 128, 32, 2, 2, true, 0, true>(st, a) : launch_cfg<128, 128, 32, 2, 2, true>(st, a);
+    // gate || up whose two weight blocks lie back to back: with raw partial sums the dual kernel has nothing to fuse, so
+    // the launch is a plain GEMM over the 2 N stacked rows (column N + n of a partial row is up[n], which is the dual
+    // kernel's raw layout), on the BK = 64 tile that fetches whole 128-byte lines
+    MfmaGemmArgs b = a;
+    if (a.dual && a.dual_offset == a.N) { b.dual = 0; b.N = 2 * a.N; }
+    if (b.dual) e = q8 ? launch_cfg<128, 128, 32, 2, 2, true, 0, true>(st, a) : launch_cfg<128, 128, 32, 2, 2, true>(st, a);
     else
-      switch (choose_cfg(a)) {
-        case 9: e = q8 ? launch_cfg<128, 64, 64, 2, 2, false, 0, true>(st, a) : launch_cfg<128, 64, 64, 2, 2, false>(st, a); break;
-        case 10: e = launch_cfg<64, 64, 64, 2, 2, false>(st, a); break;
-        case 12: e = launch_cfg<128, 128, 64, 2, 4, false>(st, a); break;
-        case 13: e = launch_cfg<64, 128, 64, 2, 2, false>(st, a); break;
-        default: e = q8 ? launch_cfg<128, 128, 64, 2, 2, false, 0, true>(st, a) : launch_cfg<128, 128, 64, 2, 2, false>(st, a); break;
+      switch (choose_cfg(b)) {
+        case 9: e = q8 ? launch_cfg<128, 64, 64, 2, 2, false, 0, true>(st, b) : launch_cfg<128, 64, 64, 2, 2, false>(st, b); break;
+        case 10: e = launch_cfg<64, 64, 64, 2, 2, false>(st, b); break;
+        case 12: e = launch_cfg<128, 128, 64, 2, 4, false>(st, b); break;
+        case 13: e = launch_cfg<64, 128, 64, 2, 2, false>(st, b); break;
+        default: e = q8 ? launch_cfg<128, 128, 64, 2, 2, false, 0, true>(st, b) : launch_cfg<128, 128, 64, 2, 2, false>(st, b); break;
       }
     if (e != hipSuccess) return e;
+    if (a.defer_reduce) return hipSuccess;
     const long items = (long)a.M * (a.N / 4);
     splitk_reduce_kernel<<<(unsigned)((items + 255) / 256), 256, 0, st>>>(a);
     return hipSuccess;
@@ -1156,6 +1224,28 @@ hipError_t launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     case 13: return launch_cfg<64, 128, 64, 2, 2, false>(st, a);     // 4 waves of 32 x 64: all of <= 128 tokens, few features
     default: return launch_cfg<128, 128, 64, 2, 2, false>(st, a);    // 1: 4 waves of 64 x 64
   }
+}
+
+hipError_t launch_hbm_read_probe(hipStream_t st, const void* buf, long rows, long row_bytes, int rb, int seg_bytes, int k_splits,
+                                 int lds_bytes, int mode, uint32_t* out) {
+  const long row_chunks = row_bytes / 16;
+  const int seg_chunks = seg_bytes / 16, L = rb * seg_chunks / 256;
+  const int tiles_per_split = (int)(row_bytes / seg_bytes / k_splits);
+  const dim3 grid((unsigned)(rows / rb), (unsigned)k_splits);
+#define MPZ_PROBE_CASE(LL)                                                                                              \
+  case LL: {                                                                                                            \
+    hipError_t e = hipFuncSetAttribute((const void*)hbm_read_probe_kernel<LL>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                       160 * 1024);                                                                     \
+    if (e != hipSuccess) return e;                                                                                      \
+    hbm_read_probe_kernel<LL><<<grid, 256, (size_t)lds_bytes, st>>>((const u32x4*)buf, row_chunks, rb, seg_chunks,     \
+                                                                     tiles_per_split, mode, out);                       \
+    return hipSuccess;                                                                                                  \
+  }
+  switch (L) {
+    MPZ_PROBE_CASE(1) MPZ_PROBE_CASE(2) MPZ_PROBE_CASE(4) MPZ_PROBE_CASE(8) MPZ_PROBE_CASE(16)
+    default: return hipErrorInvalidValue;
+  }
+#undef MPZ_PROBE_CASE
 }
 
 void launch_mfma_probe(hipStream_t st, const void* operands, int blocks, int iters, int with_lds, float* out) {

@@ -329,7 +329,8 @@ struct ProfScope {
     m->prof_flops[cat] += flops; m->prof_bytes[cat] += bytes;
     (void)hipEventRecord(e0, m->stream);
   }
-  ~ProfScope() { if (e1) (void)hipEventRecord(e1, m->stream); }
+  void end() { if (e1) (void)hipEventRecord(e1, m->stream); e1 = nullptr; }   // close the bracket before the scope ends
+  ~ProfScope() { end(); }
 };
 
 double esz(const mpz_model* m) { return m->cfg.dtype == MPZ_DTYPE_F32 ? 4.0 : 2.0; }
@@ -386,7 +387,11 @@ void launch_checked(mpz_model* m, const MfmaGemmArgs& g) {
 
 // Every base-weight GEMM of the pass goes through here (kernel selection and optional timing).  Returns false
 // (nothing launched) only when a fused rotary epilogue was requested and the shape does not allow it.
-bool gemm(mpz_model* m, const LinearArgs& a) {
+// `then`: the pre-norm that reads this GEMM's output rows next (gains, optional biases, operand rows to write).  When
+// the GEMM splits K, its reduction and that norm run as one kernel and then->done is set; otherwise the caller
+// launches the norm itself.
+struct NormAfter { const float* g; const float* b; void* x; bool done; };
+bool gemm(mpz_model* m, const LinearArgs& a, NormAfter* then = nullptr) {
   if (a.rope_cos != nullptr) {
     if (!(m->use_mfma && a.dtype == MPZ_DTYPE_BF16 && (a.n_seg == 0 || a.mfma_lora))) return false;
     MfmaGemmArgs g{};
@@ -413,7 +418,19 @@ bool gemm(mpz_model* m, const LinearArgs& a) {
     g.tile_cfg = m->force_tile_cfg;
     for (int i = 0; i < a.n_seg; ++i) g.seg[i] = a.mseg[i];
     plan_split(m, g);
-    if (mfma_gemm_supported(g)) { launch_checked(m, g); return true; }
+    if (mfma_gemm_supported(g)) {
+      if (then != nullptr && m->fuse_norm_lora && splitk_reduce_norm_supported(g) && a.N == m->cfg.d_model) {
+        g.defer_reduce = 1;
+        launch_checked(m, g);
+        ps.end();                                // (the fused kernel is booked under the norm)
+        ProfScope pn(m, MPZ_PROF_NORM, 0.0, (double)a.M * a.N * (4.0 * g.k_splits + 8.0 + esz(m)));
+        launch_splitk_reduce_norm(m->stream, g, m->cfg.norm, m->cfg.norm_eps, then->g, then->b, then->x);
+        then->done = true;
+        return true;
+      }
+      launch_checked(m, g);
+      return true;
+    }
   }
   if (a.w_scale != nullptr) {                  // no shape-agnostic kernel reads int8 weights: refuse, loudly
     m->deferred = "int8 weights: a GEMM of this pass has a shape the MFMA kernel does not take";
@@ -612,9 +629,11 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
   const int nqkv = d + 2 * dkv;
   const bool rope = c.pos == MPZ_POS_ROPE, swiglu = c.act == MPZ_ACT_SWIGLU;
 
+  bool x_ready = false;                               // b.x already holds this block's first pre-norm (see the end of the loop)
   for (int l = l0; l < l1; ++l) {
     const mpz_layer_weights& lw = m->layers[l];
-    run_qkv(m, b, l, E, S, rope, 0, b.qkv, b.h);      // pre-norm, LoRA bottleneck, projection
+    run_qkv(m, b, l, E, S, rope, 0, b.qkv, x_ready ? nullptr : b.h);      // pre-norm, LoRA bottleneck, projection
+    x_ready = false;
 
     {
       // causal-useful work: Q K^T and P V over the S (S + 1) / 2 visible (query, key) pairs of every head
@@ -666,10 +685,10 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     }
     const WeightRef wo = weight_operand(m, lw.w_o, lw.s_o, d, d);
     oa.w = wo.w; oa.w_scale = wo.scale;
-    gemm(m, oa);
-
-    // feed-forward block
-    norm(m, b.h, d, lw.ln2_g, lw.ln2_b, b.x, T);
+    // feed-forward block: its pre-norm rides on the reduction of the output projection where that splits K
+    NormAfter ffn_norm{lw.ln2_g, lw.ln2_b, b.x, false};
+    gemm(m, oa, &ffn_norm);
+    if (!ffn_norm.done) norm(m, b.h, d, lw.ln2_g, lw.ln2_b, b.x, T);
     LinearArgs ua{};
     ua.dtype = c.dtype; ua.M = T; ua.N = swiglu ? 2 * f : f; ua.K = d; ua.x = b.x; ua.w = lw.w_up; ua.w_scale = lw.s_up; ua.bias = lw.b_up;
     ua.rank = r; ua.rows_per_copy = rpc; ua.act = swiglu ? -1 : c.act;
@@ -688,7 +707,13 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     wa.rank = r; wa.rows_per_copy = rpc; wa.act = -1; wa.residual = b.h; wa.out_kind = 1; wa.out = b.h;
     const WeightRef wd = weight_operand(m, lw.w_down, lw.s_down, d, f);
     wa.w = wd.w; wa.w_scale = wd.scale;
-    gemm(m, wa);
+    if (l + 1 < l1) {                                 // likewise the next block's first pre-norm
+      NormAfter next_norm{m->layers[l + 1].ln1_g, m->layers[l + 1].ln1_b, b.x, false};
+      gemm(m, wa, &next_norm);
+      x_ready = next_norm.done;
+    } else {
+      gemm(m, wa);
+    }
   }
 }
 
@@ -1306,7 +1331,7 @@ mpz_status mpz_debug_gemm_bf16_splitk(int32_t M, int32_t N, int32_t K, const voi
 
 int32_t mpz_debug_gemm_splits(int32_t M, int32_t N, int32_t K, int32_t dual, size_t partial_elems) {
   MfmaGemmArgs g{};
-  g.M = M; g.N = N; g.K = K; g.dual = dual != 0;
+  g.M = M; g.N = N; g.K = K; g.dual = dual != 0; g.dual_offset = dual ? N : 0;
   return mfma_gemm_splits(g, partial_elems);
 }
 
@@ -1340,6 +1365,28 @@ mpz_status mpz_debug_mfma_probe(const void* operands, int32_t blocks, int32_t it
   if (with_lds < 0 || with_lds > 2) return fail(nullptr, MPZ_ERR_CONFIG, "mpz_debug_mfma_probe: with_lds outside [0, 2]");
   launch_mfma_probe((hipStream_t)hip_stream, operands, blocks, iters, with_lds, out);
   return hipGetLastError() == hipSuccess ? MPZ_OK : fail(nullptr, MPZ_ERR_DEVICE, "mpz_debug_mfma_probe: launch failed");
+}
+
+mpz_status mpz_debug_hbm_read_probe(const void* buf, int64_t rows, int64_t row_bytes, int32_t rows_per_block, int32_t seg_bytes,
+                                    int32_t k_splits, int32_t lds_bytes, int32_t mode, uint32_t* out, void* hip_stream) {
+  if (!buf || !out) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_hbm_read_probe: NULL argument");
+  if (((uintptr_t)buf & 15u) != 0) return fail(nullptr, MPZ_ERR_CONFIG, "mpz_debug_hbm_read_probe: buf must be 16-byte aligned");
+  // every access of the kernel stays inside [rows][row_bytes]: whole row blocks, whole tiles, whole splits
+  if (rows < 1 || row_bytes < 16 || rows_per_block < 1 || seg_bytes < 16 || seg_bytes % 16 || k_splits < 1 || k_splits > 65535 ||
+      rows % rows_per_block || row_bytes % ((int64_t)seg_bytes * k_splits) || rows / rows_per_block > 0x7fffffff ||
+      (int64_t)rows_per_block * seg_bytes % 4096 || lds_bytes < 0 || lds_bytes > 160 * 1024)
+    return fail(nullptr, MPZ_ERR_SHAPE, "mpz_debug_hbm_read_probe: rows % rows_per_block, row_bytes % (seg_bytes * k_splits), "
+                                        "rows_per_block * seg_bytes % 4096 must be 0; lds_bytes in [0, 160 KiB]");
+  const int64_t L = (int64_t)rows_per_block * seg_bytes / 4096;
+  if (L != 1 && L != 2 && L != 4 && L != 8 && L != 16)
+    return fail(nullptr, MPZ_ERR_SHAPE, "mpz_debug_hbm_read_probe: rows_per_block * seg_bytes must be 4, 8, 16, 32 or 64 KiB");
+  if (mode < 0 || mode > 3) return fail(nullptr, MPZ_ERR_CONFIG, "mpz_debug_hbm_read_probe: mode outside [0, 3]");
+  if ((mode & 2) && (int64_t)lds_bytes < ((mode & 1) ? 2 : 1) * (int64_t)rows_per_block * seg_bytes)
+    return fail(nullptr, MPZ_ERR_SHAPE, "mpz_debug_hbm_read_probe: mode bit 1 needs lds_bytes >= the bytes of the tiles it stages");
+  const hipError_t e = launch_hbm_read_probe((hipStream_t)hip_stream, buf, rows, row_bytes, rows_per_block, seg_bytes, k_splits,
+                                             lds_bytes, mode, out);
+  if (e != hipSuccess) return fail(nullptr, MPZ_ERR_DEVICE, std::string("mpz_debug_hbm_read_probe: ") + hipGetErrorString(e));
+  return hipGetLastError() == hipSuccess ? MPZ_OK : fail(nullptr, MPZ_ERR_DEVICE, "mpz_debug_hbm_read_probe: launch failed");
 }
 
 mpz_status mpz_debug_dequant_nf4(const void* codes, const float* absmax, void* out, int64_t n_elems, void* hip_stream) {

@@ -59,6 +59,101 @@ __global__ void __launch_bounds__(256) norm_rows_kernel(int kind, float eps, con
   }
 }
 
+// ---- split-K reduction fused with the pre-norm that follows it -----------------------------------------------
+// A projection whose output is the residual stream (h += x W) and whose K was split over blocks leaves raw fp32
+// partial sums; the next kernel of the pass is the pre-norm of those rows.  One block per token row does both.  All
+// four waves sum the row's partial sums (16-byte piece c = tid + 256 j: splits in order from split 0, bias, residual -
+// the reduction kernel's operations per element, so h has the same bits), store h and leave the row in LDS; wave 0
+// takes the statistics from there with norm_rows_kernel's lane mapping and order (the same bits again); all threads
+// then scale their own pieces.  (A wave per row, as in norm_rows_kernel, leaves a pass of 128 rows with 128 waves that
+// each walk k_splits x d floats one round trip after the other: measured at four times the two kernels it replaces.)
+template <int NV>   // d = 256 * NV
+__global__ void __launch_bounds__(256) splitk_reduce_norm_kernel(MfmaGemmArgs a, int kind, float eps,
+                                                                 const float* __restrict__ g, const float* __restrict__ b,
+                                                                 uint16_t* __restrict__ out) {
+  constexpr int D = 256 * NV, NC = 64 * NV, J = (NC + 255) / 256;       // 16-byte pieces per row, per thread
+  __shared__ __align__(16) float srow[D];
+  __shared__ float stat[2];
+  const int tid = threadIdx.x, lane = tid & 63, row = blockIdx.x;
+  const size_t plane = (size_t)a.M * a.ldp;
+  f32x4 v[J];
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int c = tid + 256 * j;
+    if (c < NC) v[j] = ((const f32x4*)(a.partial + (size_t)row * a.ldp))[c];
+  }
+  // the other splits, four at a time: their pieces are all requested before the first is added (they come from other
+  // XCDs' blocks, a fabric round trip each), and added in split order
+  for (int s = 1; s < a.k_splits; s += 4) {
+    const int ns = a.k_splits - s < 4 ? a.k_splits - s : 4;              // block-uniform
+    f32x4 t4[4][J];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (u >= ns) break;
+      const f32x4* ps = (const f32x4*)(a.partial + (s + u) * plane + (size_t)row * a.ldp);
+#pragma unroll
+      for (int j = 0; j < J; ++j) {
+        const int c = tid + 256 * j;
+        if (c < NC) t4[u][j] = ps[c];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (u >= ns) break;
+#pragma unroll
+      for (int j = 0; j < J; ++j)
+        if (tid + 256 * j < NC) v[j] += t4[u][j];
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int c = tid + 256 * j;
+    if (c >= NC) continue;
+    if (a.bias != nullptr) v[j] += ((const f32x4*)a.bias)[c];
+    if (a.residual != nullptr) v[j] += ((const f32x4*)(a.residual + (size_t)row * a.ldo))[c];
+    ((f32x4*)((float*)a.out + (size_t)row * a.ldo))[c] = v[j];
+    ((f32x4*)srow)[c] = v[j];
+  }
+  __syncthreads();
+  if (tid < 64) {
+    f32x4 w[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) w[i] = ((const f32x4*)srow)[i * 64 + lane];
+    float mean = 0.f;
+    if (kind == MPZ_NORM_LAYERNORM) {
+      float s = 0.f;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) s += (w[i][0] + w[i][1]) + (w[i][2] + w[i][3]);
+      mean = wave_sum_f32(s) / (float)D;
+    }
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { float c = w[i][e] - mean; q += c * c; }
+    const float rstd = 1.0f / sqrtf(wave_sum_f32(q) / (float)D + eps);
+    if (lane == 0) { stat[0] = mean; stat[1] = rstd; }
+  }
+  __syncthreads();
+  const float mean = stat[0], rstd = stat[1];
+  u32x2* orow = (u32x2*)(out + (int64_t)row * D);
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int c = tid + 256 * j;
+    if (c >= NC) continue;
+    const f32x4 gg = ((const f32x4*)g)[c];
+    float y[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = (v[j][e] - mean) * rstd * gg[e];
+    if (b != nullptr) {
+      const f32x4 bb = ((const f32x4*)b)[c];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) y[e] += bb[e];
+    }
+    orow[c] = u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+  }
+}
+
 // ---- pre-norm fused with the LoRA bottleneck of the projections that read its output ------------------------
 // One block = 32 token rows.  Phase A is norm_rows_kernel's arithmetic (each wave takes 8 of the rows, RB at a time
 // so that their loads travel together); the bf16 row goes to global memory for the GEMM and to an LDS tile.  Phase B
@@ -248,6 +343,23 @@ void launch_norm_lora(hipStream_t st, int kind, float eps, const float* h, const
     case 3: if (two) launch_norm_lora_t<3, 2>(st, kind, eps, h, g, b, out, a); else launch_norm_lora_t<3, 1>(st, kind, eps, h, g, b, out, a); break;
     case 4: if (two) launch_norm_lora_t<4, 2>(st, kind, eps, h, g, b, out, a); else launch_norm_lora_t<4, 1>(st, kind, eps, h, g, b, out, a); break;
     default: if (two) launch_norm_lora_t<8, 2>(st, kind, eps, h, g, b, out, a); else launch_norm_lora_t<8, 1>(st, kind, eps, h, g, b, out, a); break;
+  }
+}
+
+bool splitk_reduce_norm_supported(const MfmaGemmArgs& a) {
+  const int d = a.N;
+  return a.k_splits > 1 && a.partial != nullptr && !a.dual && a.rope_cos == nullptr && a.act < 0 && a.out_f32 && a.ce_max == nullptr &&
+         (d == 768 || d == 1024 || d == 2048 || d == 4096) && a.ldo == d && a.ldp % 4 == 0 && a.ldp >= d;
+}
+
+void launch_splitk_reduce_norm(hipStream_t st, const MfmaGemmArgs& a, int kind, float eps, const float* g, const float* b,
+                               void* out) {
+  const unsigned blocks = (unsigned)a.M;
+  switch (a.N / 256) {
+    case 3: splitk_reduce_norm_kernel<3><<<blocks, 256, 0, st>>>(a, kind, eps, g, b, (uint16_t*)out); break;
+    case 4: splitk_reduce_norm_kernel<4><<<blocks, 256, 0, st>>>(a, kind, eps, g, b, (uint16_t*)out); break;
+    case 8: splitk_reduce_norm_kernel<8><<<blocks, 256, 0, st>>>(a, kind, eps, g, b, (uint16_t*)out); break;
+    default: splitk_reduce_norm_kernel<16><<<blocks, 256, 0, st>>>(a, kind, eps, g, b, (uint16_t*)out); break;
   }
 }
 

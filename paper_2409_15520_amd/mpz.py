@@ -319,6 +319,16 @@ def mpz_debug_mfma_probe(operands_ptr: int, blocks: int, iters: int, with_lds: i
     _check(lib.mpz_debug_mfma_probe(operands_ptr, blocks, iters, int(with_lds), out_ptr, stream_ptr))
 
 
+def mpz_debug_hbm_read_probe(buf_ptr: int, rows: int, row_bytes: int, rows_per_block: int, seg_bytes: int, k_splits: int,
+                             lds_bytes: int, mode: int, out_ptr: int, stream_ptr: int):
+    lib = load_library()
+    lib.mpz_debug_hbm_read_probe.restype = C.c_int
+    lib.mpz_debug_hbm_read_probe.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_int32, C.c_void_p, C.c_void_p]
+    _check(lib.mpz_debug_hbm_read_probe(buf_ptr, rows, row_bytes, rows_per_block, seg_bytes, k_splits, lds_bytes, mode,
+                                        out_ptr, stream_ptr))
+
+
 def mpz_debug_dequant_nf4(codes_ptr: int, absmax_ptr: int, out_ptr: int, n_elems: int, stream_ptr: int):
     lib = load_library()
     lib.mpz_debug_dequant_nf4.restype = C.c_int

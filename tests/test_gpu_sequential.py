@@ -101,13 +101,21 @@ def test_two_halves_schedule_changes_no_bit(name):
     assert np.array_equal(runs[0].view(np.uint32), runs[2].view(np.uint32))
 
 
-@pytest.mark.parametrize("name", ["c2_2layers", "llama_mfma", "c2_ragged_copies"])
+FEW_TOKENS = {   # passes over 128 stacked tokens: every projection splits K (three blocks deep: both fusions across blocks)
+    "llama_few_tokens": W.get_workload("c4_llama1p1b").with_(n_layers=3, q=1, E=1, S=64),
+    "opt_few_tokens": W.get_workload("c3_opt1p3b").with_(n_layers=3, q=1, E=2, S=32, vocab=4096, max_seq=64),
+}
+
+
+@pytest.mark.parametrize("name", ["c2_2layers", "llama_mfma", "c2_ragged_copies", "llama_few_tokens", "opt_few_tokens"])
 def test_fused_norm_and_bottleneck_kernel_changes_no_bit(name):
     """The first pre-norm of a block and the LoRA bottleneck of its q/k/v projections run as one kernel where the
-    shapes allow; with the hook off they are two kernels.  Same arithmetic, same order: identical losses."""
+    shapes allow, and in passes over few tokens the reduction of a split-K projection into the residual stream runs
+    as one kernel with the pre-norm that follows; with the hook off each is two kernels.  Same arithmetic, same
+    order: identical losses."""
     import torch
     import paper_2409_15520_amd as M
-    w = CASES[name]
+    w = CASES[name] if name in CASES else FEW_TOKENS[name]
     b = make_bundle(w, b_std=0.05)
     m = gpu_model(b)
     tok = torch.from_numpy(b["tokens"]).cuda()
