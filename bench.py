@@ -86,32 +86,31 @@ def cpu_baseline_full(w, frozen, masters, tokens, labels, seed):
                       f"incl. noise and update, {dt:.1f} s"}
 
 
-def host_layers_from_device(w, frozen_dev, n_layers):
-    """The first n_layers blocks, the embeddings and the head of device-drawn weights as the host arrays the oracle
-    reads ([k_in, k_out] float32)."""
+def _host_array(t, transpose=False):
     import numpy as np
+    if t is None:
+        return None
+    a = t.float().cpu().numpy()
+    return np.ascontiguousarray(a.T) if transpose else a
 
-    def host(t, transpose=False):
-        if t is None:
-            return None
-        a = t.float().cpu().numpy()
-        return np.ascontiguousarray(a.T) if transpose else a
-    out = {"emb": host(frozen_dev["emb"]), "pos_emb": host(frozen_dev["pos_emb"]), "layers": [],
-           "lnf_g": host(frozen_dev["lnf_g"]), "lnf_b": host(frozen_dev["lnf_b"])}
-    out["lm_head"] = out["emb"] if frozen_dev["lm_head"] is frozen_dev["emb"] else host(frozen_dev["lm_head"])
-    for lw in frozen_dev["layers"][:n_layers]:
-        h = {}
-        for k, v in lw.items():
-            if k.startswith("s_"):
-                continue
-            h[k] = host(v, transpose=k.startswith("w_"))
-        out["layers"].append(h)
+
+def host_block_from_device(lw):
+    """One block of device-drawn weights as the host arrays the oracle reads ([k_in, k_out] float32)."""
+    return {k: _host_array(v, transpose=k.startswith("w_")) for k, v in lw.items() if not k.startswith("s_")}
+
+
+def host_ends_from_device(frozen_dev):
+    """Embeddings, final norm and head of device-drawn weights as host arrays (no blocks)."""
+    out = {"emb": _host_array(frozen_dev["emb"]), "pos_emb": _host_array(frozen_dev["pos_emb"]), "layers": [],
+           "lnf_g": _host_array(frozen_dev["lnf_g"]), "lnf_b": _host_array(frozen_dev["lnf_b"])}
+    out["lm_head"] = out["emb"] if frozen_dev["lm_head"] is frozen_dev["emb"] else _host_array(frozen_dev["lm_head"])
     return out
 
 
-def cpu_baseline_extrapolated(w, frozen_dev, masters, tokens, labels, seed, budget_s=25.0):
+def cpu_baseline_extrapolated(w, frozen_dev, masters, tokens, labels, seed, budget_s=12.0, max_blocks=8):
     """Large workloads: the oracle's stages timed one by one on the host for ONE perturbed copy at the workload's
-    full width, on the device-drawn weights of the first block(s), and put together as
+    full width, on the device-drawn weights of the first blocks (as many as fit into about budget_s seconds of CPU
+    work, at most max_blocks; copying a block's weights to the host is not part of the sample), and put together as
     q x (noise + 2 x (embedding + L x block + head and loss) + update term).  Says so in `sample`."""
     import numpy as np
     import workloads as W
@@ -120,7 +119,7 @@ def cpu_baseline_extrapolated(w, frozen_dev, masters, tokens, labels, seed, budg
     from oracle.precision import Precision
     lay = W.lora_layout(w)
     prec = Precision(w.dtype)
-    frozen = host_layers_from_device(w, frozen_dev, 2)       # (copying the weights back is not part of the sample)
+    frozen = host_ends_from_device(frozen_dev)
     t_start = time.perf_counter()
     z = zo.draw_z(lay, seed, 0, 0, masters.size, w.perturb_A)
     theta = zo.perturb(masters, z, +1, w.eps, prec)
@@ -134,17 +133,21 @@ def cpu_baseline_extrapolated(w, frozen_dev, masters, tokens, labels, seed, budg
     h = embed(w, frozen, tokens, prec)
     t_embed = time.perf_counter() - t0
     layer_times = []
-    for li, lw in enumerate(frozen["layers"]):
-        if li > 0 and (time.perf_counter() - t_start) + 1.1 * layer_times[0] > budget_s:
-            break                                    # a second block would overrun the sample: one block is timed
+    spent = time.perf_counter() - t_start
+    for li in range(min(w.n_layers, max_blocks)):
+        if li > 0 and spent + 1.1 * layer_times[0] > budget_s:
+            break                                    # another block would overrun the sample
+        lw = host_block_from_device(frozen_dev["layers"][li])
         t0 = time.perf_counter()
         h = decoder_layer(w, lw, li, h, lora, prec)
         layer_times.append(time.perf_counter() - t0)
+        spent += layer_times[-1]
+        del lw
     t_layer = sum(layer_times) / len(layer_times)
     t0 = time.perf_counter()
     head_loss(w, frozen, h, tokens, labels, prec)
     t_head = time.perf_counter() - t0
-    spent = time.perf_counter() - t_start
+    spent += t_head
     t_step = w.q * (t_noise + 2.0 * (t_embed + w.n_layers * t_layer + t_head) + t_update)
     toks = 2 * w.q * w.E * w.S
     return {"value": toks / t_step, "unit": "tokens/s", "cores": host_cores(), "kind": "oracle",
