@@ -129,3 +129,28 @@ def test_init_rejects_null_and_small_workspace_without_touching_the_device():
     assert lib.mpz_regen_noise(h, 1, 0, 2, -1.0) == 2
     assert "eps" in M.mpz_last_error(h)
     lib.mpz_destroy(h)
+
+
+def test_read_probe_rejects_what_its_kernel_could_not_read_in_bounds():
+    """mpz_debug_hbm_read_probe launches only when every tile of every block lies inside [rows][row_bytes]: the checks
+    run on the host, before any device call."""
+    lib = M.load_library()
+    lib.mpz_debug_hbm_read_probe.restype = C.c_int
+    lib.mpz_debug_hbm_read_probe.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_int32, C.c_void_p, C.c_void_p]
+    ok = dict(rows=256, row_bytes=4096, rb=128, seg=128, ks=2, lds=0, mode=0)
+
+    def call(buf=0x1000, out=0x1000, **kw):
+        a = dict(ok, **kw)
+        return lib.mpz_debug_hbm_read_probe(buf, a["rows"], a["row_bytes"], a["rb"], a["seg"], a["ks"], a["lds"], a["mode"], out, None)
+    assert call(buf=None) == 1 and call(out=None) == 1                    # MPZ_ERR_NULL
+    assert call(buf=0x1008) == 2                                          # MPZ_ERR_CONFIG: alignment
+    assert call(rows=200) == 3                                            # MPZ_ERR_SHAPE from here: rows not a multiple of the rows per block
+    assert call(ks=3) == 3                                                # a row does not split into 3 shares of whole tiles
+    assert call(seg=24) == 3 and call(seg=0) == 3
+    assert call(rb=96) == 3                                               # 96 x 128 B is not a whole number of 4 KiB
+    assert call(rb=128, seg=1024, row_bytes=8192) == 3                    # 128 KiB tiles: more than a thread holds
+    assert call(lds=200 * 1024) == 3
+    assert call(mode=4) == 2 and call(mode=-1) == 2
+    assert call(mode=2, lds=8192) == 3                                    # staging 16 KiB tiles needs 16 KiB of LDS
+    assert call(mode=3, lds=16384) == 3                                   # ... and 32 KiB with the activation tile

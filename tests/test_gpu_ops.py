@@ -338,3 +338,42 @@ def test_swiglu_dual_gemm_split_k(M_, ks):
     # one bf16 rounding, plus the fp32 summation error of a K = 2048 gate (about 3e-6 absolute) carried through
     # SiLU'(g) u where the gate nearly cancels
     assert np.mean(got != want) < 2e-3 and (np.abs(got - want) <= 1.01 * ulp + 1e-5 * (1.0 + np.abs(u))).all()
+
+
+@pytest.mark.parametrize("rb,seg,ks,mode", [(128, 128, 2, 0), (128, 128, 4, 3), (64, 256, 1, 1), (1, 4096, 2, 0), (32, 512, 2, 2)])
+def test_read_probe_reads_its_own_tiles(rb, seg, ks, mode):
+    """mpz_debug_hbm_read_probe (measurement hook): thread 0 of block (x, y) leaves the XOR of the 16-byte pieces it
+    fetched: pieces 0, 256, 512, ... of every tile of rows [x rb, (x + 1) rb) and of share y of the row (plus, with mode
+    bit 0, the same pieces of rows [0, rb)).  The host recomputes that from the buffer: the kernel reads what its
+    description says, in bounds, every tile once."""
+    import torch
+    import paper_2409_15520_amd as M
+    rows, row_bytes = 512 if rb > 1 else 8, 8192
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    buf = torch.randint(0, 2 ** 31 - 1, (rows * row_bytes // 4,), dtype=torch.int32, device="cuda", generator=g)
+    nbx = rows // rb
+    out = torch.zeros(nbx * ks, dtype=torch.int32, device="cuda")
+    lds = (2 if mode & 1 else 1) * rb * seg if mode & 2 else 0
+    M.mpz_debug_hbm_read_probe(buf.data_ptr(), rows, row_bytes, rb, seg, ks, lds, mode, out.data_ptr(),
+                               torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy().view(np.uint32).reshape(rows, row_bytes // 16, 4)
+    segc, L = seg // 16, rb * seg // 4096
+    tiles = row_bytes // seg // ks
+    want = np.zeros(nbx * ks, dtype=np.uint32)
+    for y in range(ks):
+        for x in range(nbx):
+            acc = np.zeros(4, dtype=np.uint32)
+            for t in range(tiles):
+                for i in range(L):
+                    c = 256 * i                                   # thread 0's pieces of a tile
+                    r, col = c // segc, (y * tiles + t) * segc + c % segc
+                    if mode & 2:                                  # through LDS: thread 0 reads back pieces (256 i) % (256 L) = 256 i
+                        pass
+                    acc ^= host[x * rb + r, col]
+                    if mode & 1:
+                        acc ^= host[r, col]
+            want[y * nbx + x] = acc[0] ^ acc[1] ^ acc[2] ^ acc[3]
+    got = out.cpu().numpy().view(np.uint32)
+    assert np.array_equal(got, want)
