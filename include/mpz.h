@@ -89,7 +89,9 @@ typedef struct {
                              nibble of byte j; s_* one fp32 absolute maximum per block of 64 consecutive input
                              channels, [k_out, k_in / 64]; W = bf16(level[code] * max).  Needs dtype BF16 and d_model,
                              d_ffn multiples of 64.  Each linear is dequantised into a workspace buffer right before
-                             its GEMM: once per pass for all the copies of that pass. */
+                             its GEMM, once per pass for all the copies of that pass; in a pass over at most 256
+                             stacked tokens the GEMMs that split K look the codes up in their own operand load
+                             instead (the same weights bit for bit, a quarter of the bytes read). */
 } mpz_config;
 
 /* Frozen parameters theta_f of one decoder block (Algorithm 1, input line).  All [dev], borrowed. */
@@ -313,6 +315,15 @@ mpz_status mpz_debug_gemm_bf16_splitk(int32_t M, int32_t N, int32_t K, const voi
 int32_t mpz_debug_gemm_splits(int32_t M, int32_t N, int32_t K, int32_t dual, size_t partial_elems);
 /* Test hook: allow (default) or forbid the split-K GEMMs inside a model's passes. */
 mpz_status mpz_debug_set_split_k(mpz_model* m, int32_t enable);
+
+/* Test hook: the split-K GEMM on 4-bit normal-float weights looked up in its own operand load (what a pass over at most
+ * 256 stacked tokens does with weight_quant = NF4): w_codes [dev] [N, K / 2] bytes (SwiGLU: [2N, K / 2], gate rows then up
+ * rows; two codes per byte, low nibble first), w_absmax [dev] [N or 2N, K / 64] fp32, 16- and 4-byte aligned; the other
+ * arguments as mpz_debug_gemm_bf16_splitk with 2 <= k_splits <= 64.  The result has the bits of mpz_debug_dequant_nf4
+ * followed by mpz_debug_gemm_bf16_splitk with the same k_splits.  Errors: NULL, SHAPE, DEVICE. */
+mpz_status mpz_debug_gemm_nf4_splitk(int32_t M, int32_t N, int32_t K, const void* x, const void* w_codes, const float* w_absmax,
+                                     const float* bias, int32_t act, const float* residual, void* out, int32_t out_f32,
+                                     int32_t k_splits, float* partial, size_t partial_elems, void* hip_stream);
 
 /* The same with weight-only int8 weights: w_codes [dev] int8 [N, K] (SwiGLU: [2N, K]), w_scale [dev] fp32 [N] ([2N]),
  * 16-byte aligned; out = act(x (codes * scale)^T + bias).  Tile configurations 1, 6, 11 and 12 only (others fall back to

@@ -88,6 +88,8 @@ struct LinearArgs {
   const void* x;              // [M, K] model dtype
   const void* w;              // [N, K] model dtype (output-major); int8 codes when w_scale is set
   const float* w_scale;       // [N] per-output-channel scales of int8 weights, or null
+  const void* w_codes;        // 4-bit weights that have not been dequantised: codes [N, K / 2] and
+  const float* w_absmax;      //   block maxima [N, K / 64]; w is then null until the launcher decides who dequantises
   const float* bias;          // [N] or null
   int n_seg; LoraSeg seg[3];
   int mfma_lora; MfmaLoraSeg mseg[3];   // the same segments in the MFMA kernels' operand layouts (when prepared)
@@ -152,6 +154,9 @@ struct MfmaGemmArgs {
   const void* x; const void* w;
   const float* w_scale;         // null: w is bf16.  Else w holds int8 codes [w_rows, K] and w_scale [w_rows] the
                                 // per-output-channel scales: the product is x . (code * scale)
+  const float* w_absmax;        // non-null (split-K launches only): w holds 4-bit normal-float codes [w_rows, K / 2]
+                                // (element 2j of a row in the low nibble of byte j) and w_absmax [w_rows, K / 64] the
+                                // block maxima; the operand load turns them into bf16(level[code] * max)
   int w_rows;                   // rows of w (N, or 2N for dual): bounds the weight buffer
   const float* bias;            // [N] (dual: [dual_offset + N]) or null
   int dual; int dual_offset;    // dual: second weight tile starts dual_offset rows below (SwiGLU gate | up)

@@ -96,7 +96,7 @@ __device__ __forceinline__ void i8x16_to_bf16(u32x4 in, u32x4& lo8, u32x4& hi8) 
 // conflict-free for BK = 32 and BK = 64.
 // HP > 0: rotary embedding fused into the epilogue for head width 64 * HP (the partner column d_head/2 away sits in
 // the same lane, HP MFMA tiles further), for output columns below rope_cols; the result is stored as bf16.
-template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP, bool WQ>
+template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP, int WQ>
 __global__ void __launch_bounds__(64 * WGN * WGM, (BN * BM * (DUAL ? 2 : 1) <= 256 * 128 && WGN * WGM == 4 && !(BN == 192 && BK == 64)) ? 2 : 1)
 gemm_bf16_kernel(MfmaGemmArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -106,7 +106,9 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   constexpr int NT = 64 * WGN * WGM;                                     // threads per block
   constexpr int TN = BN / WGN, TM = BM / WGM, NI = TN / 32, NJ = TM / 32;
   constexpr int CPR = BK / 8;                                            // 16-byte chunks per bf16 tile row
-  constexpr int WCH = WQ ? BK / 16 : CPR;                                // 16-byte chunks per W tile row (int8: 16 codes each)
+  constexpr int WCH = WQ == 2 ? BK / 32 : WQ == 1 ? BK / 16 : CPR;      // 16-byte chunks per W tile row (int8: 16 codes each, 4-bit: 32)
+  constexpr int WSH = WQ == 2 ? 2 : WQ == 1 ? 1 : 0;                     // bytes of a bf16 weight >> WSH = bytes of a stored weight
+  static_assert(WQ == 0 || WQ == 1 || (WQ == 2 && BK == 64 && !DUAL), "4-bit weights: one block of 64 input channels per K-tile");
   constexpr int LW = BN * WCH / NT, LX = BM * CPR / NT;                  // chunks per thread and tile
   static_assert(BN * WCH % NT == 0 && BM * CPR % NT == 0, "tile rows must deal out evenly to the threads");
   uint16_t* sW = (uint16_t*)smem;                        // [2 stages][NW][BN][LDS_STRIDE]
@@ -140,17 +142,36 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   // Operand fetch: raw buffer loads (per-thread byte offset in a VGPR, the K offset of the tile in an SGPR);
   // rows past the end of W or X fall outside the buffer and read as zero, so ragged M / N need no clamps.
   const __amdgpu_buffer_rsrc_t rsrcW =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.w), 0, (int)((size_t)a.w_rows * a.K * (WQ ? 1 : 2)), 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.w), 0, (int)(((size_t)a.w_rows * a.K * 2) >> WSH), 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrcX =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.x), 0, (int)((size_t)a.M * a.K * 2), 0x00020000);
   uint32_t voffW[NW][LW], voffX[LX];
   int ldsW[LW], ldsX[LX];
 #pragma unroll
   for (int i = 0; i < LW; ++i) {
-    const int c = tid + NT * i, row = c / WCH, kc = (c % WCH) * (WQ ? 16 : 8);
-    voffW[0][i] = ((uint32_t)(n0 + row) * (uint32_t)a.K + kc) * (WQ ? 1u : 2u);
-    if (DUAL) voffW[NW - 1][i] = ((uint32_t)(n0 + row + a.dual_offset) * (uint32_t)a.K + kc) * (WQ ? 1u : 2u);
+    const int c = tid + NT * i, row = c / WCH, kc = (c % WCH) * (8 << WSH);
+    voffW[0][i] = (((uint32_t)(n0 + row) * (uint32_t)a.K + kc) * 2u) >> WSH;
+    if (DUAL) voffW[NW - 1][i] = (((uint32_t)(n0 + row + a.dual_offset) * (uint32_t)a.K + kc) * 2u) >> WSH;
     ldsW[i] = row * LDS_STRIDE + kc;
+  }
+  // 4-bit weights: the block maximum of the K-tile's 64 input channels travels with every chunk of codes, and the
+  // sixteen levels sit in LDS (every lane of a wave may ask for another one; sixteen words lie in sixteen banks)
+  __shared__ float nf4_level[WQ == 2 ? 16 : 1];
+  __amdgpu_buffer_rsrc_t rsrcA = rsrcW;
+  uint32_t voffA[LW];
+  if constexpr (WQ == 2) {
+    rsrcA = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.w_absmax), 0, (int)((size_t)a.w_rows * (a.K / 64) * 4), 0x00020000);
+#pragma unroll
+    for (int i = 0; i < LW; ++i) voffA[i] = (uint32_t)(n0 + (tid + NT * i) / WCH) * (uint32_t)(a.K / 64) * 4u;
+    if (tid < 16) {
+      constexpr float kLevel[16] = {-1.0f, -0.6961928009986877f, -0.5250730514526367f, -0.39491748809814453f,
+                                    -0.28444138169288635f, -0.18477343022823334f, -0.09105003625154495f, 0.0f,
+                                    0.07958029955625534f, 0.16093020141124725f, 0.24611230194568634f,
+                                    0.33791524171829224f, 0.44070982933044434f, 0.5626170039176941f,
+                                    0.7229568362236023f, 1.0f};
+      nf4_level[tid] = kLevel[tid];
+    }
+    __syncthreads();
   }
 #pragma unroll
   for (int i = 0; i < LX; ++i) {
@@ -159,10 +180,19 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
     ldsX[i] = row * LDS_STRIDE + kc;
   }
   u32x4 rw[NSTG][NW][LW], rx[NSTG][LX];
+  float ra[NSTG][LW];                                    // 4-bit weights: block maxima of the chunks in rw
   // int8 weights: a fetched chunk is 16 codes; it becomes two 16-byte chunks of bf16 on its way into LDS
-#define MPZ_PUT_W(ptr, v)                                                          \
+#define MPZ_PUT_W(ptr, v, am)                                                      \
   {                                                                                \
-    if constexpr (WQ) {                                                            \
+    if constexpr (WQ == 2) {                                                       \
+      _Pragma("unroll") for (int wd_ = 0; wd_ < 4; ++wd_) {                        \
+        const uint32_t c_ = (v)[wd_];                                              \
+        float f_[8];                                                               \
+        _Pragma("unroll") for (int e_ = 0; e_ < 8; ++e_) f_[e_] = __fmul_rn(nf4_level[(c_ >> (4 * e_)) & 15u], (am)); \
+        *(u32x4*)((ptr) + 8 * wd_) = u32x4{pack_bf16x2(f_[0], f_[1]), pack_bf16x2(f_[2], f_[3]),  \
+                                           pack_bf16x2(f_[4], f_[5]), pack_bf16x2(f_[6], f_[7])}; \
+      }                                                                            \
+    } else if constexpr (WQ == 1) {                                                \
       u32x4 lo8_, hi8_;                                                            \
       i8x16_to_bf16(v, lo8_, hi8_);                                                \
       *(u32x4*)(ptr) = lo8_;                                                       \
@@ -176,7 +206,10 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
     const int soff = ((kt) + kt0) * BK * 2;                                        \
     _Pragma("unroll") for (int d = 0; d < NW; ++d)                                 \
       _Pragma("unroll") for (int i = 0; i < LW; ++i)                               \
-        rw[set][d][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, voffW[d][i], WQ ? soff / 2 : soff, 0); \
+        rw[set][d][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, voffW[d][i], soff >> WSH, 0); \
+    if constexpr (WQ == 2)                                                         \
+      _Pragma("unroll") for (int i = 0; i < LW; ++i)                               \
+        ra[set][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrcA, voffA[i], ((kt) + kt0) * 4, 0)); \
     _Pragma("unroll") for (int i = 0; i < LX; ++i)                                 \
       rx[set][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcX, voffX[i], soff, 0); \
     __builtin_amdgcn_sched_barrier(0);   /* keep the fetch here: the scheduler would sink it to its use */ \
@@ -185,7 +218,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
   {                                                                                \
     _Pragma("unroll") for (int d = 0; d < NW; ++d)                                 \
       _Pragma("unroll") for (int i = 0; i < LW; ++i)                               \
-        MPZ_PUT_W(sW + ((stage) * NW + d) * TILE_W + ldsW[i], rw[set][d][i])       \
+        MPZ_PUT_W(sW + ((stage) * NW + d) * TILE_W + ldsW[i], rw[set][d][i], ra[set][i]) \
     _Pragma("unroll") for (int i = 0; i < LX; ++i)                                 \
       *(u32x4*)(sX + (stage) * TILE_X + ldsX[i]) = rx[set][i];                     \
     __builtin_amdgcn_sched_barrier(0);                                             \
@@ -233,8 +266,10 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
         if (c >= (s * NV + KS - 1) / KS && c < ((s + 1) * NV + KS - 1) / KS) {     \
           if (c < NW * LW) {                                                       \
             const int d = c / LW, i = c % LW;                                      \
-            MPZ_PUT_W(sW + ((nxt) * NW + d) * TILE_W + ldsW[i], rw[sset][d][i])    \
-            rw[lset][d][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, voffW[d][i], WQ ? soff / 2 : soff, 0); \
+            MPZ_PUT_W(sW + ((nxt) * NW + d) * TILE_W + ldsW[i], rw[sset][d][i], ra[sset][i]) \
+            rw[lset][d][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, voffW[d][i], soff >> WSH, 0); \
+            if constexpr (WQ == 2)                                                 \
+              ra[lset][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrcA, voffA[i], ((ktl) + kt0) * 4, 0)); \
           } else {                                                                 \
             const int i = c - NW * LW;                                             \
             *(u32x4*)(sX + (nxt) * TILE_X + ldsX[i]) = rx[sset][i];                \
@@ -244,7 +279,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
       }                                                                            \
       MPZ_MFMAS(s & 1)                                                             \
     }                                                                              \
-    sched_phase<NM, NF, NW * LW, LX, WQ ? 2 : 1, KS>();                            \
+    sched_phase<NM, NF, NW * LW, LX, WQ == 2 ? 4 : WQ == 1 ? 2 : 1, KS>();                            \
   }
 
   f32x16 acc[NW][NI][NJ];
@@ -320,7 +355,7 @@ gemm_bf16_kernel(MfmaGemmArgs a) {
 
   // int8 weights: the accumulators hold x . codes; the per-output-channel scale turns them into x . W before
   // anything else (low-rank term, bias) is added
-  if constexpr (WQ) {
+  if constexpr (WQ == 1) {
 #pragma unroll
     for (int d = 0; d < NW; ++d)
 #pragma unroll
@@ -946,7 +981,7 @@ __global__ void __launch_bounds__(256) pack_factors_vec_kernel(const float* __re
 // The numbered configurations (BN x BM x BK, waves) are listed where they are instantiated, in launch_gemm_mfma;
 // choose_cfg picks among 6 (256 x 256 x 64, 8 waves: large problems), 12 and 1 (128 x 128 x 64 with 8 or 4 waves),
 // 11 (192 x 128 x 64), 9 and 10 (128 x 64 and 64 x 64: problems with fewer tiles than CUs).  LDS = stages x (BN + BM) x (BK + 8) x 2 bytes, or the epilogue strips if those are larger.
-template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP = 0, bool WQ = false>
+template <int BN, int BM, int BK, int WGN, int WGM, bool DUAL, int HP = 0, int WQ = 0>
 hipError_t launch_cfg(hipStream_t st, const MfmaGemmArgs& a) {
   constexpr size_t lds_stages = (size_t)2 * ((DUAL ? 2 : 1) * BN + BM) * (BK + 8) * 2;
   constexpr size_t lds_strips = (size_t)WGN * WGM * 32 * (BN / WGN + 4) * 4;          // epilogue: one strip per wave
@@ -982,14 +1017,14 @@ bool cfg_ok(const MfmaGemmArgs& a, int cfg) {
 
 // split K: output features per block.  Wide or long-K projections stream through 128-feature tiles, the others through
 // 64-feature tiles (twice the blocks); a dual launch has one tile shape.
-int split_tile_bn(const MfmaGemmArgs& a) { return (a.dual || a.N >= 8192 || a.K >= 8192 || a.w_scale != nullptr) ? 128 : 64; }
+int split_tile_bn(const MfmaGemmArgs& a) { return (a.dual || a.N >= 8192 || a.K >= 8192 || a.w_scale != nullptr || a.w_absmax != nullptr) ? 128 : 64; }
 
 int choose_cfg(const MfmaGemmArgs& a) {
   // split K (at most 256 stacked tokens): a block takes all the tokens it can (the weights are then fetched from HBM
   // once) and as few output features as the low-rank segments allow, so that there are many blocks to stream them
   if (a.k_splits > 1) {
     const int forced = a.tile_cfg % 100;                 // measurement: tile_cfg = 100 k_splits + tile
-    if (a.w_scale == nullptr && (forced == 1 || forced == 9 || forced == 10 || forced == 12 || forced == 13) && cfg_ok(a, forced)) return forced;
+    if (a.w_scale == nullptr && a.w_absmax == nullptr && (forced == 1 || forced == 9 || forced == 10 || forced == 12 || forced == 13) && cfg_ok(a, forced)) return forced;
     if (split_tile_bn(a) == 128 || !cfg_ok(a, 13)) return a.M <= 64 ? 9 : 1;     // 128 features x 64 or 128 tokens
     return a.M <= 64 ? 10 : 13;                                                   // 64 features x 64 or 128 tokens
   }
@@ -1064,6 +1099,9 @@ bool mfma_gemm_supported(const MfmaGemmArgs& a) {
   if (a.K % 64 || a.N % 4 || a.M < 1 || a.N < 1) return false;
   if ((size_t)a.M * a.K * 2 >= ((size_t)1 << 31) || (size_t)(a.dual ? 2 : 1) * a.N * a.K * 2 >= ((size_t)1 << 31)) return false;
   if (a.w_scale != nullptr && (a.K % 16 || ((uintptr_t)a.w_scale & 15))) return false;
+  if (a.w_absmax != nullptr && (a.k_splits <= 1 || a.w_scale != nullptr || ((uintptr_t)a.w_absmax & 3) || ((uintptr_t)a.w & 15) ||
+                                (a.dual && a.dual_offset != a.N) || (size_t)a.w_rows * (a.K / 64) * 4 >= ((size_t)1 << 31)))
+    return false;
   for (int s = 0; s < a.n_seg; ++s)
     if (a.seg[s].rp % 16) return false;
   if (!cfg_ok(a, 1)) return false;
@@ -1178,6 +1216,8 @@ hipError_t launch_gemm_mfma(hipStream_t st, const MfmaGemmArgs& a) {
     MfmaGemmArgs b = a;
     if (a.dual && a.dual_offset == a.N) { b.dual = 0; b.N = 2 * a.N; }
     if (b.dual) e = q8 ? launch_cfg<128, 128, 32, 2, 2, true, 0, true>(st, a) : launch_cfg<128, 128, 32, 2, 2, true>(st, a);
+    else if (a.w_absmax != nullptr)          // 4-bit codes looked up in the operand load: the two 128-feature tiles
+      e = choose_cfg(b) == 9 ? launch_cfg<128, 64, 64, 2, 2, false, 0, 2>(st, b) : launch_cfg<128, 128, 64, 2, 2, false, 0, 2>(st, b);
     else
       switch (choose_cfg(b)) {
         case 9: e = q8 ? launch_cfg<128, 64, 64, 2, 2, false, 0, true>(st, b) : launch_cfg<128, 64, 64, 2, 2, false>(st, b); break;

@@ -362,17 +362,24 @@ Buffers view(const mpz_model* m, int E, int S) {
 // The frozen weight of one block linear as the GEMM reads it.  4-bit weights are dequantised to bf16 here, into the
 // one workspace buffer every linear shares (stream order keeps a GEMM ahead of the next dequantisation): once per
 // pass, whatever the number of copies in it (Appendix D: the inner loop dequantises once per step).
-struct WeightRef { const void* w; const float* scale; };
-WeightRef weight_operand(mpz_model* m, const void* w, const float* s, int N, int K) {
-  if (m->cfg.weight_quant != MPZ_WEIGHT_QUANT_NF4) return {w, s};
+// A pass over few stacked tokens is bound by the weight stream, and there the split-K GEMM looks the 4-bit codes up in
+// its own operand load (a quarter of the bytes, no bf16 round trip through HBM): such a pass hands the codes on
+// (w_codes / w_absmax) and gemm() dequantises only if the launch turns out not to split K.
+struct WeightRef { const void* w; const float* scale; const void* codes; const float* absmax; };
+const void* dequantised(mpz_model* m, const void* codes, const float* absmax, int N, int K) {
   ProfScope ps(m, MPZ_PROF_PACK, 0.0, (double)N * K * (0.5 + 4.0 / 64.0 + 2.0));
-  launch_nf4_dequant(m->stream, w, s, m->buf.wq, (int64_t)N * K);
-  return {m->buf.wq, nullptr};
+  launch_nf4_dequant(m->stream, codes, absmax, m->buf.wq, (int64_t)N * K);
+  return m->buf.wq;
 }
-
+WeightRef weight_operand(mpz_model* m, const void* w, const float* s, int N, int K, int M) {
+  if (m->cfg.weight_quant != MPZ_WEIGHT_QUANT_NF4) return {w, s, nullptr, nullptr};
+  if (m->use_mfma && m->split_k && m->buf.splitk != nullptr && M <= 256) return {nullptr, nullptr, w, s};
+  return {dequantised(m, w, s, N, K), nullptr, nullptr, nullptr};
+}
+void set_weight(LinearArgs& a, const WeightRef& r) { a.w = r.w; a.w_scale = r.scale; a.w_codes = r.codes; a.w_absmax = r.absmax; }
 // Few stacked tokens: let k_splits blocks share an output tile (see MfmaGemmArgs).  Called once the shape and the
 // epilogue of g are filled in, before mfma_gemm_supported.
-void plan_split(const mpz_model* m, MfmaGemmArgs& g) {
+void plan_split(const mpz_model* m, MfmaGemmArgs& g) {      // (g.w_absmax, if any, is already set: the tile depends on it)
   g.k_splits = 1; g.partial = nullptr; g.ldp = 0;
   if (m->buf.splitk == nullptr || !m->split_k) return;
   const int ks = mfma_gemm_splits(g, m->buf.splitk_elems);
@@ -392,51 +399,57 @@ void launch_checked(mpz_model* m, const MfmaGemmArgs& g) {
 // launches the norm itself.
 struct NormAfter { const float* g; const float* b; void* x; bool done; };
 bool gemm(mpz_model* m, const LinearArgs& a, NormAfter* then = nullptr) {
-  if (a.rope_cos != nullptr) {
-    if (!(m->use_mfma && a.dtype == MPZ_DTYPE_BF16 && (a.n_seg == 0 || a.mfma_lora))) return false;
-    MfmaGemmArgs g{};
-    g.M = a.M; g.N = a.N; g.K = a.K; g.x = a.x; g.w = a.w; g.w_scale = a.w_scale; g.w_rows = a.N; g.bias = a.bias;
-    g.n_seg = a.n_seg; g.rows_per_copy = a.rows_per_copy; g.act = -1; g.out_f32 = 0; g.out = a.out; g.ldo = a.N;
+  const bool rope = a.rope_cos != nullptr;
+  MfmaGemmArgs g{};
+  bool use_mfma_gemm = false;
+  if (m->use_mfma && a.dtype == MPZ_DTYPE_BF16 && (a.n_seg == 0 || a.mfma_lora)) {
+    g.M = a.M; g.N = a.N; g.K = a.K; g.x = a.x; g.w = a.w; g.w_scale = a.w_scale; g.w_rows = a.N; g.bias = a.bias; g.dual = 0; g.dual_offset = 0;
+    g.n_seg = a.n_seg; g.rows_per_copy = a.rows_per_copy;
     for (int i = 0; i < a.n_seg; ++i) g.seg[i] = a.mseg[i];
-    g.rope_cos = a.rope_cos; g.rope_sin = a.rope_sin; g.rope_cols = a.rope_cols; g.rope_dh = a.rope_dh; g.S = a.S;
-    g.rope_pos = a.rope_pos;
-    g.tile_cfg = m->force_tile_cfg;
+    g.tile_cfg = m->force_tile_cfg; g.out = a.out; g.ldo = a.N;
+    if (rope) {
+      g.act = -1; g.out_f32 = 0;
+      g.rope_cos = a.rope_cos; g.rope_sin = a.rope_sin; g.rope_cols = a.rope_cols; g.rope_dh = a.rope_dh; g.S = a.S;
+      g.rope_pos = a.rope_pos;
+    } else {
+      g.act = a.act; g.residual = a.residual;
+      g.out_f32 = a.out_kind != 0;                 // bf16 models stage in fp32
+    }
+    // 4-bit weights nobody has dequantised yet: the split-K kernel reads the codes itself; a launch that does not
+    // split K gets them dequantised below (the workspace buffer is where they will be)
+    if (a.w_codes != nullptr) { g.w = a.w_codes; g.w_absmax = a.w_absmax; }
     plan_split(m, g);
-    if (!mfma_gemm_supported(g)) return false;
-    ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)a.N * a.K, 2.0 * ((double)a.M * a.K + (double)a.N * a.K + (double)a.M * a.N));
-    launch_checked(m, g);
-    return true;
+    if (a.w_codes != nullptr && g.k_splits <= 1) { g.w = m->buf.wq; g.w_absmax = nullptr; }
+    use_mfma_gemm = mfma_gemm_supported(g);
+  }
+  if (rope && !use_mfma_gemm) return false;         // nothing launched: the caller goes on without the fused rotation
+  LinearArgs dense = a;                             // the same linear with weights every kernel can read
+  if (a.w_codes != nullptr && !(use_mfma_gemm && g.k_splits > 1)) {
+    dense.w = dequantised(m, a.w_codes, a.w_absmax, a.N, a.K);
+    dense.w_codes = nullptr; dense.w_absmax = nullptr;
   }
   ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)a.N * a.K,
-               esz(m) * ((double)a.M * a.K + (double)a.N * a.K) + (a.out_kind == 0 ? esz(m) : 4.0) * a.M * (double)a.N +
-                   (a.residual ? 4.0 * a.M * (double)a.N : 0.0));
-  if (m->use_mfma && a.dtype == MPZ_DTYPE_BF16 && (a.n_seg == 0 || a.mfma_lora)) {
-    MfmaGemmArgs g{};
-    g.M = a.M; g.N = a.N; g.K = a.K; g.x = a.x; g.w = a.w; g.w_scale = a.w_scale; g.w_rows = a.N; g.bias = a.bias; g.dual = 0; g.dual_offset = 0;
-    g.n_seg = a.n_seg; g.rows_per_copy = a.rows_per_copy; g.act = a.act; g.residual = a.residual;
-    g.out_f32 = a.out_kind != 0; g.out = a.out; g.ldo = a.N;   // bf16 models stage in fp32
-    g.tile_cfg = m->force_tile_cfg;
-    for (int i = 0; i < a.n_seg; ++i) g.seg[i] = a.mseg[i];
-    plan_split(m, g);
-    if (mfma_gemm_supported(g)) {
-      if (then != nullptr && m->fuse_norm_lora && splitk_reduce_norm_supported(g) && a.N == m->cfg.d_model) {
-        g.defer_reduce = 1;
-        launch_checked(m, g);
-        ps.end();                                // (the fused kernel is booked under the norm)
-        ProfScope pn(m, MPZ_PROF_NORM, 0.0, (double)a.M * a.N * (4.0 * g.k_splits + 8.0 + esz(m)));
-        launch_splitk_reduce_norm(m->stream, g, m->cfg.norm, m->cfg.norm_eps, then->g, then->b, then->x);
-        then->done = true;
-        return true;
-      }
+               rope ? 2.0 * ((double)a.M * a.K + (double)a.N * a.K + (double)a.M * a.N)
+                    : esz(m) * ((double)a.M * a.K + (double)a.N * a.K) + (a.out_kind == 0 ? esz(m) : 4.0) * a.M * (double)a.N +
+                          (a.residual ? 4.0 * a.M * (double)a.N : 0.0));
+  if (use_mfma_gemm) {
+    if (!rope && then != nullptr && m->fuse_norm_lora && splitk_reduce_norm_supported(g) && a.N == m->cfg.d_model) {
+      g.defer_reduce = 1;
       launch_checked(m, g);
+      ps.end();                                  // (the fused kernel is booked under the norm)
+      ProfScope pn(m, MPZ_PROF_NORM, 0.0, (double)a.M * a.N * (4.0 * g.k_splits + 8.0 + esz(m)));
+      launch_splitk_reduce_norm(m->stream, g, m->cfg.norm, m->cfg.norm_eps, then->g, then->b, then->x);
+      then->done = true;
       return true;
     }
+    launch_checked(m, g);
+    return true;
   }
   if (a.w_scale != nullptr) {                  // no shape-agnostic kernel reads int8 weights: refuse, loudly
     m->deferred = "int8 weights: a GEMM of this pass has a shape the MFMA kernel does not take";
     return true;
   }
-  launch_linear_simple(m->stream, a);
+  launch_linear_simple(m->stream, dense);
   return true;
 }
 
@@ -447,8 +460,12 @@ bool gemm_swiglu_mfma(mpz_model* m, const LinearArgs& a, int f, void* u_out) {
   g.M = a.M; g.N = f; g.K = a.K; g.x = a.x; g.w = a.w; g.w_scale = a.w_scale; g.w_rows = 2 * f; g.bias = a.bias; g.dual = 1; g.dual_offset = f;
   g.rows_per_copy = a.rows_per_copy; g.act = -1; g.out_f32 = 0; g.out = u_out; g.ldo = f;
   g.tile_cfg = m->force_tile_cfg;
+  if (a.w_codes != nullptr) { g.w = a.w_codes; g.w_absmax = a.w_absmax; }
   plan_split(m, g);
-  if (!mfma_gemm_supported(g)) return false;
+  const bool dequantise = a.w_codes != nullptr && g.k_splits <= 1;
+  if (dequantise) { g.w = m->buf.wq; g.w_absmax = nullptr; }
+  if (!mfma_gemm_supported(g)) return false;     // (nothing launched: the caller's plain GEMM dequantises for itself)
+  if (dequantise) dequantised(m, a.w_codes, a.w_absmax, 2 * f, a.K);
   ProfScope ps(m, MPZ_PROF_GEMM, 2.0 * a.M * (double)(2 * f) * a.K,
                2.0 * ((double)a.M * a.K + 2.0 * f * a.K + (double)a.M * f));
   launch_checked(m, g);
@@ -597,8 +614,7 @@ void run_qkv(mpz_model* m, const Buffers& b, int l, int E, int S, bool rope, int
       ProfScope ps(m, MPZ_PROF_LORA_DOWN, 2.0 * T * (double)d * nt * r, esz(m) * T * ((double)d + (double)nt * r));
       launch_lora_down_simple(st, da);
     }
-    const WeightRef wq = weight_operand(m, lw.w_qkv, lw.s_qkv, nqkv, d);
-    qa.w = wq.w; qa.w_scale = wq.scale;
+    set_weight(qa, weight_operand(m, lw.w_qkv, lw.s_qkv, nqkv, d, T));
     if (rope) {
       qa.out_kind = 0; qa.out = b.qkv;
       qa.rope_cos = b.rope_cos; qa.rope_sin = b.rope_sin; qa.rope_cols = d + dkv; qa.rope_dh = dh; qa.S = S;
@@ -683,8 +699,7 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
       oa.seg[0].col_begin = 0; oa.seg[0].col_end = d; oa.seg[0].t = b.t; oa.seg[0].t_stride = r; oa.seg[0].t_off = 0;
       oa.seg[0].Bc = b.pert + find_tensor(m, l, 3, 1)->offset; oa.seg[0].copy_stride = m->P * m->cstep;
     }
-    const WeightRef wo = weight_operand(m, lw.w_o, lw.s_o, d, d);
-    oa.w = wo.w; oa.w_scale = wo.scale;
+    set_weight(oa, weight_operand(m, lw.w_o, lw.s_o, d, d, T));
     // feed-forward block: its pre-norm rides on the reduction of the output projection where that splits K
     NormAfter ffn_norm{lw.ln2_g, lw.ln2_b, b.x, false};
     gemm(m, oa, &ffn_norm);
@@ -693,8 +708,7 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     ua.dtype = c.dtype; ua.M = T; ua.N = swiglu ? 2 * f : f; ua.K = d; ua.x = b.x; ua.w = lw.w_up; ua.w_scale = lw.s_up; ua.bias = lw.b_up;
     ua.rank = r; ua.rows_per_copy = rpc; ua.act = swiglu ? -1 : c.act;
     ua.out_kind = swiglu ? 2 : 0; ua.out = swiglu ? b.stage : b.u;
-    const WeightRef wu = weight_operand(m, lw.w_up, lw.s_up, swiglu ? 2 * f : f, d);
-    ua.w = wu.w; ua.w_scale = wu.scale;
+    set_weight(ua, weight_operand(m, lw.w_up, lw.s_up, swiglu ? 2 * f : f, d, T));
     if (!(swiglu && gemm_swiglu_mfma(m, ua, f, b.u))) {
       gemm(m, ua);
       if (swiglu) {
@@ -705,8 +719,7 @@ void run_layers(mpz_model* m, float* h, int l0, int l1, int E, int S) {
     LinearArgs wa{};
     wa.dtype = c.dtype; wa.M = T; wa.N = d; wa.K = f; wa.x = b.u; wa.w = lw.w_down; wa.w_scale = lw.s_down; wa.bias = lw.b_down;
     wa.rank = r; wa.rows_per_copy = rpc; wa.act = -1; wa.residual = b.h; wa.out_kind = 1; wa.out = b.h;
-    const WeightRef wd = weight_operand(m, lw.w_down, lw.s_down, d, f);
-    wa.w = wd.w; wa.w_scale = wd.scale;
+    set_weight(wa, weight_operand(m, lw.w_down, lw.s_down, d, f, T));
     if (l + 1 < l1) {                                 // likewise the next block's first pre-norm
       NormAfter next_norm{m->layers[l + 1].ln1_g, m->layers[l + 1].ln1_b, b.x, false};
       gemm(m, wa, &next_norm);
@@ -1327,6 +1340,25 @@ mpz_status mpz_debug_gemm_bf16_splitk(int32_t M, int32_t N, int32_t K, const voi
   if (le != hipSuccess) return fail(nullptr, MPZ_ERR_DEVICE, std::string("mpz_debug_gemm_bf16_splitk: ") + hipGetErrorString(le));
   if (check_device(nullptr, "mpz_debug_gemm_bf16_splitk") != MPZ_OK) return MPZ_ERR_DEVICE;
   return MPZ_OK;
+}
+
+mpz_status mpz_debug_gemm_nf4_splitk(int32_t M, int32_t N, int32_t K, const void* x, const void* w_codes, const float* w_absmax,
+                                     const float* bias, int32_t act, const float* residual, void* out, int32_t out_f32,
+                                     int32_t k_splits, float* partial, size_t partial_elems, void* hip_stream) {
+  if (!x || !w_codes || !w_absmax || !out || !partial) return fail(nullptr, MPZ_ERR_NULL, "mpz_debug_gemm_nf4_splitk: NULL argument");
+  if (k_splits < 2 || k_splits > 64) return fail(nullptr, MPZ_ERR_SHAPE, "mpz_debug_gemm_nf4_splitk: k_splits outside [2, 64]");
+  if (K % 64 || N % 4 || M < 1 || N < 1) return fail(nullptr, MPZ_ERR_SHAPE, "shape not supported by the MFMA GEMM (K % 64, N % 4)");
+  MfmaGemmArgs g{};
+  g.M = M; g.N = N; g.K = K; g.x = x; g.w = w_codes; g.w_absmax = w_absmax; g.w_rows = N; g.bias = bias; g.rows_per_copy = M; g.act = act;
+  g.residual = residual; g.out_f32 = out_f32; g.out = out; g.ldo = N; g.tile_cfg = 100 * k_splits;
+  if (act == MPZ_ACT_SWIGLU) { g.dual = 1; g.dual_offset = N; g.w_rows = 2 * N; g.act = -1; }
+  if (mfma_gemm_splits(g, partial_elems) != k_splits)
+    return fail(nullptr, MPZ_ERR_SHAPE, "mpz_debug_gemm_nf4_splitk: k_splits does not fit K or the partial buffer");
+  g.k_splits = k_splits; g.partial = partial; g.ldp = (g.dual ? 2 : 1) * N;
+  if (!mfma_gemm_supported(g)) return fail(nullptr, MPZ_ERR_SHAPE, "shape or alignment not supported by the MFMA GEMM");
+  const hipError_t le = launch_gemm_mfma((hipStream_t)hip_stream, g);
+  if (le != hipSuccess) return fail(nullptr, MPZ_ERR_DEVICE, std::string("mpz_debug_gemm_nf4_splitk: ") + hipGetErrorString(le));
+  return check_device(nullptr, "mpz_debug_gemm_nf4_splitk");
 }
 
 int32_t mpz_debug_gemm_splits(int32_t M, int32_t N, int32_t K, int32_t dual, size_t partial_elems) {

@@ -288,6 +288,18 @@ def mpz_debug_gemm_bf16_splitk(M: int, N: int, K: int, x_ptr: int, w_ptr: int, b
                                           partial_ptr, partial_elems, stream_ptr))
 
 
+def mpz_debug_gemm_nf4_splitk(M: int, N: int, K: int, x_ptr: int, codes_ptr: int, absmax_ptr: int, bias_ptr: Optional[int],
+                              act: int, residual_ptr: Optional[int], out_ptr: int, out_f32: bool, k_splits: int,
+                              partial_ptr: int, partial_elems: int, stream_ptr: int):
+    lib = load_library()
+    lib.mpz_debug_gemm_nf4_splitk.restype = C.c_int
+    lib.mpz_debug_gemm_nf4_splitk.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t,
+                                              C.c_void_p]
+    _check(lib.mpz_debug_gemm_nf4_splitk(M, N, K, x_ptr, codes_ptr, absmax_ptr, bias_ptr, act, residual_ptr, out_ptr,
+                                         int(out_f32), k_splits, partial_ptr, partial_elems, stream_ptr))
+
+
 def mpz_debug_gemm_splits(M: int, N: int, K: int, dual: bool, partial_elems: int) -> int:
     lib = load_library()
     lib.mpz_debug_gemm_splits.restype = C.c_int32

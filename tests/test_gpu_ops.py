@@ -377,3 +377,55 @@ def test_read_probe_reads_its_own_tiles(rb, seg, ks, mode):
             want[y * nbx + x] = acc[0] ^ acc[1] ^ acc[2] ^ acc[3]
     got = out.cpu().numpy().view(np.uint32)
     assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("M_,N_,K_,act,resid,ks", [(128, 512, 1024, -1, False, 2), (64, 388, 2048, -1, True, 4),
+                                                   (128, 256, 1024, 2, False, 2), (100, 132, 4096, 0, False, 8),
+                                                   (256, 4096, 4096, -1, True, 3)])
+def test_gemm_nf4_codes_in_the_operand_load(M_, N_, K_, act, resid, ks):
+    """Passes over few tokens read 4-bit weights as codes inside the split-K GEMM (looked up and scaled on the way into
+    LDS) instead of from a dequantised bf16 buffer.  Same weights bf16(level[code] * max), same K order: the output has
+    the bits of mpz_debug_dequant_nf4 followed by the bf16 split-K GEMM with the same split count and tile - for plain,
+    residual, ReLU and stacked gate / up (SwiGLU) launches, whole and ragged tiles, token counts on both tile heights."""
+    import torch
+    import paper_2409_15520_amd as M
+    st = torch.cuda.current_stream().cuda_stream
+    g = torch.Generator(device="cuda")
+    g.manual_seed(M_ * 31 + N_)
+    rows = 2 * N_ if act == 2 else N_
+    codes = torch.randint(0, 256, (rows, K_ // 2), dtype=torch.uint8, device="cuda", generator=g)
+    absmax = (0.048 * (0.5 + torch.rand(rows, K_ // 64, device="cuda", generator=g))).float().contiguous()
+    x = torch.randn(M_, K_, device="cuda", generator=g).to(torch.bfloat16)
+    res = torch.randn(M_, N_, device="cuda", generator=g).float() if resid else None
+    w = torch.empty(rows, K_, dtype=torch.bfloat16, device="cuda")
+    M.mpz_debug_dequant_nf4(codes.data_ptr(), absmax.data_ptr(), w.data_ptr(), rows * K_, st)
+    cap = ks * M_ * rows
+    part = torch.empty(cap, dtype=torch.float32, device="cuda")
+    outs = []
+    for which in ("codes", "dense"):
+        out = torch.full((M_, N_), float("nan"), dtype=torch.float32 if resid else torch.bfloat16, device="cuda")
+        rp = res.data_ptr() if resid else None
+        if which == "codes":
+            M.mpz_debug_gemm_nf4_splitk(M_, N_, K_, x.data_ptr(), codes.data_ptr(), absmax.data_ptr(), None, act, rp,
+                                        out.data_ptr(), resid, ks, part.data_ptr(), cap, st)
+        else:
+            tile = 9 if M_ <= 64 else 1                     # the tile the code path uses (128 features x 64 / 128 tokens)
+            M.mpz_debug_gemm_bf16_splitk(M_, N_, K_, x.data_ptr(), w.data_ptr(), None, act, rp, out.data_ptr(), resid,
+                                         ks + 1000 * tile, part.data_ptr(), cap, st)
+        torch.cuda.synchronize()
+        outs.append(out.float().cpu().numpy())
+    assert np.isfinite(outs[0]).all()
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+    # and it is the product: fp64 reference on the dequantised weights (tolerance: fp32 accumulation + one bf16 rounding)
+    wd = w.float().cpu().numpy().astype(np.float64)
+    xd = x.float().cpu().numpy().astype(np.float64)
+    ref = xd @ wd[:N_].T
+    if act == 2:
+        up = xd @ wd[N_:].T
+        ref = ref / (1.0 + np.exp(-ref)) * up
+    elif act == 0:
+        ref = np.maximum(ref, 0.0)
+    if resid:
+        ref = ref + res.cpu().numpy().astype(np.float64)
+    tol = 1e-5 if resid else 1.0 / 128
+    assert np.abs(outs[0] - ref).max() <= tol * (1.0 + np.abs(ref).max())
