@@ -1136,7 +1136,9 @@ int mfma_gemm_splits(const MfmaGemmArgs& a, size_t partial_capacity) {
   const int n_rows = (a.dual && a.dual_offset == a.N) ? 2 * a.N : a.N;     // stacked gate || up runs as one plain GEMM
   const long tiles = (long)((n_rows + bn - 1) / bn) * (a.M > 128 ? 2 : 1);
   if (tiles >= 256) return 1;                            // enough blocks without it
-  long ks = (255 + tiles) / tiles;
+  // 4-bit codes looked up in the operand load: those blocks are bound by their own look-ups, not by memory, and a CU holds
+  // two of them - as many splits as still fit that (measured best on all four 7B-shaped projections at 128 tokens)
+  long ks = a.w_absmax != nullptr ? 512 / tiles : (255 + tiles) / tiles;
   const long by_k = a.K / 512, by_traffic = a.K / (4L * a.M);
   ks = ks < by_k ? ks : by_k;
   ks = ks < by_traffic ? ks : by_traffic;
